@@ -1,0 +1,112 @@
+"""ctypes binding of attn_oracle.c (plain C, fp64) -- test infrastructure only.
+
+The arithmetic lives in attn_oracle.c; this file only marshals numpy arrays.  Inputs are
+bf16 bit patterns held in numpy uint16 arrays of shape [B,H,S,D] (C-contiguous); outputs
+are float64.  See attn_oracle.c for the definition that is implemented (textbook scaled
+dot-product attention in the natural-log, max-stabilised form; the paper's kernel-suite
+section names the operator, its debugging table fixes the log base).
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "attn_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle_attn.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile attn_oracle.c with gcc (OpenMP) into liboracle_attn.so next to it."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+                               "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        u16p = ctypes.POINTER(ctypes.c_uint16)
+        f64p = ctypes.POINTER(ctypes.c_double)
+        i = ctypes.c_int
+        lib.oracle_attn_fwd.argtypes = [u16p, u16p, u16p, i, i, i, i, ctypes.c_float, i,
+                                        f64p, f64p, f64p]
+        lib.oracle_attn_fwd.restype = i
+        lib.oracle_attn_bwd.argtypes = [u16p, u16p, u16p, u16p, i, i, i, i, ctypes.c_float, i,
+                                        f64p, f64p, f64p, f64p]
+        lib.oracle_attn_bwd.restype = i
+        lib.oracle_num_threads.argtypes = []
+        lib.oracle_num_threads.restype = i
+        _lib = lib
+    return _lib
+
+
+def num_threads():
+    """OpenMP threads the oracle will use (omp_get_max_threads)."""
+    return int(_load().oracle_num_threads())
+
+
+def _u16(x, shape=None):
+    x = np.ascontiguousarray(x)
+    if x.dtype != np.uint16:
+        raise TypeError("oracle inputs are bf16 bit patterns in uint16 arrays")
+    if x.ndim != 4 or (shape is not None and x.shape != shape):
+        raise ValueError("oracle inputs must all be [B,H,S,D] of one shape")
+    return x
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct)) if a is not None else None
+
+
+def attn_fwd(Q, K, V, scale, causal, want_probs=False):
+    """O [B,H,S,D] f64, LSE [B,H,S] f64 (natural log) [, P [B,H,S,S] f64]."""
+    Q = _u16(Q); K = _u16(K, Q.shape); V = _u16(V, Q.shape)
+    B, H, S, D = Q.shape
+    O = np.empty((B, H, S, D), np.float64)
+    LSE = np.empty((B, H, S), np.float64)
+    P = np.empty((B, H, S, S), np.float64) if want_probs else None
+    rc = _load().oracle_attn_fwd(_p(Q, ctypes.c_uint16), _p(K, ctypes.c_uint16),
+                                 _p(V, ctypes.c_uint16), B, H, S, D,
+                                 ctypes.c_float(np.float32(scale)), int(bool(causal)),
+                                 _p(O, ctypes.c_double), _p(LSE, ctypes.c_double),
+                                 _p(P, ctypes.c_double))
+    if rc != 0:
+        raise RuntimeError("oracle_attn_fwd failed (rc=%d)" % rc)
+    return (O, LSE, P) if want_probs else (O, LSE)
+
+
+def attn_probs(Q, K, V, scale, causal):
+    """The full probability matrix P [B,H,S,S] (zeros outside the mask); small shapes only."""
+    return attn_fwd(Q, K, V, scale, causal, want_probs=True)[2]
+
+
+def attn_bwd(Q, K, V, dO, scale, causal, want_dscores=False):
+    """dQ, dK, dV [B,H,S,D] f64 [, dS [B,H,S,S] f64] for upstream gradient dO on O."""
+    Q = _u16(Q); K = _u16(K, Q.shape); V = _u16(V, Q.shape); dO = _u16(dO, Q.shape)
+    B, H, S, D = Q.shape
+    dQ = np.empty((B, H, S, D), np.float64)
+    dK = np.empty_like(dQ)
+    dV = np.empty_like(dQ)
+    dS = np.empty((B, H, S, S), np.float64) if want_dscores else None
+    rc = _load().oracle_attn_bwd(_p(Q, ctypes.c_uint16), _p(K, ctypes.c_uint16),
+                                 _p(V, ctypes.c_uint16), _p(dO, ctypes.c_uint16),
+                                 B, H, S, D, ctypes.c_float(np.float32(scale)),
+                                 int(bool(causal)), _p(dQ, ctypes.c_double),
+                                 _p(dK, ctypes.c_double), _p(dV, ctypes.c_double),
+                                 _p(dS, ctypes.c_double))
+    if rc != 0:
+        raise RuntimeError("oracle_attn_bwd failed (rc=%d)" % rc)
+    return (dQ, dK, dV, dS) if want_dscores else (dQ, dK, dV)
+
+
+def attn_dscores(Q, K, V, dO, scale, causal):
+    """dS [B,H,S,S] = P * (dP - delta) (zeros outside the mask); small shapes only."""
+    return attn_bwd(Q, K, V, dO, scale, causal, want_dscores=True)[3]
