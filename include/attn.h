@@ -1,0 +1,111 @@
+/*
+ * attn.h -- C ABI of the MI355X (gfx950) fused scaled-dot-product attention library.
+ *
+ * The operator is the fused attention kernel that the paper's kernel suite benchmarks
+ * against SDPA/FlashAttention (kernel-suite section; attention rows of the microbenchmark
+ * table, shape written there as (B,Hq,Hkv,S,D), bf16, causal) in the natural-log,
+ * max-stabilised "flash-attention-style" form its debugging table prescribes:
+ *
+ *     s_ij = scale * sum_d Q_id K_jd          j <= i only if causal (diagonal included)
+ *     LSE_i = ln sum_j exp(s_ij)              natural log
+ *     O_id  = sum_j exp(s_ij - LSE_i) V_jd
+ *
+ * and its gradient for an upstream gradient dO on O (LSE carries no gradient).
+ *
+ * Conventions common to every call
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library never
+ *     allocates, frees, synchronises or changes the current device; it only enqueues
+ *     kernels on `hip_stream` (a hipStream_t passed as void*, NULL = default stream) and
+ *     returns.  The caller keeps the buffers alive until that work has completed.
+ *   - Q, K, V, O, dO, dQ, dK, dV hold bf16 elements and all use the same element strides
+ *     (stride_b, stride_h, stride_s) with the D axis contiguous.  A contiguous [B,H,S,D]
+ *     tensor has stride_s = D, stride_h = S*D, stride_b = H*S*D; [B,S,H,D] storage is
+ *     expressible too.  Strides must be multiples of 8 elements and base pointers 16-byte
+ *     aligned (the kernels use 16-byte loads).
+ *   - LSE (and the backward's internal delta) are fp32, contiguous [B,H,S].
+ *   - Outputs are fully overwritten; nothing is accumulated into caller buffers and no
+ *     buffer's previous contents are ever relied on (the paper's debugging table lists
+ *     uninitialised reused gradient buffers as a bug class).
+ *   - Outputs must not alias inputs.
+ *   - Every entry point validates its arguments on the host before launching anything and
+ *     returns ATTN_OK (0) or a negative attn_status.  No exceptions, no abort, no logging.
+ *     Validation needs no GPU.  The calls are re-entrant; there is no global mutable state.
+ */
+#ifndef MI355_ATTN_H
+#define MI355_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ATTN_OK = 0,
+    ATTN_ERR_NULL = -1,      /* a required pointer is NULL                                  */
+    ATTN_ERR_SHAPE = -2,     /* B,H,S < 1, D not in {64,128}, or a size overflows int32      */
+    ATTN_ERR_STRIDE = -3,    /* a stride is < its minimum or not a multiple of 8 elements    */
+    ATTN_ERR_ALIGN = -4,     /* a tensor pointer is not 16-byte aligned (LSE: 4-byte)        */
+    ATTN_ERR_WORKSPACE = -5, /* workspace NULL/misaligned or smaller than required           */
+    ATTN_ERR_SCALE = -6,     /* scale is not a finite number > 0                             */
+    ATTN_ERR_LAUNCH = -7     /* the HIP runtime refused a launch (hipGetLastError != 0)      */
+} attn_status;
+
+/* Problem description shared by forward and backward (host memory, read during the call). */
+typedef struct {
+    int32_t B, H, S, D;   /* batch, heads, sequence length (S_q == S_k), head dim (64 or 128) */
+    int64_t stride_b;     /* element strides of all bf16 tensors; the D axis has stride 1     */
+    int64_t stride_h;
+    int64_t stride_s;
+    float scale;          /* multiplies Q.K^T before the softmax; finite and > 0              */
+    int32_t causal;       /* 0: every key visible; otherwise key j visible to query i iff j<=i */
+} attn_params_t;
+
+/* Fill strides for a contiguous [B,H,S,D] tensor.  Pure host function. */
+void attn_params_contiguous(attn_params_t *p, int32_t B, int32_t H, int32_t S, int32_t D,
+                            float scale, int32_t causal);
+
+/*
+ * Forward (paper: fused attention forward row of the microbenchmark table).
+ *   Q,K,V : in,  bf16 device [B,H,S,D] by strides
+ *   O     : out, bf16 device, same strides
+ *   LSE   : out, fp32 device, contiguous [B,H,S], natural log of sum_j exp(s_ij)
+ * Enqueues one kernel on hip_stream.
+ */
+int attn_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
+             const attn_params_t *p, void *hip_stream);
+
+/*
+ * Bytes of device workspace attn_bwd needs for this problem (fp32 delta [B,H,S], rounded
+ * up to 256 bytes).  Pure host function; returns 0 for an invalid problem.
+ */
+size_t attn_bwd_workspace_bytes(const attn_params_t *p);
+
+/*
+ * Backward (paper: fused attention backward row of the microbenchmark table).  P is
+ * recomputed from Q, K and the forward's LSE; dK/dV are accumulated per key block in
+ * registers, dQ per query block, so no atomics are used and results are deterministic.
+ *   Q,K,V,O,dO : in,  bf16 device (O and LSE as produced by attn_fwd)
+ *   LSE        : in,  fp32 device [B,H,S]
+ *   dQ,dK,dV   : out, bf16 device, same strides as the inputs
+ *   workspace  : device scratch of at least attn_bwd_workspace_bytes(p) bytes, 256-byte
+ *                aligned; contents undefined on entry and on exit (the library initialises
+ *                everything it reads)
+ * Enqueues three kernels on hip_stream: delta = rowsum(dO*O), dK/dV, dQ.
+ */
+int attn_bwd(const void *Q, const void *K, const void *V, const void *O, const void *dO,
+             const float *LSE, void *dQ, void *dK, void *dV,
+             void *workspace, size_t workspace_bytes,
+             const attn_params_t *p, void *hip_stream);
+
+/* Static, NUL-terminated description of a status code.  Never NULL. */
+const char *attn_status_string(int status);
+
+/* ABI version: major*1000 + minor. */
+int attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MI355_ATTN_H */

@@ -1,0 +1,8 @@
+"""MI355X-native fused scaled-dot-product attention (forward + backward) behind a C ABI.
+
+`attn_fwd` / `attn_bwd` marshal torch device tensors into libmi355attn.so (hand-written
+HIP kernels for gfx950).  `workloads` holds the seeded synthetic inputs.
+"""
+from . import workloads  # noqa: F401
+from .binding import (AttnError, AttnParams, attn_bwd, attn_bwd_workspace_bytes,  # noqa: F401
+                      attn_fwd, attn_version, lib, make_params, status_string)

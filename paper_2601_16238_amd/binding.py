@@ -1,0 +1,166 @@
+"""ctypes binding of libmi355attn.so -- argument marshalling only.
+
+Every step of the attention path runs inside the HIP library; this file passes device
+pointers of torch tensors (PyTorch is used for device memory and streams only) through the
+C ABI declared in include/attn.h.  There is no CPU or PyTorch fallback: if the library has
+not been built, loading fails with an error.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmi355attn.so")
+
+ATTN_OK = 0
+ATTN_ERR_NULL = -1
+ATTN_ERR_SHAPE = -2
+ATTN_ERR_STRIDE = -3
+ATTN_ERR_ALIGN = -4
+ATTN_ERR_WORKSPACE = -5
+ATTN_ERR_SCALE = -6
+ATTN_ERR_LAUNCH = -7
+
+EXPORTS = ("attn_params_contiguous", "attn_fwd", "attn_bwd_workspace_bytes", "attn_bwd",
+           "attn_status_string", "attn_version")
+
+
+class AttnParams(ctypes.Structure):
+    """Mirror of attn_params_t."""
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("S", ctypes.c_int32),
+                ("D", ctypes.c_int32), ("stride_b", ctypes.c_int64),
+                ("stride_h", ctypes.c_int64), ("stride_s", ctypes.c_int64),
+                ("scale", ctypes.c_float), ("causal", ctypes.c_int32)]
+
+
+class AttnError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, status_string(status), status))
+
+
+_lib = None
+
+
+def lib():
+    """Load the HIP library (built in-tree by build.py); raise if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libmi355attn.so is not built (%s missing): run "
+                "`python -c 'import __graft_entry__ as g; g.build()'` first; "
+                "there is no fallback path" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, pp = ctypes.c_void_p, ctypes.POINTER(AttnParams)
+        L.attn_params_contiguous.argtypes = [pp] + [ctypes.c_int32] * 4 + [ctypes.c_float,
+                                                                           ctypes.c_int32]
+        L.attn_params_contiguous.restype = None
+        L.attn_fwd.argtypes = [vp, vp, vp, vp, vp, pp, vp]
+        L.attn_fwd.restype = ctypes.c_int
+        L.attn_bwd_workspace_bytes.argtypes = [pp]
+        L.attn_bwd_workspace_bytes.restype = ctypes.c_size_t
+        L.attn_bwd.argtypes = [vp] * 9 + [vp, ctypes.c_size_t, pp, vp]
+        L.attn_bwd.restype = ctypes.c_int
+        L.attn_status_string.argtypes = [ctypes.c_int]
+        L.attn_status_string.restype = ctypes.c_char_p
+        L.attn_version.argtypes = []
+        L.attn_version.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status):
+    return lib().attn_status_string(int(status)).decode()
+
+
+def attn_version():
+    return int(lib().attn_version())
+
+
+def make_params(B, H, S, D, scale, causal, strides=None):
+    """attn_params_t for a [B,H,S,D] tensor; strides=(sb, sh, ss) in elements or None for
+    contiguous."""
+    p = AttnParams()
+    lib().attn_params_contiguous(ctypes.byref(p), B, H, S, D, float(scale), int(bool(causal)))
+    if strides is not None:
+        p.stride_b, p.stride_h, p.stride_s = (int(s) for s in strides)
+    return p
+
+
+def _params_for(t, scale, causal):
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise ValueError("expected a [B,H,S,D] tensor with a contiguous D axis")
+    B, H, S, D = t.shape
+    return make_params(B, H, S, D, scale, causal, (t.stride(0), t.stride(1), t.stride(2)))
+
+
+def _same_layout(ref, *ts):
+    for t in ts:
+        if t.shape != ref.shape or t.stride() != ref.stride() or t.dtype != ref.dtype \
+                or t.device != ref.device:
+            raise ValueError("all bf16 tensors must share shape, strides, dtype and device")
+
+
+def _stream_ptr(torch, stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def attn_fwd(Q, K, V, scale, causal, O=None, LSE=None, stream=None):
+    """O, LSE = attention forward.  Q,K,V: bf16 device tensors [B,H,S,D] with equal strides.
+    Enqueues on `stream` (default: torch's current stream); does not synchronise."""
+    import torch
+    if Q.dtype != torch.bfloat16 or not Q.is_cuda:
+        raise ValueError("Q,K,V must be bf16 tensors on the GPU")
+    _same_layout(Q, K, V)
+    if O is None:
+        O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    else:
+        _same_layout(Q, O)
+    B, H, S, D = Q.shape
+    if LSE is None:
+        LSE = torch.empty((B, H, S), dtype=torch.float32, device=Q.device)
+    elif LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != (B, H, S):
+        raise ValueError("LSE must be a contiguous fp32 [B,H,S] tensor")
+    p = _params_for(Q, scale, causal)
+    rc = lib().attn_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(),
+                        ctypes.byref(p), _stream_ptr(torch, stream))
+    if rc != ATTN_OK:
+        raise AttnError(rc, "attn_fwd")
+    return O, LSE
+
+
+def attn_bwd_workspace_bytes(B, H, S, D):
+    p = make_params(B, H, S, D, 1.0, False)
+    return int(lib().attn_bwd_workspace_bytes(ctypes.byref(p)))
+
+
+def attn_bwd(Q, K, V, O, dO, LSE, scale, causal, dQ=None, dK=None, dV=None, workspace=None,
+             stream=None):
+    """dQ, dK, dV = attention backward for upstream gradient dO (all bf16, same strides)."""
+    import torch
+    if Q.dtype != torch.bfloat16 or not Q.is_cuda:
+        raise ValueError("tensors must be bf16 on the GPU")
+    _same_layout(Q, K, V, O, dO)
+    outs = []
+    for t in (dQ, dK, dV):
+        if t is None:
+            t = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+        else:
+            _same_layout(Q, t)
+        outs.append(t)
+    dQ, dK, dV = outs
+    B, H, S, D = Q.shape
+    if LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != (B, H, S):
+        raise ValueError("LSE must be a contiguous fp32 [B,H,S] tensor")
+    p = _params_for(Q, scale, causal)
+    need = int(lib().attn_bwd_workspace_bytes(ctypes.byref(p)))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    rc = lib().attn_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(),
+                        LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+                        workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                        ctypes.byref(p), _stream_ptr(torch, stream))
+    if rc != ATTN_OK:
+        raise AttnError(rc, "attn_bwd")
+    return dQ, dK, dV

@@ -1,0 +1,126 @@
+// C ABI of the attention library: host-side validation and dispatch only.
+#include "../../include/attn.h"
+#include "attn_launch.hpp"
+
+#include <cmath>
+#include <limits>
+
+namespace {
+
+constexpr size_t kWsAlign = 256;
+
+int check_params(const attn_params_t *p)
+{
+    if (!p) return ATTN_ERR_NULL;
+    if (p->B < 1 || p->H < 1 || p->S < 1) return ATTN_ERR_SHAPE;
+    if (p->D != 64 && p->D != 128) return ATTN_ERR_SHAPE;
+    // B*H*S rows must be indexable with int32 (LSE / delta offsets, grid sizes).
+    const int64_t rows = (int64_t)p->B * p->H * p->S;
+    if (rows > (int64_t)std::numeric_limits<int32_t>::max()) return ATTN_ERR_SHAPE;
+    if (p->stride_s < p->D || p->stride_h < 1 || p->stride_b < 1) return ATTN_ERR_STRIDE;
+    if (p->stride_s % 8 || p->stride_h % 8 || p->stride_b % 8) return ATTN_ERR_STRIDE;
+    if (!std::isfinite(p->scale) || !(p->scale > 0.0f)) return ATTN_ERR_SCALE;
+    return ATTN_OK;
+}
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+void attn_params_contiguous(attn_params_t *p, int32_t B, int32_t H, int32_t S, int32_t D,
+                            float scale, int32_t causal)
+{
+    if (!p) return;
+    p->B = B; p->H = H; p->S = S; p->D = D;
+    p->stride_s = D;
+    p->stride_h = (int64_t)S * D;
+    p->stride_b = (int64_t)H * S * D;
+    p->scale = scale;
+    p->causal = causal;
+}
+
+int attn_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
+             const attn_params_t *p, void *hip_stream)
+{
+    if (!Q || !K || !V || !O || !LSE) return ATTN_ERR_NULL;
+    const int rc = check_params(p);
+    if (rc != ATTN_OK) return rc;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) ||
+        !aligned(LSE, 4))
+        return ATTN_ERR_ALIGN;
+    attn::FwdArgs a;
+    a.Q = static_cast<const attn::bf16 *>(Q);
+    a.K = static_cast<const attn::bf16 *>(K);
+    a.V = static_cast<const attn::bf16 *>(V);
+    a.O = static_cast<attn::bf16 *>(O);
+    a.LSE = LSE;
+    a.stride_b = p->stride_b; a.stride_h = p->stride_h; a.stride_s = p->stride_s;
+    a.S = p->S; a.H = p->H; a.BH = p->B * p->H;
+    a.nqt = 0;
+    a.scale_log2e = p->scale * 1.4426950408889634f;
+    return attn::launch_fwd(a, p->D, p->causal != 0, static_cast<hipStream_t>(hip_stream)) == 0
+               ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+size_t attn_bwd_workspace_bytes(const attn_params_t *p)
+{
+    if (check_params(p) != ATTN_OK) return 0;
+    const size_t rows = (size_t)p->B * p->H * p->S;
+    return (rows * sizeof(float) + kWsAlign - 1) / kWsAlign * kWsAlign;
+}
+
+int attn_bwd(const void *Q, const void *K, const void *V, const void *O, const void *dO,
+             const float *LSE, void *dQ, void *dK, void *dV,
+             void *workspace, size_t workspace_bytes,
+             const attn_params_t *p, void *hip_stream)
+{
+    if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_NULL;
+    const int rc = check_params(p);
+    if (rc != ATTN_OK) return rc;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) ||
+        !aligned(dO, 16) || !aligned(dQ, 16) || !aligned(dK, 16) || !aligned(dV, 16) ||
+        !aligned(LSE, 4))
+        return ATTN_ERR_ALIGN;
+    if (!workspace || !aligned(workspace, kWsAlign) ||
+        workspace_bytes < attn_bwd_workspace_bytes(p))
+        return ATTN_ERR_WORKSPACE;
+    attn::BwdArgs a;
+    a.Q = static_cast<const attn::bf16 *>(Q);
+    a.K = static_cast<const attn::bf16 *>(K);
+    a.V = static_cast<const attn::bf16 *>(V);
+    a.O = static_cast<const attn::bf16 *>(O);
+    a.dO = static_cast<const attn::bf16 *>(dO);
+    a.LSE = LSE;
+    a.delta = static_cast<float *>(workspace);
+    a.dQ = static_cast<attn::bf16 *>(dQ);
+    a.dK = static_cast<attn::bf16 *>(dK);
+    a.dV = static_cast<attn::bf16 *>(dV);
+    a.stride_b = p->stride_b; a.stride_h = p->stride_h; a.stride_s = p->stride_s;
+    a.S = p->S; a.H = p->H; a.BH = p->B * p->H;
+    a.ntile = 0;
+    a.scale = p->scale;
+    a.scale_log2e = p->scale * 1.4426950408889634f;
+    return attn::launch_bwd(a, p->D, p->causal != 0, static_cast<hipStream_t>(hip_stream)) == 0
+               ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+const char *attn_status_string(int status)
+{
+    switch (status) {
+        case ATTN_OK: return "ok";
+        case ATTN_ERR_NULL: return "a required pointer is NULL";
+        case ATTN_ERR_SHAPE: return "unsupported shape (B,H,S >= 1, D in {64,128}, B*H*S < 2^31)";
+        case ATTN_ERR_STRIDE: return "bad stride (D contiguous, strides multiples of 8 elements, stride_s >= D)";
+        case ATTN_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
+        case ATTN_ERR_WORKSPACE: return "workspace missing, misaligned (256 B) or too small";
+        case ATTN_ERR_SCALE: return "scale must be finite and > 0";
+        case ATTN_ERR_LAUNCH: return "HIP kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int attn_version(void) { return 1000; }
+
+}  // extern "C"

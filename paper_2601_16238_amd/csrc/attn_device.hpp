@@ -1,0 +1,97 @@
+// Device-side building blocks shared by the forward and backward attention kernels
+// (gfx950 / CDNA4 only: wave64, bf16 MFMA 32x32x16, LDS transpose reads).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace attn {
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// D = A(32x16) * B(16x32) + C, bf16 in, fp32 accumulate.
+// Lane l holds A[l%32][8*(l/32)..+7], B[8*(l/32)..+7][l%32] and, in C/D register i,
+// element [8*(i/4) + 4*(l/32) + i%4][l%32].
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Row of a 32x32 accumulator block held in register i by a lane of half h = lane/32.
+__device__ __forceinline__ constexpr int acc_row(int i, int h) { return 8 * (i / 4) + 4 * h + (i % 4); }
+
+// Exchange between lane l and lane l^32: returns {value of the lower-half partner or self,
+// value of the upper-half partner or self}; max/sum of the pair is symmetric in the two.
+__device__ __forceinline__ float xhalf_max(float x)
+{
+    u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+}
+__device__ __forceinline__ float xhalf_sum(float x)
+{
+    u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r.x) + __uint_as_float(r.y);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// Eight fp32 -> bf16x8 (round to nearest even; v_cvt_pk_bf16_f32 on gfx950).
+__device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3,
+                                        float a4, float a5, float a6, float a7)
+{
+    typedef float f32x8 __attribute__((ext_vector_type(8)));
+    f32x8 v = {a0, a1, a2, a3, a4, a5, a6, a7};
+    return __builtin_convertvector(v, bf16x8);
+}
+__device__ __forceinline__ bf16x4 pack4(float a0, float a1, float a2, float a3)
+{
+    f32x4 v = {a0, a1, a2, a3};
+    return __builtin_convertvector(v, bf16x4);
+}
+
+// LDS transpose read (ds_read_b64_tr_b16).  Within each group of 16 lanes, source lane
+// s = 4*e + c points at 4 consecutive 16-bit elements ("row e, chunk c"); result lane i
+// receives, in element e, element i%4 of the chunk addressed by source lane 4*e + i/4.
+// I.e. the group reads a 4-row x 16-column tile and every lane gets one column.
+__device__ __forceinline__ s16x4 lds_read_tr(const bf16 *p)
+{
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3))) *)(p));
+}
+__device__ __forceinline__ bf16x8 join8(s16x4 lo, s16x4 hi)
+{
+    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// 16-byte global load / LDS access of 8 bf16.
+__device__ __forceinline__ u32x4 ld_global16(const bf16 *p) { return *(const u32x4 *)p; }
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// Work-group id -> position in a virtual order in which consecutive positions land on the
+// same XCD.  Work-groups are handed to the 8 XCDs round-robin by linear id, each XCD has
+// its own L2, so giving one XCD a contiguous range of (head, query tile) pairs keeps the
+// K/V of a head in one L2.  Bijection on [0,total) for any total.
+__device__ __forceinline__ int xcd_contiguous_order(int id, int total)
+{
+    constexpr int kXcd = 8;
+    const int x = id % kXcd, pos = id / kXcd;
+    const int full = total / kXcd, rem = total % kXcd;
+    const int start = x * full + (x < rem ? x : rem);
+    return start + pos;
+}
+
+}  // namespace attn

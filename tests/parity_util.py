@@ -1,0 +1,50 @@
+"""Helpers for the GPU parity tests: host<->device marshalling and error metrics."""
+import numpy as np
+import torch
+
+from paper_2601_16238_amd import workloads as wl
+
+# Tolerances of the benchmark spec: bf16 outputs within max-abs 2e-2 and mean-abs 2e-3
+# of the fp64 oracle, fp32 LSE within 1e-5.
+TOL_MAX, TOL_MEAN, TOL_LSE = 2e-2, 2e-3, 1e-5
+
+
+def to_dev(bits):
+    """uint16 bf16 bit patterns (numpy) -> bf16 torch tensor on cuda:0 (same bytes)."""
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def to_f64(t):
+    """bf16/fp32 device tensor -> float64 numpy (exact widening)."""
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def bf16_round(x):
+    """fp64 -> nearest bf16 (via fp32) -> fp64: the rounding floor of a bf16 output."""
+    return wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(x.astype(np.float32))).astype(np.float64)
+
+
+def errs(got, ref):
+    d = np.abs(got - ref)
+    return float(d.max()), float(d.mean())
+
+
+def check_bf16(name, got, ref, tol_max=TOL_MAX, tol_mean=TOL_MEAN, floor_gate=True):
+    """Assert a bf16 output is within the stated tolerance of the oracle and, as a tighter
+    internal gate, within a small multiple of the error that rounding the exact result to
+    bf16 already makes (so a real bug cannot hide inside the loose official bound)."""
+    assert np.isfinite(got).all(), "%s has non-finite values" % name
+    emax, emean = errs(got, ref)
+    fmax, fmean = errs(bf16_round(ref), ref)
+    msg = "%s: max %.3e mean %.3e (floor max %.3e mean %.3e)" % (name, emax, emean, fmax, fmean)
+    assert emax <= tol_max and emean <= tol_mean, msg
+    if floor_gate:
+        assert emax <= 4.0 * fmax + 1e-6 and emean <= 3.0 * fmean + 1e-7, "floor gate, " + msg
+    return emax, emean, fmax, fmean
+
+
+def check_lse(got, ref, tol=TOL_LSE):
+    assert np.isfinite(got).all()
+    emax = float(np.abs(got - ref).max())
+    assert emax <= tol, "LSE: max %.3e > %.1e" % (emax, tol)
+    return emax
