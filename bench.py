@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Attention benchmark: one "step" = attn_fwd + attn_bwd over one synthetic batch.
+
+Prints ONE JSON line.  `value` is fwd+bwd TFLOP/s under the usual attention-benchmark FLOP
+convention (4*B*H*S^2*D forward, halved if causal; backward 2.5x forward), inputs resident
+in HBM before the timed region.  Timing follows the paper's protocol for its fused-attention
+microbenchmark: seeded inputs, warm-up, synchronise around the timed region, mean latency.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published)
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="long_causal",
+                    help="one of paper_2601_16238_amd.workloads.WORKLOADS")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all", action="store_true",
+                    help="also time every other workload (reported under 'other_workloads')")
+    return ap.parse_args()
+
+
+def time_calls(torch, fn, n):
+    """Mean milliseconds per call of fn over n back-to-back calls, by events on the current
+    stream (the stream the library launches on)."""
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(n):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / n
+
+
+def measure(torch, attn, wl, w, steps, warmup):
+    import numpy as np
+    from paper_2601_16238_amd import binding
+    x = wl.make_inputs(w)
+
+    def dev(b):
+        return torch.from_numpy(b.view(np.int16)).cuda().view(torch.bfloat16)
+
+    Q, K, V, dO = (dev(x[k]) for k in ("Q", "K", "V", "dO"))
+    del x
+    scale, causal = wl.default_scale(w.D), w.causal
+    O = torch.empty_like(Q)
+    LSE = torch.empty((w.B, w.H, w.S), dtype=torch.float32, device="cuda")
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
+    ws = torch.empty(attn.attn_bwd_workspace_bytes(w.B, w.H, w.S, w.D), dtype=torch.uint8,
+                     device="cuda")
+
+    def fwd():
+        attn.attn_fwd(Q, K, V, scale, causal, O=O, LSE=LSE)
+
+    def bwd(stages=None):
+        attn.attn_bwd(Q, K, V, O, dO, LSE, scale, causal, dQ=dQ, dK=dK, dV=dV, workspace=ws,
+                      stages=stages)
+
+    def step():
+        fwd()
+        bwd()
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ms_step = time_calls(torch, step, steps)
+    wall = time.perf_counter() - t0
+    n = max(3, steps // 2)
+    ms = {"fwd": time_calls(torch, fwd, n), "bwd": time_calls(torch, bwd, n),
+          "bwd_delta": time_calls(torch, lambda: bwd(binding.STAGE_DELTA), n),
+          "bwd_dkdv": time_calls(torch, lambda: bwd(binding.STAGE_DKDV), n),
+          "bwd_dq": time_calls(torch, lambda: bwd(binding.STAGE_DQ), n)}
+    f_fwd = wl.fwd_flops(w.B, w.H, w.S, w.D, causal)
+    f_bwd = wl.bwd_flops(w.B, w.H, w.S, w.D, causal)
+    res = {
+        "ms_per_step": ms_step, "ms": ms, "wall_s": wall,
+        "tflops_fwdbwd": (f_fwd + f_bwd) / (ms_step * 1e-3) / 1e12,
+        "tflops_fwd": f_fwd / (ms["fwd"] * 1e-3) / 1e12,
+        "tflops_bwd": f_bwd / (ms["bwd"] * 1e-3) / 1e12,
+        "gbs_fwd": wl.fwd_bytes(w.B, w.H, w.S, w.D) / (ms["fwd"] * 1e-3) / 1e9,
+        "gbs_bwd": wl.bwd_bytes(w.B, w.H, w.S, w.D) / (ms["bwd"] * 1e-3) / 1e9,
+    }
+    # Algorithmic FLOPs per launch of each MFMA kernel (GEMM = 2*N_s*D flops, N_s = S^2 or
+    # S^2/2): forward 2 GEMMs; dK/dV kernel 4 (S, dP, dV, dK); dQ kernel 1 (dQ -- its
+    # recomputed S and dP are overhead, not algorithmic work).
+    gemm = f_fwd / 2.0
+    kern = {"attn_fwd_kernel": (2 * gemm, ms["fwd"]), "attn_bwd_dkdv_kernel": (4 * gemm, ms["bwd_dkdv"]),
+            "attn_bwd_dq_kernel": (1 * gemm, ms["bwd_dq"])}
+    res["kernels"] = {k: {"ms": t, "achieved_tflops": f / (t * 1e-3) / 1e12,
+                          "frac": f / (t * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+                      for k, (f, t) in kern.items()}
+    return res
+
+
+def cpu_baseline(wl, w):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload: forward +
+    backward of as many whole heads as fit in roughly 10-30 s of CPU work."""
+    import oracle
+    per_head = 4.5 * wl.fwd_flops(1, 1, w.S, w.D, w.causal)   # oracle executes ~9 GEMM-equivalents
+    heads = int(max(1, min(w.B * w.H, (8e9 * 20) // max(per_head, 1))))
+    x = wl.make_inputs(w, heads=range(heads))
+    t0 = time.perf_counter()
+    oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], w.causal)
+    oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], w.causal)
+    dt = time.perf_counter() - t0
+    flops = heads * 3.5 * wl.fwd_flops(1, 1, w.S, w.D, w.causal)
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": dt,
+            "sample": "fwd+bwd of the first %d of %d heads of %s at full S=%d (fp64, convention FLOPs)"
+                      % (heads, w.B * w.H, w.name, w.S)}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build is single-GPU (attention shards over batch*heads with no "
+              "exchange; nothing here uses a second GPU). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2601_16238_amd as attn
+    from paper_2601_16238_amd import workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    attn.lib()  # fail loudly if the HIP library is not built
+    w = wl.WORKLOADS[a.workload]
+    r = measure(torch, attn, wl, w, a.steps, a.warmup)
+    dom = max(r["kernels"], key=lambda k: r["kernels"][k]["ms"])
+    out = {
+        "metric": "attention fwd+bwd TFLOP/s (FLOPs = 4*B*H*S^2*D fwd, /2 causal, bwd = 2.5x fwd)",
+        "value": r["tflops_fwdbwd"], "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: B=%d H=%d S=%d D=%d causal=%s" % (w.name, w.B, w.H, w.S, w.D, w.causal),
+                   "seed": w.seed},
+        "frac_of_bf16_peak": {"fwd": r["tflops_fwd"] / PEAK_BF16_TFLOPS,
+                              "fwd_bwd": r["tflops_fwdbwd"] / PEAK_BF16_TFLOPS,
+                              "peak_tflops": PEAK_BF16_TFLOPS},
+        "tflops": {"fwd": r["tflops_fwd"], "bwd": r["tflops_bwd"], "fwd_bwd": r["tflops_fwdbwd"]},
+        "ms": r["ms"],
+        "algorithmic_gbs": {"fwd": r["gbs_fwd"], "bwd": r["gbs_bwd"], "hbm_peak": PEAK_HBM_GBS},
+        "roofline": {"kernel": dom, "bound": "mfma", "achieved": r["kernels"][dom]["achieved_tflops"],
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": r["kernels"][dom]["frac"],
+                     "traffic": None},
+        "roofline_all": r["kernels"],
+    }
+    if a.all:
+        others = {}
+        for name, ow in wl.WORKLOADS.items():
+            if name == w.name:
+                continue
+            o = measure(torch, attn, wl, ow, max(5, a.steps // 2), a.warmup)
+            others[name] = {"ms": o["ms"], "tflops_fwd": o["tflops_fwd"], "tflops_fwdbwd": o["tflops_fwdbwd"],
+                            "frac_fwd": o["tflops_fwd"] / PEAK_BF16_TFLOPS,
+                            "frac_fwdbwd": o["tflops_fwdbwd"] / PEAK_BF16_TFLOPS,
+                            "gbs_fwd": o["gbs_fwd"], "gbs_bwd": o["gbs_bwd"]}
+            torch.cuda.empty_cache()
+        out["other_workloads"] = others
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, w)
+        out["cpu_baseline"]["nproc"] = os.cpu_count()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

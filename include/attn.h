@@ -99,6 +99,22 @@ int attn_bwd(const void *Q, const void *K, const void *V, const void *O, const v
              void *workspace, size_t workspace_bytes,
              const attn_params_t *p, void *hip_stream);
 
+/*
+ * Profiling aid: attn_bwd restricted to a subset of its three kernels, so that each can be
+ * timed on its own with events on the caller's stream.  `stages` is a bit mask of
+ * ATTN_BWD_STAGE_*; attn_bwd is attn_bwd_stages with all three bits.  The dK/dV and dQ
+ * stages read delta from the workspace, so it must hold the delta stage's result of an
+ * earlier call on the same problem.  Validation and errors as attn_bwd; stages == 0 or
+ * unknown bits give ATTN_ERR_SHAPE.
+ */
+#define ATTN_BWD_STAGE_DELTA 1u
+#define ATTN_BWD_STAGE_DKDV 2u
+#define ATTN_BWD_STAGE_DQ 4u
+int attn_bwd_stages(const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                    const float *LSE, void *dQ, void *dK, void *dV,
+                    void *workspace, size_t workspace_bytes,
+                    const attn_params_t *p, void *hip_stream, uint32_t stages);
+
 /* Static, NUL-terminated description of a status code.  Never NULL. */
 const char *attn_status_string(int status);
 

@@ -21,7 +21,9 @@ ATTN_ERR_SCALE = -6
 ATTN_ERR_LAUNCH = -7
 
 EXPORTS = ("attn_params_contiguous", "attn_fwd", "attn_bwd_workspace_bytes", "attn_bwd",
-           "attn_status_string", "attn_version")
+           "attn_bwd_stages", "attn_status_string", "attn_version")
+STAGE_DELTA, STAGE_DKDV, STAGE_DQ = 1, 2, 4
+STAGE_ALL = 7
 
 
 class AttnParams(ctypes.Structure):
@@ -61,6 +63,8 @@ def lib():
         L.attn_bwd_workspace_bytes.restype = ctypes.c_size_t
         L.attn_bwd.argtypes = [vp] * 9 + [vp, ctypes.c_size_t, pp, vp]
         L.attn_bwd.restype = ctypes.c_int
+        L.attn_bwd_stages.argtypes = [vp] * 9 + [vp, ctypes.c_size_t, pp, vp, ctypes.c_uint32]
+        L.attn_bwd_stages.restype = ctypes.c_int
         L.attn_status_string.argtypes = [ctypes.c_int]
         L.attn_status_string.restype = ctypes.c_char_p
         L.attn_version.argtypes = []
@@ -136,8 +140,10 @@ def attn_bwd_workspace_bytes(B, H, S, D):
 
 
 def attn_bwd(Q, K, V, O, dO, LSE, scale, causal, dQ=None, dK=None, dV=None, workspace=None,
-             stream=None):
-    """dQ, dK, dV = attention backward for upstream gradient dO (all bf16, same strides)."""
+             stream=None, stages=None):
+    """dQ, dK, dV = attention backward for upstream gradient dO (all bf16, same strides).
+    `stages` (profiling aid) restricts the call to a subset of its kernels through
+    attn_bwd_stages; None calls attn_bwd."""
     import torch
     if Q.dtype != torch.bfloat16 or not Q.is_cuda:
         raise ValueError("tensors must be bf16 on the GPU")
@@ -157,10 +163,14 @@ def attn_bwd(Q, K, V, O, dO, LSE, scale, causal, dQ=None, dK=None, dV=None, work
     need = int(lib().attn_bwd_workspace_bytes(ctypes.byref(p)))
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
-    rc = lib().attn_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(),
-                        LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
-                        workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                        ctypes.byref(p), _stream_ptr(torch, stream))
+    args = (Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(),
+            LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+            workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+            ctypes.byref(p), _stream_ptr(torch, stream))
+    if stages is None:
+        rc = lib().attn_bwd(*args)
+    else:
+        rc = lib().attn_bwd_stages(*args, int(stages))
     if rc != ATTN_OK:
         raise AttnError(rc, "attn_bwd")
     return dQ, dK, dV

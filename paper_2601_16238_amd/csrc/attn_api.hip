@@ -76,6 +76,16 @@ int attn_bwd(const void *Q, const void *K, const void *V, const void *O, const v
              void *workspace, size_t workspace_bytes,
              const attn_params_t *p, void *hip_stream)
 {
+    return attn_bwd_stages(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, p,
+                           hip_stream,
+                           ATTN_BWD_STAGE_DELTA | ATTN_BWD_STAGE_DKDV | ATTN_BWD_STAGE_DQ);
+}
+
+int attn_bwd_stages(const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                    const float *LSE, void *dQ, void *dK, void *dV,
+                    void *workspace, size_t workspace_bytes,
+                    const attn_params_t *p, void *hip_stream, uint32_t stages)
+{
     if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_NULL;
     const int rc = check_params(p);
     if (rc != ATTN_OK) return rc;
@@ -86,6 +96,7 @@ int attn_bwd(const void *Q, const void *K, const void *V, const void *O, const v
     if (!workspace || !aligned(workspace, kWsAlign) ||
         workspace_bytes < attn_bwd_workspace_bytes(p))
         return ATTN_ERR_WORKSPACE;
+    if (stages == 0 || (stages & ~7u)) return ATTN_ERR_SHAPE;
     attn::BwdArgs a;
     a.Q = static_cast<const attn::bf16 *>(Q);
     a.K = static_cast<const attn::bf16 *>(K);
@@ -102,7 +113,8 @@ int attn_bwd(const void *Q, const void *K, const void *V, const void *O, const v
     a.ntile = 0;
     a.scale = p->scale;
     a.scale_log2e = p->scale * 1.4426950408889634f;
-    return attn::launch_bwd(a, p->D, p->causal != 0, static_cast<hipStream_t>(hip_stream)) == 0
+    return attn::launch_bwd(a, p->D, p->causal != 0, static_cast<hipStream_t>(hip_stream),
+                            stages) == 0
                ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 

@@ -369,45 +369,53 @@ static void allow_lds(K kernel, int bytes)
     hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-template <int D, int NW>
-static int launch_bwd_nw(BwdArgs a, bool causal, hipStream_t st)
+template <int D, int NW, bool CAUSAL>
+static int launch_bwd_main(BwdArgs a, hipStream_t st, unsigned stages)
 {
     using C = BwdCfg<D, NW>;
     a.ntile = (a.S + C::kBlk - 1) / C::kBlk;
     const dim3 grid(a.ntile * a.BH), block(C::kThreads);
-    if (causal) {
-        allow_lds(attn_bwd_dkdv_kernel<D, NW, true>, C::kLdsBytes);
-        allow_lds(attn_bwd_dq_kernel<D, NW, true>, C::kLdsBytes);
-        hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, NW, true>), grid, block, C::kLdsBytes, st, a);
-        hipLaunchKernelGGL((attn_bwd_dq_kernel<D, NW, true>), grid, block, C::kLdsBytes, st, a);
-    } else {
-        allow_lds(attn_bwd_dkdv_kernel<D, NW, false>, C::kLdsBytes);
-        allow_lds(attn_bwd_dq_kernel<D, NW, false>, C::kLdsBytes);
-        hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, NW, false>), grid, block, C::kLdsBytes, st, a);
-        hipLaunchKernelGGL((attn_bwd_dq_kernel<D, NW, false>), grid, block, C::kLdsBytes, st, a);
+    if (stages & 2u) {
+        allow_lds(attn_bwd_dkdv_kernel<D, NW, CAUSAL>, C::kLdsBytes);
+        hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, NW, CAUSAL>), grid, block, C::kLdsBytes, st, a);
+    }
+    if (stages & 4u) {
+        allow_lds(attn_bwd_dq_kernel<D, NW, CAUSAL>, C::kLdsBytes);
+        hipLaunchKernelGGL((attn_bwd_dq_kernel<D, NW, CAUSAL>), grid, block, C::kLdsBytes, st, a);
     }
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-template <int D>
-static int launch_bwd_d(const BwdArgs &a, bool causal, hipStream_t st)
+template <int D, int NW>
+static int launch_bwd_nw(const BwdArgs &a, bool causal, hipStream_t st, unsigned stages)
 {
-    constexpr int RPB = 256 / (D / 8);
-    const int64_t rows = (int64_t)a.BH * a.S;
-    hipLaunchKernelGGL((attn_bwd_delta_kernel<D>), dim3((unsigned)((rows + RPB - 1) / RPB)),
-                       dim3(256), 0, st, a);
-    if (hipGetLastError() != hipSuccess) return -1;
-    const int blocks32 = (a.S + 31) / 32;
-    if (blocks32 >= 8) return launch_bwd_nw<D, 8>(a, causal, st);
-    if (blocks32 >= 4) return launch_bwd_nw<D, 4>(a, causal, st);
-    if (blocks32 == 3) return launch_bwd_nw<D, 3>(a, causal, st);
-    if (blocks32 == 2) return launch_bwd_nw<D, 2>(a, causal, st);
-    return launch_bwd_nw<D, 1>(a, causal, st);
+    return causal ? launch_bwd_main<D, NW, true>(a, st, stages)
+                  : launch_bwd_main<D, NW, false>(a, st, stages);
 }
 
-int launch_bwd(const BwdArgs &a, int D, bool causal, hipStream_t st)
+template <int D>
+static int launch_bwd_d(const BwdArgs &a, bool causal, hipStream_t st, unsigned stages)
 {
-    return D == 128 ? launch_bwd_d<128>(a, causal, st) : launch_bwd_d<64>(a, causal, st);
+    if (stages & 1u) {
+        constexpr int RPB = 256 / (D / 8);
+        const int64_t rows = (int64_t)a.BH * a.S;
+        hipLaunchKernelGGL((attn_bwd_delta_kernel<D>), dim3((unsigned)((rows + RPB - 1) / RPB)),
+                           dim3(256), 0, st, a);
+        if (hipGetLastError() != hipSuccess) return -1;
+    }
+    if (!(stages & 6u)) return 0;
+    const int blocks32 = (a.S + 31) / 32;
+    if (blocks32 >= 8) return launch_bwd_nw<D, 8>(a, causal, st, stages);
+    if (blocks32 >= 4) return launch_bwd_nw<D, 4>(a, causal, st, stages);
+    if (blocks32 == 3) return launch_bwd_nw<D, 3>(a, causal, st, stages);
+    if (blocks32 == 2) return launch_bwd_nw<D, 2>(a, causal, st, stages);
+    return launch_bwd_nw<D, 1>(a, causal, st, stages);
+}
+
+int launch_bwd(const BwdArgs &a, int D, bool causal, hipStream_t st, unsigned stages)
+{
+    return D == 128 ? launch_bwd_d<128>(a, causal, st, stages)
+                    : launch_bwd_d<64>(a, causal, st, stages);
 }
 
 }  // namespace attn

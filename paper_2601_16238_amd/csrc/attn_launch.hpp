@@ -32,6 +32,7 @@ struct BwdArgs {
 
 // Each returns 0 on success, -1 if the HIP runtime reported a launch error.
 int launch_fwd(const FwdArgs &a, int D, bool causal, hipStream_t st);
-int launch_bwd(const BwdArgs &a, int D, bool causal, hipStream_t st);
+// `stages`: bit 0 delta, bit 1 dK/dV, bit 2 dQ.
+int launch_bwd(const BwdArgs &a, int D, bool causal, hipStream_t st, unsigned stages);
 
 }  // namespace attn

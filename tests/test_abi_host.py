@@ -1,0 +1,118 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol, and
+argument validation returns the documented status codes without touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2601_16238_amd as attn
+from paper_2601_16238_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "attn.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(attn_\w+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    names = declared_functions()
+    assert "attn_fwd" in names and "attn_bwd" in names and "attn_bwd_workspace_bytes" in names
+    L = attn.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_version_and_status_strings():
+    assert attn.attn_version() == 1000
+    seen = set()
+    for code in range(0, -8, -1):
+        s = attn.status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 8
+    assert attn.status_string(-99) == "unknown status"
+
+
+def test_params_contiguous_and_workspace_size():
+    p = attn.make_params(4, 32, 4096, 128, 0.0883, True)
+    assert (p.stride_s, p.stride_h, p.stride_b) == (128, 4096 * 128, 32 * 4096 * 128)
+    assert attn.attn_bwd_workspace_bytes(4, 32, 4096, 128) == 4 * 32 * 4096 * 4
+    assert attn.attn_bwd_workspace_bytes(1, 1, 1, 64) == 256          # rounded up
+    assert attn.attn_bwd_workspace_bytes(1, 1, 1, 96) == 0            # invalid D
+
+
+FAKE = 0x1000  # a non-NULL, 16-byte aligned address; never dereferenced on the host
+
+
+def call_fwd(p, Q=FAKE, K=FAKE, V=FAKE, O=FAKE, LSE=FAKE):
+    return attn.lib().attn_fwd(Q, K, V, O, LSE, ctypes.byref(p) if p is not None else None, None)
+
+
+def call_bwd(p, ws=FAKE, ws_bytes=1 << 40, ptr=FAKE, stages=None):
+    args = [ptr] * 9 + [ws, ws_bytes, ctypes.byref(p), None]
+    if stages is None:
+        return attn.lib().attn_bwd(*args)
+    return attn.lib().attn_bwd_stages(*args, stages)
+
+
+@pytest.mark.parametrize("mutate,code", [
+    (lambda p: setattr(p, "B", 0), binding.ATTN_ERR_SHAPE),
+    (lambda p: setattr(p, "S", 0), binding.ATTN_ERR_SHAPE),
+    (lambda p: setattr(p, "D", 96), binding.ATTN_ERR_SHAPE),
+    (lambda p: setattr(p, "stride_s", 60), binding.ATTN_ERR_STRIDE),
+    (lambda p: setattr(p, "stride_h", 132), binding.ATTN_ERR_STRIDE),
+    (lambda p: setattr(p, "scale", 0.0), binding.ATTN_ERR_SCALE),
+    (lambda p: setattr(p, "scale", -1.0), binding.ATTN_ERR_SCALE),
+    (lambda p: setattr(p, "scale", float("nan")), binding.ATTN_ERR_SCALE),
+    (lambda p: setattr(p, "scale", float("inf")), binding.ATTN_ERR_SCALE),
+])
+def test_bad_params_rejected_before_any_launch(mutate, code):
+    p = attn.make_params(1, 2, 128, 64, 0.125, False)
+    mutate(p)
+    assert call_fwd(p) == code
+    assert call_bwd(p) == code
+
+
+def test_null_alignment_and_workspace_errors():
+    p = attn.make_params(1, 2, 128, 64, 0.125, False)
+    assert call_fwd(p, Q=None) == binding.ATTN_ERR_NULL
+    assert call_fwd(p, LSE=None) == binding.ATTN_ERR_NULL
+    assert call_fwd(None) == binding.ATTN_ERR_NULL
+    assert call_fwd(p, K=FAKE + 8) == binding.ATTN_ERR_ALIGN
+    assert call_fwd(p, LSE=FAKE + 2) == binding.ATTN_ERR_ALIGN
+    assert call_bwd(p, ptr=None) == binding.ATTN_ERR_NULL
+    assert call_bwd(p, ptr=FAKE + 2) == binding.ATTN_ERR_ALIGN
+    assert call_bwd(p, ws=None) == binding.ATTN_ERR_WORKSPACE
+    assert call_bwd(p, ws=FAKE + 16) == binding.ATTN_ERR_WORKSPACE
+    assert call_bwd(p, ws_bytes=1023) == binding.ATTN_ERR_WORKSPACE
+    assert call_bwd(p, stages=0) == binding.ATTN_ERR_SHAPE
+    assert call_bwd(p, stages=8) == binding.ATTN_ERR_SHAPE
+
+
+def test_row_count_overflow_is_a_shape_error():
+    p = attn.make_params(1 << 15, 1 << 10, 1 << 10, 64, 0.125, False)
+    assert call_fwd(p) == binding.ATTN_ERR_SHAPE
+
+
+def test_workloads_are_seeded_and_shaped():
+    from paper_2601_16238_amd import workloads as wl
+    import numpy as np
+    a = wl.make_inputs("tiny")
+    b = wl.make_inputs("tiny")
+    assert a["Q"].shape == (1, 2, 128, 64) and a["Q"].dtype == np.uint16
+    for k in ("Q", "K", "V", "dO"):
+        assert np.array_equal(a[k], b[k])
+    sub = wl.make_inputs("vit_cifar", heads=[0, 5, 767])
+    full = wl.make_inputs("vit_cifar")
+    assert sub["K"].shape == (1, 3, 65, 64)
+    assert np.array_equal(sub["K"][0, 1], full["K"].reshape(768, 65, 64)[5])
+    x = wl.bf16_bits_to_f32(wl.make_inputs("minigpt")["V"])
+    assert abs(float(x.std()) - 0.5) < 0.01
+    # bf16 rounding: nearest-even on the 16 dropped bits
+    f = np.array([1.0, 1.00390625, 1.01171875, -3.0e38], np.float32)
+    assert list(wl.f32_to_bf16_bits(f)) == [0x3F80, 0x3F80, 0x3F82, 0xFF62]
