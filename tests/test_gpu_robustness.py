@@ -1,0 +1,113 @@
+"""GPU regression guards for the bug classes the paper's debugging table lists for its
+attention kernel: buffers reused across iterations without initialisation, launch
+configurations, and call-interface (stride) handling."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2601_16238_amd as attn
+from paper_2601_16238_amd import workloads as wl
+from parity_util import check_bf16, check_lse, to_dev, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def poison(*ts):
+    for t in ts:
+        if t.dtype == torch.uint8:
+            t.fill_(0x7F)
+        else:
+            t.fill_(float("nan"))
+
+
+@pytest.mark.parametrize("B,H,S,D,causal", [(2, 2, 300, 64, True), (1, 2, 257, 128, False)])
+def test_poisoned_outputs_and_workspace_repeat_bit_identical(B, H, S, D, causal):
+    """Outputs and workspace are filled with NaN / garbage before every call; twelve
+    consecutive fwd+bwd calls on the same buffers must give bit-identical, finite results
+    (no atomics, nothing accumulated into caller buffers)."""
+    print("case poison_repeat", B, H, S, D, causal, flush=True)
+    x = wl.random_inputs(B, H, S, D, seed=300 + S)
+    Q, K, V, dO = (to_dev(x[k]) for k in ("Q", "K", "V", "dO"))
+    O = torch.empty_like(Q)
+    LSE = torch.empty((B, H, S), dtype=torch.float32, device="cuda")
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
+    ws = torch.empty(attn.attn_bwd_workspace_bytes(B, H, S, D), dtype=torch.uint8, device="cuda")
+    first = None
+    for it in range(12):
+        poison(O, LSE, dQ, dK, dV, ws)
+        attn.attn_fwd(Q, K, V, x["scale"], causal, O=O, LSE=LSE)
+        attn.attn_bwd(Q, K, V, O, dO, LSE, x["scale"], causal, dQ=dQ, dK=dK, dV=dV, workspace=ws)
+        torch.cuda.synchronize()
+        cur = [t.clone() for t in (O, LSE, dQ, dK, dV)]
+        for t in cur:
+            assert torch.isfinite(t.float()).all(), "iteration %d produced non-finite values" % it
+        if first is None:
+            first = cur
+        else:
+            for a, b in zip(first, cur):
+                assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), "iteration %d differs" % it
+    ref = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], causal)
+    for nm, t, r in zip(("dQ", "dK", "dV"), first[2:], ref):
+        check_bf16(nm, to_f64(t), r)
+
+
+def test_bshd_strides_and_side_stream():
+    """[B,S,H,D] storage viewed as [B,H,S,D] (stride_h = D, stride_s = H*D), launched on a
+    non-default stream."""
+    print("case bshd_strides", flush=True)
+    B, H, S, D, causal = 2, 3, 200, 64, True
+    x = wl.random_inputs(B, H, S, D, seed=41)
+
+    def bshd(bits):
+        t = to_dev(bits)                                   # [B,H,S,D] contiguous
+        return t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)  # same values, BSHD memory
+
+    Q, K, V, dO = (bshd(x[k]) for k in ("Q", "K", "V", "dO"))
+    assert Q.stride() == (S * H * D, D, H * D, 1)
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(st):
+        O, LSE = attn.attn_fwd(Q, K, V, x["scale"], causal, stream=st)
+        dQ, dK, dV = attn.attn_bwd(Q, K, V, O, dO, LSE, x["scale"], causal, stream=st)
+    st.synchronize()
+    assert O.stride() == Q.stride() and dK.stride() == Q.stride()
+    Oref, Lref = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], causal)
+    ref = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], causal)
+    check_bf16("O", to_f64(O), Oref)
+    check_lse(to_f64(LSE), Lref)
+    for nm, t, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), ref):
+        check_bf16(nm, to_f64(t), r)
+
+
+def test_isolated_backward_from_oracle_O_and_LSE():
+    """Backward fed with bf16(O_oracle) and fp32(LSE_oracle) instead of the GPU forward's
+    outputs: isolates the backward kernels from the forward."""
+    print("case isolated_bwd", flush=True)
+    B, H, S, D, causal = 1, 2, 333, 128, True
+    x = wl.random_inputs(B, H, S, D, seed=42)
+    Oref, Lref = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], causal)
+    ref = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], causal)
+    Q, K, V, dO = (to_dev(x[k]) for k in ("Q", "K", "V", "dO"))
+    O = torch.from_numpy(Oref).to(torch.bfloat16).cuda()
+    LSE = torch.from_numpy(Lref).to(torch.float32).cuda()
+    dQ, dK, dV = attn.attn_bwd(Q, K, V, O, dO, LSE, x["scale"], causal)
+    torch.cuda.synchronize()
+    for nm, t, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), ref):
+        check_bf16(nm, to_f64(t), r)
+
+
+def test_large_scores_do_not_overflow():
+    """Scores of several hundred (outlier rows of the long-sequence workload): the running
+    max must track them; compare with the oracle at 1e-5 + 1e-5*|LSE|."""
+    print("case large_scores", flush=True)
+    B, H, S, D = 1, 2, 500, 128
+    x = wl.random_inputs(B, H, S, D, seed=43, sigma=8.0)
+    Oref, Lref = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], True)
+    assert Lref.max() > 100
+    O, LSE = attn.attn_fwd(to_dev(x["Q"]), to_dev(x["K"]), to_dev(x["V"]), x["scale"], True)
+    torch.cuda.synchronize()
+    got = to_f64(LSE)
+    assert np.isfinite(got).all() and (np.abs(got - Lref) <= 1e-5 + 1e-5 * np.abs(Lref)).all()
+    d = np.abs(to_f64(O) - Oref)
+    assert d.max() <= 2e-2 * max(1.0, np.abs(Oref).max()) and np.isfinite(d).all()
