@@ -45,7 +45,8 @@ typedef enum {
     ATTN_OK = 0,
     ATTN_ERR_NULL = -1,      /* a required pointer is NULL                                  */
     ATTN_ERR_SHAPE = -2,     /* B,H,S < 1, D not in {64,128}, or a size overflows int32      */
-    ATTN_ERR_STRIDE = -3,    /* a stride is < its minimum or not a multiple of 8 elements    */
+    ATTN_ERR_STRIDE = -3,    /* a stride is < its minimum, not a multiple of 8 elements, or
+                                (S + 512) * stride_s * 2 bytes does not fit in 32 bits        */
     ATTN_ERR_ALIGN = -4,     /* a tensor pointer is not 16-byte aligned (LSE: 4-byte)        */
     ATTN_ERR_WORKSPACE = -5, /* workspace NULL/misaligned or smaller than required           */
     ATTN_ERR_SCALE = -6,     /* scale is not a finite number > 0                             */

@@ -10,7 +10,10 @@ OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libmi355attn.so")
 SOURCES = ["attn_api.hip", "attn_fwd.hip", "attn_bwd.hip"]
 # -packed-fp32-ops: never let the compiler form v_pk_*_f32 instructions.
+# -fno-honor-nans (device only): fmaxf lowers to bare v_max/v_max3 without canonicalising
+# moves; the kernels never produce or test NaNs.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=fast",
+         "-Xarch_device", "-fno-honor-nans",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument"]
 

@@ -19,6 +19,9 @@ int check_params(const attn_params_t *p)
     if (rows > (int64_t)std::numeric_limits<int32_t>::max()) return ATTN_ERR_SHAPE;
     if (p->stride_s < p->D || p->stride_h < 1 || p->stride_b < 1) return ATTN_ERR_STRIDE;
     if (p->stride_s % 8 || p->stride_h % 8 || p->stride_b % 8) return ATTN_ERR_STRIDE;
+    // One head's rows (plus the look-ahead tiles the kernels fetch past the end, which read
+    // as zero) are addressed with 32-bit byte offsets.
+    if (((int64_t)p->S + 512) * p->stride_s * 2 >= ((int64_t)1 << 32)) return ATTN_ERR_STRIDE;
     if (!std::isfinite(p->scale) || !(p->scale > 0.0f)) return ATTN_ERR_SCALE;
     return ATTN_OK;
 }

@@ -81,6 +81,23 @@ __device__ __forceinline__ bf16x8 join8(s16x4 lo, s16x4 hi)
 __device__ __forceinline__ u32x4 ld_global16(const bf16 *p) { return *(const u32x4 *)p; }
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+// Raw buffer loads: byte offset = per-lane voff + wave-uniform soff into a resource that
+// covers `bytes` bytes from `p`; reads past the end return 0 instead of faulting, which is
+// how ragged tails and tiles past the end of a sequence are fetched.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ u32x4 buf_load16(rsrc_t r, uint32_t voff, uint32_t soff)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0);
+}
+__device__ __forceinline__ u32x2 buf_load8(rsrc_t r, uint32_t voff, uint32_t soff)
+{
+    return __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, 0);
+}
+
 // Work-group id -> position in a virtual order in which consecutive positions land on the
 // same XCD.  Work-groups are handed to the 8 XCDs round-robin by linear id, each XCD has
 // its own L2, so giving one XCD a contiguous range of (head, query tile) pairs keeps the

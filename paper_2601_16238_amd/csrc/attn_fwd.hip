@@ -13,7 +13,18 @@
 //   - bf16(P^T) is already in the B-operand layout of the second MFMA,
 //     O^T = V^T P^T (d x queries), once the contraction index is enumerated in the order
 //     the accumulator holds it (key = 8*(t/4) + 4*(l/32) + t%4 within 16 keys).
-// V^T fragments come from row-major V in LDS through the LDS transpose read.
+// V is transposed once per work-group while it is staged into LDS (4x4 register
+// transposes), in exactly that key order, so both MFMA operands that come from LDS are
+// plain 16-byte reads (the LDS transpose read runs at about a third of that rate).
+//
+// Software pipeline (per wave): the MFMAs of S^T(j+1) are issued in the same block as the
+// softmax arithmetic of tile j, so the matrix pipe and the vector ALU overlap inside one
+// wave as well as across the two waves of a SIMD.  The vector ALU issue port is the scarce
+// resource (it also carries the MFMA issue and the LDS read returns), so the common path
+// does no max reduction at all: probabilities are taken relative to a reference max that is
+// only moved when a partial row sum shows that some probability outgrew 2^10 (the O
+// accumulator and row sum are then rescaled and the sub-tile redone).  Any reference gives
+// the same O and LSE after the final division by the row sum.
 #include "attn_device.hpp"
 #include "attn_launch.hpp"
 
@@ -24,23 +35,33 @@ struct FwdCfg {
     static constexpr int kThreads = NW * 64;
     static constexpr int kBR = NW * 32;
     static constexpr int kBC = 64;
-    static constexpr int kLd = D + 8;               // LDS row stride (elements): +16 B skew
-    static constexpr int kTileElems = kBC * kLd;    // one K or V tile
-    static constexpr int kLdsBytes = 2 * 2 * kTileElems * 2;  // K,V double-buffered
-    static constexpr int kChunks = kBC * D / 8;     // 16-byte chunks per tile
-    static constexpr int kChunksPerThread = (kChunks + kThreads - 1) / kThreads;
+    static constexpr int kLdK = D + 8;              // K tile [key][d], rows skewed by 16 B
+    static constexpr int kKTile = kBC * kLdK;
+    static constexpr int kLdV = kBC + 8;            // V^T tile [d][key order], rows skewed
+    static constexpr int kVTile = D * kLdV;
+    static constexpr int kLdsBytes = (3 * kKTile + 2 * kVTile) * 2;   // K x3, V^T x2
+    static constexpr int kKChunks = kBC * D / 8;    // 16-byte chunks of a K tile
+    static constexpr int kKPerThread = (kKChunks + kThreads - 1) / kThreads;
+    static constexpr int kVMicro = (kBC / 4) * (D / 4);   // 4 keys x 4 d micro-tiles of a V tile
+    static constexpr int kVPerThread = (kVMicro + kThreads - 1) / kThreads;
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 CU exceeded");
 };
 
+// A sub-tile's probabilities are taken relative to a reference max that is only moved when
+// one lane's partial row sum (16 keys) exceeds this bound, i.e. some exp2 argument > ~10.
+constexpr float kOverflow = 1024.0f;
+constexpr float kMinusHuge = -1.0e30f;  // initial reference: finite, so masked -inf scores give 0
+
 template <int D, int NW, bool CAUSAL>
-__global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const FwdArgs a)
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
+attn_fwd_kernel(const FwdArgs a)
 {
     using C = FwdCfg<D, NW>;
     constexpr int KS = D / 16;  // contraction steps of K Q^T
     constexpr int DB = D / 32;  // 32-row blocks of O^T
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16 *Ks = reinterpret_cast<bf16 *>(smem);  // [2][BC][kLd]
-    bf16 *Vs = Ks + 2 * C::kTileElems;          // [2][BC][kLd]
+    bf16 *Ks = reinterpret_cast<bf16 *>(smem);  // [3][64][kLdK]
+    bf16 *Vs = Ks + 3 * C::kKTile;              // [2][D][kLdV]
 
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, r = l & 31, h = l >> 5;
     const int S = a.S;
@@ -66,120 +87,241 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const FwdArgs a)
     const int q_end = min(S, (qt + 1) * C::kBR);
     const int n_kt = ((CAUSAL ? q_end : S) + C::kBC - 1) / C::kBC;
 
-    // Global -> register prefetch of one K and one V tile (rows clamped to S-1: finite
-    // data, masked to probability 0 below).
-    u32x4 kreg[C::kChunksPerThread], vreg[C::kChunksPerThread];
-    auto prefetch = [&](int kt) {
+    // ---- staging: global -> registers -> LDS.  Rows past S-1 and tiles past the last one
+    // lie outside the head's buffer resource and read as zero (masked to probability 0).
+    const uint32_t head_bytes = (uint32_t)(((int64_t)(S - 1) * a.stride_s + D) * 2);
+    const rsrc_t Kr = make_rsrc(Kp, head_bytes), Vr = make_rsrc(Vp, head_bytes);
+    const uint32_t row_bytes = (uint32_t)a.stride_s * 2u;
+    const uint32_t tile_bytes = C::kBC * row_bytes;
+    u32x4 kreg[C::kKPerThread];
+    u32x2 vreg[C::kVPerThread][4];
+    auto load_k = [&](int kt) {
 #pragma unroll
-        for (int n = 0; n < C::kChunksPerThread; ++n) {
+        for (int n = 0; n < C::kKPerThread; ++n) {
             const int c = tid + n * C::kThreads;
-            if (C::kChunks % C::kThreads == 0 || c < C::kChunks) {
+            if (C::kKChunks % C::kThreads == 0 || c < C::kKChunks) {
                 const int row = c / (D / 8), col = (c % (D / 8)) * 8;
-                int kr = kt * C::kBC + row;
-                kr = kr < S ? kr : S - 1;
-                kreg[n] = ld_global16(Kp + (int64_t)kr * a.stride_s + col);
-                vreg[n] = ld_global16(Vp + (int64_t)kr * a.stride_s + col);
+                kreg[n] = buf_load16(Kr, row * row_bytes + col * 2, kt * tile_bytes);
             }
         }
     };
-    auto commit = [&](int buf) {
+    auto store_k = [&](int buf) {
 #pragma unroll
-        for (int n = 0; n < C::kChunksPerThread; ++n) {
+        for (int n = 0; n < C::kKPerThread; ++n) {
             const int c = tid + n * C::kThreads;
-            if (C::kChunks % C::kThreads == 0 || c < C::kChunks) {
+            if (C::kKChunks % C::kThreads == 0 || c < C::kKChunks) {
                 const int row = c / (D / 8), col = (c % (D / 8)) * 8;
-                *(u32x4 *)(Ks + buf * C::kTileElems + row * C::kLd + col) = kreg[n];
-                *(u32x4 *)(Vs + buf * C::kTileElems + row * C::kLd + col) = vreg[n];
+                *(u32x4 *)(Ks + buf * C::kKTile + row * C::kLdK + col) = kreg[n];
+            }
+        }
+    };
+    // V micro-tile mt: a wave covers 32 keys x 32 d as 8 key groups x 8 d groups.
+    auto v_coords = [&](int mt, int &key0, int &d0) {
+        const int blk = mt >> 6;
+        key0 = 32 * (blk & 1) + 4 * (mt & 7);
+        d0 = 32 * (blk >> 1) + 4 * ((mt >> 3) & 7);
+    };
+    auto load_v = [&](int kt) {
+#pragma unroll
+        for (int n = 0; n < C::kVPerThread; ++n) {
+            const int mt = tid + n * C::kThreads;
+            if (C::kVMicro % C::kThreads == 0 || mt < C::kVMicro) {
+                int key0, d0;
+                v_coords(mt, key0, d0);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    vreg[n][i] = buf_load8(Vr, (key0 + i) * row_bytes + d0 * 2, kt * tile_bytes);
+            }
+        }
+    };
+    auto store_v = [&](int buf) {
+#pragma unroll
+        for (int n = 0; n < C::kVPerThread; ++n) {
+            const int mt = tid + n * C::kThreads;
+            if (C::kVMicro % C::kThreads == 0 || mt < C::kVMicro) {
+                int key0, d0;
+                v_coords(mt, key0, d0);
+                // position of key0 (a multiple of 4) in the MFMA contraction order:
+                // key = 16cc + 8u + 4hh + e  ->  16cc + 8hh + 4u + e
+                const int kpos = (key0 & ~15) | ((key0 & 4) << 1) | ((key0 & 8) >> 1);
+                bf16 *dst = Vs + buf * C::kVTile + d0 * C::kLdV + kpos;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    // column d0+j of the 4x4 micro-tile: keys key0..key0+3
+                    const unsigned sel = (j & 1) ? 0x07060302u : 0x05040100u;
+                    const int hw = j >> 1;  // which dword of the 8-byte row piece
+                    u32x2 col;
+                    col.x = __builtin_amdgcn_perm(vreg[n][1][hw], vreg[n][0][hw], sel);
+                    col.y = __builtin_amdgcn_perm(vreg[n][3][hw], vreg[n][2][hw], sel);
+                    *(u32x2 *)(dst + j * C::kLdV) = col;
+                }
             }
         }
     };
 
-    float m = -INFINITY;  // running max of c*s (log2 units), identical in lanes l and l^32
+    float m = kMinusHuge;  // reference max of c*s (log2 units), identical in lanes l and l^32
     float lsum = 0.f;     // running sum of this lane's half of the keys
     f32x16 o[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
-
     const float c = a.scale_log2e;
-    // transpose-read source role of this lane: row (l%16)/4 of a 4-row group, 4-element
-    // chunk (l%4) of the 16 columns served by its 16-lane group.
-    const int tr_row = 4 * h + ((l & 15) >> 2);
-    const int tr_col = ((l >> 4) & 1) * 16 + (l & 3) * 4;
 
-    prefetch(0);
-    for (int kt = 0; kt < n_kt; ++kt) {
-        const int buf = kt & 1;
-        commit(buf);
-        __syncthreads();
-        if (kt + 1 < n_kt) prefetch(kt + 1);
+    // ---- MFMA steps and their LDS operand fetches.  Work proceeds in sub-tiles of 32 keys
+    // (one 32x32 score block per wave).  One step is four (D=128) MFMAs whose A fragments
+    // are fetched a step ahead into the other of two fragment sets, so the LDS latency hides
+    // behind the previous step's MFMAs.
+    constexpr int NKQ = KS / 4;  // K Q^T steps per sub-tile, four contraction steps each
+    auto ld_k = [&](const bf16 *Kt, int kq, bf16x8 (&f)[4]) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            f[t] = *(const bf16x8 *)(Kt + r * C::kLdK + (4 * kq + t) * 16 + 8 * h);
+    };
+    auto mm_k = [&](int kq, const bf16x8 (&f)[4], f32x16 &t0) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) t0 = mfma32(f[t], qf[4 * kq + t], t0);
+    };
+    // V^T fragment: lane (d = 32*db + l%32, half h) holds the 8 keys of contraction step cc
+    // that its half owns, contiguous in the staged order.
+    auto ld_v = [&](const bf16 *Vt, int cc, bf16x8 (&f)[4]) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+            f[db] = *(const bf16x8 *)(Vt + (32 * db + r) * C::kLdV + 16 * cc + 8 * h);
+    };
+    auto mm_v = [&](const bf16x8 (&f)[4], bf16x8 p) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db) o[db] = mfma32(f[db], p, o[db]);
+    };
+    // exp2 of eight scores against the reference max, fp32 row-sum, and bf16 pack
+    auto softmax8 = [&](const f32x16 &t, int i0, float &psum) -> bf16x8 {
+        float e[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            e[i] = fast_exp2(__builtin_fmaf(t[i0 + i], c, -m));
+            psum += e[i];
+        }
+        return pack8(e[0], e[1], e[2], e[3], e[4], e[5], e[6], e[7]);
+    };
+#define ATTN_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-        const int kb = kt * C::kBC;
-        const bool active = !CAUSAL || kb <= q0 + 31;  // wave-uniform
-        if (active) {
-            const bf16 *Kt = Ks + buf * C::kTileElems;
-            const bf16 *Vt = Vs + buf * C::kTileElems;
-            f32x16 s0, s1;
+    // One 32-key sub-tile g = 2*kt + u for an active wave: softmax and P V of sub-tile g
+    // (scores in cur) overlapped with S^T of sub-tile g+1 (into nxt; one sub-tile past the
+    // end reads zero rows and is unused).  Four fragment sets rotate through the steps
+    //   K0 (f0), K1 (f1): S^T(g+1) += K Q^T      V0 (f2), V1 (f3): O^T += V^T P^T(g)
+    // and every set is fetched two steps before it is consumed; the K fragments of sub-tile
+    // g+2 (tile kt+1, resident since the previous iteration) are fetched during V0/V1.
+    bf16x8 f0[4], f1[4], f2[4], f3[4];
+    auto subtile = [&](int kt, int u, int kbuf_next, bool masked, f32x16 &cur, f32x16 &nxt) {
+        const bf16 *Kn = Ks + kbuf_next * C::kKTile + u * 32 * C::kLdK;  // rows of sub-tile g+2
+        const bf16 *Vt = Vs + (kt & 1) * C::kVTile + 32 * u;
+        // The two waves that share a SIMD (w and w+4) take turns at the higher issue
+        // priority, one sub-tile each; otherwise the older wave always wins arbitration,
+        // runs ahead, and then idles at the tile barrier while the younger one catches up.
+        if (NW == 8) {
+            if (((w >> 2) ^ u) & 1) __builtin_amdgcn_s_setprio(0);
+            else __builtin_amdgcn_s_setprio(2);
+        }
+        // ---- K0
+        ld_v(Vt, 0, f2);
+        if (NKQ == 1) ld_v(Vt, 1, f3);
 #pragma unroll
-            for (int i = 0; i < 16; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
+        for (int i = 0; i < 16; ++i) nxt[i] = 0.f;
+        if (masked) {
+            // Ragged tail and causal mask: only sub-tiles that touch the end or the diagonal.
+            const int lim = (CAUSAL ? qc : S - 1) - (kt * C::kBC + 32 * u) - 4 * h;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8 k0 = *(const bf16x8 *)(Kt + r * C::kLd + ks * 16 + 8 * h);
-                const bf16x8 k1 = *(const bf16x8 *)(Kt + (32 + r) * C::kLd + ks * 16 + 8 * h);
-                s0 = mfma32(k0, qf[ks], s0);
-                s1 = mfma32(k1, qf[ks], s1);
-            }
-            // Ragged tail and causal mask: only tiles that touch the end or the diagonal.
-            const bool need_mask = (kb + C::kBC > S) || (CAUSAL && kb + C::kBC - 1 > q0);
-            if (need_mask) {
-                const int lim = (CAUSAL ? qc : S - 1) - kb - 4 * h;  // last visible key offset
+            for (int i = 0; i < 16; ++i)
+                if (8 * (i / 4) + (i % 4) > lim) cur[i] = -INFINITY;
+        }
+        float psum = 0.f;
+        bf16x8 p0 = softmax8(cur, 0, psum);
+        mm_k(0, f0, nxt);
+        ATTN_FENCE();
+        // ---- K1
+        if (NKQ > 1) {
+            ld_v(Vt, 1, f3);
+            mm_k(1, f1, nxt);
+        }
+        bf16x8 p1 = softmax8(cur, 8, psum);
+        // Rare path: some probability outgrew 2^10 relative to the reference max (always so
+        // for a wave's first sub-tile).  Move the reference to the true running max, rescale
+        // what has been accumulated, and redo this sub-tile's probabilities.
+        if (__builtin_amdgcn_ballot_w64(psum > kOverflow) != 0) {
+            float mx = cur[0];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int ko = 8 * (i / 4) + (i % 4);
-                    if (ko > lim) s0[i] = -INFINITY;
-                    if (ko + 32 > lim) s1[i] = -INFINITY;
-                }
-            }
-            float mx = fmaxf(s0[0], s1[0]);
-#pragma unroll
-            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, fmaxf(s0[i], s1[i]));
-            mx = xhalf_max(mx);
-            const float m_new = fmaxf(m, mx * c);
+            for (int i = 1; i < 16; i += 3)
+                mx = fmaxf(mx, fmaxf(cur[i], fmaxf(cur[i + 1], cur[i + 2])));
+            mx = xhalf_max(mx) * c;
+            const float m_new = fmaxf(m, mx);
             const float alpha = fast_exp2(m - m_new);
             m = m_new;
-            float psum = 0.f;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                s0[i] = fast_exp2(__builtin_fmaf(s0[i], c, -m_new));
-                s1[i] = fast_exp2(__builtin_fmaf(s1[i], c, -m_new));
-                psum += s0[i] + s1[i];
-            }
-            lsum = lsum * alpha + psum;
+            lsum *= alpha;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-
-            // bf16(P^T) as B operands: contraction step cc covers keys 16*cc .. 16*cc+15.
-            bf16x8 pf[4];
-            pf[0] = pack8(s0[0], s0[1], s0[2], s0[3], s0[4], s0[5], s0[6], s0[7]);
-            pf[1] = pack8(s0[8], s0[9], s0[10], s0[11], s0[12], s0[13], s0[14], s0[15]);
-            pf[2] = pack8(s1[0], s1[1], s1[2], s1[3], s1[4], s1[5], s1[6], s1[7]);
-            pf[3] = pack8(s1[8], s1[9], s1[10], s1[11], s1[12], s1[13], s1[14], s1[15]);
-#pragma unroll
-            for (int cc = 0; cc < 4; ++cc) {
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    // V^T fragment: lane (d = 32*db + l%32, half h) needs V[16cc + 4h + e][d]
-                    // in elements 0..3 and V[16cc + 8 + 4h + e][d] in elements 4..7.
-                    const bf16 *vp = Vt + (16 * cc + tr_row) * C::kLd + 32 * db + tr_col;
-                    const bf16x8 vf = join8(lds_read_tr(vp), lds_read_tr(vp + 8 * C::kLd));
-                    o[db] = mfma32(vf, pf[cc], o[db]);
-                }
-            }
+            psum = 0.f;
+            p0 = softmax8(cur, 0, psum);
+            p1 = softmax8(cur, 8, psum);
         }
+        ATTN_FENCE();
+        // ---- V0
+        ld_k(Kn, 0, f0);
+        mm_v(f2, p0);
+        ATTN_FENCE();
+        // ---- V1
+        if (NKQ > 1) ld_k(Kn, 1, f1);
+        mm_v(f3, p1);
+        lsum += psum;
+        ATTN_FENCE();
+    };
+
+    // ---- prologue: K(0), K(1), V(0) resident; K(2), V(1) in flight; first S^T block computed
+    // and the K fragments of the second sub-tile on their way.
+    load_k(0);
+    load_v(0);
+    store_k(0);
+    load_k(1);
+    store_v(0);
+    store_k(1);
+    load_k(2);
+    load_v(1);
+    __syncthreads();
+    f32x16 sa, sb;
+    {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sa[i] = 0.f;
+        ld_k(Ks, 0, f0);
+        if (NKQ > 1) ld_k(Ks, 1, f1);
+        mm_k(0, f0, sa);
+        if (NKQ > 1) mm_k(1, f1, sa);
+        ATTN_FENCE();
+        ld_k(Ks + 32 * C::kLdK, 0, f0);
+        if (NKQ > 1) ld_k(Ks + 32 * C::kLdK, 1, f1);
     }
+
+    // One loop iteration = one staged tile of 64 keys = two sub-tiles, then staging of
+    // K(kt+2), V(kt+1) (loaded one iteration ago) and the next global loads.  During
+    // iteration kt the waves read K(kt) (second half) and K(kt+1) (first half), so K is
+    // triple-buffered (tile t in buffer t%3) and K(kt+2) goes to the third buffer; V(kt+1)
+    // replaces V(kt-1), whose last readers finished before the previous barrier.
+    int kb0 = 0, kb1 = 1, kb2 = 2;  // buffers of K(kt), K(kt+1), K(kt+2)
+    for (int kt = 0; kt < n_kt; ++kt) {
+        const int kb = kt * C::kBC;
+        // wave-uniform: does the wave see any key of the sub-tile / must it mask some
+        if (!CAUSAL || kb <= q0 + 31)
+            subtile(kt, 0, kb1, (kb + 32 > S) || (CAUSAL && kb + 31 > q0), sa, sb);
+        if (!CAUSAL || kb + 32 <= q0 + 31)
+            subtile(kt, 1, kb1, (kb + 64 > S) || (CAUSAL && kb + 63 > q0), sb, sa);
+        store_k(kb2);
+        store_v((kt + 1) & 1);
+        load_k(kt + 3);
+        load_v(kt + 2);
+        __syncthreads();
+        const int t = kb0; kb0 = kb1; kb1 = kb2; kb2 = t;
+    }
+#undef ATTN_FENCE
 
     // Epilogue: O = O_acc / l, LSE = ln2 * (m + log2 l).
     const float lt = xhalf_sum(lsum);
@@ -198,21 +340,21 @@ __global__ void __launch_bounds__(NW * 64) attn_fwd_kernel(const FwdArgs a)
     }
 }
 
+template <int D, int NW, bool CAUSAL>
+static int launch_fwd_kernel(const FwdArgs &a, hipStream_t st)
+{
+    using C = FwdCfg<D, NW>;
+    hipFuncSetAttribute((const void *)attn_fwd_kernel<D, NW, CAUSAL>,
+                        hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+    hipLaunchKernelGGL((attn_fwd_kernel<D, NW, CAUSAL>), dim3(a.nqt * a.BH), dim3(C::kThreads),
+                       C::kLdsBytes, st, a);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 template <int D, int NW>
 static int launch_fwd_nw(const FwdArgs &a, bool causal, hipStream_t st)
 {
-    using C = FwdCfg<D, NW>;
-    const dim3 grid(a.nqt * a.BH), block(C::kThreads);
-    if (causal) {
-        hipFuncSetAttribute((const void *)attn_fwd_kernel<D, NW, true>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-        hipLaunchKernelGGL((attn_fwd_kernel<D, NW, true>), grid, block, C::kLdsBytes, st, a);
-    } else {
-        hipFuncSetAttribute((const void *)attn_fwd_kernel<D, NW, false>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-        hipLaunchKernelGGL((attn_fwd_kernel<D, NW, false>), grid, block, C::kLdsBytes, st, a);
-    }
-    return hipGetLastError() == hipSuccess ? 0 : -1;
+    return causal ? launch_fwd_kernel<D, NW, true>(a, st) : launch_fwd_kernel<D, NW, false>(a, st);
 }
 
 // Waves per work-group: 8 (256 query rows) unless the sequence is too short to fill them.
