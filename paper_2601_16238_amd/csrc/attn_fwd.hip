@@ -35,13 +35,13 @@ struct FwdCfg {
     static constexpr int kThreads = NW * 64;
     static constexpr int kBR = NW * 32;
     static constexpr int kBC = 64;
-    static constexpr int kLdK = D + 8;              // K tile [key][d], rows skewed by 16 B
-    static constexpr int kKTile = kBC * kLdK;
+    static constexpr int kKTile = kBC * D;          // K tile [key][d], 16-byte chunks XOR-swizzled
+    static constexpr int kKRowsPerDma = 1024 / (D * 2);        // rows one wave-wide 16 B/lane load fills
+    static constexpr int kKDmas = kBC / kKRowsPerDma;          // such loads per tile
+    static constexpr int kKDmaPerWave = (kKDmas + NW - 1) / NW;
     static constexpr int kLdV = kBC + 8;            // V^T tile [d][key order], rows skewed
     static constexpr int kVTile = D * kLdV;
     static constexpr int kLdsBytes = (3 * kKTile + 2 * kVTile) * 2;   // K x3, V^T x2
-    static constexpr int kKChunks = kBC * D / 8;    // 16-byte chunks of a K tile
-    static constexpr int kKPerThread = (kKChunks + kThreads - 1) / kThreads;
     static constexpr int kVMicro = (kBC / 4) * (D / 4);   // 4 keys x 4 d micro-tiles of a V tile
     static constexpr int kVPerThread = (kVMicro + kThreads - 1) / kThreads;
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 CU exceeded");
@@ -60,7 +60,7 @@ attn_fwd_kernel(const FwdArgs a)
     constexpr int KS = D / 16;  // contraction steps of K Q^T
     constexpr int DB = D / 32;  // 32-row blocks of O^T
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16 *Ks = reinterpret_cast<bf16 *>(smem);  // [3][64][kLdK]
+    bf16 *Ks = reinterpret_cast<bf16 *>(smem);  // [3][64][D] swizzled
     bf16 *Vs = Ks + 3 * C::kKTile;              // [2][D][kLdV]
 
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, r = l & 31, h = l >> 5;
@@ -93,25 +93,23 @@ attn_fwd_kernel(const FwdArgs a)
     const rsrc_t Kr = make_rsrc(Kp, head_bytes), Vr = make_rsrc(Vp, head_bytes);
     const uint32_t row_bytes = (uint32_t)a.stride_s * 2u;
     const uint32_t tile_bytes = C::kBC * row_bytes;
-    u32x4 kreg[C::kKPerThread];
+    // K goes global -> LDS directly (no registers): one wave-wide load of 16 B per lane fills
+    // 1 KB of LDS in lane order, so the tile is stored unpadded and bank conflicts are avoided
+    // by XOR-swizzling the 16-byte chunk index with the row: a lane fetches the chunk that
+    // belongs at its LDS position.  Chunk c of row k sits at chunk position c ^ swz(k).
+    constexpr int CPR = D / 8;  // 16-byte chunks per row
+    auto swz = [](int row) { return CPR == 16 ? (row & 15) : ((row >> 1) & 7); };
     u32x2 vreg[C::kVPerThread][4];
-    auto load_k = [&](int kt) {
+    auto dma_k = [&](int kt, int buf) {
 #pragma unroll
-        for (int n = 0; n < C::kKPerThread; ++n) {
-            const int c = tid + n * C::kThreads;
-            if (C::kKChunks % C::kThreads == 0 || c < C::kKChunks) {
-                const int row = c / (D / 8), col = (c % (D / 8)) * 8;
-                kreg[n] = buf_load16(Kr, row * row_bytes + col * 2, kt * tile_bytes);
-            }
-        }
-    };
-    auto store_k = [&](int buf) {
-#pragma unroll
-        for (int n = 0; n < C::kKPerThread; ++n) {
-            const int c = tid + n * C::kThreads;
-            if (C::kKChunks % C::kThreads == 0 || c < C::kKChunks) {
-                const int row = c / (D / 8), col = (c % (D / 8)) * 8;
-                *(u32x4 *)(Ks + buf * C::kKTile + row * C::kLdK + col) = kreg[n];
+        for (int n = 0; n < C::kKDmaPerWave; ++n) {
+            const int ii = w + n * NW;  // which 1 KB piece of the tile (wave-uniform)
+            if (C::kKDmas % NW == 0 || ii < C::kKDmas) {
+                const int row = ii * C::kKRowsPerDma + l / CPR;
+                const int chunk = (l % CPR) ^ swz(row);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    Kr, (void __attribute__((address_space(3))) *)(Ks + buf * C::kKTile + ii * 512),
+                    16, row * row_bytes + chunk * 16, kt * tile_bytes, 0, 0);
             }
         }
     };
@@ -173,10 +171,14 @@ attn_fwd_kernel(const FwdArgs a)
     // are fetched a step ahead into the other of two fragment sets, so the LDS latency hides
     // behind the previous step's MFMAs.
     constexpr int NKQ = KS / 4;  // K Q^T steps per sub-tile, four contraction steps each
+    // element offset of this lane's fragment for contraction step ks within a 32-row half
+    // tile (rows r and 32+r have the same swizzle)
+    int koff[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) koff[ks] = r * D + (((2 * ks + h) ^ swz(r)) * 8);
     auto ld_k = [&](const bf16 *Kt, int kq, bf16x8 (&f)[4]) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-            f[t] = *(const bf16x8 *)(Kt + r * C::kLdK + (4 * kq + t) * 16 + 8 * h);
+        for (int t = 0; t < 4; ++t) f[t] = *(const bf16x8 *)(Kt + koff[4 * kq + t]);
     };
     auto mm_k = [&](int kq, const bf16x8 (&f)[4], f32x16 &t0) {
 #pragma unroll
@@ -212,8 +214,9 @@ attn_fwd_kernel(const FwdArgs a)
     // and every set is fetched two steps before it is consumed; the K fragments of sub-tile
     // g+2 (tile kt+1, resident since the previous iteration) are fetched during V0/V1.
     bf16x8 f0[4], f1[4], f2[4], f3[4];
-    auto subtile = [&](int kt, int u, int kbuf_next, bool masked, f32x16 &cur, f32x16 &nxt) {
-        const bf16 *Kn = Ks + kbuf_next * C::kKTile + u * 32 * C::kLdK;  // rows of sub-tile g+2
+    auto subtile = [&](int kt, int u, int kbuf_next, int kbuf_fill, bool masked, f32x16 &cur,
+                       f32x16 &nxt) {
+        const bf16 *Kn = Ks + kbuf_next * C::kKTile + u * 32 * D;  // rows of sub-tile g+2
         const bf16 *Vt = Vs + (kt & 1) * C::kVTile + 32 * u;
         // The two waves that share a SIMD (w and w+4) take turns at the higher issue
         // priority, one sub-tile each; otherwise the older wave always wins arbitration,
@@ -225,6 +228,7 @@ attn_fwd_kernel(const FwdArgs a)
         // ---- K0
         ld_v(Vt, 0, f2);
         if (NKQ == 1) ld_v(Vt, 1, f3);
+        if (u == 0) dma_k(kt + 2, kbuf_fill);  // K(kt+2) -> the buffer freed at the last barrier
 #pragma unroll
         for (int i = 0; i < 16; ++i) nxt[i] = 0.f;
         if (masked) {
@@ -266,26 +270,25 @@ attn_fwd_kernel(const FwdArgs a)
             p1 = softmax8(cur, 8, psum);
         }
         ATTN_FENCE();
-        // ---- V0
+        // ---- V0 (first sub-tile: V(kt+1), fetched an iteration ago, is transposed into LDS)
         ld_k(Kn, 0, f0);
         mm_v(f2, p0);
+        if (u == 0) store_v((kt + 1) & 1);
         ATTN_FENCE();
-        // ---- V1
+        // ---- V1 (first sub-tile: start fetching V(kt+2))
         if (NKQ > 1) ld_k(Kn, 1, f1);
         mm_v(f3, p1);
+        if (u == 0) load_v(kt + 2);
         lsum += psum;
         ATTN_FENCE();
     };
 
-    // ---- prologue: K(0), K(1), V(0) resident; K(2), V(1) in flight; first S^T block computed
-    // and the K fragments of the second sub-tile on their way.
-    load_k(0);
+    // ---- prologue: K(0), K(1), V(0) resident; V(1) in flight; first S^T block computed and
+    // the K fragments of the second sub-tile on their way.
+    dma_k(0, 0);
+    dma_k(1, 1);
     load_v(0);
-    store_k(0);
-    load_k(1);
     store_v(0);
-    store_k(1);
-    load_k(2);
     load_v(1);
     __syncthreads();
     f32x16 sa, sb;
@@ -297,27 +300,28 @@ attn_fwd_kernel(const FwdArgs a)
         mm_k(0, f0, sa);
         if (NKQ > 1) mm_k(1, f1, sa);
         ATTN_FENCE();
-        ld_k(Ks + 32 * C::kLdK, 0, f0);
-        if (NKQ > 1) ld_k(Ks + 32 * C::kLdK, 1, f1);
+        ld_k(Ks + 32 * D, 0, f0);
+        if (NKQ > 1) ld_k(Ks + 32 * D, 1, f1);
     }
 
-    // One loop iteration = one staged tile of 64 keys = two sub-tiles, then staging of
-    // K(kt+2), V(kt+1) (loaded one iteration ago) and the next global loads.  During
-    // iteration kt the waves read K(kt) (second half) and K(kt+1) (first half), so K is
-    // triple-buffered (tile t in buffer t%3) and K(kt+2) goes to the third buffer; V(kt+1)
-    // replaces V(kt-1), whose last readers finished before the previous barrier.
-    int kb0 = 0, kb1 = 1, kb2 = 2;  // buffers of K(kt), K(kt+1), K(kt+2)
+    // One loop iteration = one staged tile of 64 keys = two sub-tiles.  Staging is folded
+    // into the first sub-tile's steps.  During iteration kt the waves read K(kt) (second
+    // half) and K(kt+1) (first half), so K is triple-buffered and K(kt+2) streams into the
+    // third buffer; V(kt+1) replaces V(kt-1), whose last readers finished before the
+    // previous barrier.
+    int kb1 = 1, kb2 = 2, kb0 = 0;  // buffers of K(kt+1), K(kt+2), K(kt)
     for (int kt = 0; kt < n_kt; ++kt) {
         const int kb = kt * C::kBC;
         // wave-uniform: does the wave see any key of the sub-tile / must it mask some
-        if (!CAUSAL || kb <= q0 + 31)
-            subtile(kt, 0, kb1, (kb + 32 > S) || (CAUSAL && kb + 31 > q0), sa, sb);
+        if (!CAUSAL || kb <= q0 + 31) {
+            subtile(kt, 0, kb1, kb2, (kb + 32 > S) || (CAUSAL && kb + 31 > q0), sa, sb);
+        } else {
+            dma_k(kt + 2, kb2);
+            store_v((kt + 1) & 1);
+            load_v(kt + 2);
+        }
         if (!CAUSAL || kb + 32 <= q0 + 31)
-            subtile(kt, 1, kb1, (kb + 64 > S) || (CAUSAL && kb + 63 > q0), sb, sa);
-        store_k(kb2);
-        store_v((kt + 1) & 1);
-        load_k(kt + 3);
-        load_v(kt + 2);
+            subtile(kt, 1, kb1, kb2, (kb + 64 > S) || (CAUSAL && kb + 63 > q0), sb, sa);
         __syncthreads();
         const int t = kb0; kb0 = kb1; kb1 = kb2; kb2 = t;
     }
