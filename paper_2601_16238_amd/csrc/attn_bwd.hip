@@ -80,6 +80,7 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dkdv_kernel(const BwdArgs a)
 
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, r = l & 31, h = l >> 5;
     const int S = a.S;
+    ATTN_CYCLES_BEGIN();
     const int v = xcd_contiguous_order(blockIdx.x, a.ntile * a.BH);
     const int bh = v / a.ntile, kt = v % a.ntile;  // causal: key block 0 is the heaviest
     const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
@@ -225,6 +226,7 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dkdv_kernel(const BwdArgs a)
                                                dk[db][4 * g + 2] * sc, dk[db][4 * g + 3] * sc);
             }
     }
+    ATTN_CYCLES_END(1);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -241,6 +243,7 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const BwdArgs a)
 
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, r = l & 31, h = l >> 5;
     const int S = a.S;
+    ATTN_CYCLES_BEGIN();
     const int v = xcd_contiguous_order(blockIdx.x, a.ntile * a.BH);
     const int bh = v / a.ntile;
     const int qt = CAUSAL ? a.ntile - 1 - (v % a.ntile) : v % a.ntile;  // heaviest first
@@ -358,6 +361,7 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const BwdArgs a)
                     pack4(dq[db][4 * g] * sc, dq[db][4 * g + 1] * sc,
                           dq[db][4 * g + 2] * sc, dq[db][4 * g + 3] * sc);
     }
+    ATTN_CYCLES_END(2);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -411,6 +415,14 @@ static int launch_bwd_d(const BwdArgs &a, bool causal, hipStream_t st, unsigned 
     if (blocks32 == 2) return launch_bwd_nw<D, 2>(a, causal, st, stages);
     return launch_bwd_nw<D, 1>(a, causal, st, stages);
 }
+
+#ifdef ATTN_CYCLES
+extern "C" void attn_debug_cycles_bwd(unsigned long long *out, int reset)
+{
+    hipMemcpyFromSymbol(out, HIP_SYMBOL(g_attn_cycles), sizeof(g_attn_cycles));
+    if (reset) { unsigned long long z[4][4] = {}; hipMemcpyToSymbol(HIP_SYMBOL(g_attn_cycles), z, sizeof(z)); }
+}
+#endif
 
 int launch_bwd(const BwdArgs &a, int D, bool causal, hipStream_t st, unsigned stages)
 {

@@ -98,6 +98,27 @@ __device__ __forceinline__ u32x2 buf_load8(rsrc_t r, uint32_t voff, uint32_t sof
     return __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, 0);
 }
 
+// Cycle accounting for development builds (-DATTN_CYCLES): every work-group adds its
+// elapsed shader cycles and 100 MHz wall ticks to a per-kernel slot, so that a change can be
+// judged in cycles although the shader clock floats with load.  Not compiled into the
+// product library.
+#ifdef ATTN_CYCLES
+static __device__ unsigned long long g_attn_cycles[4][4];  // [slot][cycles, wall ticks, work-groups]
+#define ATTN_CYCLES_BEGIN() \
+    const long long attn_c0_ = __builtin_readcyclecounter(), attn_r0_ = wall_clock64()
+#define ATTN_CYCLES_END(slot)                                                                  \
+    do {                                                                                       \
+        if (threadIdx.x == 0) {                                                                \
+            atomicAdd(&g_attn_cycles[slot][0], (unsigned long long)(__builtin_readcyclecounter() - attn_c0_)); \
+            atomicAdd(&g_attn_cycles[slot][1], (unsigned long long)(wall_clock64() - attn_r0_));             \
+            atomicAdd(&g_attn_cycles[slot][2], 1ull);                                          \
+        }                                                                                      \
+    } while (0)
+#else
+#define ATTN_CYCLES_BEGIN() ((void)0)
+#define ATTN_CYCLES_END(slot) ((void)0)
+#endif
+
 // Work-group id -> position in a virtual order in which consecutive positions land on the
 // same XCD.  Work-groups are handed to the 8 XCDs round-robin by linear id, each XCD has
 // its own L2, so giving one XCD a contiguous range of (head, query tile) pairs keeps the

@@ -65,6 +65,7 @@ attn_fwd_kernel(const FwdArgs a)
 
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, r = l & 31, h = l >> 5;
     const int S = a.S;
+    ATTN_CYCLES_BEGIN();
 
     // (head, query tile) of this work-group; causal tiles are issued heaviest first.
     const int v = xcd_contiguous_order(blockIdx.x, a.nqt * a.BH);
@@ -342,6 +343,7 @@ attn_fwd_kernel(const FwdArgs a)
             }
         if (h == 0) a.LSE[(int64_t)bh * S + q] = (m + fast_log2(lt)) * kLn2;
     }
+    ATTN_CYCLES_END(0);
 }
 
 template <int D, int NW, bool CAUSAL>
@@ -383,6 +385,14 @@ static int launch_fwd_d(FwdArgs a, bool causal, hipStream_t st)
         default: return launch_fwd_nw<D, 1>(a, causal, st);
     }
 }
+
+#ifdef ATTN_CYCLES
+extern "C" void attn_debug_cycles_fwd(unsigned long long *out, int reset)
+{
+    hipMemcpyFromSymbol(out, HIP_SYMBOL(g_attn_cycles), sizeof(g_attn_cycles));
+    if (reset) { unsigned long long z[4][4] = {}; hipMemcpyToSymbol(HIP_SYMBOL(g_attn_cycles), z, sizeof(z)); }
+}
+#endif
 
 int launch_fwd(const FwdArgs &a, int D, bool causal, hipStream_t st)
 {
