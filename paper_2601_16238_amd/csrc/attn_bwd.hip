@@ -81,8 +81,8 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dkdv_kernel(const BwdArgs a)
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, r = l & 31, h = l >> 5;
     const int S = a.S;
     ATTN_CYCLES_BEGIN();
-    const int v = xcd_contiguous_order(blockIdx.x, a.ntile * a.BH);
-    const int bh = v / a.ntile, kt = v % a.ntile;  // causal: key block 0 is the heaviest
+    int bh, kt;  // causal: key block 0 is the heaviest
+    xcd_heavy_first(blockIdx.x, a.ntile, a.BH, bh, kt);
     const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
     const bf16 *Qp = a.Q + base, *Gp = a.dO + base;
     const float *Lp = a.LSE + (int64_t)bh * S, *Dp = a.delta + (int64_t)bh * S;
@@ -244,9 +244,9 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const BwdArgs a)
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, r = l & 31, h = l >> 5;
     const int S = a.S;
     ATTN_CYCLES_BEGIN();
-    const int v = xcd_contiguous_order(blockIdx.x, a.ntile * a.BH);
-    const int bh = v / a.ntile;
-    const int qt = CAUSAL ? a.ntile - 1 - (v % a.ntile) : v % a.ntile;  // heaviest first
+    int bh, rank;
+    xcd_heavy_first(blockIdx.x, a.ntile, a.BH, bh, rank);
+    const int qt = CAUSAL ? a.ntile - 1 - rank : rank;  // heaviest first
     const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
     const bf16 *Kp = a.K + base, *Vp = a.V + base;
 

@@ -132,4 +132,23 @@ __device__ __forceinline__ int xcd_contiguous_order(int id, int total)
     return start + pos;
 }
 
+// (head, tile rank) of a work-group for kernels whose tiles have unequal cost (causal):
+// rank 0 is meant to be the heaviest tile.  Each XCD owns BH/8 whole heads (K/V or Q/dO of a
+// head stay in one L2) and walks them rank-major -- all its heads' heaviest tiles first -- so
+// the long work-groups start first and the short ones fill the tail.  Falls back to the
+// contiguous order when the heads do not divide evenly over the XCDs.
+__device__ __forceinline__ void xcd_heavy_first(int id, int ntile, int BH, int &bh, int &rank)
+{
+    constexpr int kXcd = 8;
+    if (BH % kXcd == 0) {
+        const int hpx = BH / kXcd, x = id % kXcd, pos = id / kXcd;
+        rank = pos / hpx;
+        bh = x * hpx + pos % hpx;
+    } else {
+        const int v = xcd_contiguous_order(id, ntile * BH);
+        bh = v / ntile;
+        rank = v % ntile;
+    }
+}
+
 }  // namespace attn

@@ -68,9 +68,9 @@ attn_fwd_kernel(const FwdArgs a)
     ATTN_CYCLES_BEGIN();
 
     // (head, query tile) of this work-group; causal tiles are issued heaviest first.
-    const int v = xcd_contiguous_order(blockIdx.x, a.nqt * a.BH);
-    const int bh = v / a.nqt;
-    const int qt = CAUSAL ? a.nqt - 1 - (v % a.nqt) : v % a.nqt;
+    int bh, rank;
+    xcd_heavy_first(blockIdx.x, a.nqt, a.BH, bh, rank);
+    const int qt = CAUSAL ? a.nqt - 1 - rank : rank;
     const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
     const bf16 *Qp = a.Q + base, *Kp = a.K + base, *Vp = a.V + base;
 
