@@ -78,8 +78,9 @@ int attn_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
              const attn_params_t *p, void *hip_stream);
 
 /*
- * Bytes of device workspace attn_bwd needs for this problem (fp32 delta [B,H,S], rounded
- * up to 256 bytes).  Pure host function; returns 0 for an invalid problem.
+ * Bytes of device workspace attn_bwd needs for this problem: two fp32 values per query row
+ * ([B*H][2][S]: delta = rowsum(dO*O), and LSE rescaled to base 2), rounded up to 256 bytes.
+ * Pure host function; returns 0 for an invalid problem.
  */
 size_t attn_bwd_workspace_bytes(const attn_params_t *p);
 
@@ -93,7 +94,7 @@ size_t attn_bwd_workspace_bytes(const attn_params_t *p);
  *   workspace  : device scratch of at least attn_bwd_workspace_bytes(p) bytes, 256-byte
  *                aligned; contents undefined on entry and on exit (the library initialises
  *                everything it reads)
- * Enqueues three kernels on hip_stream: delta = rowsum(dO*O), dK/dV, dQ.
+ * Enqueues three kernels on hip_stream: row statistics (delta, rescaled LSE), dK/dV, dQ.
  */
 int attn_bwd(const void *Q, const void *K, const void *V, const void *O, const void *dO,
              const float *LSE, void *dQ, void *dK, void *dV,
@@ -104,7 +105,7 @@ int attn_bwd(const void *Q, const void *K, const void *V, const void *O, const v
  * Profiling aid: attn_bwd restricted to a subset of its three kernels, so that each can be
  * timed on its own with events on the caller's stream.  `stages` is a bit mask of
  * ATTN_BWD_STAGE_*; attn_bwd is attn_bwd_stages with all three bits.  The dK/dV and dQ
- * stages read delta from the workspace, so it must hold the delta stage's result of an
+ * stages read the row statistics from the workspace, so it must hold the delta stage's result of an
  * earlier call on the same problem.  Validation and errors as attn_bwd; stages == 0 or
  * unknown bits give ATTN_ERR_SHAPE.
  */

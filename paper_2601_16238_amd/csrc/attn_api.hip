@@ -71,7 +71,7 @@ size_t attn_bwd_workspace_bytes(const attn_params_t *p)
 {
     if (check_params(p) != ATTN_OK) return 0;
     const size_t rows = (size_t)p->B * p->H * p->S;
-    return (rows * sizeof(float) + kWsAlign - 1) / kWsAlign * kWsAlign;
+    return (2 * rows * sizeof(float) + kWsAlign - 1) / kWsAlign * kWsAlign;
 }
 
 int attn_bwd(const void *Q, const void *K, const void *V, const void *O, const void *dO,

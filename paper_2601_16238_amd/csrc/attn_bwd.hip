@@ -21,7 +21,9 @@
 namespace attn {
 
 // ---------------------------------------------------------------------------------------
-// 1. delta = rowsum(dO * O), fp32, contiguous [B,H,S].  D/8 lanes per row, 16-byte loads.
+// 1. Row statistics, fp32, workspace layout [B*H][2][S]: delta = rowsum(dO * O), then
+// lse2 = LSE * log2(e) (the main kernels run the softmax on exp2).  D/8 lanes per row,
+// 16-byte loads.
 // ---------------------------------------------------------------------------------------
 template <int D>
 __global__ void __launch_bounds__(256) attn_bwd_delta_kernel(const BwdArgs a)
@@ -43,7 +45,11 @@ __global__ void __launch_bounds__(256) attn_bwd_delta_kernel(const BwdArgs a)
     }
 #pragma unroll
     for (int s = LPR / 2; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
-    if (row < rows && sub == 0) a.delta[row] = acc;
+    if (row < rows && sub == 0) {
+        const int64_t bh = row / a.S, i = row % a.S;
+        a.delta[(2 * bh) * a.S + i] = acc;
+        a.delta[(2 * bh + 1) * a.S + i] = a.LSE[row] * kLog2e;
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -65,166 +71,268 @@ struct BwdCfg {
 };
 
 // ---------------------------------------------------------------------------------------
-// 2. dK, dV.  Work-group = NW waves, wave = 32 keys, loop over query tiles of 64 rows.
+// 2. dK, dV.  Work-group = 8 waves = 4 producer/consumer pairs sharing a SIMD each; a pair
+// owns 32 keys and the work-group streams the head's Q and dO rows through LDS in slots of
+// 32 rows.  The K/V fragments plus two 32 x D fp32 accumulators do not fit one wave's 256
+// registers, and a wave alternating between the exp-heavy and the accumulate-heavy half
+// cannot overlap them, so the halves go to different waves:
+//   producer (waves 0-3), slot t:   S = Q K^T, dP = dO V^T, P = exp2(c S - lse2),
+//                                   dS = P o (dP - delta); bf16 P and dS -> LDS exchange
+//   consumer (waves 4-7), slot t-1: dV^T += dO^T P, dK^T += Q^T dS   (transpose LDS reads)
+// Both issue 16 MFMAs per slot (D = 128); the producer's VALU work overlaps the consumer's
+// MFMAs on the shared SIMD.  One barrier per slot.
+//
+// Q/dO slots go global -> LDS directly, kAhead slots ahead, into a ring of kAhead + 2 slots
+// (the producer's, the consumer's, and those in flight); rows are stored unpadded with the
+// 16-byte chunk index XOR-swizzled by the row so that both the producer's row reads and the
+// consumer's transpose reads are bank-conflict free.
 // ---------------------------------------------------------------------------------------
-template <int D, int NW, bool CAUSAL>
-__global__ void __launch_bounds__(NW * 64) attn_bwd_dkdv_kernel(const BwdArgs a)
-{
-    using C = BwdCfg<D, NW>;
-    constexpr int KS = D / 16, DB = D / 32;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16 *Qs = reinterpret_cast<bf16 *>(smem);      // [2][64][kLd]
-    bf16 *Gs = Qs + 2 * C::kTileElems;              // [2][64][kLd]  (dO)
-    float *Ls = reinterpret_cast<float *>(Gs + 2 * C::kTileElems);  // [2][64] LSE*log2e
-    float *Ds = Ls + 2 * C::kTile;                                  // [2][64] delta
+template <int D>
+struct DkdvCfg {
+    static constexpr int kWaves = 8;
+    static constexpr int kThreads = kWaves * 64;
+    static constexpr int kPairs = 4;
+    static constexpr int kBlk = kPairs * 32;         // keys owned by the work-group
+    static constexpr int kRows = 32;                 // query rows per slot
+    static constexpr int kAhead = 3;                 // slots requested ahead of the producer
+    static constexpr int kRing = kAhead + 2;
+    static constexpr int kRowBytes = D * 2;
+    static constexpr int kTensorBytes = kRows * kRowBytes;   // Q part of a slot; dO follows
+    static constexpr int kSlotBytes = 2 * kTensorBytes;
+    static constexpr int kStatBytes = 2 * kRows * 4;         // lse2[32], delta[32]
+    static constexpr int kXchgBytes = 2 * kPairs * 4 * 1024; // [2][pair][P0,P1,dS0,dS1][64] x 16 B
+    static constexpr int kOffStat = kRing * kSlotBytes;
+    static constexpr int kOffXchg = kOffStat + kRing * kStatBytes;
+    static constexpr int kLdsBytes = kOffXchg + kXchgBytes;
+    static constexpr int kDmaPerTensor = kTensorBytes / 1024; // wave-wide 1 KB transfers
+    // Only the producers stream: the compiler makes every wave wait for all of its own
+    // outstanding transfers before a transpose read, which would stall the consumers.
+    static constexpr int kDmaPerWave = 2 * kDmaPerTensor / kPairs;
+    static constexpr int kStatWave = kPairs - 1;     // the producer that also fetches the stats
+    static_assert(kDmaPerTensor % kPairs == 0, "transfers divide evenly over the producers");
+    static_assert(kOffXchg % 16 == 0 && kLdsBytes <= 160 * 1024, "LDS layout");
+};
 
-    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, r = l & 31, h = l >> 5;
+// Wait until at most N of this wave's vector-memory operations are outstanding and all its
+// LDS operations are done, then join the work-group barrier.  Unlike __syncthreads this
+// leaves the newest global->LDS transfers in flight across the barrier.
+template <int N>
+__device__ __forceinline__ void wait_vm_and_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+template <int D, bool CAUSAL>
+__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2)))
+attn_bwd_dkdv_kernel(const BwdArgs a)
+{
+    using C = DkdvCfg<D>;
+    constexpr int KS = D / 16, DB = D / 32, CPR = D / 8, RB = C::kRowBytes;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int tid = threadIdx.x, l = tid & 63, r = l & 31, h = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool producer = w < C::kPairs;
+    const int pair = w & (C::kPairs - 1);
     const int S = a.S;
     ATTN_CYCLES_BEGIN();
     int bh, kt;  // causal: key block 0 is the heaviest
     xcd_heavy_first(blockIdx.x, a.ntile, a.BH, bh, kt);
     const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
-    const bf16 *Qp = a.Q + base, *Gp = a.dO + base;
-    const float *Lp = a.LSE + (int64_t)bh * S, *Dp = a.delta + (int64_t)bh * S;
 
-    const int k0 = kt * C::kBlk + w * 32;  // first key of this wave
+    const int k0 = kt * C::kBlk + pair * 32;  // first key of this pair
     const int key = k0 + r;
     const int keyc = key < S ? key : S - 1;
+    const int n_slot = (S + C::kRows - 1) / C::kRows;
+    const int t0 = CAUSAL ? kt * (C::kBlk / C::kRows) : 0;  // first slot with a visible row
 
-    // K and V fragments (B operands): lane holds K[key][16ks + 8h .. +7].
-    bf16x8 kf[KS], vf[KS];
+    // chunk position swizzle: rows 0..15 get 16 distinct values (row reads of 16 lanes hit 16
+    // different 16-byte bank groups) and 4 consecutive rows differ in the upper two bits (the
+    // 4 rows x 64 bytes of a transpose read spread over all banks)
+    auto swz = [](int row) {
+        return CPR == 16 ? (((row & 3) << 2) | ((row >> 2) & 3))
+                         : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+    };
+
+    // ---- global -> LDS streaming of slot t into ring position rs.  Rows past S-1 lie
+    // outside the head's buffer resource and read as zero.
+    const uint32_t head_bytes = (uint32_t)(((int64_t)(S - 1) * a.stride_s + D) * 2);
+    const rsrc_t Qr = make_rsrc(a.Q + base, head_bytes), Gr = make_rsrc(a.dO + base, head_bytes);
+    const rsrc_t Wr = make_rsrc(a.delta + (int64_t)bh * 2 * S, (uint32_t)S * 8u);
+    const uint32_t row_bytes = (uint32_t)a.stride_s * 2u;
+    uint32_t dma_voff[C::kDmaPerWave];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        kf[ks] = as_bf16x8(ld_global16(a.K + base + (int64_t)keyc * a.stride_s + ks * 16 + 8 * h));
-        vf[ks] = as_bf16x8(ld_global16(a.V + base + (int64_t)keyc * a.stride_s + ks * 16 + 8 * h));
+    for (int n = 0; n < C::kDmaPerWave; ++n) {
+        const int grp = pair + (n % (C::kDmaPerWave / 2)) * C::kPairs;
+        const int row = grp * (64 / CPR) + l / CPR;
+        dma_voff[n] = row * row_bytes + (((l % CPR) ^ swz(row)) << 4);
     }
-
-    const int n_qt = (S + C::kTile - 1) / C::kTile;
-    const int qt_begin = CAUSAL ? (kt * C::kBlk) / C::kTile : 0;
-
-    u32x4 qreg[C::kChunksPerThread], greg[C::kChunksPerThread];
-    float lreg = 0.f, dreg = 0.f;
-    auto prefetch = [&](int qt) {
+    // stats: lanes 0-31 fetch lse2 (second half of the head's workspace), 32-63 delta
+    const uint32_t stat_voff = (uint32_t)(h ? r : S + r) * 4u;
+    auto dma_slot = [&](int t, int rs) {
+        if (w == C::kStatWave)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                Wr, (void __attribute__((address_space(3))) *)(smem + C::kOffStat + rs * C::kStatBytes),
+                4, (int)stat_voff, t * C::kRows * 4, 0, 0);
 #pragma unroll
-        for (int n = 0; n < C::kChunksPerThread; ++n) {
-            const int c = tid + n * C::kThreads;
-            if (C::kChunks % C::kThreads == 0 || c < C::kChunks) {
-                const int row = c / (D / 8), col = (c % (D / 8)) * 8;
-                int qr = qt * C::kTile + row;
-                qr = qr < S ? qr : S - 1;
-                qreg[n] = ld_global16(Qp + (int64_t)qr * a.stride_s + col);
-                greg[n] = ld_global16(Gp + (int64_t)qr * a.stride_s + col);
-            }
-        }
-        if (tid < C::kTile) {
-            int qr = qt * C::kTile + tid;
-            qr = qr < S ? qr : S - 1;
-            lreg = Lp[qr] * kLog2e;
-            dreg = Dp[qr];
+        for (int n = 0; n < C::kDmaPerWave; ++n) {
+            const int tensor = n / (C::kDmaPerWave / 2);  // Q transfers first, then dO
+            const int grp = pair + (n % (C::kDmaPerWave / 2)) * C::kPairs;  // 1 KB piece
+            char *dst = smem + rs * C::kSlotBytes + tensor * C::kTensorBytes + grp * 1024;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                tensor == 0 ? Qr : Gr, (void __attribute__((address_space(3))) *)dst, 16,
+                (int)dma_voff[n], (int)(t * C::kRows * row_bytes), 0, 0);
         }
     };
-    auto commit = [&](int buf) {
-#pragma unroll
-        for (int n = 0; n < C::kChunksPerThread; ++n) {
-            const int c = tid + n * C::kThreads;
-            if (C::kChunks % C::kThreads == 0 || c < C::kChunks) {
-                const int row = c / (D / 8), col = (c % (D / 8)) * 8;
-                *(u32x4 *)(Qs + buf * C::kTileElems + row * C::kLd + col) = qreg[n];
-                *(u32x4 *)(Gs + buf * C::kTileElems + row * C::kLd + col) = greg[n];
-            }
-        }
-        if (tid < C::kTile) {
-            Ls[buf * C::kTile + tid] = lreg;
-            Ds[buf * C::kTile + tid] = dreg;
-        }
+    // Before slot t is used: this wave's transfers of slot t must have landed (those of the
+    // kAhead-1 newer slots may stay in flight) and everyone must be done with slot t-2.
+    auto slot_barrier = [&]() {
+        if (w == C::kStatWave) wait_vm_and_barrier<(C::kAhead - 1) * (C::kDmaPerWave + 1)>();
+        else wait_vm_and_barrier<(C::kAhead - 1) * C::kDmaPerWave>();
     };
+    // wave-uniform: does slot t hold a real row that sees some key of the pair
+    auto active = [&](int t) {
+        return t * C::kRows < S && (!CAUSAL || t * C::kRows + 31 >= k0);
+    };
+    auto ring_next = [](int x) { return x + 1 == C::kRing ? 0 : x + 1; };
 
-    f32x16 dv[DB], dk[DB];
+    if (producer)
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { dv[db][i] = 0.f; dk[db][i] = 0.f; }
+        for (int i = 0; i < C::kAhead; ++i) dma_slot(t0 + i, i);
 
-    const float c = a.scale_log2e;
-    const int tr_row = 4 * h + ((l & 15) >> 2);
-    const int tr_col = ((l >> 4) & 1) * 16 + (l & 3) * 4;
+    bf16x8 *const Xs = reinterpret_cast<bf16x8 *>(smem + C::kOffXchg) + pair * 256 + l;
 
-    if (qt_begin < n_qt) prefetch(qt_begin);
-    for (int qt = qt_begin; qt < n_qt; ++qt) {
-        const int buf = (qt - qt_begin) & 1;
-        commit(buf);
-        __syncthreads();
-        if (qt + 1 < n_qt) prefetch(qt + 1);
+    if (producer) {
+        // K and V fragments (B operands): lane holds K[key][16ks + 8h .. +7].
+        bf16x8 kf[KS], vf[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            kf[ks] = as_bf16x8(ld_global16(a.K + base + (int64_t)keyc * a.stride_s + ks * 16 + 8 * h));
+            vf[ks] = as_bf16x8(ld_global16(a.V + base + (int64_t)keyc * a.stride_s + ks * 16 + 8 * h));
+        }
+        // make sure no register load is counted among the streamed transfers any more
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const float c = a.scale_log2e;
+        const int lane_off = r * RB + ((h ^ swz(r)) << 4);  // chunk 2ks+h of row r: ^ (ks*32)
 
-        const bf16 *Qt = Qs + buf * C::kTileElems;
-        const bf16 *Gt = Gs + buf * C::kTileElems;
+        int rs = 0;  // ring position of slot t
+        for (int t = t0; t < n_slot; ++t) {
+            slot_barrier();
+            int rd = rs + C::kAhead;
+            rd = rd >= C::kRing ? rd - C::kRing : rd;
+            dma_slot(t + C::kAhead, rd);
+            if (active(t)) {
+                const char *Qt = smem + rs * C::kSlotBytes;
+                const float *st = reinterpret_cast<const float *>(smem + C::kOffStat + rs * C::kStatBytes);
+                const int q_lo = t * C::kRows;
+                f32x16 s, dp;
+                {
+                    f32x16 zero;
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const int q_lo = qt * C::kTile + qb * 32;
-            // wave-uniform: some row of the block is a real row that sees some key of the wave
-            const bool active = q_lo < S && (!CAUSAL || q_lo + 31 >= k0);
-            if (!active) continue;
-            f32x16 s, dp;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8 qa = *(const bf16x8 *)(Qt + (qb * 32 + r) * C::kLd + ks * 16 + 8 * h);
-                const bf16x8 ga = *(const bf16x8 *)(Gt + (qb * 32 + r) * C::kLd + ks * 16 + 8 * h);
-                s = mfma32(qa, kf[ks], s);
-                dp = mfma32(ga, vf[ks], dp);
-            }
-            // register i <-> query row q_lo + 8*(i/4) + 4h + i%4; this lane's key is fixed
-            const bool need_mask = (q_lo + 32 > S) || (CAUSAL && q_lo < k0 + 31);
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const f32x4 l4 = *(const f32x4 *)(Ls + buf * C::kTile + qb * 32 + 8 * g + 4 * h);
-                const f32x4 d4 = *(const f32x4 *)(Ds + buf * C::kTile + qb * 32 + 8 * g + 4 * h);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int i = 4 * g + e;
-                    float p = fast_exp2(__builtin_fmaf(s[i], c, -l4[e]));
-                    if (need_mask) {
-                        const int qi = q_lo + 8 * g + 4 * h + e;
-                        if (qi >= S || (CAUSAL && key > qi)) p = 0.f;
-                    }
-                    s[i] = p;
-                    dp[i] = p * (dp[i] - d4[e]);
+                    for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+                    s = mfma32(*(const bf16x8 *)(Qt + lane_off), kf[0], zero);
+                    dp = mfma32(*(const bf16x8 *)(Qt + C::kTensorBytes + lane_off), vf[0], zero);
                 }
+#pragma unroll
+                for (int ks = 1; ks < KS; ++ks) {
+                    const int off = lane_off ^ (ks * 32);
+                    s = mfma32(*(const bf16x8 *)(Qt + off), kf[ks], s);
+                    dp = mfma32(*(const bf16x8 *)(Qt + C::kTensorBytes + off), vf[ks], dp);
+                }
+                // register i <-> query row q_lo + 8*(i/4) + 4h + i%4; the lane's key is fixed
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 l4 = *(const f32x4 *)(st + 8 * g + 4 * h);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        s[4 * g + e] = fast_exp2(__builtin_fmaf(s[4 * g + e], c, -l4[e]));
+                }
+                if ((q_lo + 32 > S) || (CAUSAL && q_lo < k0 + 31)) {
+                    // visible row offsets: >= key - q_lo (causal) and <= S - 1 - q_lo
+                    const int lo = (CAUSAL ? key - q_lo : -64) - 4 * h;
+                    const int hi = S - 1 - q_lo - 4 * h;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int ro = 8 * (i / 4) + (i % 4);
+                        if (ro < lo || ro > hi) s[i] = 0.f;
+                    }
+                }
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 d4 = *(const f32x4 *)(st + 32 + 8 * g + 4 * h);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) dp[4 * g + e] = s[4 * g + e] * (dp[4 * g + e] - d4[e]);
+                }
+                bf16x8 *x = Xs + (t & 1) * (C::kPairs * 256);
+                x[0] = pack8(s[0], s[1], s[2], s[3], s[4], s[5], s[6], s[7]);
+                x[64] = pack8(s[8], s[9], s[10], s[11], s[12], s[13], s[14], s[15]);
+                x[128] = pack8(dp[0], dp[1], dp[2], dp[3], dp[4], dp[5], dp[6], dp[7]);
+                x[192] = pack8(dp[8], dp[9], dp[10], dp[11], dp[12], dp[13], dp[14], dp[15]);
             }
-            bf16x8 pb[2], sb[2];
-            pb[0] = pack8(s[0], s[1], s[2], s[3], s[4], s[5], s[6], s[7]);
-            pb[1] = pack8(s[8], s[9], s[10], s[11], s[12], s[13], s[14], s[15]);
-            sb[0] = pack8(dp[0], dp[1], dp[2], dp[3], dp[4], dp[5], dp[6], dp[7]);
-            sb[1] = pack8(dp[8], dp[9], dp[10], dp[11], dp[12], dp[13], dp[14], dp[15]);
+            rs = ring_next(rs);
+        }
+        wait_vm_and_barrier<0>();  // the consumers' last slot
+    } else {
+        f32x16 dv[DB], dk[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { dv[db][i] = 0.f; dk[db][i] = 0.f; }
+        // transpose-read addresses: the 16-lane group reads rows 4h+e (e = 0..3), +8 for the
+        // second read, 64 bytes of d block db per row; byte offset within a slot tensor
+        int tr_off[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int row = 8 * j + 4 * h + ((l & 15) >> 2);
+            const int chunk = 2 * ((l >> 4) & 1) + ((l >> 1) & 1);
+            tr_off[j] = row * RB + ((chunk ^ swz(row)) << 4) + (l & 1) * 8;
+        }
+        auto consume = [&](int t, int rs) {
+            const char *Qt = smem + rs * C::kSlotBytes;
+            const char *Gt = Qt + C::kTensorBytes;
+            const bf16x8 *x = Xs + (t & 1) * (C::kPairs * 256);
+            const bf16x8 pv[2] = {x[0], x[64]}, sv[2] = {x[128], x[192]};
 #pragma unroll
             for (int cc = 0; cc < 2; ++cc) {
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    const int off = (qb * 32 + 16 * cc + tr_row) * C::kLd + 32 * db + tr_col;
-                    const bf16x8 gT = join8(lds_read_tr(Gt + off), lds_read_tr(Gt + off + 8 * C::kLd));
-                    dv[db] = mfma32(gT, pb[cc], dv[db]);
-                    const bf16x8 qT = join8(lds_read_tr(Qt + off), lds_read_tr(Qt + off + 8 * C::kLd));
-                    dk[db] = mfma32(qT, sb[cc], dk[db]);
+                    // d block db = chunks 4db..4db+3: flips bits 6.. of the swizzled offset
+                    const int o0 = (tr_off[0] ^ (db << 6)) + cc * 16 * RB;
+                    const int o1 = (tr_off[1] ^ (db << 6)) + cc * 16 * RB;
+                    const bf16x8 gT = join8(lds_read_tr((const bf16 *)(Gt + o0)),
+                                            lds_read_tr((const bf16 *)(Gt + o1)));
+                    dv[db] = mfma32(gT, pv[cc], dv[db]);
+                    const bf16x8 qT = join8(lds_read_tr((const bf16 *)(Qt + o0)),
+                                            lds_read_tr((const bf16 *)(Qt + o1)));
+                    dk[db] = mfma32(qT, sv[cc], dk[db]);
                 }
             }
-        }
-    }
+        };
 
-    if (key < S) {
-        bf16 *dKp = a.dK + base + (int64_t)key * a.stride_s;
-        bf16 *dVp = a.dV + base + (int64_t)key * a.stride_s;
-        const float sc = a.scale;
+        int rs = 0;  // ring position of the producers' slot t; the consumers' is one behind
+        for (int t = t0; t < n_slot; ++t) {
+            wait_vm_and_barrier<0>();
+            if (t > t0 && active(t - 1)) consume(t - 1, rs == 0 ? C::kRing - 1 : rs - 1);
+            rs = ring_next(rs);
+        }
+        wait_vm_and_barrier<0>();
+        if (n_slot > t0 && active(n_slot - 1)) consume(n_slot - 1, rs == 0 ? C::kRing - 1 : rs - 1);
+
+        if (key < S) {
+            bf16 *dKp = a.dK + base + (int64_t)key * a.stride_s;
+            bf16 *dVp = a.dV + base + (int64_t)key * a.stride_s;
+            const float sc = a.scale;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int col = 32 * db + 8 * g + 4 * h;
-                *(bf16x4 *)(dVp + col) = pack4(dv[db][4 * g], dv[db][4 * g + 1],
-                                               dv[db][4 * g + 2], dv[db][4 * g + 3]);
-                *(bf16x4 *)(dKp + col) = pack4(dk[db][4 * g] * sc, dk[db][4 * g + 1] * sc,
-                                               dk[db][4 * g + 2] * sc, dk[db][4 * g + 3] * sc);
-            }
+                for (int g = 0; g < 4; ++g) {
+                    const int col = 32 * db + 8 * g + 4 * h;
+                    *(bf16x4 *)(dVp + col) = pack4(dv[db][4 * g], dv[db][4 * g + 1],
+                                                   dv[db][4 * g + 2], dv[db][4 * g + 3]);
+                    *(bf16x4 *)(dKp + col) = pack4(dk[db][4 * g] * sc, dk[db][4 * g + 1] * sc,
+                                                   dk[db][4 * g + 2] * sc, dk[db][4 * g + 3] * sc);
+                }
+        }
     }
     ATTN_CYCLES_END(1);
 }
@@ -261,7 +369,7 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const BwdArgs a)
         gf[ks] = as_bf16x8(ld_global16(a.dO + base + (int64_t)qc * a.stride_s + ks * 16 + 8 * h));
     }
     const float lse2 = a.LSE[(int64_t)bh * S + qc] * kLog2e;
-    const float delta = a.delta[(int64_t)bh * S + qc];
+    const float delta = a.delta[(int64_t)bh * 2 * S + qc];
 
     const int q_end = min(S, (qt + 1) * C::kBlk);
     const int n_kt = ((CAUSAL ? q_end : S) + C::kTile - 1) / C::kTile;
@@ -373,28 +481,43 @@ static void allow_lds(K kernel, int bytes)
     hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-template <int D, int NW, bool CAUSAL>
-static int launch_bwd_main(BwdArgs a, hipStream_t st, unsigned stages)
+template <int D, bool CAUSAL>
+static int launch_dkdv(BwdArgs a, hipStream_t st)
 {
-    using C = BwdCfg<D, NW>;
+    using C = DkdvCfg<D>;
     a.ntile = (a.S + C::kBlk - 1) / C::kBlk;
-    const dim3 grid(a.ntile * a.BH), block(C::kThreads);
-    if (stages & 2u) {
-        allow_lds(attn_bwd_dkdv_kernel<D, NW, CAUSAL>, C::kLdsBytes);
-        hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, NW, CAUSAL>), grid, block, C::kLdsBytes, st, a);
-    }
-    if (stages & 4u) {
-        allow_lds(attn_bwd_dq_kernel<D, NW, CAUSAL>, C::kLdsBytes);
-        hipLaunchKernelGGL((attn_bwd_dq_kernel<D, NW, CAUSAL>), grid, block, C::kLdsBytes, st, a);
-    }
+    allow_lds(attn_bwd_dkdv_kernel<D, CAUSAL>, C::kLdsBytes);
+    hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL>), dim3(a.ntile * a.BH),
+                       dim3(C::kThreads), C::kLdsBytes, st, a);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-template <int D, int NW>
-static int launch_bwd_nw(const BwdArgs &a, bool causal, hipStream_t st, unsigned stages)
+template <int D, int NW, bool CAUSAL>
+static int launch_dq(BwdArgs a, hipStream_t st)
 {
-    return causal ? launch_bwd_main<D, NW, true>(a, st, stages)
-                  : launch_bwd_main<D, NW, false>(a, st, stages);
+    using C = BwdCfg<D, NW>;
+    a.ntile = (a.S + C::kBlk - 1) / C::kBlk;
+    allow_lds(attn_bwd_dq_kernel<D, NW, CAUSAL>, C::kLdsBytes);
+    hipLaunchKernelGGL((attn_bwd_dq_kernel<D, NW, CAUSAL>), dim3(a.ntile * a.BH),
+                       dim3(C::kThreads), C::kLdsBytes, st, a);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+template <int D, bool CAUSAL>
+static int launch_bwd_dc(const BwdArgs &a, hipStream_t st, unsigned stages)
+{
+    const int blocks32 = (a.S + 31) / 32;
+    if (stages & 2u) {
+        if (launch_dkdv<D, CAUSAL>(a, st)) return -1;
+    }
+    if (stages & 4u) {
+        if (blocks32 >= 8) return launch_dq<D, 8, CAUSAL>(a, st);
+        if (blocks32 >= 4) return launch_dq<D, 4, CAUSAL>(a, st);
+        if (blocks32 == 3) return launch_dq<D, 3, CAUSAL>(a, st);
+        if (blocks32 == 2) return launch_dq<D, 2, CAUSAL>(a, st);
+        return launch_dq<D, 1, CAUSAL>(a, st);
+    }
+    return 0;
 }
 
 template <int D>
@@ -408,12 +531,7 @@ static int launch_bwd_d(const BwdArgs &a, bool causal, hipStream_t st, unsigned 
         if (hipGetLastError() != hipSuccess) return -1;
     }
     if (!(stages & 6u)) return 0;
-    const int blocks32 = (a.S + 31) / 32;
-    if (blocks32 >= 8) return launch_bwd_nw<D, 8>(a, causal, st, stages);
-    if (blocks32 >= 4) return launch_bwd_nw<D, 4>(a, causal, st, stages);
-    if (blocks32 == 3) return launch_bwd_nw<D, 3>(a, causal, st, stages);
-    if (blocks32 == 2) return launch_bwd_nw<D, 2>(a, causal, st, stages);
-    return launch_bwd_nw<D, 1>(a, causal, st, stages);
+    return causal ? launch_bwd_dc<D, true>(a, st, stages) : launch_bwd_dc<D, false>(a, st, stages);
 }
 
 #ifdef ATTN_CYCLES

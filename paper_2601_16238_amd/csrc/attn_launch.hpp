@@ -22,7 +22,7 @@ struct FwdArgs {
 struct BwdArgs {
     const bf16 *Q, *K, *V, *O, *dO;
     const float *LSE;
-    float *delta;       // workspace [B,H,S]
+    float *delta;       // workspace [B*H][2][S]: delta, then LSE * log2(e)
     bf16 *dQ, *dK, *dV;
     int64_t stride_b, stride_h, stride_s;
     int S, H, BH;

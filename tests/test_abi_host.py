@@ -41,7 +41,7 @@ def test_version_and_status_strings():
 def test_params_contiguous_and_workspace_size():
     p = attn.make_params(4, 32, 4096, 128, 0.0883, True)
     assert (p.stride_s, p.stride_h, p.stride_b) == (128, 4096 * 128, 32 * 4096 * 128)
-    assert attn.attn_bwd_workspace_bytes(4, 32, 4096, 128) == 4 * 32 * 4096 * 4
+    assert attn.attn_bwd_workspace_bytes(4, 32, 4096, 128) == 2 * 4 * 32 * 4096 * 4
     assert attn.attn_bwd_workspace_bytes(1, 1, 1, 64) == 256          # rounded up
     assert attn.attn_bwd_workspace_bytes(1, 1, 1, 96) == 0            # invalid D
 
