@@ -33,6 +33,23 @@ def test_fwd_small(B, H, S, D, causal):
     check_lse(to_f64(LSE), Lref)
 
 
+# Sequence lengths around the tile sizes: 32-key sub-tiles, 64-key tiles, 256-query blocks.
+SWEEP_S = [2, 32, 34, 63, 64, 95, 127, 129, 160, 161, 192, 255, 256, 259, 383, 385, 641]
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("causal", [False, True])
+def test_fwd_length_sweep(D, causal):
+    for S in SWEEP_S:
+        print("case fwd_length_sweep", S, D, causal, flush=True)
+        x = wl.random_inputs(1, 2, S, D, seed=600 + S)
+        Oref, Lref = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], causal)
+        O, LSE = attn.attn_fwd(to_dev(x["Q"]), to_dev(x["K"]), to_dev(x["V"]), x["scale"], causal)
+        torch.cuda.synchronize()
+        check_bf16("S=%d O" % S, to_f64(O), Oref)
+        check_lse(to_f64(LSE), Lref)
+
+
 @pytest.mark.parametrize("name", ["tiny", "vit_cifar", "minigpt"])
 def test_fwd_workload_full(name):
     print("case fwd_workload_full", name, flush=True)
