@@ -21,6 +21,12 @@
  *   dS_ij = P_ij (dP_ij - delta_i)
  *   dQ_id = scale sum_j dS_ij K_jd ;   dK_jd = scale sum_i dS_ij Q_id
  *
+ * Grouped-query form (the paper's benchmark shape is written (B,Hq,Hkv,S,D) and its
+ * kernel-suite discussion is about grouped-query prefill): Q, O, dO, dQ have Hq heads, K, V,
+ * dK, dV have Hkv heads, Hq = G*Hkv; query head h reads K/V head h / G, and dK, dV of a K/V
+ * head are the sums of the formulas above over the G query heads that read it.  Hkv = Hq is
+ * plain multi-head attention.
+ *
  * Inputs are bf16 bit patterns (uint16) laid out contiguously as [B,H,S,D]; they are
  * widened exactly to double.  `scale` is the fp32 value the GPU receives, widened to
  * double.  All arithmetic is double; exp/log are libm's.  There is no tiling, no online
@@ -86,14 +92,15 @@ static inline int thread_id(void)
  * explicit zeros outside allowed(i) -- for small test shapes only.
  * Returns 0, or -1 on allocation failure / bad shape.
  */
-int oracle_attn_fwd(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
-                    int B, int H, int S, int D, float scale_f32, int causal,
-                    double *O, double *LSE, double *P_out)
+int oracle_attn_fwd_gqa(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
+                        int B, int H, int Hkv, int S, int D, float scale_f32, int causal,
+                        double *O, double *LSE, double *P_out)
 {
-    if (B < 1 || H < 1 || S < 1 || D < 1) return -1;
-    const size_t BH = (size_t)B * H, n = BH * S * D;
+    if (B < 1 || H < 1 || Hkv < 1 || H % Hkv != 0 || S < 1 || D < 1) return -1;
+    const int G = H / Hkv; /* query heads per K/V head */
+    const size_t BH = (size_t)B * H, n = BH * S * D, nkv = (size_t)B * Hkv * S * D;
     const double scale = (double)scale_f32;
-    double *Q = widen(Qb, n), *K = widen(Kb, n), *V = widen(Vb, n);
+    double *Q = widen(Qb, n), *K = widen(Kb, nkv), *V = widen(Vb, nkv);
     const int nt = oracle_num_threads();
     double *scratch = (double *)malloc((size_t)nt * S * sizeof(double)); /* one row per thread */
     const int fail = (!Q || !K || !V || !scratch);
@@ -107,7 +114,8 @@ int oracle_attn_fwd(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
                     const size_t bh = (size_t)r / S;
                     const int i = (int)((size_t)r % S);
                     const double *q = Q + (bh * S + i) * D;
-                    const double *Kh = K + bh * S * D, *Vh = V + bh * S * D;
+                    const size_t bkv = (bh / H) * Hkv + (bh % H) / G; /* K/V head of this row */
+                    const double *Kh = K + bkv * S * D, *Vh = V + bkv * S * D;
                     const int na = n_allowed(i, S, causal);
                     double m = -INFINITY;
                     for (int j = 0; j < na; ++j) {
@@ -137,21 +145,31 @@ int oracle_attn_fwd(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
     return fail ? -1 : 0;
 }
 
+int oracle_attn_fwd(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
+                    int B, int H, int S, int D, float scale_f32, int causal,
+                    double *O, double *LSE, double *P_out)
+{
+    return oracle_attn_fwd_gqa(Qb, Kb, Vb, B, H, H, S, D, scale_f32, causal, O, LSE, P_out);
+}
+
 /*
  * Backward.  Recomputes LSE and P in fp64 from Q,K (it never sees the GPU's O or LSE).
  * dQ,dK,dV: [B,H,S,D] double.  dS_out (optional): [B,H,S,S] double, for small shapes.
  * Pass 1 (row-wise):    LSE_i, delta_i, dQ_i.
- * Pass 2 (column-wise): dK_j, dV_j from P_ij and dS_ij recomputed for column j.
+ * Pass 2 (column-wise): dK_j, dV_j from P_ij and dS_ij recomputed for column j, summed over
+ *                       the query heads of the group in head order.
+ * dQ: [B,H,S,D]; dK,dV: [B,Hkv,S,D].
  */
-int oracle_attn_bwd(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
-                    const uint16_t *dOb,
-                    int B, int H, int S, int D, float scale_f32, int causal,
-                    double *dQ, double *dK, double *dV, double *dS_out)
+int oracle_attn_bwd_gqa(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
+                        const uint16_t *dOb,
+                        int B, int H, int Hkv, int S, int D, float scale_f32, int causal,
+                        double *dQ, double *dK, double *dV, double *dS_out)
 {
-    if (B < 1 || H < 1 || S < 1 || D < 1) return -1;
-    const size_t BH = (size_t)B * H, n = BH * S * D;
+    if (B < 1 || H < 1 || Hkv < 1 || H % Hkv != 0 || S < 1 || D < 1) return -1;
+    const int G = H / Hkv;
+    const size_t BH = (size_t)B * H, n = BH * S * D, BHkv = (size_t)B * Hkv, nkv = BHkv * S * D;
     const double scale = (double)scale_f32;
-    double *Q = widen(Qb, n), *K = widen(Kb, n), *V = widen(Vb, n), *dO = widen(dOb, n);
+    double *Q = widen(Qb, n), *K = widen(Kb, nkv), *V = widen(Vb, nkv), *dO = widen(dOb, n);
     double *LSE = (double *)malloc(BH * S * sizeof(double));
     double *delta = (double *)malloc(BH * S * sizeof(double));
     const int nt = oracle_num_threads();
@@ -170,7 +188,8 @@ int oracle_attn_bwd(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
                     const int i = (int)((size_t)r % S);
                     const double *q = Q + (bh * S + i) * D;
                     const double *g = dO + (bh * S + i) * D;
-                    const double *Kh = K + bh * S * D, *Vh = V + bh * S * D;
+                    const size_t bkv = (bh / H) * Hkv + (bh % H) / G;
+                    const double *Kh = K + bkv * S * D, *Vh = V + bkv * S * D;
                     const int na = n_allowed(i, S, causal);
                     double m = -INFINITY;
                     for (int j = 0; j < na; ++j) {
@@ -207,22 +226,25 @@ int oracle_attn_bwd(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
                 }
                 /* pass 2: one key column at a time (implicit barrier above) */
 #pragma omp for schedule(dynamic, 16)
-                for (long long r = 0; r < (long long)(BH * S); ++r) {
-                    const size_t bh = (size_t)r / S;
+                for (long long r = 0; r < (long long)(BHkv * S); ++r) {
+                    const size_t bkv = (size_t)r / S;
                     const int j = (int)((size_t)r % S);
-                    const double *k = K + (bh * S + j) * D;
-                    const double *v = V + (bh * S + j) * D;
-                    const double *Qh = Q + bh * S * D, *Gh = dO + bh * S * D;
-                    double *dk = dK + (bh * S + j) * D, *dv = dV + (bh * S + j) * D;
+                    const double *k = K + (bkv * S + j) * D;
+                    const double *v = V + (bkv * S + j) * D;
+                    double *dk = dK + (bkv * S + j) * D, *dv = dV + (bkv * S + j) * D;
                     for (int d = 0; d < D; ++d) { dk[d] = 0.0; dv[d] = 0.0; }
                     const int i0 = causal ? j : 0; /* rows i with j in allowed(i) */
-                    for (int i = i0; i < S; ++i) {
-                        const double *q = Qh + (size_t)i * D, *g = Gh + (size_t)i * D;
-                        double acc = 0.0, dp = 0.0;
-                        for (int d = 0; d < D; ++d) { acc += q[d] * k[d]; dp += g[d] * v[d]; }
-                        const double p = exp(scale * acc - LSE[bh * S + i]);
-                        const double dsij = p * (dp - delta[bh * S + i]);
-                        for (int d = 0; d < D; ++d) { dv[d] += p * g[d]; dk[d] += dsij * q[d]; }
+                    for (int gq = 0; gq < G; ++gq) { /* the query heads that read this K/V head */
+                        const size_t bh = (bkv / Hkv) * H + (bkv % Hkv) * G + gq;
+                        const double *Qh = Q + bh * S * D, *Gh = dO + bh * S * D;
+                        for (int i = i0; i < S; ++i) {
+                            const double *q = Qh + (size_t)i * D, *g = Gh + (size_t)i * D;
+                            double acc = 0.0, dp = 0.0;
+                            for (int d = 0; d < D; ++d) { acc += q[d] * k[d]; dp += g[d] * v[d]; }
+                            const double p = exp(scale * acc - LSE[bh * S + i]);
+                            const double dsij = p * (dp - delta[bh * S + i]);
+                            for (int d = 0; d < D; ++d) { dv[d] += p * g[d]; dk[d] += dsij * q[d]; }
+                        }
                     }
                     for (int d = 0; d < D; ++d) dk[d] *= scale;
                 }
@@ -231,4 +253,12 @@ int oracle_attn_bwd(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
     }
     free(Q); free(K); free(V); free(dO); free(LSE); free(delta); free(scratch);
     return fail ? -1 : 0;
+}
+
+int oracle_attn_bwd(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
+                    const uint16_t *dOb,
+                    int B, int H, int S, int D, float scale_f32, int causal,
+                    double *dQ, double *dK, double *dV, double *dS_out)
+{
+    return oracle_attn_bwd_gqa(Qb, Kb, Vb, dOb, B, H, H, S, D, scale_f32, causal, dQ, dK, dV, dS_out);
 }

@@ -36,12 +36,12 @@ def _load():
         u16p = ctypes.POINTER(ctypes.c_uint16)
         f64p = ctypes.POINTER(ctypes.c_double)
         i = ctypes.c_int
-        lib.oracle_attn_fwd.argtypes = [u16p, u16p, u16p, i, i, i, i, ctypes.c_float, i,
-                                        f64p, f64p, f64p]
-        lib.oracle_attn_fwd.restype = i
-        lib.oracle_attn_bwd.argtypes = [u16p, u16p, u16p, u16p, i, i, i, i, ctypes.c_float, i,
-                                        f64p, f64p, f64p, f64p]
-        lib.oracle_attn_bwd.restype = i
+        lib.oracle_attn_fwd_gqa.argtypes = [u16p, u16p, u16p, i, i, i, i, i, ctypes.c_float, i,
+                                            f64p, f64p, f64p]
+        lib.oracle_attn_fwd_gqa.restype = i
+        lib.oracle_attn_bwd_gqa.argtypes = [u16p, u16p, u16p, u16p, i, i, i, i, i, ctypes.c_float,
+                                            i, f64p, f64p, f64p, f64p]
+        lib.oracle_attn_bwd_gqa.restype = i
         lib.oracle_num_threads.argtypes = []
         lib.oracle_num_threads.restype = i
         _lib = lib
@@ -62,22 +62,33 @@ def _u16(x, shape=None):
     return x
 
 
+def _kv(x, qshape):
+    """K or V: [B,Hkv,S,D] with Hkv dividing the query head count (Hkv = H: multi-head)."""
+    x = _u16(x)
+    B, H, S, D = qshape
+    if x.shape[0] != B or x.shape[2] != S or x.shape[3] != D or x.shape[1] < 1 or H % x.shape[1]:
+        raise ValueError("K/V must be [B,Hkv,S,D] with Hkv dividing H")
+    return x
+
+
 def _p(a, ct):
     return a.ctypes.data_as(ctypes.POINTER(ct)) if a is not None else None
 
 
 def attn_fwd(Q, K, V, scale, causal, want_probs=False):
-    """O [B,H,S,D] f64, LSE [B,H,S] f64 (natural log) [, P [B,H,S,S] f64]."""
-    Q = _u16(Q); K = _u16(K, Q.shape); V = _u16(V, Q.shape)
+    """O [B,H,S,D] f64, LSE [B,H,S] f64 (natural log) [, P [B,H,S,S] f64].
+    K, V: [B,Hkv,S,D]; query head h reads K/V head h // (H // Hkv)."""
+    Q = _u16(Q); K = _kv(K, Q.shape); V = _u16(V, K.shape)
     B, H, S, D = Q.shape
+    Hkv = K.shape[1]
     O = np.empty((B, H, S, D), np.float64)
     LSE = np.empty((B, H, S), np.float64)
     P = np.empty((B, H, S, S), np.float64) if want_probs else None
-    rc = _load().oracle_attn_fwd(_p(Q, ctypes.c_uint16), _p(K, ctypes.c_uint16),
-                                 _p(V, ctypes.c_uint16), B, H, S, D,
-                                 ctypes.c_float(np.float32(scale)), int(bool(causal)),
-                                 _p(O, ctypes.c_double), _p(LSE, ctypes.c_double),
-                                 _p(P, ctypes.c_double))
+    rc = _load().oracle_attn_fwd_gqa(_p(Q, ctypes.c_uint16), _p(K, ctypes.c_uint16),
+                                     _p(V, ctypes.c_uint16), B, H, Hkv, S, D,
+                                     ctypes.c_float(np.float32(scale)), int(bool(causal)),
+                                     _p(O, ctypes.c_double), _p(LSE, ctypes.c_double),
+                                     _p(P, ctypes.c_double))
     if rc != 0:
         raise RuntimeError("oracle_attn_fwd failed (rc=%d)" % rc)
     return (O, LSE, P) if want_probs else (O, LSE)
@@ -89,19 +100,20 @@ def attn_probs(Q, K, V, scale, causal):
 
 
 def attn_bwd(Q, K, V, dO, scale, causal, want_dscores=False):
-    """dQ, dK, dV [B,H,S,D] f64 [, dS [B,H,S,S] f64] for upstream gradient dO on O."""
-    Q = _u16(Q); K = _u16(K, Q.shape); V = _u16(V, Q.shape); dO = _u16(dO, Q.shape)
+    """dQ [B,H,S,D], dK, dV [B,Hkv,S,D] f64 [, dS [B,H,S,S] f64] for upstream gradient dO on O."""
+    Q = _u16(Q); K = _kv(K, Q.shape); V = _u16(V, K.shape); dO = _u16(dO, Q.shape)
     B, H, S, D = Q.shape
+    Hkv = K.shape[1]
     dQ = np.empty((B, H, S, D), np.float64)
-    dK = np.empty_like(dQ)
-    dV = np.empty_like(dQ)
+    dK = np.empty((B, Hkv, S, D), np.float64)
+    dV = np.empty_like(dK)
     dS = np.empty((B, H, S, S), np.float64) if want_dscores else None
-    rc = _load().oracle_attn_bwd(_p(Q, ctypes.c_uint16), _p(K, ctypes.c_uint16),
-                                 _p(V, ctypes.c_uint16), _p(dO, ctypes.c_uint16),
-                                 B, H, S, D, ctypes.c_float(np.float32(scale)),
-                                 int(bool(causal)), _p(dQ, ctypes.c_double),
-                                 _p(dK, ctypes.c_double), _p(dV, ctypes.c_double),
-                                 _p(dS, ctypes.c_double))
+    rc = _load().oracle_attn_bwd_gqa(_p(Q, ctypes.c_uint16), _p(K, ctypes.c_uint16),
+                                     _p(V, ctypes.c_uint16), _p(dO, ctypes.c_uint16),
+                                     B, H, Hkv, S, D, ctypes.c_float(np.float32(scale)),
+                                     int(bool(causal)), _p(dQ, ctypes.c_double),
+                                     _p(dK, ctypes.c_double), _p(dV, ctypes.c_double),
+                                     _p(dS, ctypes.c_double))
     if rc != 0:
         raise RuntimeError("oracle_attn_bwd failed (rc=%d)" % rc)
     return (dQ, dK, dV, dS) if want_dscores else (dQ, dK, dV)

@@ -242,3 +242,77 @@ def test_stability_with_large_scores():
     assert np.isfinite(O).all() and np.isfinite(LSE).all() and LSE.max() > 300
     s = torch.tensor(f64(x["Q"])[0, 0] @ f64(x["K"])[0, 0].T)
     np.testing.assert_allclose(LSE[0, 0], torch.logsumexp(s, -1).numpy(), rtol=1e-14, atol=1e-11)
+
+
+# ---- grouped-query heads (the paper's benchmark shape is written (B,Hq,Hkv,S,D)) ----------
+# K/V head of query head h is h // (Hq // Hkv); dK, dV of a K/V head sum over its group.
+
+def gqa_inputs(B, Hq, Hkv, S, D, seed):
+    x = rnd(B, Hq, S, D, seed)
+    kv = rnd(B, Hkv, S, D, seed + 1000)
+    x["K"], x["V"] = kv["K"], kv["V"]
+    return x
+
+
+GQA_CASES = [(1, 4, 2, 33, 16, False), (2, 6, 2, 20, 8, True), (1, 8, 1, 17, 16, True),
+             (1, 4, 1, 65, 64, False), (1, 3, 3, 9, 8, True)]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,S,D,causal", GQA_CASES)
+def test_gqa_equals_multihead_on_repeated_kv(B, Hq, Hkv, S, D, causal):
+    """Reduction to the multi-head case pinned above: repeating every K/V head G times gives
+    the same O, LSE and dQ, and the K/V gradients are the sums over each group."""
+    x = gqa_inputs(B, Hq, Hkv, S, D, seed=40 + S)
+    G = Hq // Hkv
+    Kr, Vr = np.repeat(x["K"], G, axis=1), np.repeat(x["V"], G, axis=1)
+    O, LSE = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], causal)
+    dQ, dK, dV = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], causal)
+    Om, Lm = oracle.attn_fwd(x["Q"], Kr, Vr, x["scale"], causal)
+    dQm, dKm, dVm = oracle.attn_bwd(x["Q"], Kr, Vr, x["dO"], x["scale"], causal)
+    assert dK.shape == (B, Hkv, S, D) and dV.shape == (B, Hkv, S, D)
+    np.testing.assert_allclose(O, Om, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(LSE, Lm, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(dQ, dQm, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(dK, dKm.reshape(B, Hkv, G, S, D).sum(2), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dV, dVm.reshape(B, Hkv, G, S, D).sum(2), rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,S,D,causal", GQA_CASES[:3])
+def test_gqa_against_torch_fp64_autograd(B, Hq, Hkv, S, D, causal):
+    """Independent library route: repeat_interleave of the K/V heads inside the autograd graph,
+    so torch itself sums the group's gradients."""
+    x = gqa_inputs(B, Hq, Hkv, S, D, seed=50 + S)
+    G = Hq // Hkv
+    t = {k: torch.tensor(f64(x[k]), dtype=torch.float64, requires_grad=(k != "dO"))
+         for k in ("Q", "K", "V", "dO")}
+    Kt, Vt = t["K"].repeat_interleave(G, dim=1), t["V"].repeat_interleave(G, dim=1)
+    s = (t["Q"] @ Kt.transpose(-1, -2)) * float(np.float32(x["scale"]))
+    if causal:
+        s = s.masked_fill(~torch.ones(S, S, dtype=torch.bool).tril(), float("-inf"))
+    o_t = torch.softmax(s, dim=-1) @ Vt
+    gq, gk, gv = torch.autograd.grad(o_t, (t["Q"], t["K"], t["V"]), grad_outputs=t["dO"])
+    O, LSE = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], causal)
+    dQ, dK, dV = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], causal)
+    np.testing.assert_allclose(O, o_t.detach().numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(LSE, torch.logsumexp(s, dim=-1).detach().numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dQ, gq.numpy(), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(dK, gk.numpy(), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(dV, gv.numpy(), rtol=0, atol=1e-11)
+
+
+def test_gqa_head_mapping_is_blocked_not_interleaved():
+    """Query heads 0..G-1 read K/V head 0, G..2G-1 read head 1, ...: with V constant per K/V
+    head, O of a query head equals the constant of head h // G (and not h % Hkv)."""
+    B, Hq, Hkv, S, D = 1, 6, 3, 11, 8
+    x = gqa_inputs(B, Hq, Hkv, S, D, seed=61)
+    consts = np.array([1.0, -2.0, 0.5])
+    V = bits(np.broadcast_to(consts[None, :, None, None], (B, Hkv, S, D)).copy())
+    O, _ = oracle.attn_fwd(x["Q"], x["K"], V, x["scale"], False)
+    for h in range(Hq):
+        np.testing.assert_allclose(O[0, h], consts[h // (Hq // Hkv)], rtol=0, atol=1e-13)
+
+
+def test_gqa_rejects_non_dividing_head_counts():
+    x = gqa_inputs(1, 4, 3, 5, 8, seed=62)
+    with pytest.raises(ValueError):
+        oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], False)
