@@ -44,7 +44,8 @@ extern "C" {
 typedef enum {
     ATTN_OK = 0,
     ATTN_ERR_NULL = -1,      /* a required pointer is NULL                                  */
-    ATTN_ERR_SHAPE = -2,     /* B,H,S < 1, D not in {64,128}, or a size overflows int32      */
+    ATTN_ERR_SHAPE = -2,     /* B,H,S < 1, D not in {64,128}, Hkv not dividing Hq, or a size
+                                overflows int32                                             */
     ATTN_ERR_STRIDE = -3,    /* a stride is < its minimum, not a multiple of 8 elements, or
                                 (S + 512) * stride_s * 2 bytes does not fit in 32 bits        */
     ATTN_ERR_ALIGN = -4,     /* a tensor pointer is not 16-byte aligned (LSE: 4-byte)        */
@@ -116,6 +117,47 @@ int attn_bwd_stages(const void *Q, const void *K, const void *V, const void *O, 
                     const float *LSE, void *dQ, void *dK, void *dV,
                     void *workspace, size_t workspace_bytes,
                     const attn_params_t *p, void *hip_stream, uint32_t stages);
+
+/*
+ * Grouped-query variant (paper: the microbenchmark table writes the attention shape as
+ * (B,Hq,Hkv,S,D) and the kernel-suite discussion is about grouped-query prefill).  Q, O, dO,
+ * dQ have Hq heads and share the q_* strides; K, V, dK, dV have Hkv heads and share the kv_*
+ * strides; Hq must be a multiple of Hkv and query head h reads K/V head h / (Hq/Hkv).  dK and
+ * dV of a K/V head are summed over the Hq/Hkv query heads that read it, inside the kernel
+ * (no atomics, deterministic).  LSE and the workspace are per QUERY head: LSE is [B,Hq,S].
+ * Hkv == Hq is ordinary multi-head attention: attn_fwd / attn_bwd are exactly these calls
+ * with both stride sets equal.  Everything else (pointers, alignment, ownership, errors,
+ * stream semantics) is as for attn_fwd / attn_bwd; a head count that does not divide gives
+ * ATTN_ERR_SHAPE, the stride rules apply to both stride sets.
+ */
+typedef struct {
+    int32_t B, Hq, Hkv, S, D;
+    int64_t q_stride_b, q_stride_h, q_stride_s;     /* Q, O, dO, dQ: element strides, D contiguous */
+    int64_t kv_stride_b, kv_stride_h, kv_stride_s;  /* K, V, dK, dV                               */
+    float scale;
+    int32_t causal;
+} attn_gqa_params_t;
+
+/* Fill strides for contiguous [B,Hq,S,D] and [B,Hkv,S,D] tensors.  Pure host function. */
+void attn_gqa_params_contiguous(attn_gqa_params_t *p, int32_t B, int32_t Hq, int32_t Hkv,
+                                int32_t S, int32_t D, float scale, int32_t causal);
+
+int attn_fwd_gqa(const void *Q, const void *K, const void *V, void *O, float *LSE,
+                 const attn_gqa_params_t *p, void *hip_stream);
+
+/* Two fp32 values per QUERY row ([B*Hq][2][S]), rounded up to 256 bytes; 0 if invalid. */
+size_t attn_bwd_gqa_workspace_bytes(const attn_gqa_params_t *p);
+
+int attn_bwd_gqa(const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                 const float *LSE, void *dQ, void *dK, void *dV,
+                 void *workspace, size_t workspace_bytes,
+                 const attn_gqa_params_t *p, void *hip_stream);
+
+/* Profiling aid, as attn_bwd_stages. */
+int attn_bwd_gqa_stages(const void *Q, const void *K, const void *V, const void *O,
+                        const void *dO, const float *LSE, void *dQ, void *dK, void *dV,
+                        void *workspace, size_t workspace_bytes,
+                        const attn_gqa_params_t *p, void *hip_stream, uint32_t stages);
 
 /* Static, NUL-terminated description of a status code.  Never NULL. */
 const char *attn_status_string(int status);

@@ -21,7 +21,9 @@ ATTN_ERR_SCALE = -6
 ATTN_ERR_LAUNCH = -7
 
 EXPORTS = ("attn_params_contiguous", "attn_fwd", "attn_bwd_workspace_bytes", "attn_bwd",
-           "attn_bwd_stages", "attn_status_string", "attn_version")
+           "attn_bwd_stages", "attn_gqa_params_contiguous", "attn_fwd_gqa",
+           "attn_bwd_gqa_workspace_bytes", "attn_bwd_gqa", "attn_bwd_gqa_stages",
+           "attn_status_string", "attn_version")
 STAGE_DELTA, STAGE_DKDV, STAGE_DQ = 1, 2, 4
 STAGE_ALL = 7
 
@@ -31,6 +33,16 @@ class AttnParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("S", ctypes.c_int32),
                 ("D", ctypes.c_int32), ("stride_b", ctypes.c_int64),
                 ("stride_h", ctypes.c_int64), ("stride_s", ctypes.c_int64),
+                ("scale", ctypes.c_float), ("causal", ctypes.c_int32)]
+
+
+class AttnGqaParams(ctypes.Structure):
+    """Mirror of attn_gqa_params_t."""
+    _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("S", ctypes.c_int32), ("D", ctypes.c_int32),
+                ("q_stride_b", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
+                ("q_stride_s", ctypes.c_int64), ("kv_stride_b", ctypes.c_int64),
+                ("kv_stride_h", ctypes.c_int64), ("kv_stride_s", ctypes.c_int64),
                 ("scale", ctypes.c_float), ("causal", ctypes.c_int32)]
 
 
@@ -65,6 +77,18 @@ def lib():
         L.attn_bwd.restype = ctypes.c_int
         L.attn_bwd_stages.argtypes = [vp] * 9 + [vp, ctypes.c_size_t, pp, vp, ctypes.c_uint32]
         L.attn_bwd_stages.restype = ctypes.c_int
+        gp = ctypes.POINTER(AttnGqaParams)
+        L.attn_gqa_params_contiguous.argtypes = [gp] + [ctypes.c_int32] * 5 + [ctypes.c_float,
+                                                                               ctypes.c_int32]
+        L.attn_gqa_params_contiguous.restype = None
+        L.attn_fwd_gqa.argtypes = [vp, vp, vp, vp, vp, gp, vp]
+        L.attn_fwd_gqa.restype = ctypes.c_int
+        L.attn_bwd_gqa_workspace_bytes.argtypes = [gp]
+        L.attn_bwd_gqa_workspace_bytes.restype = ctypes.c_size_t
+        L.attn_bwd_gqa.argtypes = [vp] * 9 + [vp, ctypes.c_size_t, gp, vp]
+        L.attn_bwd_gqa.restype = ctypes.c_int
+        L.attn_bwd_gqa_stages.argtypes = [vp] * 9 + [vp, ctypes.c_size_t, gp, vp, ctypes.c_uint32]
+        L.attn_bwd_gqa_stages.restype = ctypes.c_int
         L.attn_status_string.argtypes = [ctypes.c_int]
         L.attn_status_string.restype = ctypes.c_char_p
         L.attn_version.argtypes = []
@@ -173,4 +197,96 @@ def attn_bwd(Q, K, V, O, dO, LSE, scale, causal, dQ=None, dK=None, dV=None, work
         rc = lib().attn_bwd_stages(*args, int(stages))
     if rc != ATTN_OK:
         raise AttnError(rc, "attn_bwd")
+    return dQ, dK, dV
+
+
+# ---- grouped-query heads: Q, O, dO, dQ are [B,Hq,S,D]; K, V, dK, dV are [B,Hkv,S,D] ----------
+
+def make_gqa_params(B, Hq, Hkv, S, D, scale, causal, q_strides=None, kv_strides=None):
+    """attn_gqa_params_t; strides=(sb, sh, ss) in elements or None for contiguous."""
+    p = AttnGqaParams()
+    lib().attn_gqa_params_contiguous(ctypes.byref(p), B, Hq, Hkv, S, D, float(scale),
+                                     int(bool(causal)))
+    if q_strides is not None:
+        p.q_stride_b, p.q_stride_h, p.q_stride_s = (int(s) for s in q_strides)
+    if kv_strides is not None:
+        p.kv_stride_b, p.kv_stride_h, p.kv_stride_s = (int(s) for s in kv_strides)
+    return p
+
+
+def _gqa_params_for(q, k, scale, causal):
+    for t in (q, k):
+        if t.dim() != 4 or t.stride(3) != 1:
+            raise ValueError("expected [B,H,S,D] tensors with a contiguous D axis")
+    B, Hq, S, D = q.shape
+    if k.shape[0] != B or k.shape[2] != S or k.shape[3] != D:
+        raise ValueError("K/V must be [B,Hkv,S,D] matching Q in B, S and D")
+    return make_gqa_params(B, Hq, k.shape[1], S, D, scale, causal, q.stride()[:3], k.stride()[:3])
+
+
+def attn_fwd_gqa(Q, K, V, scale, causal, O=None, LSE=None, stream=None):
+    """O [B,Hq,S,D], LSE [B,Hq,S] = grouped-query attention forward; K, V: [B,Hkv,S,D]."""
+    import torch
+    if Q.dtype != torch.bfloat16 or not Q.is_cuda:
+        raise ValueError("Q,K,V must be bf16 tensors on the GPU")
+    _same_layout(K, V)
+    if O is None:
+        O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    else:
+        _same_layout(Q, O)
+    B, H, S, D = Q.shape
+    if LSE is None:
+        LSE = torch.empty((B, H, S), dtype=torch.float32, device=Q.device)
+    elif LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != (B, H, S):
+        raise ValueError("LSE must be a contiguous fp32 [B,Hq,S] tensor")
+    p = _gqa_params_for(Q, K, scale, causal)
+    rc = lib().attn_fwd_gqa(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                            LSE.data_ptr(), ctypes.byref(p), _stream_ptr(torch, stream))
+    if rc != ATTN_OK:
+        raise AttnError(rc, "attn_fwd_gqa")
+    return O, LSE
+
+
+def attn_bwd_gqa_workspace_bytes(B, Hq, Hkv, S, D):
+    p = make_gqa_params(B, Hq, Hkv, S, D, 1.0, False)
+    return int(lib().attn_bwd_gqa_workspace_bytes(ctypes.byref(p)))
+
+
+def attn_bwd_gqa(Q, K, V, O, dO, LSE, scale, causal, dQ=None, dK=None, dV=None, workspace=None,
+                 stream=None, stages=None):
+    """dQ [B,Hq,S,D], dK, dV [B,Hkv,S,D] = grouped-query attention backward."""
+    import torch
+    if Q.dtype != torch.bfloat16 or not Q.is_cuda:
+        raise ValueError("tensors must be bf16 on the GPU")
+    _same_layout(Q, O, dO)
+    _same_layout(K, V)
+    if dQ is None:
+        dQ = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    else:
+        _same_layout(Q, dQ)
+    outs = []
+    for t in (dK, dV):
+        if t is None:
+            t = torch.empty_strided(K.shape, K.stride(), dtype=K.dtype, device=K.device)
+        else:
+            _same_layout(K, t)
+        outs.append(t)
+    dK, dV = outs
+    B, H, S, D = Q.shape
+    if LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != (B, H, S):
+        raise ValueError("LSE must be a contiguous fp32 [B,Hq,S] tensor")
+    p = _gqa_params_for(Q, K, scale, causal)
+    need = int(lib().attn_bwd_gqa_workspace_bytes(ctypes.byref(p)))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    args = (Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(),
+            LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
+            workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+            ctypes.byref(p), _stream_ptr(torch, stream))
+    if stages is None:
+        rc = lib().attn_bwd_gqa(*args)
+    else:
+        rc = lib().attn_bwd_gqa_stages(*args, int(stages))
+    if rc != ATTN_OK:
+        raise AttnError(rc, "attn_bwd_gqa")
     return dQ, dK, dV

@@ -9,21 +9,50 @@ namespace {
 
 constexpr size_t kWsAlign = 256;
 
+int check_strides(int32_t S, int32_t D, int64_t sb, int64_t sh, int64_t ss)
+{
+    if (ss < D || sh < 1 || sb < 1) return ATTN_ERR_STRIDE;
+    if (ss % 8 || sh % 8 || sb % 8) return ATTN_ERR_STRIDE;
+    // One head's rows (plus the look-ahead tiles the kernels fetch past the end, which read
+    // as zero) are addressed with 32-bit byte offsets.
+    if (((int64_t)S + 512) * ss * 2 >= ((int64_t)1 << 32)) return ATTN_ERR_STRIDE;
+    return ATTN_OK;
+}
+
+int check_params(const attn_gqa_params_t *p)
+{
+    if (!p) return ATTN_ERR_NULL;
+    if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->S < 1) return ATTN_ERR_SHAPE;
+    if (p->Hq % p->Hkv != 0) return ATTN_ERR_SHAPE;
+    if (p->D != 64 && p->D != 128) return ATTN_ERR_SHAPE;
+    // B*Hq*S rows must be indexable with int32 (LSE / workspace offsets, grid sizes).
+    const int64_t rows = (int64_t)p->B * p->Hq * p->S;
+    if (rows > (int64_t)std::numeric_limits<int32_t>::max()) return ATTN_ERR_SHAPE;
+    int rc = check_strides(p->S, p->D, p->q_stride_b, p->q_stride_h, p->q_stride_s);
+    if (rc != ATTN_OK) return rc;
+    rc = check_strides(p->S, p->D, p->kv_stride_b, p->kv_stride_h, p->kv_stride_s);
+    if (rc != ATTN_OK) return rc;
+    if (!std::isfinite(p->scale) || !(p->scale > 0.0f)) return ATTN_ERR_SCALE;
+    return ATTN_OK;
+}
+
+// Multi-head parameters as the grouped-query ones with one query head per K/V head.
+attn_gqa_params_t as_gqa(const attn_params_t &p)
+{
+    attn_gqa_params_t g;
+    g.B = p.B; g.Hq = p.H; g.Hkv = p.H; g.S = p.S; g.D = p.D;
+    g.q_stride_b = g.kv_stride_b = p.stride_b;
+    g.q_stride_h = g.kv_stride_h = p.stride_h;
+    g.q_stride_s = g.kv_stride_s = p.stride_s;
+    g.scale = p.scale; g.causal = p.causal;
+    return g;
+}
+
 int check_params(const attn_params_t *p)
 {
     if (!p) return ATTN_ERR_NULL;
-    if (p->B < 1 || p->H < 1 || p->S < 1) return ATTN_ERR_SHAPE;
-    if (p->D != 64 && p->D != 128) return ATTN_ERR_SHAPE;
-    // B*H*S rows must be indexable with int32 (LSE / delta offsets, grid sizes).
-    const int64_t rows = (int64_t)p->B * p->H * p->S;
-    if (rows > (int64_t)std::numeric_limits<int32_t>::max()) return ATTN_ERR_SHAPE;
-    if (p->stride_s < p->D || p->stride_h < 1 || p->stride_b < 1) return ATTN_ERR_STRIDE;
-    if (p->stride_s % 8 || p->stride_h % 8 || p->stride_b % 8) return ATTN_ERR_STRIDE;
-    // One head's rows (plus the look-ahead tiles the kernels fetch past the end, which read
-    // as zero) are addressed with 32-bit byte offsets.
-    if (((int64_t)p->S + 512) * p->stride_s * 2 >= ((int64_t)1 << 32)) return ATTN_ERR_STRIDE;
-    if (!std::isfinite(p->scale) || !(p->scale > 0.0f)) return ATTN_ERR_SCALE;
-    return ATTN_OK;
+    const attn_gqa_params_t g = as_gqa(*p);
+    return check_params(&g);
 }
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -44,8 +73,21 @@ void attn_params_contiguous(attn_params_t *p, int32_t B, int32_t H, int32_t S, i
     p->causal = causal;
 }
 
-int attn_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
-             const attn_params_t *p, void *hip_stream)
+void attn_gqa_params_contiguous(attn_gqa_params_t *p, int32_t B, int32_t Hq, int32_t Hkv,
+                                int32_t S, int32_t D, float scale, int32_t causal)
+{
+    if (!p) return;
+    p->B = B; p->Hq = Hq; p->Hkv = Hkv; p->S = S; p->D = D;
+    p->q_stride_s = p->kv_stride_s = D;
+    p->q_stride_h = p->kv_stride_h = (int64_t)S * D;
+    p->q_stride_b = (int64_t)Hq * S * D;
+    p->kv_stride_b = (int64_t)Hkv * S * D;
+    p->scale = scale;
+    p->causal = causal;
+}
+
+int attn_fwd_gqa(const void *Q, const void *K, const void *V, void *O, float *LSE,
+                 const attn_gqa_params_t *p, void *hip_stream)
 {
     if (!Q || !K || !V || !O || !LSE) return ATTN_ERR_NULL;
     const int rc = check_params(p);
@@ -59,19 +101,91 @@ int attn_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
     a.V = static_cast<const attn::bf16 *>(V);
     a.O = static_cast<attn::bf16 *>(O);
     a.LSE = LSE;
-    a.stride_b = p->stride_b; a.stride_h = p->stride_h; a.stride_s = p->stride_s;
-    a.S = p->S; a.H = p->H; a.BH = p->B * p->H;
+    a.stride_b = p->q_stride_b; a.stride_h = p->q_stride_h; a.stride_s = p->q_stride_s;
+    a.kv_stride_b = p->kv_stride_b; a.kv_stride_h = p->kv_stride_h; a.kv_stride_s = p->kv_stride_s;
+    a.S = p->S; a.H = p->Hq; a.BH = p->B * p->Hq; a.group = p->Hq / p->Hkv;
     a.nqt = 0;
     a.scale_log2e = p->scale * 1.4426950408889634f;
     return attn::launch_fwd(a, p->D, p->causal != 0, static_cast<hipStream_t>(hip_stream)) == 0
                ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
-size_t attn_bwd_workspace_bytes(const attn_params_t *p)
+int attn_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
+             const attn_params_t *p, void *hip_stream)
+{
+    if (!p) return ATTN_ERR_NULL;
+    const attn_gqa_params_t g = as_gqa(*p);
+    return attn_fwd_gqa(Q, K, V, O, LSE, &g, hip_stream);
+}
+
+size_t attn_bwd_gqa_workspace_bytes(const attn_gqa_params_t *p)
 {
     if (check_params(p) != ATTN_OK) return 0;
-    const size_t rows = (size_t)p->B * p->H * p->S;
+    const size_t rows = (size_t)p->B * p->Hq * p->S;
     return (2 * rows * sizeof(float) + kWsAlign - 1) / kWsAlign * kWsAlign;
+}
+
+size_t attn_bwd_workspace_bytes(const attn_params_t *p)
+{
+    if (!p) return 0;
+    const attn_gqa_params_t g = as_gqa(*p);
+    return attn_bwd_gqa_workspace_bytes(&g);
+}
+
+static int bwd_impl(const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                    const float *LSE, void *dQ, void *dK, void *dV,
+                    void *workspace, size_t workspace_bytes,
+                    const attn_gqa_params_t *p, void *hip_stream, uint32_t stages)
+{
+    if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_NULL;
+    const int rc = check_params(p);
+    if (rc != ATTN_OK) return rc;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) ||
+        !aligned(dO, 16) || !aligned(dQ, 16) || !aligned(dK, 16) || !aligned(dV, 16) ||
+        !aligned(LSE, 4))
+        return ATTN_ERR_ALIGN;
+    if (!workspace || !aligned(workspace, kWsAlign) ||
+        workspace_bytes < attn_bwd_gqa_workspace_bytes(p))
+        return ATTN_ERR_WORKSPACE;
+    if (stages == 0 || (stages & ~7u)) return ATTN_ERR_SHAPE;
+    attn::BwdArgs a;
+    a.Q = static_cast<const attn::bf16 *>(Q);
+    a.K = static_cast<const attn::bf16 *>(K);
+    a.V = static_cast<const attn::bf16 *>(V);
+    a.O = static_cast<const attn::bf16 *>(O);
+    a.dO = static_cast<const attn::bf16 *>(dO);
+    a.LSE = LSE;
+    a.delta = static_cast<float *>(workspace);
+    a.dQ = static_cast<attn::bf16 *>(dQ);
+    a.dK = static_cast<attn::bf16 *>(dK);
+    a.dV = static_cast<attn::bf16 *>(dV);
+    a.stride_b = p->q_stride_b; a.stride_h = p->q_stride_h; a.stride_s = p->q_stride_s;
+    a.kv_stride_b = p->kv_stride_b; a.kv_stride_h = p->kv_stride_h; a.kv_stride_s = p->kv_stride_s;
+    a.S = p->S; a.H = p->Hq; a.BH = p->B * p->Hq; a.group = p->Hq / p->Hkv;
+    a.ntile = 0;
+    a.scale = p->scale;
+    a.scale_log2e = p->scale * 1.4426950408889634f;
+    return attn::launch_bwd(a, p->D, p->causal != 0, static_cast<hipStream_t>(hip_stream),
+                            stages) == 0
+               ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+int attn_bwd_gqa(const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                 const float *LSE, void *dQ, void *dK, void *dV,
+                 void *workspace, size_t workspace_bytes,
+                 const attn_gqa_params_t *p, void *hip_stream)
+{
+    return bwd_impl(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, p, hip_stream,
+                    ATTN_BWD_STAGE_DELTA | ATTN_BWD_STAGE_DKDV | ATTN_BWD_STAGE_DQ);
+}
+
+int attn_bwd_gqa_stages(const void *Q, const void *K, const void *V, const void *O,
+                        const void *dO, const float *LSE, void *dQ, void *dK, void *dV,
+                        void *workspace, size_t workspace_bytes,
+                        const attn_gqa_params_t *p, void *hip_stream, uint32_t stages)
+{
+    return bwd_impl(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, p, hip_stream,
+                    stages);
 }
 
 int attn_bwd(const void *Q, const void *K, const void *V, const void *O, const void *dO,
@@ -89,36 +203,10 @@ int attn_bwd_stages(const void *Q, const void *K, const void *V, const void *O, 
                     void *workspace, size_t workspace_bytes,
                     const attn_params_t *p, void *hip_stream, uint32_t stages)
 {
-    if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_NULL;
-    const int rc = check_params(p);
-    if (rc != ATTN_OK) return rc;
-    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) ||
-        !aligned(dO, 16) || !aligned(dQ, 16) || !aligned(dK, 16) || !aligned(dV, 16) ||
-        !aligned(LSE, 4))
-        return ATTN_ERR_ALIGN;
-    if (!workspace || !aligned(workspace, kWsAlign) ||
-        workspace_bytes < attn_bwd_workspace_bytes(p))
-        return ATTN_ERR_WORKSPACE;
-    if (stages == 0 || (stages & ~7u)) return ATTN_ERR_SHAPE;
-    attn::BwdArgs a;
-    a.Q = static_cast<const attn::bf16 *>(Q);
-    a.K = static_cast<const attn::bf16 *>(K);
-    a.V = static_cast<const attn::bf16 *>(V);
-    a.O = static_cast<const attn::bf16 *>(O);
-    a.dO = static_cast<const attn::bf16 *>(dO);
-    a.LSE = LSE;
-    a.delta = static_cast<float *>(workspace);
-    a.dQ = static_cast<attn::bf16 *>(dQ);
-    a.dK = static_cast<attn::bf16 *>(dK);
-    a.dV = static_cast<attn::bf16 *>(dV);
-    a.stride_b = p->stride_b; a.stride_h = p->stride_h; a.stride_s = p->stride_s;
-    a.S = p->S; a.H = p->H; a.BH = p->B * p->H;
-    a.ntile = 0;
-    a.scale = p->scale;
-    a.scale_log2e = p->scale * 1.4426950408889634f;
-    return attn::launch_bwd(a, p->D, p->causal != 0, static_cast<hipStream_t>(hip_stream),
-                            stages) == 0
-               ? ATTN_OK : ATTN_ERR_LAUNCH;
+    if (!p) return ATTN_ERR_NULL;
+    const attn_gqa_params_t g = as_gqa(*p);
+    return bwd_impl(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, &g, hip_stream,
+                    stages);
 }
 
 const char *attn_status_string(int status)
@@ -126,7 +214,7 @@ const char *attn_status_string(int status)
     switch (status) {
         case ATTN_OK: return "ok";
         case ATTN_ERR_NULL: return "a required pointer is NULL";
-        case ATTN_ERR_SHAPE: return "unsupported shape (B,H,S >= 1, D in {64,128}, B*H*S < 2^31)";
+        case ATTN_ERR_SHAPE: return "unsupported shape (B,H,S >= 1, D in {64,128}, Hkv divides Hq, B*H*S < 2^31)";
         case ATTN_ERR_STRIDE: return "bad stride (D contiguous, strides multiples of 8 elements, stride_s >= D)";
         case ATTN_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
         case ATTN_ERR_WORKSPACE: return "workspace missing, misaligned (256 B) or too small";
@@ -136,6 +224,6 @@ const char *attn_status_string(int status)
     }
 }
 
-int attn_version(void) { return 1000; }
+int attn_version(void) { return 1001; }
 
 }  // extern "C"

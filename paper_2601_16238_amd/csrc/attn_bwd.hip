@@ -136,9 +136,13 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     const int pair = w & (C::kPairs - 1);
     const int S = a.S;
     ATTN_CYCLES_BEGIN();
-    int bh, kt;  // causal: key block 0 is the heaviest
-    xcd_heavy_first(blockIdx.x, a.ntile, a.BH, bh, kt);
-    const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
+    // The work-group owns 128 keys of one K/V head and sums over the `group` query heads that
+    // read it (grouped-query attention; group == 1 is multi-head attention).
+    const int Hkv = a.H / a.group;
+    int bkv, kt;  // causal: key block 0 is the heaviest
+    xcd_heavy_first(blockIdx.x, a.ntile, a.BH / a.group, bkv, kt);
+    const int64_t base_kv = (int64_t)(bkv / Hkv) * a.kv_stride_b + (int64_t)(bkv % Hkv) * a.kv_stride_h;
+    const int bh0 = (bkv / Hkv) * a.H + (bkv % Hkv) * a.group;  // first query head of the group
 
     const int k0 = kt * C::kBlk + pair * 32;  // first key of this pair
     const int key = k0 + r;
@@ -157,8 +161,13 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     // ---- global -> LDS streaming of slot t into ring position rs.  Rows past S-1 lie
     // outside the head's buffer resource and read as zero.
     const uint32_t head_bytes = (uint32_t)(((int64_t)(S - 1) * a.stride_s + D) * 2);
-    const rsrc_t Qr = make_rsrc(a.Q + base, head_bytes), Gr = make_rsrc(a.dO + base, head_bytes);
-    const rsrc_t Wr = make_rsrc(a.delta + (int64_t)bh * 2 * S, (uint32_t)S * 8u);
+    rsrc_t Qr, Gr, Wr;  // Q, dO and row statistics of the current query head
+    auto set_head = [&](int bh) {
+        const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
+        Qr = make_rsrc(a.Q + base, head_bytes);
+        Gr = make_rsrc(a.dO + base, head_bytes);
+        Wr = make_rsrc(a.delta + (int64_t)bh * 2 * S, (uint32_t)S * 8u);
+    };
     const uint32_t row_bytes = (uint32_t)a.stride_s * 2u;
     uint32_t dma_voff[C::kDmaPerWave];
 #pragma unroll
@@ -196,10 +205,6 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     };
     auto ring_next = [](int x) { return x + 1 == C::kRing ? 0 : x + 1; };
 
-    if (producer)
-#pragma unroll
-        for (int i = 0; i < C::kAhead; ++i) dma_slot(t0 + i, i);
-
     bf16x8 *const Xs = reinterpret_cast<bf16x8 *>(smem + C::kOffXchg) + pair * 256 + l;
 
     if (producer) {
@@ -207,14 +212,20 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
         bf16x8 kf[KS], vf[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            kf[ks] = as_bf16x8(ld_global16(a.K + base + (int64_t)keyc * a.stride_s + ks * 16 + 8 * h));
-            vf[ks] = as_bf16x8(ld_global16(a.V + base + (int64_t)keyc * a.stride_s + ks * 16 + 8 * h));
+            kf[ks] = as_bf16x8(ld_global16(a.K + base_kv + (int64_t)keyc * a.kv_stride_s + ks * 16 + 8 * h));
+            vf[ks] = as_bf16x8(ld_global16(a.V + base_kv + (int64_t)keyc * a.kv_stride_s + ks * 16 + 8 * h));
         }
         // make sure no register load is counted among the streamed transfers any more
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         const float c = a.scale_log2e;
         const int lane_off = r * RB + ((h ^ swz(r)) << 4);  // chunk 2ks+h of row r: ^ (ks*32)
 
+        for (int gq = 0; gq < a.group; ++gq) {
+        // every wave is done with the previous query head's ring and exchange buffers
+        if (gq > 0) wait_vm_and_barrier<0>();
+        set_head(bh0 + gq);
+#pragma unroll
+        for (int i = 0; i < C::kAhead; ++i) dma_slot(t0 + i, i);
         int rs = 0;  // ring position of slot t
         for (int t = t0; t < n_slot; ++t) {
             slot_barrier();
@@ -272,6 +283,7 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
             rs = ring_next(rs);
         }
         wait_vm_and_barrier<0>();  // the consumers' last slot
+        }
     } else {
         f32x16 dv[DB], dk[DB];
 #pragma unroll
@@ -309,6 +321,8 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
             }
         };
 
+        for (int gq = 0; gq < a.group; ++gq) {
+        if (gq > 0) wait_vm_and_barrier<0>();
         int rs = 0;  // ring position of the producers' slot t; the consumers' is one behind
         for (int t = t0; t < n_slot; ++t) {
             wait_vm_and_barrier<0>();
@@ -317,10 +331,11 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
         }
         wait_vm_and_barrier<0>();
         if (n_slot > t0 && active(n_slot - 1)) consume(n_slot - 1, rs == 0 ? C::kRing - 1 : rs - 1);
+        }
 
         if (key < S) {
-            bf16 *dKp = a.dK + base + (int64_t)key * a.stride_s;
-            bf16 *dVp = a.dV + base + (int64_t)key * a.stride_s;
+            bf16 *dKp = a.dK + base_kv + (int64_t)key * a.kv_stride_s;
+            bf16 *dVp = a.dV + base_kv + (int64_t)key * a.kv_stride_s;
             const float sc = a.scale;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -356,7 +371,10 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const BwdArgs a)
     xcd_heavy_first(blockIdx.x, a.ntile, a.BH, bh, rank);
     const int qt = CAUSAL ? a.ntile - 1 - rank : rank;  // heaviest first
     const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
-    const bf16 *Kp = a.K + base, *Vp = a.V + base;
+    // grouped-query heads: query head h reads K/V head h / group
+    const int64_t base_kv = (int64_t)(bh / a.H) * a.kv_stride_b +
+                            (int64_t)((bh % a.H) / a.group) * a.kv_stride_h;
+    const bf16 *Kp = a.K + base_kv, *Vp = a.V + base_kv;
 
     const int q0 = qt * C::kBlk + w * 32;
     const int q = q0 + r;
@@ -383,8 +401,8 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const BwdArgs a)
                 const int row = c / (D / 8), col = (c % (D / 8)) * 8;
                 int kr = kt * C::kTile + row;
                 kr = kr < S ? kr : S - 1;
-                kreg[n] = ld_global16(Kp + (int64_t)kr * a.stride_s + col);
-                vreg[n] = ld_global16(Vp + (int64_t)kr * a.stride_s + col);
+                kreg[n] = ld_global16(Kp + (int64_t)kr * a.kv_stride_s + col);
+                vreg[n] = ld_global16(Vp + (int64_t)kr * a.kv_stride_s + col);
             }
         }
     };
@@ -487,7 +505,7 @@ static int launch_dkdv(BwdArgs a, hipStream_t st)
     using C = DkdvCfg<D>;
     a.ntile = (a.S + C::kBlk - 1) / C::kBlk;
     allow_lds(attn_bwd_dkdv_kernel<D, CAUSAL>, C::kLdsBytes);
-    hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL>), dim3(a.ntile * a.BH),
+    hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL>), dim3(a.ntile * (a.BH / a.group)),
                        dim3(C::kThreads), C::kLdsBytes, st, a);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }

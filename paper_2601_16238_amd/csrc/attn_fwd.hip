@@ -72,7 +72,10 @@ attn_fwd_kernel(const FwdArgs a)
     xcd_heavy_first(blockIdx.x, a.nqt, a.BH, bh, rank);
     const int qt = CAUSAL ? a.nqt - 1 - rank : rank;
     const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
-    const bf16 *Qp = a.Q + base, *Kp = a.K + base, *Vp = a.V + base;
+    // grouped-query heads: query head h reads K/V head h / group
+    const int64_t base_kv = (int64_t)(bh / a.H) * a.kv_stride_b +
+                            (int64_t)((bh % a.H) / a.group) * a.kv_stride_h;
+    const bf16 *Qp = a.Q + base, *Kp = a.K + base_kv, *Vp = a.V + base_kv;
 
     const int q0 = qt * C::kBR + w * 32;  // first query row of this wave
     const int q = q0 + r;                 // this lane's query row
@@ -90,9 +93,9 @@ attn_fwd_kernel(const FwdArgs a)
 
     // ---- staging: global -> registers -> LDS.  Rows past S-1 and tiles past the last one
     // lie outside the head's buffer resource and read as zero (masked to probability 0).
-    const uint32_t head_bytes = (uint32_t)(((int64_t)(S - 1) * a.stride_s + D) * 2);
+    const uint32_t head_bytes = (uint32_t)(((int64_t)(S - 1) * a.kv_stride_s + D) * 2);
     const rsrc_t Kr = make_rsrc(Kp, head_bytes), Vr = make_rsrc(Vp, head_bytes);
-    const uint32_t row_bytes = (uint32_t)a.stride_s * 2u;
+    const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2u;
     const uint32_t tile_bytes = C::kBC * row_bytes;
     // K goes global -> LDS directly (no registers): one wave-wide load of 16 B per lane fills
     // 1 KB of LDS in lane order, so the tile is stored unpadded and bank conflicts are avoided

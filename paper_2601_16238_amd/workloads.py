@@ -106,6 +106,56 @@ def random_inputs(B, H, S, D, seed, sigma=1.0):
     return out
 
 
+# ---- grouped-query heads (the microbenchmark table's shape tuple carries Hq and Hkv) ---------
+GqaWorkload = namedtuple("GqaWorkload", "name B Hq Hkv S D causal sigma seed note")
+
+GQA_WORKLOADS = {w.name: w for w in [
+    GqaWorkload("gqa_cmp", 4, 32, 8, 4096, 128, True, 1.0, 1007,
+                "the comparison shape with 4 query heads per K/V head, causal"),
+    GqaWorkload("mqa_small", 2, 8, 1, 300, 64, True, 1.0, 1008, "multi-query, ragged length"),
+]}
+
+
+def random_gqa_inputs(B, Hq, Hkv, S, D, seed, sigma=1.0):
+    """Seeded bf16 N(0, sigma^2) tensors: Q, dO [B,Hq,S,D]; K, V [B,Hkv,S,D]."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = {}
+    for name, heads in (("Q", Hq), ("K", Hkv), ("V", Hkv), ("dO", Hq)):
+        x = rng.standard_normal((B, heads, S, D), dtype=np.float32) * np.float32(sigma)
+        out[name] = f32_to_bf16_bits(x)
+    out["scale"] = default_scale(D)
+    return out
+
+
+def make_gqa_inputs(w, kv_heads=None):
+    """Draw Q, K, V, dO for grouped-query workload `w` (a GqaWorkload or its name), draw order
+    Q, K, V, dO.  `kv_heads` (flat b*Hkv+hkv indices) returns only those K/V heads and the
+    query heads of their groups, as [1,n*G,S,D] and [1,n,S,D] arrays drawn identically."""
+    if isinstance(w, str):
+        w = GQA_WORKLOADS[w]
+    rng = np.random.Generator(np.random.PCG64(w.seed))
+    G = w.Hq // w.Hkv
+    out = {}
+    for name, heads in (("Q", w.Hq), ("K", w.Hkv), ("V", w.Hkv), ("dO", w.Hq)):
+        x = rng.standard_normal((w.B * heads, w.S, w.D), dtype=np.float32)
+        if w.sigma != 1.0:
+            x *= np.float32(w.sigma)
+        if kv_heads is not None:
+            kv = np.asarray(list(kv_heads), dtype=np.int64)
+            if heads == w.Hkv:
+                sel = kv
+            else:  # the G query heads of K/V head (b, hkv) are b*Hq + hkv*G + 0..G-1
+                b, hk = kv // w.Hkv, kv % w.Hkv
+                sel = ((b * w.Hq + hk * G)[:, None] + np.arange(G)[None, :]).reshape(-1)
+            x = x[sel]
+            out[name] = f32_to_bf16_bits(x).reshape(1, x.shape[0], w.S, w.D)
+        else:
+            out[name] = f32_to_bf16_bits(x).reshape(w.B, heads, w.S, w.D)
+    out["scale"] = default_scale(w.D)
+    out["causal"] = bool(w.causal)
+    return out
+
+
 def fwd_flops(B, H, S, D, causal):
     """Benchmark FLOP convention: 4*B*H*S^2*D forward, halved under a causal mask."""
     f = 4.0 * B * H * S * S * D

@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported_and_bound():
 
 
 def test_version_and_status_strings():
-    assert attn.attn_version() == 1000
+    assert attn.attn_version() == 1001
     seen = set()
     for code in range(0, -8, -1):
         s = attn.status_string(code)
@@ -116,3 +116,67 @@ def test_workloads_are_seeded_and_shaped():
     # bf16 rounding: nearest-even on the 16 dropped bits
     f = np.array([1.0, 1.00390625, 1.01171875, -3.0e38], np.float32)
     assert list(wl.f32_to_bf16_bits(f)) == [0x3F80, 0x3F80, 0x3F82, 0xFF62]
+
+
+# ---- grouped-query entry points ----------------------------------------------------------
+
+def call_fwd_gqa(p, ptr=FAKE):
+    return attn.lib().attn_fwd_gqa(ptr, ptr, ptr, ptr, ptr, ctypes.byref(p), None)
+
+
+def call_bwd_gqa(p, ws=FAKE, ws_bytes=1 << 40, stages=None):
+    args = [FAKE] * 9 + [ws, ws_bytes, ctypes.byref(p), None]
+    if stages is None:
+        return attn.lib().attn_bwd_gqa(*args)
+    return attn.lib().attn_bwd_gqa_stages(*args, stages)
+
+
+def test_gqa_params_contiguous_and_workspace_size():
+    p = attn.make_gqa_params(4, 32, 8, 4096, 128, 0.0883, True)
+    assert (p.q_stride_s, p.q_stride_h, p.q_stride_b) == (128, 4096 * 128, 32 * 4096 * 128)
+    assert (p.kv_stride_s, p.kv_stride_h, p.kv_stride_b) == (128, 4096 * 128, 8 * 4096 * 128)
+    # the workspace is per QUERY row
+    assert attn.attn_bwd_gqa_workspace_bytes(4, 32, 8, 4096, 128) == 2 * 4 * 32 * 4096 * 4
+    assert attn.attn_bwd_gqa_workspace_bytes(1, 6, 4, 16, 64) == 0     # 4 does not divide 6
+
+
+@pytest.mark.parametrize("mutate,code", [
+    (lambda p: setattr(p, "Hkv", 3), binding.ATTN_ERR_SHAPE),           # 3 does not divide 8
+    (lambda p: setattr(p, "Hkv", 0), binding.ATTN_ERR_SHAPE),
+    (lambda p: setattr(p, "Hkv", 16), binding.ATTN_ERR_SHAPE),          # more K/V than query heads
+    (lambda p: setattr(p, "D", 32), binding.ATTN_ERR_SHAPE),
+    (lambda p: setattr(p, "kv_stride_s", 60), binding.ATTN_ERR_STRIDE),
+    (lambda p: setattr(p, "kv_stride_h", 132), binding.ATTN_ERR_STRIDE),
+    (lambda p: setattr(p, "q_stride_b", 4), binding.ATTN_ERR_STRIDE),
+    (lambda p: setattr(p, "kv_stride_s", 1 << 24), binding.ATTN_ERR_STRIDE),  # 32-bit row offsets
+    (lambda p: setattr(p, "scale", 0.0), binding.ATTN_ERR_SCALE),
+])
+def test_gqa_bad_params_rejected_before_any_launch(mutate, code):
+    p = attn.make_gqa_params(1, 8, 2, 128, 64, 0.125, False)
+    mutate(p)
+    assert call_fwd_gqa(p) == code
+    assert call_bwd_gqa(p) == code
+
+
+def test_gqa_null_workspace_and_stage_errors():
+    p = attn.make_gqa_params(1, 8, 2, 128, 64, 0.125, False)
+    assert call_fwd_gqa(p, ptr=None) == binding.ATTN_ERR_NULL
+    assert call_fwd_gqa(p, ptr=FAKE + 8) == binding.ATTN_ERR_ALIGN
+    assert call_bwd_gqa(p, ws=None) == binding.ATTN_ERR_WORKSPACE
+    assert call_bwd_gqa(p, ws_bytes=8 * 128 * 8 - 1) == binding.ATTN_ERR_WORKSPACE
+    assert call_bwd_gqa(p, stages=0) == binding.ATTN_ERR_SHAPE
+    assert call_bwd_gqa(p, stages=16) == binding.ATTN_ERR_SHAPE
+
+
+def test_gqa_workloads_are_seeded_and_group_selection_matches():
+    from paper_2601_16238_amd import workloads as wl
+    import numpy as np
+    w = wl.GQA_WORKLOADS["mqa_small"]
+    a, b = wl.make_gqa_inputs(w), wl.make_gqa_inputs(w)
+    assert a["Q"].shape == (w.B, w.Hq, w.S, w.D) and a["K"].shape == (w.B, w.Hkv, w.S, w.D)
+    for k in ("Q", "K", "V", "dO"):
+        assert np.array_equal(a[k], b[k])
+    sub = wl.make_gqa_inputs(w, kv_heads=[1])            # batch 1's only K/V head and its group
+    assert sub["Q"].shape == (1, w.Hq, w.S, w.D) and sub["K"].shape == (1, 1, w.S, w.D)
+    assert np.array_equal(sub["K"][0, 0], a["K"][1, 0])
+    assert np.array_equal(sub["Q"][0], a["Q"][1])
