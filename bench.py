@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="long_causal",
-                    help="one of paper_2601_16238_amd.workloads.WORKLOADS")
+                    help="one of paper_2601_16238_amd.workloads.WORKLOADS or GQA_WORKLOADS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true",
                     help="also time every other workload (reported under 'other_workloads')")
@@ -63,7 +63,9 @@ def time_calls(torch, fn, n):
 def measure(torch, attn, wl, w, steps, warmup):
     import numpy as np
     from paper_2601_16238_amd import binding
-    x = wl.make_inputs(w)
+    gqa = hasattr(w, "Hq")   # grouped-query workload: K, V, dK, dV have Hkv heads
+    H, Hkv = (w.Hq, w.Hkv) if gqa else (w.H, w.H)
+    x = wl.make_gqa_inputs(w) if gqa else wl.make_inputs(w)
 
     def dev(b):
         return torch.from_numpy(b.view(np.int16)).cuda().view(torch.bfloat16)
@@ -72,17 +74,18 @@ def measure(torch, attn, wl, w, steps, warmup):
     del x
     scale, causal = wl.default_scale(w.D), w.causal
     O = torch.empty_like(Q)
-    LSE = torch.empty((w.B, w.H, w.S), dtype=torch.float32, device="cuda")
-    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
-    ws = torch.empty(attn.attn_bwd_workspace_bytes(w.B, w.H, w.S, w.D), dtype=torch.uint8,
+    LSE = torch.empty((w.B, H, w.S), dtype=torch.float32, device="cuda")
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(K)
+    ws = torch.empty(attn.attn_bwd_gqa_workspace_bytes(w.B, H, Hkv, w.S, w.D), dtype=torch.uint8,
                      device="cuda")
+    fwd_call, bwd_call = (attn.attn_fwd_gqa, attn.attn_bwd_gqa) if gqa else (attn.attn_fwd, attn.attn_bwd)
 
     def fwd():
-        attn.attn_fwd(Q, K, V, scale, causal, O=O, LSE=LSE)
+        fwd_call(Q, K, V, scale, causal, O=O, LSE=LSE)
 
     def bwd(stages=None):
-        attn.attn_bwd(Q, K, V, O, dO, LSE, scale, causal, dQ=dQ, dK=dK, dV=dV, workspace=ws,
-                      stages=stages)
+        bwd_call(Q, K, V, O, dO, LSE, scale, causal, dQ=dQ, dK=dK, dV=dV, workspace=ws,
+                 stages=stages)
 
     def step():
         fwd()
@@ -99,15 +102,18 @@ def measure(torch, attn, wl, w, steps, warmup):
           "bwd_delta": time_calls(torch, lambda: bwd(binding.STAGE_DELTA), n),
           "bwd_dkdv": time_calls(torch, lambda: bwd(binding.STAGE_DKDV), n),
           "bwd_dq": time_calls(torch, lambda: bwd(binding.STAGE_DQ), n)}
-    f_fwd = wl.fwd_flops(w.B, w.H, w.S, w.D, causal)
-    f_bwd = wl.bwd_flops(w.B, w.H, w.S, w.D, causal)
+    f_fwd = wl.fwd_flops(w.B, H, w.S, w.D, causal)
+    f_bwd = wl.bwd_flops(w.B, H, w.S, w.D, causal)
+    # algorithmic bytes: Q-shaped tensors have H heads, K/V-shaped ones Hkv
+    t_q, t_kv, lse_b = w.B * H * w.S * w.D * 2, w.B * Hkv * w.S * w.D * 2, w.B * H * w.S * 4
+    b_fwd, b_bwd = 2 * t_q + 2 * t_kv + lse_b, 4 * t_q + 4 * t_kv + lse_b
     res = {
         "ms_per_step": ms_step, "ms": ms, "wall_s": wall,
         "tflops_fwdbwd": (f_fwd + f_bwd) / (ms_step * 1e-3) / 1e12,
         "tflops_fwd": f_fwd / (ms["fwd"] * 1e-3) / 1e12,
         "tflops_bwd": f_bwd / (ms["bwd"] * 1e-3) / 1e12,
-        "gbs_fwd": wl.fwd_bytes(w.B, w.H, w.S, w.D) / (ms["fwd"] * 1e-3) / 1e9,
-        "gbs_bwd": wl.bwd_bytes(w.B, w.H, w.S, w.D) / (ms["bwd"] * 1e-3) / 1e9,
+        "gbs_fwd": b_fwd / (ms["fwd"] * 1e-3) / 1e9,
+        "gbs_bwd": b_bwd / (ms["bwd"] * 1e-3) / 1e9,
     }
     # Algorithmic FLOPs per launch of each MFMA kernel (GEMM = 2*N_s*D flops, N_s = S^2 or
     # S^2/2): forward 2 GEMMs; dK/dV kernel 4 (S, dP, dV, dK); dQ kernel 1 (dQ -- its
@@ -127,22 +133,26 @@ def cpu_baseline(wl, w):
     in roughly 15 s of CPU work (the reported figure is from that second run)."""
     import oracle
 
+    gqa = hasattr(w, "Hq")   # grouped-query: a "head" of the sample is a K/V head with its group
+    n_heads = w.B * (w.Hkv if gqa else w.H)
+    per_head = (w.Hq // w.Hkv) if gqa else 1
+
     def run(heads):
-        x = wl.make_inputs(w, heads=range(heads))
+        x = wl.make_gqa_inputs(w, kv_heads=range(heads)) if gqa else wl.make_inputs(w, heads=range(heads))
         t0 = time.perf_counter()
         oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], w.causal)
         oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], w.causal)
         return time.perf_counter() - t0
 
     heads, dt = 1, run(1)
-    more = int(min(w.B * w.H, 15.0 // max(dt, 1e-3)))
+    more = int(min(n_heads, 15.0 // max(dt, 1e-3)))
     if more > 1:
         heads, dt = more, run(more)
-    flops = heads * 3.5 * wl.fwd_flops(1, 1, w.S, w.D, w.causal)
+    flops = heads * per_head * 3.5 * wl.fwd_flops(1, 1, w.S, w.D, w.causal)
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
             "kind": "oracle", "seconds": dt,
-            "sample": "fwd+bwd of the first %d of %d heads of %s at full S=%d (fp64, convention FLOPs)"
-                      % (heads, w.B * w.H, w.name, w.S)}
+            "sample": "fwd+bwd of the first %d of %d %sheads of %s at full S=%d (fp64, convention FLOPs)"
+                      % (heads, n_heads, "K/V " if gqa else "", w.name, w.S)}
 
 
 def main():
@@ -159,7 +169,7 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     attn.lib()  # fail loudly if the HIP library is not built
-    w = wl.WORKLOADS[a.workload]
+    w = wl.WORKLOADS[a.workload] if a.workload in wl.WORKLOADS else wl.GQA_WORKLOADS[a.workload]
     if a.calib_copy:
         src = torch.empty(CALIB_COPY_BYTES // 2, dtype=torch.bfloat16, device="cuda").normal_()
         dst = torch.empty_like(src)
@@ -173,7 +183,8 @@ def main():
         "value": r["tflops_fwdbwd"], "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s: B=%d H=%d S=%d D=%d causal=%s" % (w.name, w.B, w.H, w.S, w.D, w.causal),
+        "config": {"workload": "%s: %s" % (w.name, " ".join(
+            "%s=%s" % (k, getattr(w, k)) for k in w._fields if k in ("B", "H", "Hq", "Hkv", "S", "D", "causal"))),
                    "seed": w.seed},
         "frac_of_bf16_peak": {"fwd": r["tflops_fwd"] / PEAK_BF16_TFLOPS,
                               "fwd_bwd": r["tflops_fwdbwd"] / PEAK_BF16_TFLOPS,
@@ -188,11 +199,13 @@ def main():
     }
     if a.all:
         others = {}
-        for name, ow in wl.WORKLOADS.items():
+        for name, ow in list(wl.WORKLOADS.items()) + list(wl.GQA_WORKLOADS.items()):
             if name == w.name:
                 continue
             o = measure(torch, attn, wl, ow, max(5, a.steps // 2), a.warmup)
-            others[name] = {"ms": o["ms"], "tflops_fwd": o["tflops_fwd"], "tflops_fwdbwd": o["tflops_fwdbwd"],
+            others[name] = {"shape": {k: getattr(ow, k) for k in ow._fields if k in
+                                      ("B", "H", "Hq", "Hkv", "S", "D", "causal")},
+                            "ms": o["ms"], "tflops_fwd": o["tflops_fwd"], "tflops_fwdbwd": o["tflops_fwdbwd"],
                             "frac_fwd": o["tflops_fwd"] / PEAK_BF16_TFLOPS,
                             "frac_fwdbwd": o["tflops_fwdbwd"] / PEAK_BF16_TFLOPS,
                             "gbs_fwd": o["gbs_fwd"], "gbs_bwd": o["gbs_bwd"]}
