@@ -456,11 +456,14 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const BwdArgs a)
             const bool need_mask = (k_lo + 32 > S) || (CAUSAL && k_lo + 31 > q0);
             const int lim = (CAUSAL ? qc : S - 1) - k_lo - 4 * h;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float p = fast_exp2(__builtin_fmaf(s[i], c, -lse2));
-                if (need_mask && (8 * (i / 4) + (i % 4) > lim)) p = 0.f;
-                dp[i] = p * (dp[i] - delta);
+            for (int i = 0; i < 16; ++i) s[i] = fast_exp2(__builtin_fmaf(s[i], c, -lse2));
+            if (need_mask) {  // wave-uniform: only blocks on the diagonal or at the ragged end
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (8 * (i / 4) + (i % 4) > lim) s[i] = 0.f;
             }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dp[i] = s[i] * (dp[i] - delta);
             bf16x8 sb[2];
             sb[0] = pack8(dp[0], dp[1], dp[2], dp[3], dp[4], dp[5], dp[6], dp[7]);
             sb[1] = pack8(dp[8], dp[9], dp[10], dp[11], dp[12], dp[13], dp[14], dp[15]);
