@@ -80,7 +80,7 @@ int attn_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
 
 /*
  * Bytes of device workspace attn_bwd needs for this problem: two fp32 values per query row
- * ([B*H][2][S]: delta = rowsum(dO*O), and LSE rescaled to base 2), rounded up to 256 bytes.
+ * ([B*H][2][S]: -rowsum(dO*O), and LSE rescaled to base 2), rounded up to 256 bytes.
  * Pure host function; returns 0 for an invalid problem.
  */
 size_t attn_bwd_workspace_bytes(const attn_params_t *p);

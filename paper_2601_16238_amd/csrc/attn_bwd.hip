@@ -21,8 +21,10 @@
 namespace attn {
 
 // ---------------------------------------------------------------------------------------
-// 1. Row statistics, fp32, workspace layout [B*H][2][S]: delta = rowsum(dO * O), then
-// lse2 = LSE * log2(e) (the main kernels run the softmax on exp2).  D/8 lanes per row,
+// 1. Row statistics, fp32, workspace layout [B*H][2][S]: -delta = -rowsum(dO * O), then
+// lse2 = LSE * log2(e) (the main kernels run the softmax on exp2).  delta is stored negated
+// because the main kernels start the dP = dO V^T accumulation from it, which yields
+// dP - delta without a subtraction per element.  D/8 lanes per row,
 // 16-byte loads.
 // ---------------------------------------------------------------------------------------
 template <int D>
@@ -47,7 +49,7 @@ __global__ void __launch_bounds__(256) attn_bwd_delta_kernel(const BwdArgs a)
     for (int s = LPR / 2; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
     if (row < rows && sub == 0) {
         const int64_t bh = row / a.S, i = row % a.S;
-        a.delta[(2 * bh) * a.S + i] = acc;
+        a.delta[(2 * bh) * a.S + i] = -acc;  // negated: it seeds the dP accumulators
         a.delta[(2 * bh + 1) * a.S + i] = a.LSE[row] * kLog2e;
     }
 }
@@ -238,11 +240,19 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
                 const int q_lo = t * C::kRows;
                 f32x16 s, dp;
                 {
-                    f32x16 zero;
+                    // register i <-> query row q_lo + 8*(i/4) + 4h + i%4.  The dP accumulator
+                    // starts from -delta of its row, so that it ends as dP - delta.
+                    f32x16 zero, nd;
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const f32x4 d4 = *(const f32x4 *)(st + 32 + 8 * g + 4 * h);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) nd[4 * g + e] = d4[e];
+                    }
 #pragma unroll
                     for (int i = 0; i < 16; ++i) zero[i] = 0.f;
                     s = mfma32(*(const bf16x8 *)(Qt + lane_off), kf[0], zero);
-                    dp = mfma32(*(const bf16x8 *)(Qt + C::kTensorBytes + lane_off), vf[0], zero);
+                    dp = mfma32(*(const bf16x8 *)(Qt + C::kTensorBytes + lane_off), vf[0], nd);
                 }
 #pragma unroll
                 for (int ks = 1; ks < KS; ++ks) {
@@ -250,7 +260,7 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
                     s = mfma32(*(const bf16x8 *)(Qt + off), kf[ks], s);
                     dp = mfma32(*(const bf16x8 *)(Qt + C::kTensorBytes + off), vf[ks], dp);
                 }
-                // register i <-> query row q_lo + 8*(i/4) + 4h + i%4; the lane's key is fixed
+                // the lane's key is fixed; P = exp2(c S - lse2) per row
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const f32x4 l4 = *(const f32x4 *)(st + 8 * g + 4 * h);
@@ -269,11 +279,7 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
                     }
                 }
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const f32x4 d4 = *(const f32x4 *)(st + 32 + 8 * g + 4 * h);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) dp[4 * g + e] = s[4 * g + e] * (dp[4 * g + e] - d4[e]);
-                }
+                for (int i = 0; i < 16; ++i) dp[i] *= s[i];  // dS = P o (dP - delta)
                 bf16x8 *x = Xs + (t & 1) * (C::kPairs * 256);
                 x[0] = pack8(s[0], s[1], s[2], s[3], s[4], s[5], s[6], s[7]);
                 x[64] = pack8(s[8], s[9], s[10], s[11], s[12], s[13], s[14], s[15]);
@@ -387,7 +393,13 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const BwdArgs a)
         gf[ks] = as_bf16x8(ld_global16(a.dO + base + (int64_t)qc * a.stride_s + ks * 16 + 8 * h));
     }
     const float lse2 = a.LSE[(int64_t)bh * S + qc] * kLog2e;
-    const float delta = a.delta[(int64_t)bh * 2 * S + qc];
+    // -delta of this lane's query, replicated: the dP accumulators start from it
+    f32x16 nd;
+    {
+        const float ndelta = a.delta[(int64_t)bh * 2 * S + qc];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) nd[i] = ndelta;
+    }
 
     const int q_end = min(S, (qt + 1) * C::kBlk);
     const int n_kt = ((CAUSAL ? q_end : S) + C::kTile - 1) / C::kTile;
@@ -444,13 +456,19 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const BwdArgs a)
             if (!active) continue;
             f32x16 s, dp;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
-#pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 const bf16x8 ka = *(const bf16x8 *)(Kt + (kb2 * 32 + r) * C::kLd + ks * 16 + 8 * h);
                 const bf16x8 va = *(const bf16x8 *)(Vt + (kb2 * 32 + r) * C::kLd + ks * 16 + 8 * h);
-                s = mfma32(ka, qf[ks], s);
-                dp = mfma32(va, gf[ks], dp);
+                if (ks == 0) {
+                    f32x16 zero;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+                    s = mfma32(ka, qf[0], zero);
+                    dp = mfma32(va, gf[0], nd);  // ends as dP - delta
+                } else {
+                    s = mfma32(ka, qf[ks], s);
+                    dp = mfma32(va, gf[ks], dp);
+                }
             }
             // register i <-> key k_lo + 8*(i/4) + 4h + i%4; this lane's query is fixed
             const bool need_mask = (k_lo + 32 > S) || (CAUSAL && k_lo + 31 > q0);
@@ -463,7 +481,7 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const BwdArgs a)
                     if (8 * (i / 4) + (i % 4) > lim) s[i] = 0.f;
             }
 #pragma unroll
-            for (int i = 0; i < 16; ++i) dp[i] = s[i] * (dp[i] - delta);
+            for (int i = 0; i < 16; ++i) dp[i] *= s[i];  // dS = P o (dP - delta)
             bf16x8 sb[2];
             sb[0] = pack8(dp[0], dp[1], dp[2], dp[3], dp[4], dp[5], dp[6], dp[7]);
             sb[1] = pack8(dp[8], dp[9], dp[10], dp[11], dp[12], dp[13], dp[14], dp[15]);

@@ -26,7 +26,7 @@ struct FwdArgs {
 struct BwdArgs {
     const bf16 *Q, *K, *V, *O, *dO;
     const float *LSE;
-    float *delta;       // workspace [B*H][2][S]: delta, then LSE * log2(e)
+    float *delta;       // workspace [B*H][2][S]: -delta, then LSE * log2(e)
     bf16 *dQ, *dK, *dV;
     int64_t stride_b, stride_h, stride_s;
     int64_t kv_stride_b, kv_stride_h, kv_stride_s;
