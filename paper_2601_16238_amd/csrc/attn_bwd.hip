@@ -55,24 +55,6 @@ __global__ void __launch_bounds__(256) attn_bwd_delta_kernel(const BwdArgs a)
 }
 
 // ---------------------------------------------------------------------------------------
-// Tile staging shared by kernels 2 and 3: two bf16 tiles of 64 rows x D (row-major, skewed
-// rows) and, for kernel 2, the 64 LSE / delta values of the rows, double-buffered.
-// ---------------------------------------------------------------------------------------
-template <int D, int NW>
-struct BwdCfg {
-    static constexpr int kThreads = NW * 64;
-    static constexpr int kBlk = NW * 32;            // rows owned by the work-group
-    static constexpr int kTile = 64;                // rows streamed per iteration
-    static constexpr int kLd = D + 8;
-    static constexpr int kTileElems = kTile * kLd;
-    static constexpr int kRowStatBytes = 2 * 2 * kTile * 4;   // lse2, delta double-buffered
-    static constexpr int kLdsBytes = 2 * 2 * kTileElems * 2 + kRowStatBytes;
-    static constexpr int kChunks = kTile * D / 8;
-    static constexpr int kChunksPerThread = (kChunks + kThreads - 1) / kThreads;
-    static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 CU exceeded");
-};
-
-// ---------------------------------------------------------------------------------------
 // 2. dK, dV.  Work-group = 8 waves = 4 producer/consumer pairs sharing a SIMD each; a pair
 // owns 32 keys and the work-group streams the head's Q and dO rows through LDS in slots of
 // 32 rows.  The K/V fragments plus two 32 x D fp32 accumulators do not fit one wave's 256
@@ -114,15 +96,6 @@ struct DkdvCfg {
     static_assert(kDmaPerTensor % kPairs == 0, "transfers divide evenly over the producers");
     static_assert(kOffXchg % 16 == 0 && kLdsBytes <= 160 * 1024, "LDS layout");
 };
-
-// Wait until at most N of this wave's vector-memory operations are outstanding and all its
-// LDS operations are done, then join the work-group barrier.  Unlike __syncthreads this
-// leaves the newest global->LDS transfers in flight across the barrier.
-template <int N>
-__device__ __forceinline__ void wait_vm_and_barrier()
-{
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
-}
 
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2)))
@@ -359,18 +332,37 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
 }
 
 // ---------------------------------------------------------------------------------------
-// 3. dQ.  Work-group = NW waves, wave = 32 queries, loop over key tiles of 64 rows.
+// 3. dQ.  Work-group = NW waves, wave = 32 queries (Q, dO fragments and the 32 x D fp32
+// accumulator in registers), loop over key tiles of 64 rows.  K and V tiles go global -> LDS
+// directly, two tiles ahead, into a ring of three; rows are stored unpadded with the 16-byte
+// chunk index XOR-swizzled by the row (same swizzle as kernel 2) so that the row reads for
+// S^T = K Q^T, dP^T = V dO^T and the transpose reads for dQ^T += K^T dS^T are conflict free.
 // ---------------------------------------------------------------------------------------
-template <int D, int NW, bool CAUSAL>
-__global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const BwdArgs a)
-{
-    using C = BwdCfg<D, NW>;
-    constexpr int KS = D / 16, DB = D / 32;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16 *Ks = reinterpret_cast<bf16 *>(smem);  // [2][64][kLd]
-    bf16 *Vs = Ks + 2 * C::kTileElems;          // [2][64][kLd]
+template <int D, int NW>
+struct DqCfg {
+    static constexpr int kThreads = NW * 64;
+    static constexpr int kBlk = NW * 32;             // queries owned by the work-group
+    static constexpr int kTile = 64;                 // keys per tile
+    static constexpr int kRing = 3;
+    static constexpr int kRowBytes = D * 2;
+    static constexpr int kTensorBytes = kTile * kRowBytes;   // K part of a tile; V follows
+    static constexpr int kTileBytes = 2 * kTensorBytes;
+    static constexpr int kLdsBytes = kRing * kTileBytes;
+    static constexpr int kDmaPerTile = kTileBytes / 1024;     // wave-wide 1 KB transfers
+    static constexpr int kDmaPerWave = (kDmaPerTile + NW - 1) / NW;
+    static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 CU exceeded");
+};
 
-    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, r = l & 31, h = l >> 5;
+template <int D, int NW, bool CAUSAL>
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
+attn_bwd_dq_kernel(const BwdArgs a)
+{
+    using C = DqCfg<D, NW>;
+    constexpr int KS = D / 16, DB = D / 32, CPR = D / 8, RB = C::kRowBytes;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int tid = threadIdx.x, l = tid & 63, r = l & 31, h = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int S = a.S;
     ATTN_CYCLES_BEGIN();
     int bh, rank;
@@ -380,11 +372,38 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const BwdArgs a)
     // grouped-query heads: query head h reads K/V head h / group
     const int64_t base_kv = (int64_t)(bh / a.H) * a.kv_stride_b +
                             (int64_t)((bh % a.H) / a.group) * a.kv_stride_h;
-    const bf16 *Kp = a.K + base_kv, *Vp = a.V + base_kv;
 
     const int q0 = qt * C::kBlk + w * 32;
     const int q = q0 + r;
     const int qc = q < S ? q : S - 1;
+    const int q_end = min(S, (qt + 1) * C::kBlk);
+    const int n_kt = ((CAUSAL ? q_end : S) + C::kTile - 1) / C::kTile;
+
+    auto swz = [](int row) {
+        return CPR == 16 ? (((row & 3) << 2) | ((row >> 2) & 3))
+                         : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+    };
+
+    // ---- streaming of tile kt into ring position pos; rows past S-1 read as zero
+    const uint32_t head_bytes = (uint32_t)(((int64_t)(S - 1) * a.kv_stride_s + D) * 2);
+    const desc_t Kd = make_desc(a.K + base_kv, head_bytes), Vd = make_desc(a.V + base_kv, head_bytes);
+    const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2u;
+    const uint32_t lds0 = lds_address(smem);
+    auto dma_tile = [&](int kt, int pos) {
+#pragma unroll
+        for (int n = 0; n < C::kDmaPerWave; ++n) {
+            // wave-uniform 1 KB piece; a wave with nothing left repeats an earlier piece so
+            // that every wave has the same number of transfers in flight
+            const int i = (w + n * NW) % C::kDmaPerTile;
+            const int tensor = i / (C::kDmaPerTile / 2), grp = i % (C::kDmaPerTile / 2);
+            const int row = grp * (64 / CPR) + l / CPR;
+            const uint32_t voff = row * row_bytes + (((l % CPR) ^ swz(row)) << 4);
+            dma16(tensor ? Vd : Kd, lds0 + pos * C::kTileBytes + tensor * C::kTensorBytes + grp * 1024,
+                  voff, kt * C::kTile * row_bytes);
+        }
+    };
+    dma_tile(0, 0);
+    if (n_kt > 1) dma_tile(1, 1);
 
     bf16x8 qf[KS], gf[KS];
 #pragma unroll
@@ -392,7 +411,7 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const BwdArgs a)
         qf[ks] = as_bf16x8(ld_global16(a.Q + base + (int64_t)qc * a.stride_s + ks * 16 + 8 * h));
         gf[ks] = as_bf16x8(ld_global16(a.dO + base + (int64_t)qc * a.stride_s + ks * 16 + 8 * h));
     }
-    const float lse2 = a.LSE[(int64_t)bh * S + qc] * kLog2e;
+    const float lse2 = a.delta[(int64_t)bh * 2 * S + S + qc];
     // -delta of this lane's query, replicated: the dP accumulators start from it
     f32x16 nd;
     {
@@ -401,35 +420,6 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const BwdArgs a)
         for (int i = 0; i < 16; ++i) nd[i] = ndelta;
     }
 
-    const int q_end = min(S, (qt + 1) * C::kBlk);
-    const int n_kt = ((CAUSAL ? q_end : S) + C::kTile - 1) / C::kTile;
-
-    u32x4 kreg[C::kChunksPerThread], vreg[C::kChunksPerThread];
-    auto prefetch = [&](int kt) {
-#pragma unroll
-        for (int n = 0; n < C::kChunksPerThread; ++n) {
-            const int c = tid + n * C::kThreads;
-            if (C::kChunks % C::kThreads == 0 || c < C::kChunks) {
-                const int row = c / (D / 8), col = (c % (D / 8)) * 8;
-                int kr = kt * C::kTile + row;
-                kr = kr < S ? kr : S - 1;
-                kreg[n] = ld_global16(Kp + (int64_t)kr * a.kv_stride_s + col);
-                vreg[n] = ld_global16(Vp + (int64_t)kr * a.kv_stride_s + col);
-            }
-        }
-    };
-    auto commit = [&](int buf) {
-#pragma unroll
-        for (int n = 0; n < C::kChunksPerThread; ++n) {
-            const int c = tid + n * C::kThreads;
-            if (C::kChunks % C::kThreads == 0 || c < C::kChunks) {
-                const int row = c / (D / 8), col = (c % (D / 8)) * 8;
-                *(u32x4 *)(Ks + buf * C::kTileElems + row * C::kLd + col) = kreg[n];
-                *(u32x4 *)(Vs + buf * C::kTileElems + row * C::kLd + col) = vreg[n];
-            }
-        }
-    };
-
     f32x16 dq[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -437,38 +427,43 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const BwdArgs a)
         for (int i = 0; i < 16; ++i) dq[db][i] = 0.f;
 
     const float c = a.scale_log2e;
-    const int tr_row = 4 * h + ((l & 15) >> 2);
-    const int tr_col = ((l >> 4) & 1) * 16 + (l & 3) * 4;
+    const int lane_off = r * RB + ((h ^ swz(r)) << 4);  // chunk 2ks+h of row r: ^ (ks*32)
+    int tr_off[2];  // transpose reads: rows 4h+e (+8), 64 bytes of d block 0 per row
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int row = 8 * j + 4 * h + ((l & 15) >> 2);
+        const int chunk = 2 * ((l >> 4) & 1) + ((l >> 1) & 1);
+        tr_off[j] = row * RB + ((chunk ^ swz(row)) << 4) + (l & 1) * 8;
+    }
 
-    prefetch(0);
+    int pos = 0;
     for (int kt = 0; kt < n_kt; ++kt) {
-        const int buf = kt & 1;
-        commit(buf);
-        __syncthreads();
-        if (kt + 1 < n_kt) prefetch(kt + 1);
+        // tile kt must have landed; tile kt+1 (if any) may stay in flight
+        if (kt + 1 < n_kt) wait_vm_and_barrier<C::kDmaPerWave>();
+        else wait_vm_and_barrier<0>();
+        if (kt + 2 < n_kt) dma_tile(kt + 2, pos == 0 ? 2 : pos - 1);  // the tile freed by the barrier
 
-        const bf16 *Kt = Ks + buf * C::kTileElems;
-        const bf16 *Vt = Vs + buf * C::kTileElems;
+        const char *Kt = smem + pos * C::kTileBytes;
+        const char *Vt = Kt + C::kTensorBytes;
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2) {
             const int k_lo = kt * C::kTile + kb2 * 32;
             const bool active = k_lo < S && (!CAUSAL || k_lo <= q0 + 31);  // wave-uniform
             if (!active) continue;
             f32x16 s, dp;
+            {
+                f32x16 zero;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8 ka = *(const bf16x8 *)(Kt + (kb2 * 32 + r) * C::kLd + ks * 16 + 8 * h);
-                const bf16x8 va = *(const bf16x8 *)(Vt + (kb2 * 32 + r) * C::kLd + ks * 16 + 8 * h);
-                if (ks == 0) {
-                    f32x16 zero;
+                for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+                const int off = kb2 * 32 * RB + lane_off;
+                s = mfma32(*(const bf16x8 *)(Kt + off), qf[0], zero);
+                dp = mfma32(*(const bf16x8 *)(Vt + off), gf[0], nd);  // ends as dP - delta
+            }
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) zero[i] = 0.f;
-                    s = mfma32(ka, qf[0], zero);
-                    dp = mfma32(va, gf[0], nd);  // ends as dP - delta
-                } else {
-                    s = mfma32(ka, qf[ks], s);
-                    dp = mfma32(va, gf[ks], dp);
-                }
+            for (int ks = 1; ks < KS; ++ks) {
+                const int off = kb2 * 32 * RB + (lane_off ^ (ks * 32));
+                s = mfma32(*(const bf16x8 *)(Kt + off), qf[ks], s);
+                dp = mfma32(*(const bf16x8 *)(Vt + off), gf[ks], dp);
             }
             // register i <-> key k_lo + 8*(i/4) + 4h + i%4; this lane's query is fixed
             const bool need_mask = (k_lo + 32 > S) || (CAUSAL && k_lo + 31 > q0);
@@ -489,13 +484,19 @@ __global__ void __launch_bounds__(NW * 64) attn_bwd_dq_kernel(const BwdArgs a)
             for (int cc = 0; cc < 2; ++cc) {
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    const int off = (kb2 * 32 + 16 * cc + tr_row) * C::kLd + 32 * db + tr_col;
-                    const bf16x8 kT = join8(lds_read_tr(Kt + off), lds_read_tr(Kt + off + 8 * C::kLd));
+                    // d block db = chunks 4db..4db+3: flips bits 6.. of the swizzled offset
+                    const int o0 = (tr_off[0] ^ (db << 6)) + (kb2 * 32 + cc * 16) * RB;
+                    const int o1 = (tr_off[1] ^ (db << 6)) + (kb2 * 32 + cc * 16) * RB;
+                    const bf16x8 kT = join8(lds_read_tr((const bf16 *)(Kt + o0)),
+                                            lds_read_tr((const bf16 *)(Kt + o1)));
                     dq[db] = mfma32(kT, sb[cc], dq[db]);
                 }
             }
         }
+        pos = pos == 2 ? 0 : pos + 1;
     }
+    // no transfer may still be in flight when the work-group's LDS is released
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     if (q < S) {
         bf16 *dQp = a.dQ + base + (int64_t)q * a.stride_s;
@@ -534,7 +535,7 @@ static int launch_dkdv(BwdArgs a, hipStream_t st)
 template <int D, int NW, bool CAUSAL>
 static int launch_dq(BwdArgs a, hipStream_t st)
 {
-    using C = BwdCfg<D, NW>;
+    using C = DqCfg<D, NW>;
     a.ntile = (a.S + C::kBlk - 1) / C::kBlk;
     allow_lds(attn_bwd_dq_kernel<D, NW, CAUSAL>, C::kLdsBytes);
     hipLaunchKernelGGL((attn_bwd_dq_kernel<D, NW, CAUSAL>), dim3(a.ntile * a.BH),

@@ -98,6 +98,71 @@ __device__ __forceinline__ u32x2 buf_load8(rsrc_t r, uint32_t voff, uint32_t sof
     return __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, 0);
 }
 
+// Global -> LDS transfer issued from inline assembly: 16 bytes per lane, lane i lands at LDS
+// byte address lds_addr + 16 i; the global byte offset is voff (per lane) + soff (uniform)
+// into the raw buffer `desc`, and offsets at or past its size read as zero.  Written as
+// assembly so that the compiler does not see the transfer: it would otherwise make a wave
+// wait for ALL of its outstanding transfers before any later transpose read of LDS.  The
+// caller orders transfers and reads itself (s_waitcnt vmcnt + barrier) and must wait for
+// vmcnt(0) before the work-group ends.
+typedef u32x4 desc_t;
+__device__ __forceinline__ desc_t make_desc(const void *p, uint32_t bytes)
+{
+    const uint64_t a = (uint64_t)p;
+    desc_t d;
+    d.x = __builtin_amdgcn_readfirstlane((uint32_t)a);
+    d.y = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32) & 0xffffu);
+    d.z = __builtin_amdgcn_readfirstlane(bytes);
+    d.w = 0x00020000u;
+    return d;
+}
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char *)p;
+}
+__device__ __forceinline__ void dma16(desc_t desc, uint32_t lds_addr, uint32_t voff, uint32_t soff)
+{
+    // lds_addr and soff are wave-uniform; readfirstlane makes that known to the compiler
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 ::"s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(desc),
+                 "s"(__builtin_amdgcn_readfirstlane(soff))
+                 : "memory");
+}
+// Same with 4 bytes per lane: lane i lands at lds_addr + 4 i.
+__device__ __forceinline__ void dma4(desc_t desc, uint32_t lds_addr, uint32_t voff, uint32_t soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 ::"s"(lds_addr), "v"(voff), "s"(desc), "s"(soff)
+                 : "memory");
+}
+// Wait until at most N of this wave's vector-memory operations are outstanding and all its
+// LDS operations are done, then join the work-group barrier.  Unlike __syncthreads this
+// leaves the newest global -> LDS transfers in flight across the barrier.
+template <int N>
+__device__ __forceinline__ void wait_vm_and_barrier()
+{
+    // The vmcnt wait is assembly because the compiler does not know about the transfers; the
+    // lgkmcnt(0) wait is the builtin so that the compiler DOES know that no LDS operation is
+    // pending after the barrier (otherwise its first wait after the barrier is a full
+    // lgkmcnt(0) that also covers the reads issued since).  0xC07F = vmcnt 63, expcnt 7,
+    // lgkmcnt 0 in the gfx9 encoding.
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// A kernel-argument scalar that is first used inside the main loop is fetched by a scalar
+// load the compiler is free to leave pending at loop entry; scalar loads complete out of
+// order, so the loop would then contain an s_waitcnt lgkmcnt(0) that also drains every LDS
+// read issued in that iteration.  Passing the value through this function pins its load (and
+// the wait for it) to the point of the call.
+__device__ __forceinline__ float pin_scalar(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, x)));
+}
+__device__ __forceinline__ int pin_scalar(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
 // Cycle accounting for development builds (-DATTN_CYCLES): every work-group adds its
 // elapsed shader cycles and 100 MHz wall ticks to a per-kernel slot, so that a change can be
 // judged in cycles although the shader clock floats with load.  Not compiled into the
@@ -117,6 +182,30 @@ static __device__ unsigned long long g_attn_cycles[4][4];  // [slot][cycles, wal
 #else
 #define ATTN_CYCLES_BEGIN() ((void)0)
 #define ATTN_CYCLES_END(slot) ((void)0)
+#endif
+// Finer split for development builds (-DATTN_CYCLES -DATTN_PHASES): a wave accumulates the
+// cycles between successive ATTN_PHASE(n) marks into bucket n; thread `tid0` of every
+// work-group adds its buckets to slot 3, starting at entry `first`.
+#if defined(ATTN_CYCLES) && defined(ATTN_PHASES)
+#define ATTN_PHASE_INIT() \
+    long long attn_pt_ = __builtin_readcyclecounter(); unsigned long long attn_pa_[4] = {0, 0, 0, 0}
+#define ATTN_PHASE(n)                                                  \
+    do {                                                               \
+        const long long t_ = __builtin_readcyclecounter();             \
+        attn_pa_[n] += (unsigned long long)(t_ - attn_pt_);            \
+        attn_pt_ = t_;                                                 \
+    } while (0)
+#define ATTN_PHASE_END(tid0, first)                                    \
+    do {                                                               \
+        if ((int)threadIdx.x == (tid0)) {                              \
+            for (int n_ = 0; n_ + (first) < 4; ++n_)                   \
+                atomicAdd(&g_attn_cycles[3][(first) + n_], attn_pa_[n_]); \
+        }                                                              \
+    } while (0)
+#else
+#define ATTN_PHASE_INIT() ((void)0)
+#define ATTN_PHASE(n) ((void)0)
+#define ATTN_PHASE_END(tid0, first) ((void)0)
 #endif
 
 // Work-group id -> position in a virtual order in which consecutive positions land on the
