@@ -436,6 +436,11 @@ attn_bwd_dq_kernel(const BwdArgs a)
         tr_off[j] = row * RB + ((chunk ^ swz(row)) << 4) + (l & 1) * 8;
     }
 
+    // All register loads above must be complete before the loop: the compiler would otherwise
+    // place its own vmcnt waits for them at their first use inside the loop, where they would
+    // also wait for the tile transfers (which it does not see) in every iteration.
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+
     int pos = 0;
     for (int kt = 0; kt < n_kt; ++kt) {
         // tile kt must have landed; tile kt+1 (if any) may stay in flight
