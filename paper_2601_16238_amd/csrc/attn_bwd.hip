@@ -264,11 +264,21 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
         wait_vm_and_barrier<0>();  // the consumers' last slot
         }
     } else {
-        f32x16 dv[DB], dk[DB];
+        // Consumers.  Wave 4+cw accumulates ONE output for the 64 keys of two producers
+        // (2*(cw>>1) and the next): dV^T += dO^T P for even cw, dK^T += Q^T dS for odd cw.
+        // Each transposed fragment read from LDS then feeds two MFMAs (one per key block),
+        // which halves the consumers' LDS traffic against one wave per 32 keys and both
+        // outputs.
+        const int cw = w - C::kPairs;
+        const int kind = cw & 1, half = cw >> 1;
+        const int kA = kt * C::kBlk + half * 64, kB = kA + 32;  // first keys of the two blocks
+        f32x16 acc[2][DB];
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) { dv[db][i] = 0.f; dk[db][i] = 0.f; }
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[kb][db][i] = 0.f;
         // transpose-read addresses: the 16-lane group reads rows 4h+e (e = 0..3), +8 for the
         // second read, 64 bytes of d block db per row; byte offset within a slot tensor
         int tr_off[2];
@@ -278,11 +288,25 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
             const int chunk = 2 * ((l >> 4) & 1) + ((l >> 1) & 1);
             tr_off[j] = row * RB + ((chunk ^ swz(row)) << 4) + (l & 1) * 8;
         }
+        // wave-uniform: does slot t hold a real row that sees some key of the block at kfirst
+        auto block_active = [&](int t, int kfirst) {
+            return t * C::kRows < S && (!CAUSAL || t * C::kRows + 31 >= kfirst);
+        };
+        const bf16x8 *const Xc = reinterpret_cast<const bf16x8 *>(smem + C::kOffXchg) +
+                                 (2 * half) * 256 + kind * 128 + l;
         auto consume = [&](int t, int rs) {
-            const char *Qt = smem + rs * C::kSlotBytes;
-            const char *Gt = Qt + C::kTensorBytes;
-            const bf16x8 *x = Xs + (t & 1) * (C::kPairs * 256);
-            const bf16x8 pv[2] = {x[0], x[64]}, sv[2] = {x[128], x[192]};
+            const bool actA = block_active(t, kA), actB = block_active(t, kB);
+            if (!actA) return;  // kA < kB: then the second block is not active either
+            const char *Tt = smem + rs * C::kSlotBytes + (kind ? 0 : C::kTensorBytes);
+            const bf16x8 *x = Xc + (t & 1) * (C::kPairs * 256);
+            const bf16x8 opA[2] = {x[0], x[64]};
+            // Slots above the diagonal of the second key block: its producer wrote nothing,
+            // so the block gets zero operands (a second code path without its MFMAs makes
+            // the compiler spill the accumulators).
+            bf16x8 opB[2];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) opB[0][i] = opB[1][i] = 0;
+            if (actB) { opB[0] = x[256]; opB[1] = x[256 + 64]; }
 #pragma unroll
             for (int cc = 0; cc < 2; ++cc) {
 #pragma unroll
@@ -290,12 +314,10 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
                     // d block db = chunks 4db..4db+3: flips bits 6.. of the swizzled offset
                     const int o0 = (tr_off[0] ^ (db << 6)) + cc * 16 * RB;
                     const int o1 = (tr_off[1] ^ (db << 6)) + cc * 16 * RB;
-                    const bf16x8 gT = join8(lds_read_tr((const bf16 *)(Gt + o0)),
-                                            lds_read_tr((const bf16 *)(Gt + o1)));
-                    dv[db] = mfma32(gT, pv[cc], dv[db]);
-                    const bf16x8 qT = join8(lds_read_tr((const bf16 *)(Qt + o0)),
-                                            lds_read_tr((const bf16 *)(Qt + o1)));
-                    dk[db] = mfma32(qT, sv[cc], dk[db]);
+                    const bf16x8 T = join8(lds_read_tr((const bf16 *)(Tt + o0)),
+                                           lds_read_tr((const bf16 *)(Tt + o1)));
+                    acc[0][db] = mfma32(T, opA[cc], acc[0][db]);
+                    acc[1][db] = mfma32(T, opB[cc], acc[1][db]);
                 }
             }
         };
@@ -305,27 +327,28 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
         int rs = 0;  // ring position of the producers' slot t; the consumers' is one behind
         for (int t = t0; t < n_slot; ++t) {
             wait_vm_and_barrier<0>();
-            if (t > t0 && active(t - 1)) consume(t - 1, rs == 0 ? C::kRing - 1 : rs - 1);
+            if (t > t0) consume(t - 1, rs == 0 ? C::kRing - 1 : rs - 1);
             rs = ring_next(rs);
         }
         wait_vm_and_barrier<0>();
-        if (n_slot > t0 && active(n_slot - 1)) consume(n_slot - 1, rs == 0 ? C::kRing - 1 : rs - 1);
+        if (n_slot > t0) consume(n_slot - 1, rs == 0 ? C::kRing - 1 : rs - 1);
         }
 
-        if (key < S) {
-            bf16 *dKp = a.dK + base_kv + (int64_t)key * a.kv_stride_s;
-            bf16 *dVp = a.dV + base_kv + (int64_t)key * a.kv_stride_s;
-            const float sc = a.scale;
+        bf16 *const out = kind ? a.dK : a.dV;
+        const float sc = kind ? a.scale : 1.f;
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+        for (int kb = 0; kb < 2; ++kb) {
+            const int okey = kA + 32 * kb + r;
+            if (okey < S) {
+                bf16 *op = out + base_kv + (int64_t)okey * a.kv_stride_s;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int col = 32 * db + 8 * g + 4 * h;
-                    *(bf16x4 *)(dVp + col) = pack4(dv[db][4 * g], dv[db][4 * g + 1],
-                                                   dv[db][4 * g + 2], dv[db][4 * g + 3]);
-                    *(bf16x4 *)(dKp + col) = pack4(dk[db][4 * g] * sc, dk[db][4 * g + 1] * sc,
-                                                   dk[db][4 * g + 2] * sc, dk[db][4 * g + 3] * sc);
-                }
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        *(bf16x4 *)(op + 32 * db + 8 * g + 4 * h) =
+                            pack4(acc[kb][db][4 * g] * sc, acc[kb][db][4 * g + 1] * sc,
+                                  acc[kb][db][4 * g + 2] * sc, acc[kb][db][4 * g + 3] * sc);
+            }
         }
     }
     ATTN_CYCLES_END(1);
