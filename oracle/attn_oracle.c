@@ -27,6 +27,14 @@
  * head are the sums of the formulas above over the G query heads that read it.  Hkv = Hq is
  * plain multi-head attention.
  *
+ * Rectangular form (queries and keys of different lengths, e.g. decoding or chunked prefill
+ * against a longer key/value cache): Q, O, dO, dQ have Sq rows, K, V, dK, dV have Sk rows, and
+ * the causal mask is aligned to the bottom-right corner, i.e. the LAST query row sees every
+ * key: allowed(i) = {0 .. i + Sk - Sq}.  That is the mask of square causal attention over Sk
+ * positions restricted to its last Sq query rows (the paper does not spell the alignment
+ * out; this is the reading under which a cached prefix keeps its meaning).  Causal with
+ * Sk < Sq would leave rows without any key and is rejected.  Sq = Sk is the square form.
+ *
  * Inputs are bf16 bit patterns (uint16) laid out contiguously as [B,H,S,D]; they are
  * widened exactly to double.  `scale` is the fp32 value the GPU receives, widened to
  * double.  All arithmetic is double; exp/log are libm's.  There is no tiling, no online
@@ -66,7 +74,11 @@ static double *widen(const uint16_t *x, size_t n)
     return y;
 }
 
-static inline int n_allowed(int i, int S, int causal) { return causal ? i + 1 : S; }
+/* number of keys row i may attend to: keys 0 .. n_allowed-1 */
+static inline int n_allowed(int i, int Sq, int Sk, int causal)
+{
+    return causal ? i + 1 + (Sk - Sq) : Sk;
+}
 
 int oracle_num_threads(void)
 {
@@ -87,27 +99,29 @@ static inline int thread_id(void)
 }
 
 /*
- * Forward.  O: [B,H,S,D] double, LSE: [B,H,S] double.
- * P_out (optional, may be NULL): [B,H,S,S] double, the full probability matrix with
+ * Forward.  O: [B,H,Sq,D] double, LSE: [B,H,Sq] double; K, V: [B,Hkv,Sk,D].
+ * P_out (optional, may be NULL): [B,H,Sq,Sk] double, the full probability matrix with
  * explicit zeros outside allowed(i) -- for small test shapes only.
  * Returns 0, or -1 on allocation failure / bad shape.
  */
-int oracle_attn_fwd_gqa(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
-                        int B, int H, int Hkv, int S, int D, float scale_f32, int causal,
-                        double *O, double *LSE, double *P_out)
+int oracle_attn_fwd_rect(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
+                         int B, int H, int Hkv, int S, int Sk, int D, float scale_f32, int causal,
+                         double *O, double *LSE, double *P_out)
 {
-    if (B < 1 || H < 1 || Hkv < 1 || H % Hkv != 0 || S < 1 || D < 1) return -1;
+    /* S is the query length Sq throughout this function */
+    if (B < 1 || H < 1 || Hkv < 1 || H % Hkv != 0 || S < 1 || Sk < 1 || D < 1) return -1;
+    if (causal && Sk < S) return -1;
     const int G = H / Hkv; /* query heads per K/V head */
-    const size_t BH = (size_t)B * H, n = BH * S * D, nkv = (size_t)B * Hkv * S * D;
+    const size_t BH = (size_t)B * H, n = BH * S * D, nkv = (size_t)B * Hkv * Sk * D;
     const double scale = (double)scale_f32;
     double *Q = widen(Qb, n), *K = widen(Kb, nkv), *V = widen(Vb, nkv);
     const int nt = oracle_num_threads();
-    double *scratch = (double *)malloc((size_t)nt * S * sizeof(double)); /* one row per thread */
+    double *scratch = (double *)malloc((size_t)nt * Sk * sizeof(double)); /* one row per thread */
     const int fail = (!Q || !K || !V || !scratch);
     if (!fail) {
 #pragma omp parallel num_threads(nt)
         {
-            double *s = scratch + (size_t)thread_id() * S;
+            double *s = scratch + (size_t)thread_id() * Sk;
             {
 #pragma omp for schedule(dynamic, 16)
                 for (long long r = 0; r < (long long)(BH * S); ++r) {
@@ -115,8 +129,8 @@ int oracle_attn_fwd_gqa(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *
                     const int i = (int)((size_t)r % S);
                     const double *q = Q + (bh * S + i) * D;
                     const size_t bkv = (bh / H) * Hkv + (bh % H) / G; /* K/V head of this row */
-                    const double *Kh = K + bkv * S * D, *Vh = V + bkv * S * D;
-                    const int na = n_allowed(i, S, causal);
+                    const double *Kh = K + bkv * Sk * D, *Vh = V + bkv * Sk * D;
+                    const int na = n_allowed(i, S, Sk, causal);
                     double m = -INFINITY;
                     for (int j = 0; j < na; ++j) {
                         double acc = 0.0;
@@ -132,17 +146,24 @@ int oracle_attn_fwd_gqa(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *
                     for (int d = 0; d < D; ++d) o[d] = 0.0;
                     for (int j = 0; j < na; ++j) {
                         const double p = exp(s[j] - lse);
-                        if (P_out) P_out[(bh * S + i) * S + j] = p;
+                        if (P_out) P_out[(bh * S + i) * Sk + j] = p;
                         for (int d = 0; d < D; ++d) o[d] += p * Vh[(size_t)j * D + d];
                     }
                     if (P_out)
-                        for (int j = na; j < S; ++j) P_out[(bh * S + i) * S + j] = 0.0;
+                        for (int j = na; j < Sk; ++j) P_out[(bh * S + i) * Sk + j] = 0.0;
                 }
             }
         }
     }
     free(Q); free(K); free(V); free(scratch);
     return fail ? -1 : 0;
+}
+
+int oracle_attn_fwd_gqa(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
+                        int B, int H, int Hkv, int S, int D, float scale_f32, int causal,
+                        double *O, double *LSE, double *P_out)
+{
+    return oracle_attn_fwd_rect(Qb, Kb, Vb, B, H, Hkv, S, S, D, scale_f32, causal, O, LSE, P_out);
 }
 
 int oracle_attn_fwd(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
@@ -154,32 +175,34 @@ int oracle_attn_fwd(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
 
 /*
  * Backward.  Recomputes LSE and P in fp64 from Q,K (it never sees the GPU's O or LSE).
- * dQ,dK,dV: [B,H,S,D] double.  dS_out (optional): [B,H,S,S] double, for small shapes.
+ * dS_out (optional): [B,H,Sq,Sk] double, for small shapes.
  * Pass 1 (row-wise):    LSE_i, delta_i, dQ_i.
  * Pass 2 (column-wise): dK_j, dV_j from P_ij and dS_ij recomputed for column j, summed over
  *                       the query heads of the group in head order.
- * dQ: [B,H,S,D]; dK,dV: [B,Hkv,S,D].
+ * dQ: [B,H,Sq,D]; dK,dV: [B,Hkv,Sk,D].
  */
-int oracle_attn_bwd_gqa(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
-                        const uint16_t *dOb,
-                        int B, int H, int Hkv, int S, int D, float scale_f32, int causal,
-                        double *dQ, double *dK, double *dV, double *dS_out)
+int oracle_attn_bwd_rect(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
+                         const uint16_t *dOb,
+                         int B, int H, int Hkv, int S, int Sk, int D, float scale_f32, int causal,
+                         double *dQ, double *dK, double *dV, double *dS_out)
 {
-    if (B < 1 || H < 1 || Hkv < 1 || H % Hkv != 0 || S < 1 || D < 1) return -1;
+    /* S is the query length Sq throughout this function */
+    if (B < 1 || H < 1 || Hkv < 1 || H % Hkv != 0 || S < 1 || Sk < 1 || D < 1) return -1;
+    if (causal && Sk < S) return -1;
     const int G = H / Hkv;
-    const size_t BH = (size_t)B * H, n = BH * S * D, BHkv = (size_t)B * Hkv, nkv = BHkv * S * D;
+    const size_t BH = (size_t)B * H, n = BH * S * D, BHkv = (size_t)B * Hkv, nkv = BHkv * Sk * D;
     const double scale = (double)scale_f32;
     double *Q = widen(Qb, n), *K = widen(Kb, nkv), *V = widen(Vb, nkv), *dO = widen(dOb, n);
     double *LSE = (double *)malloc(BH * S * sizeof(double));
     double *delta = (double *)malloc(BH * S * sizeof(double));
     const int nt = oracle_num_threads();
-    double *scratch = (double *)malloc((size_t)nt * 2 * S * sizeof(double)); /* two rows per thread */
+    double *scratch = (double *)malloc((size_t)nt * 2 * Sk * sizeof(double)); /* two rows per thread */
     const int fail = (!Q || !K || !V || !dO || !LSE || !delta || !scratch);
     if (!fail) {
 #pragma omp parallel num_threads(nt)
         {
-            double *s = scratch + (size_t)thread_id() * 2 * S;
-            double *ds = s + S;
+            double *s = scratch + (size_t)thread_id() * 2 * Sk;
+            double *ds = s + Sk;
             {
                 /* pass 1: one query row at a time */
 #pragma omp for schedule(dynamic, 16)
@@ -189,8 +212,8 @@ int oracle_attn_bwd_gqa(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *
                     const double *q = Q + (bh * S + i) * D;
                     const double *g = dO + (bh * S + i) * D;
                     const size_t bkv = (bh / H) * Hkv + (bh % H) / G;
-                    const double *Kh = K + bkv * S * D, *Vh = V + bkv * S * D;
-                    const int na = n_allowed(i, S, causal);
+                    const double *Kh = K + bkv * Sk * D, *Vh = V + bkv * Sk * D;
+                    const int na = n_allowed(i, S, Sk, causal);
                     double m = -INFINITY;
                     for (int j = 0; j < na; ++j) {
                         double acc = 0.0;
@@ -217,23 +240,25 @@ int oracle_attn_bwd_gqa(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *
                     for (int d = 0; d < D; ++d) dq[d] = 0.0;
                     for (int j = 0; j < na; ++j) {
                         const double dsij = s[j] * (ds[j] - del);
-                        if (dS_out) dS_out[(bh * S + i) * S + j] = dsij;
+                        if (dS_out) dS_out[(bh * S + i) * Sk + j] = dsij;
                         for (int d = 0; d < D; ++d) dq[d] += dsij * Kh[(size_t)j * D + d];
                     }
                     for (int d = 0; d < D; ++d) dq[d] *= scale;
                     if (dS_out)
-                        for (int j = na; j < S; ++j) dS_out[(bh * S + i) * S + j] = 0.0;
+                        for (int j = na; j < Sk; ++j) dS_out[(bh * S + i) * Sk + j] = 0.0;
                 }
                 /* pass 2: one key column at a time (implicit barrier above) */
 #pragma omp for schedule(dynamic, 16)
-                for (long long r = 0; r < (long long)(BHkv * S); ++r) {
-                    const size_t bkv = (size_t)r / S;
-                    const int j = (int)((size_t)r % S);
-                    const double *k = K + (bkv * S + j) * D;
-                    const double *v = V + (bkv * S + j) * D;
-                    double *dk = dK + (bkv * S + j) * D, *dv = dV + (bkv * S + j) * D;
+                for (long long r = 0; r < (long long)(BHkv * Sk); ++r) {
+                    const size_t bkv = (size_t)r / Sk;
+                    const int j = (int)((size_t)r % Sk);
+                    const double *k = K + (bkv * Sk + j) * D;
+                    const double *v = V + (bkv * Sk + j) * D;
+                    double *dk = dK + (bkv * Sk + j) * D, *dv = dV + (bkv * Sk + j) * D;
                     for (int d = 0; d < D; ++d) { dk[d] = 0.0; dv[d] = 0.0; }
-                    const int i0 = causal ? j : 0; /* rows i with j in allowed(i) */
+                    /* rows i with j in allowed(i): j <= i + Sk - Sq */
+                    int i0 = causal ? j - (Sk - S) : 0;
+                    if (i0 < 0) i0 = 0;
                     for (int gq = 0; gq < G; ++gq) { /* the query heads that read this K/V head */
                         const size_t bh = (bkv / Hkv) * H + (bkv % Hkv) * G + gq;
                         const double *Qh = Q + bh * S * D, *Gh = dO + bh * S * D;
@@ -253,6 +278,15 @@ int oracle_attn_bwd_gqa(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *
     }
     free(Q); free(K); free(V); free(dO); free(LSE); free(delta); free(scratch);
     return fail ? -1 : 0;
+}
+
+int oracle_attn_bwd_gqa(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
+                        const uint16_t *dOb,
+                        int B, int H, int Hkv, int S, int D, float scale_f32, int causal,
+                        double *dQ, double *dK, double *dV, double *dS_out)
+{
+    return oracle_attn_bwd_rect(Qb, Kb, Vb, dOb, B, H, Hkv, S, S, D, scale_f32, causal,
+                                dQ, dK, dV, dS_out);
 }
 
 int oracle_attn_bwd(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,

@@ -36,12 +36,12 @@ def _load():
         u16p = ctypes.POINTER(ctypes.c_uint16)
         f64p = ctypes.POINTER(ctypes.c_double)
         i = ctypes.c_int
-        lib.oracle_attn_fwd_gqa.argtypes = [u16p, u16p, u16p, i, i, i, i, i, ctypes.c_float, i,
-                                            f64p, f64p, f64p]
-        lib.oracle_attn_fwd_gqa.restype = i
-        lib.oracle_attn_bwd_gqa.argtypes = [u16p, u16p, u16p, u16p, i, i, i, i, i, ctypes.c_float,
-                                            i, f64p, f64p, f64p, f64p]
-        lib.oracle_attn_bwd_gqa.restype = i
+        lib.oracle_attn_fwd_rect.argtypes = [u16p, u16p, u16p, i, i, i, i, i, i, ctypes.c_float, i,
+                                             f64p, f64p, f64p]
+        lib.oracle_attn_fwd_rect.restype = i
+        lib.oracle_attn_bwd_rect.argtypes = [u16p, u16p, u16p, u16p, i, i, i, i, i, i,
+                                             ctypes.c_float, i, f64p, f64p, f64p, f64p]
+        lib.oracle_attn_bwd_rect.restype = i
         lib.oracle_num_threads.argtypes = []
         lib.oracle_num_threads.restype = i
         _lib = lib
@@ -63,11 +63,12 @@ def _u16(x, shape=None):
 
 
 def _kv(x, qshape):
-    """K or V: [B,Hkv,S,D] with Hkv dividing the query head count (Hkv = H: multi-head)."""
+    """K or V: [B,Hkv,Sk,D] with Hkv dividing the query head count (Hkv = H: multi-head);
+    Sk may differ from the query length (rectangular attention)."""
     x = _u16(x)
     B, H, S, D = qshape
-    if x.shape[0] != B or x.shape[2] != S or x.shape[3] != D or x.shape[1] < 1 or H % x.shape[1]:
-        raise ValueError("K/V must be [B,Hkv,S,D] with Hkv dividing H")
+    if x.shape[0] != B or x.shape[3] != D or x.shape[1] < 1 or H % x.shape[1]:
+        raise ValueError("K/V must be [B,Hkv,Sk,D] with Hkv dividing H")
     return x
 
 
@@ -76,16 +77,17 @@ def _p(a, ct):
 
 
 def attn_fwd(Q, K, V, scale, causal, want_probs=False):
-    """O [B,H,S,D] f64, LSE [B,H,S] f64 (natural log) [, P [B,H,S,S] f64].
-    K, V: [B,Hkv,S,D]; query head h reads K/V head h // (H // Hkv)."""
+    """O [B,H,Sq,D] f64, LSE [B,H,Sq] f64 (natural log) [, P [B,H,Sq,Sk] f64].
+    K, V: [B,Hkv,Sk,D]; query head h reads K/V head h // (H // Hkv).  With causal=True and
+    Sk > Sq the mask is aligned bottom-right: row i sees keys 0 .. i + Sk - Sq."""
     Q = _u16(Q); K = _kv(K, Q.shape); V = _u16(V, K.shape)
     B, H, S, D = Q.shape
-    Hkv = K.shape[1]
+    Hkv, Sk = K.shape[1], K.shape[2]
     O = np.empty((B, H, S, D), np.float64)
     LSE = np.empty((B, H, S), np.float64)
-    P = np.empty((B, H, S, S), np.float64) if want_probs else None
-    rc = _load().oracle_attn_fwd_gqa(_p(Q, ctypes.c_uint16), _p(K, ctypes.c_uint16),
-                                     _p(V, ctypes.c_uint16), B, H, Hkv, S, D,
+    P = np.empty((B, H, S, Sk), np.float64) if want_probs else None
+    rc = _load().oracle_attn_fwd_rect(_p(Q, ctypes.c_uint16), _p(K, ctypes.c_uint16),
+                                     _p(V, ctypes.c_uint16), B, H, Hkv, S, Sk, D,
                                      ctypes.c_float(np.float32(scale)), int(bool(causal)),
                                      _p(O, ctypes.c_double), _p(LSE, ctypes.c_double),
                                      _p(P, ctypes.c_double))
@@ -95,22 +97,22 @@ def attn_fwd(Q, K, V, scale, causal, want_probs=False):
 
 
 def attn_probs(Q, K, V, scale, causal):
-    """The full probability matrix P [B,H,S,S] (zeros outside the mask); small shapes only."""
+    """The full probability matrix P [B,H,Sq,Sk] (zeros outside the mask); small shapes only."""
     return attn_fwd(Q, K, V, scale, causal, want_probs=True)[2]
 
 
 def attn_bwd(Q, K, V, dO, scale, causal, want_dscores=False):
-    """dQ [B,H,S,D], dK, dV [B,Hkv,S,D] f64 [, dS [B,H,S,S] f64] for upstream gradient dO on O."""
+    """dQ [B,H,Sq,D], dK, dV [B,Hkv,Sk,D] f64 [, dS [B,H,Sq,Sk] f64] for upstream gradient dO on O."""
     Q = _u16(Q); K = _kv(K, Q.shape); V = _u16(V, K.shape); dO = _u16(dO, Q.shape)
     B, H, S, D = Q.shape
-    Hkv = K.shape[1]
+    Hkv, Sk = K.shape[1], K.shape[2]
     dQ = np.empty((B, H, S, D), np.float64)
-    dK = np.empty((B, Hkv, S, D), np.float64)
+    dK = np.empty((B, Hkv, Sk, D), np.float64)
     dV = np.empty_like(dK)
-    dS = np.empty((B, H, S, S), np.float64) if want_dscores else None
-    rc = _load().oracle_attn_bwd_gqa(_p(Q, ctypes.c_uint16), _p(K, ctypes.c_uint16),
+    dS = np.empty((B, H, S, Sk), np.float64) if want_dscores else None
+    rc = _load().oracle_attn_bwd_rect(_p(Q, ctypes.c_uint16), _p(K, ctypes.c_uint16),
                                      _p(V, ctypes.c_uint16), _p(dO, ctypes.c_uint16),
-                                     B, H, Hkv, S, D, ctypes.c_float(np.float32(scale)),
+                                     B, H, Hkv, S, Sk, D, ctypes.c_float(np.float32(scale)),
                                      int(bool(causal)), _p(dQ, ctypes.c_double),
                                      _p(dK, ctypes.c_double), _p(dV, ctypes.c_double),
                                      _p(dS, ctypes.c_double))
@@ -120,5 +122,5 @@ def attn_bwd(Q, K, V, dO, scale, causal, want_dscores=False):
 
 
 def attn_dscores(Q, K, V, dO, scale, causal):
-    """dS [B,H,S,S] = P * (dP - delta) (zeros outside the mask); small shapes only."""
+    """dS [B,H,Sq,Sk] = P * (dP - delta) (zeros outside the mask); small shapes only."""
     return attn_bwd(Q, K, V, dO, scale, causal, want_dscores=True)[3]

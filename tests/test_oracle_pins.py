@@ -316,3 +316,96 @@ def test_gqa_rejects_non_dividing_head_counts():
     x = gqa_inputs(1, 4, 3, 5, 8, seed=62)
     with pytest.raises(ValueError):
         oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], False)
+
+
+# ---- rectangular attention: Sq query rows against Sk keys, causal mask aligned bottom-right --
+# (decoding / chunked prefill against a longer key-value cache).  Row i sees keys 0..i+Sk-Sq.
+
+def rect_inputs(B, Hq, Hkv, Sq, Sk, D, seed):
+    x = rnd(B, Hq, Sq, D, seed)
+    kv = rnd(B, Hkv, Sk, D, seed + 2000)
+    x["K"], x["V"] = kv["K"], kv["V"]
+    return x
+
+
+RECT_CASES = [(1, 2, 2, 1, 9, 8), (2, 2, 1, 3, 17, 16), (1, 4, 2, 5, 5, 8), (1, 1, 1, 7, 40, 16),
+              (1, 2, 2, 33, 65, 64)]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D", RECT_CASES)
+def test_rect_causal_is_the_tail_of_square_causal(B, Hq, Hkv, Sq, Sk, D):
+    """Reduction to the square case pinned above.  Put the Sq query rows at the END of a
+    square problem of length Sk (any rows in front, here zeros, with zero upstream gradient):
+    the tail of O, LSE and dQ is the rectangular result, and since the front rows carry no
+    gradient, dK and dV are the rectangular ones as well."""
+    x = rect_inputs(B, Hq, Hkv, Sq, Sk, D, seed=70 + Sq)
+    Qs = np.zeros((B, Hq, Sk, D), np.uint16); Qs[:, :, Sk - Sq:] = x["Q"]
+    Gs = np.zeros((B, Hq, Sk, D), np.uint16); Gs[:, :, Sk - Sq:] = x["dO"]
+    O, LSE = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], True)
+    dQ, dK, dV = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], True)
+    Os, Ls = oracle.attn_fwd(Qs, x["K"], x["V"], x["scale"], True)
+    dQs, dKs, dVs = oracle.attn_bwd(Qs, x["K"], x["V"], Gs, x["scale"], True)
+    assert O.shape == (B, Hq, Sq, D) and dK.shape == (B, Hkv, Sk, D)
+    np.testing.assert_allclose(O, Os[:, :, Sk - Sq:], rtol=0, atol=1e-14)
+    np.testing.assert_allclose(LSE, Ls[:, :, Sk - Sq:], rtol=0, atol=1e-14)
+    np.testing.assert_allclose(dQ, dQs[:, :, Sk - Sq:], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(dK, dKs, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dV, dVs, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D", RECT_CASES[:4] + [(1, 2, 1, 6, 3, 8)])
+def test_rect_against_torch_fp64_autograd(B, Hq, Hkv, Sq, Sk, D, causal):
+    """Independent library route with an explicit boolean mask key <= row + Sk - Sq."""
+    if causal and Sk < Sq:
+        pytest.skip("rows without keys: rejected, see test_rect_rejects_causal_with_fewer_keys")
+    x = rect_inputs(B, Hq, Hkv, Sq, Sk, D, seed=80 + Sk)
+    G = Hq // Hkv
+    t = {k: torch.tensor(f64(x[k]), dtype=torch.float64, requires_grad=(k != "dO"))
+         for k in ("Q", "K", "V", "dO")}
+    Kt, Vt = t["K"].repeat_interleave(G, dim=1), t["V"].repeat_interleave(G, dim=1)
+    s = (t["Q"] @ Kt.transpose(-1, -2)) * float(np.float32(x["scale"]))
+    if causal:
+        keep = torch.arange(Sk)[None, :] <= torch.arange(Sq)[:, None] + (Sk - Sq)
+        s = s.masked_fill(~keep, float("-inf"))
+    o_t = torch.softmax(s, dim=-1) @ Vt
+    gq, gk, gv = torch.autograd.grad(o_t, (t["Q"], t["K"], t["V"]), grad_outputs=t["dO"])
+    O, LSE = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], causal)
+    dQ, dK, dV = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], causal)
+    np.testing.assert_allclose(O, o_t.detach().numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(LSE, torch.logsumexp(s, dim=-1).detach().numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dQ, gq.numpy(), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(dK, gk.numpy(), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(dV, gv.numpy(), rtol=0, atol=1e-11)
+
+
+def test_rect_decode_row_closed_form_and_mask_shape():
+    """One query row (decoding): causal and non-causal coincide (the last row sees every key),
+    O is the softmax-weighted mean of V written out with numpy.  With Sq = 3, Sk = 5 the
+    causal probability matrix has exactly the bottom-right staircase of zeros."""
+    x = rect_inputs(1, 1, 1, 1, 13, 8, seed=91)
+    q, K, V = f64(x["Q"])[0, 0, 0], f64(x["K"])[0, 0], f64(x["V"])[0, 0]
+    s = (K @ q) * float(np.float32(x["scale"]))
+    p = np.exp(s - s.max()); p /= p.sum()
+    for causal in (False, True):
+        O, LSE = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], causal)
+        np.testing.assert_allclose(O[0, 0, 0], p @ V, rtol=0, atol=1e-14)
+        np.testing.assert_allclose(LSE[0, 0, 0], s.max() + np.log(np.exp(s - s.max()).sum()),
+                                   rtol=0, atol=1e-13)
+    y = rect_inputs(1, 1, 1, 3, 5, 8, seed=92)
+    P = oracle.attn_probs(y["Q"], y["K"], y["V"], y["scale"], True)[0, 0]
+    assert P.shape == (3, 5)
+    assert ((P > 0) == np.array([[1, 1, 1, 0, 0], [1, 1, 1, 1, 0], [1, 1, 1, 1, 1]], bool)).all()
+    np.testing.assert_allclose(P.sum(-1), 1.0, rtol=0, atol=1e-14)
+    dS = oracle.attn_dscores(y["Q"], y["K"], y["V"], y["dO"], y["scale"], True)[0, 0]
+    assert (dS[P == 0] == 0).all()
+    np.testing.assert_allclose(dS.sum(-1), 0.0, rtol=0, atol=1e-13)
+
+
+def test_rect_rejects_causal_with_fewer_keys():
+    x = rect_inputs(1, 1, 1, 6, 3, 8, seed=93)
+    oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], False)      # fine without the mask
+    with pytest.raises(RuntimeError):
+        oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], True)
+    with pytest.raises(RuntimeError):
+        oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], True)
