@@ -159,6 +159,53 @@ int attn_bwd_gqa_stages(const void *Q, const void *K, const void *V, const void 
                         void *workspace, size_t workspace_bytes,
                         const attn_gqa_params_t *p, void *hip_stream, uint32_t stages);
 
+/*
+ * Rectangular variant: Sq query rows against Sk key/value rows (decoding or chunked prefill
+ * against a longer key/value cache, cross attention; paper: the kernel-suite discussion of
+ * small-batch grouped-query prefill, the case its table reports as slower than the library
+ * baseline).  Q, O, dO, dQ are [B,Hq,Sq,D] by the q_* strides, K, V, dK, dV are [B,Hkv,Sk,D]
+ * by the kv_* strides, LSE is [B,Hq,Sq].  With causal != 0 the mask is aligned to the
+ * bottom-right corner: query row i sees keys 0 .. i + Sk - Sq, i.e. the rows are the LAST Sq
+ * positions of a causal sequence of length Sk; causal with Sk < Sq is ATTN_ERR_SHAPE.
+ * Sq == Sk is the grouped-query call above.
+ *
+ * Forward, split over the keys: when B*Hq*ceil(Sq/256) work-groups would leave most of the
+ * chip idle (decoding: Sq = 1), the key range is cut into splits that run as separate
+ * work-groups and write fp32 partial results to `workspace`; a second small kernel merges
+ * them (log-sum-exp weights).  attn_fwd_rect_workspace_bytes returns what that needs for the
+ * problem, 0 when it would not split.  workspace == NULL (with any size) is allowed and
+ * means: do not split.  A non-NULL workspace must be 256-byte aligned and at least that
+ * large, else ATTN_ERR_WORKSPACE; its contents are undefined on entry and exit.  The split
+ * plan depends only on the shape, so results are deterministic.
+ *
+ * Backward: as attn_bwd_gqa, workspace of attn_bwd_rect_workspace_bytes(p) bytes (two fp32
+ * per query row).  Keys that no row sees get zero gradients.
+ */
+typedef struct {
+    int32_t B, Hq, Hkv, Sq, Sk, D;
+    int64_t q_stride_b, q_stride_h, q_stride_s;     /* Q, O, dO, dQ: element strides, D contiguous */
+    int64_t kv_stride_b, kv_stride_h, kv_stride_s;  /* K, V, dK, dV                               */
+    float scale;
+    int32_t causal;
+} attn_rect_params_t;
+
+/* Fill strides for contiguous [B,Hq,Sq,D] and [B,Hkv,Sk,D] tensors.  Pure host function. */
+void attn_rect_params_contiguous(attn_rect_params_t *p, int32_t B, int32_t Hq, int32_t Hkv,
+                                 int32_t Sq, int32_t Sk, int32_t D, float scale, int32_t causal);
+
+size_t attn_fwd_rect_workspace_bytes(const attn_rect_params_t *p);
+
+int attn_fwd_rect(const void *Q, const void *K, const void *V, void *O, float *LSE,
+                  void *workspace, size_t workspace_bytes,
+                  const attn_rect_params_t *p, void *hip_stream);
+
+size_t attn_bwd_rect_workspace_bytes(const attn_rect_params_t *p);
+
+int attn_bwd_rect(const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                  const float *LSE, void *dQ, void *dK, void *dV,
+                  void *workspace, size_t workspace_bytes,
+                  const attn_rect_params_t *p, void *hip_stream);
+
 /* Static, NUL-terminated description of a status code.  Never NULL. */
 const char *attn_status_string(int status);
 

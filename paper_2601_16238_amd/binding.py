@@ -23,6 +23,8 @@ ATTN_ERR_LAUNCH = -7
 EXPORTS = ("attn_params_contiguous", "attn_fwd", "attn_bwd_workspace_bytes", "attn_bwd",
            "attn_bwd_stages", "attn_gqa_params_contiguous", "attn_fwd_gqa",
            "attn_bwd_gqa_workspace_bytes", "attn_bwd_gqa", "attn_bwd_gqa_stages",
+           "attn_rect_params_contiguous", "attn_fwd_rect_workspace_bytes", "attn_fwd_rect",
+           "attn_bwd_rect_workspace_bytes", "attn_bwd_rect",
            "attn_status_string", "attn_version")
 STAGE_DELTA, STAGE_DKDV, STAGE_DQ = 1, 2, 4
 STAGE_ALL = 7
@@ -40,6 +42,16 @@ class AttnGqaParams(ctypes.Structure):
     """Mirror of attn_gqa_params_t."""
     _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
                 ("S", ctypes.c_int32), ("D", ctypes.c_int32),
+                ("q_stride_b", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
+                ("q_stride_s", ctypes.c_int64), ("kv_stride_b", ctypes.c_int64),
+                ("kv_stride_h", ctypes.c_int64), ("kv_stride_s", ctypes.c_int64),
+                ("scale", ctypes.c_float), ("causal", ctypes.c_int32)]
+
+
+class AttnRectParams(ctypes.Structure):
+    """Mirror of attn_rect_params_t."""
+    _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("Sq", ctypes.c_int32), ("Sk", ctypes.c_int32), ("D", ctypes.c_int32),
                 ("q_stride_b", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
                 ("q_stride_s", ctypes.c_int64), ("kv_stride_b", ctypes.c_int64),
                 ("kv_stride_h", ctypes.c_int64), ("kv_stride_s", ctypes.c_int64),
@@ -89,6 +101,18 @@ def lib():
         L.attn_bwd_gqa.restype = ctypes.c_int
         L.attn_bwd_gqa_stages.argtypes = [vp] * 9 + [vp, ctypes.c_size_t, gp, vp, ctypes.c_uint32]
         L.attn_bwd_gqa_stages.restype = ctypes.c_int
+        rp = ctypes.POINTER(AttnRectParams)
+        L.attn_rect_params_contiguous.argtypes = [rp] + [ctypes.c_int32] * 6 + [ctypes.c_float,
+                                                                               ctypes.c_int32]
+        L.attn_rect_params_contiguous.restype = None
+        L.attn_fwd_rect_workspace_bytes.argtypes = [rp]
+        L.attn_fwd_rect_workspace_bytes.restype = ctypes.c_size_t
+        L.attn_fwd_rect.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_size_t, rp, vp]
+        L.attn_fwd_rect.restype = ctypes.c_int
+        L.attn_bwd_rect_workspace_bytes.argtypes = [rp]
+        L.attn_bwd_rect_workspace_bytes.restype = ctypes.c_size_t
+        L.attn_bwd_rect.argtypes = [vp] * 9 + [vp, ctypes.c_size_t, rp, vp]
+        L.attn_bwd_rect.restype = ctypes.c_int
         L.attn_status_string.argtypes = [ctypes.c_int]
         L.attn_status_string.restype = ctypes.c_char_p
         L.attn_version.argtypes = []
@@ -289,4 +313,112 @@ def attn_bwd_gqa(Q, K, V, O, dO, LSE, scale, causal, dQ=None, dK=None, dV=None, 
         rc = lib().attn_bwd_gqa_stages(*args, int(stages))
     if rc != ATTN_OK:
         raise AttnError(rc, "attn_bwd_gqa")
+    return dQ, dK, dV
+
+
+# ---- rectangular: Q, O, dO, dQ are [B,Hq,Sq,D]; K, V, dK, dV are [B,Hkv,Sk,D]; a causal mask
+# is aligned bottom-right (query row i sees keys 0 .. i + Sk - Sq) ------------------------------
+
+def make_rect_params(B, Hq, Hkv, Sq, Sk, D, scale, causal, q_strides=None, kv_strides=None):
+    """attn_rect_params_t; strides=(sb, sh, ss) in elements or None for contiguous."""
+    p = AttnRectParams()
+    lib().attn_rect_params_contiguous(ctypes.byref(p), B, Hq, Hkv, Sq, Sk, D, float(scale),
+                                      int(bool(causal)))
+    if q_strides is not None:
+        p.q_stride_b, p.q_stride_h, p.q_stride_s = (int(s) for s in q_strides)
+    if kv_strides is not None:
+        p.kv_stride_b, p.kv_stride_h, p.kv_stride_s = (int(s) for s in kv_strides)
+    return p
+
+
+def _rect_params_for(q, k, scale, causal):
+    for t in (q, k):
+        if t.dim() != 4 or t.stride(3) != 1:
+            raise ValueError("expected [B,H,S,D] tensors with a contiguous D axis")
+    B, Hq, Sq, D = q.shape
+    if k.shape[0] != B or k.shape[3] != D:
+        raise ValueError("K/V must be [B,Hkv,Sk,D] matching Q in B and D")
+    return make_rect_params(B, Hq, k.shape[1], Sq, k.shape[2], D, scale, causal,
+                            q.stride()[:3], k.stride()[:3])
+
+
+def attn_fwd_rect_workspace_bytes(B, Hq, Hkv, Sq, Sk, D):
+    """Bytes attn_fwd_rect needs to split this problem over the keys (0: it would not split)."""
+    p = make_rect_params(B, Hq, Hkv, Sq, Sk, D, 1.0, False)
+    return int(lib().attn_fwd_rect_workspace_bytes(ctypes.byref(p)))
+
+
+def attn_fwd_rect(Q, K, V, scale, causal, O=None, LSE=None, workspace=None, split=True,
+                  stream=None):
+    """O [B,Hq,Sq,D], LSE [B,Hq,Sq]; K, V: [B,Hkv,Sk,D].  `split=False` passes no workspace,
+    which keeps the forward in one kernel; otherwise a workspace is allocated when the
+    library's plan asks for one."""
+    import torch
+    if Q.dtype != torch.bfloat16 or not Q.is_cuda:
+        raise ValueError("Q,K,V must be bf16 tensors on the GPU")
+    _same_layout(K, V)
+    if O is None:
+        O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    else:
+        _same_layout(Q, O)
+    B, H, S, D = Q.shape
+    if LSE is None:
+        LSE = torch.empty((B, H, S), dtype=torch.float32, device=Q.device)
+    elif LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != (B, H, S):
+        raise ValueError("LSE must be a contiguous fp32 [B,Hq,Sq] tensor")
+    p = _rect_params_for(Q, K, scale, causal)
+    ws_ptr, ws_bytes = None, 0
+    if split:
+        need = int(lib().attn_fwd_rect_workspace_bytes(ctypes.byref(p)))
+        if workspace is None and need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+        if workspace is not None:
+            ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    rc = lib().attn_fwd_rect(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                             LSE.data_ptr(), ws_ptr, ws_bytes, ctypes.byref(p),
+                             _stream_ptr(torch, stream))
+    if rc != ATTN_OK:
+        raise AttnError(rc, "attn_fwd_rect")
+    return O, LSE
+
+
+def attn_bwd_rect_workspace_bytes(B, Hq, Hkv, Sq, Sk, D):
+    p = make_rect_params(B, Hq, Hkv, Sq, Sk, D, 1.0, False)
+    return int(lib().attn_bwd_rect_workspace_bytes(ctypes.byref(p)))
+
+
+def attn_bwd_rect(Q, K, V, O, dO, LSE, scale, causal, dQ=None, dK=None, dV=None, workspace=None,
+                  stream=None):
+    """dQ [B,Hq,Sq,D], dK, dV [B,Hkv,Sk,D] = rectangular attention backward."""
+    import torch
+    if Q.dtype != torch.bfloat16 or not Q.is_cuda:
+        raise ValueError("tensors must be bf16 on the GPU")
+    _same_layout(Q, O, dO)
+    _same_layout(K, V)
+    if dQ is None:
+        dQ = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    else:
+        _same_layout(Q, dQ)
+    outs = []
+    for t in (dK, dV):
+        if t is None:
+            t = torch.empty_strided(K.shape, K.stride(), dtype=K.dtype, device=K.device)
+        else:
+            _same_layout(K, t)
+        outs.append(t)
+    dK, dV = outs
+    B, H, S, D = Q.shape
+    if LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != (B, H, S):
+        raise ValueError("LSE must be a contiguous fp32 [B,Hq,Sq] tensor")
+    p = _rect_params_for(Q, K, scale, causal)
+    need = int(lib().attn_bwd_rect_workspace_bytes(ctypes.byref(p)))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    rc = lib().attn_bwd_rect(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                             dO.data_ptr(), LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(),
+                             dV.data_ptr(), workspace.data_ptr(),
+                             workspace.numel() * workspace.element_size(), ctypes.byref(p),
+                             _stream_ptr(torch, stream))
+    if rc != ATTN_OK:
+        raise AttnError(rc, "attn_bwd_rect")
     return dQ, dK, dV

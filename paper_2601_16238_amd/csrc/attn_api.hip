@@ -19,21 +19,35 @@ int check_strides(int32_t S, int32_t D, int64_t sb, int64_t sh, int64_t ss)
     return ATTN_OK;
 }
 
-int check_params(const attn_gqa_params_t *p)
+// Every entry point funnels into the rectangular, grouped-query form.
+int check_params(const attn_rect_params_t *p)
 {
     if (!p) return ATTN_ERR_NULL;
-    if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->S < 1) return ATTN_ERR_SHAPE;
+    if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->Sq < 1 || p->Sk < 1) return ATTN_ERR_SHAPE;
     if (p->Hq % p->Hkv != 0) return ATTN_ERR_SHAPE;
     if (p->D != 64 && p->D != 128) return ATTN_ERR_SHAPE;
-    // B*Hq*S rows must be indexable with int32 (LSE / workspace offsets, grid sizes).
-    const int64_t rows = (int64_t)p->B * p->Hq * p->S;
-    if (rows > (int64_t)std::numeric_limits<int32_t>::max()) return ATTN_ERR_SHAPE;
-    int rc = check_strides(p->S, p->D, p->q_stride_b, p->q_stride_h, p->q_stride_s);
+    // the causal mask is aligned bottom-right: with fewer keys than rows some rows see none
+    if (p->causal && p->Sk < p->Sq) return ATTN_ERR_SHAPE;
+    // B*Hq*Sq and B*Hkv*Sk rows must be indexable with int32 (LSE / workspace offsets, grids).
+    const int64_t lim = (int64_t)std::numeric_limits<int32_t>::max();
+    if ((int64_t)p->B * p->Hq * p->Sq > lim || (int64_t)p->B * p->Hkv * p->Sk > lim)
+        return ATTN_ERR_SHAPE;
+    int rc = check_strides(p->Sq, p->D, p->q_stride_b, p->q_stride_h, p->q_stride_s);
     if (rc != ATTN_OK) return rc;
-    rc = check_strides(p->S, p->D, p->kv_stride_b, p->kv_stride_h, p->kv_stride_s);
+    rc = check_strides(p->Sk, p->D, p->kv_stride_b, p->kv_stride_h, p->kv_stride_s);
     if (rc != ATTN_OK) return rc;
     if (!std::isfinite(p->scale) || !(p->scale > 0.0f)) return ATTN_ERR_SCALE;
     return ATTN_OK;
+}
+
+attn_rect_params_t as_rect(const attn_gqa_params_t &p)
+{
+    attn_rect_params_t g;
+    g.B = p.B; g.Hq = p.Hq; g.Hkv = p.Hkv; g.Sq = p.S; g.Sk = p.S; g.D = p.D;
+    g.q_stride_b = p.q_stride_b; g.q_stride_h = p.q_stride_h; g.q_stride_s = p.q_stride_s;
+    g.kv_stride_b = p.kv_stride_b; g.kv_stride_h = p.kv_stride_h; g.kv_stride_s = p.kv_stride_s;
+    g.scale = p.scale; g.causal = p.causal;
+    return g;
 }
 
 // Multi-head parameters as the grouped-query ones with one query head per K/V head.
@@ -48,12 +62,7 @@ attn_gqa_params_t as_gqa(const attn_params_t &p)
     return g;
 }
 
-int check_params(const attn_params_t *p)
-{
-    if (!p) return ATTN_ERR_NULL;
-    const attn_gqa_params_t g = as_gqa(*p);
-    return check_params(&g);
-}
+size_t round_ws(size_t bytes) { return (bytes + kWsAlign - 1) / kWsAlign * kWsAlign; }
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
@@ -86,8 +95,32 @@ void attn_gqa_params_contiguous(attn_gqa_params_t *p, int32_t B, int32_t Hq, int
     p->causal = causal;
 }
 
-int attn_fwd_gqa(const void *Q, const void *K, const void *V, void *O, float *LSE,
-                 const attn_gqa_params_t *p, void *hip_stream)
+void attn_rect_params_contiguous(attn_rect_params_t *p, int32_t B, int32_t Hq, int32_t Hkv,
+                                 int32_t Sq, int32_t Sk, int32_t D, float scale, int32_t causal)
+{
+    if (!p) return;
+    p->B = B; p->Hq = Hq; p->Hkv = Hkv; p->Sq = Sq; p->Sk = Sk; p->D = D;
+    p->q_stride_s = p->kv_stride_s = D;
+    p->q_stride_h = (int64_t)Sq * D;
+    p->kv_stride_h = (int64_t)Sk * D;
+    p->q_stride_b = (int64_t)Hq * Sq * D;
+    p->kv_stride_b = (int64_t)Hkv * Sk * D;
+    p->scale = scale;
+    p->causal = causal;
+}
+
+size_t attn_fwd_rect_workspace_bytes(const attn_rect_params_t *p)
+{
+    if (check_params(p) != ATTN_OK) return 0;
+    const int nsplit = attn::fwd_split_plan(p->B * p->Hq, p->Sq, p->Sk, p->D, nullptr);
+    if (nsplit <= 1) return 0;
+    const size_t rows = (size_t)p->B * p->Hq * p->Sq;
+    return round_ws((size_t)nsplit * rows * (p->D + 1) * sizeof(float));
+}
+
+int attn_fwd_rect(const void *Q, const void *K, const void *V, void *O, float *LSE,
+                  void *workspace, size_t workspace_bytes,
+                  const attn_rect_params_t *p, void *hip_stream)
 {
     if (!Q || !K || !V || !O || !LSE) return ATTN_ERR_NULL;
     const int rc = check_params(p);
@@ -95,7 +128,16 @@ int attn_fwd_gqa(const void *Q, const void *K, const void *V, void *O, float *LS
     if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) ||
         !aligned(LSE, 4))
         return ATTN_ERR_ALIGN;
+    // No workspace at all: run unsplit.  A workspace that is there must be usable.
+    int kps = 0;
+    int nsplit = workspace ? attn::fwd_split_plan(p->B * p->Hq, p->Sq, p->Sk, p->D, &kps) : 1;
+    if (workspace && (!aligned(workspace, kWsAlign) ||
+                      workspace_bytes < attn_fwd_rect_workspace_bytes(p)))
+        return ATTN_ERR_WORKSPACE;
     attn::FwdArgs a;
+    a.nsplit = nsplit; a.kps = kps;
+    a.Opart = static_cast<float *>(workspace);
+    a.LSEpart = a.Opart ? a.Opart + (size_t)nsplit * p->B * p->Hq * p->Sq * p->D : nullptr;
     a.Q = static_cast<const attn::bf16 *>(Q);
     a.K = static_cast<const attn::bf16 *>(K);
     a.V = static_cast<const attn::bf16 *>(V);
@@ -103,11 +145,19 @@ int attn_fwd_gqa(const void *Q, const void *K, const void *V, void *O, float *LS
     a.LSE = LSE;
     a.stride_b = p->q_stride_b; a.stride_h = p->q_stride_h; a.stride_s = p->q_stride_s;
     a.kv_stride_b = p->kv_stride_b; a.kv_stride_h = p->kv_stride_h; a.kv_stride_s = p->kv_stride_s;
-    a.S = p->S; a.H = p->Hq; a.BH = p->B * p->Hq; a.group = p->Hq / p->Hkv;
+    a.S = p->Sq; a.Sk = p->Sk; a.H = p->Hq; a.BH = p->B * p->Hq; a.group = p->Hq / p->Hkv;
     a.nqt = 0;
     a.scale_log2e = p->scale * 1.4426950408889634f;
     return attn::launch_fwd(a, p->D, p->causal != 0, static_cast<hipStream_t>(hip_stream)) == 0
                ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+int attn_fwd_gqa(const void *Q, const void *K, const void *V, void *O, float *LSE,
+                 const attn_gqa_params_t *p, void *hip_stream)
+{
+    if (!p) return ATTN_ERR_NULL;
+    const attn_rect_params_t g = as_rect(*p);
+    return attn_fwd_rect(Q, K, V, O, LSE, nullptr, 0, &g, hip_stream);
 }
 
 int attn_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
@@ -118,11 +168,18 @@ int attn_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
     return attn_fwd_gqa(Q, K, V, O, LSE, &g, hip_stream);
 }
 
-size_t attn_bwd_gqa_workspace_bytes(const attn_gqa_params_t *p)
+size_t attn_bwd_rect_workspace_bytes(const attn_rect_params_t *p)
 {
     if (check_params(p) != ATTN_OK) return 0;
-    const size_t rows = (size_t)p->B * p->Hq * p->S;
-    return (2 * rows * sizeof(float) + kWsAlign - 1) / kWsAlign * kWsAlign;
+    const size_t rows = (size_t)p->B * p->Hq * p->Sq;
+    return round_ws(2 * rows * sizeof(float));
+}
+
+size_t attn_bwd_gqa_workspace_bytes(const attn_gqa_params_t *p)
+{
+    if (!p) return 0;
+    const attn_rect_params_t g = as_rect(*p);
+    return attn_bwd_rect_workspace_bytes(&g);
 }
 
 size_t attn_bwd_workspace_bytes(const attn_params_t *p)
@@ -135,7 +192,7 @@ size_t attn_bwd_workspace_bytes(const attn_params_t *p)
 static int bwd_impl(const void *Q, const void *K, const void *V, const void *O, const void *dO,
                     const float *LSE, void *dQ, void *dK, void *dV,
                     void *workspace, size_t workspace_bytes,
-                    const attn_gqa_params_t *p, void *hip_stream, uint32_t stages)
+                    const attn_rect_params_t *p, void *hip_stream, uint32_t stages)
 {
     if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_NULL;
     const int rc = check_params(p);
@@ -145,7 +202,7 @@ static int bwd_impl(const void *Q, const void *K, const void *V, const void *O, 
         !aligned(LSE, 4))
         return ATTN_ERR_ALIGN;
     if (!workspace || !aligned(workspace, kWsAlign) ||
-        workspace_bytes < attn_bwd_gqa_workspace_bytes(p))
+        workspace_bytes < attn_bwd_rect_workspace_bytes(p))
         return ATTN_ERR_WORKSPACE;
     if (stages == 0 || (stages & ~7u)) return ATTN_ERR_SHAPE;
     attn::BwdArgs a;
@@ -161,7 +218,7 @@ static int bwd_impl(const void *Q, const void *K, const void *V, const void *O, 
     a.dV = static_cast<attn::bf16 *>(dV);
     a.stride_b = p->q_stride_b; a.stride_h = p->q_stride_h; a.stride_s = p->q_stride_s;
     a.kv_stride_b = p->kv_stride_b; a.kv_stride_h = p->kv_stride_h; a.kv_stride_s = p->kv_stride_s;
-    a.S = p->S; a.H = p->Hq; a.BH = p->B * p->Hq; a.group = p->Hq / p->Hkv;
+    a.S = p->Sq; a.Sk = p->Sk; a.H = p->Hq; a.BH = p->B * p->Hq; a.group = p->Hq / p->Hkv;
     a.ntile = 0;
     a.scale = p->scale;
     a.scale_log2e = p->scale * 1.4426950408889634f;
@@ -170,13 +227,23 @@ static int bwd_impl(const void *Q, const void *K, const void *V, const void *O, 
                ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
+int attn_bwd_rect(const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                  const float *LSE, void *dQ, void *dK, void *dV,
+                  void *workspace, size_t workspace_bytes,
+                  const attn_rect_params_t *p, void *hip_stream)
+{
+    return bwd_impl(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, p, hip_stream,
+                    ATTN_BWD_STAGE_DELTA | ATTN_BWD_STAGE_DKDV | ATTN_BWD_STAGE_DQ);
+}
+
 int attn_bwd_gqa(const void *Q, const void *K, const void *V, const void *O, const void *dO,
                  const float *LSE, void *dQ, void *dK, void *dV,
                  void *workspace, size_t workspace_bytes,
                  const attn_gqa_params_t *p, void *hip_stream)
 {
-    return bwd_impl(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, p, hip_stream,
-                    ATTN_BWD_STAGE_DELTA | ATTN_BWD_STAGE_DKDV | ATTN_BWD_STAGE_DQ);
+    return attn_bwd_gqa_stages(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, p,
+                               hip_stream,
+                               ATTN_BWD_STAGE_DELTA | ATTN_BWD_STAGE_DKDV | ATTN_BWD_STAGE_DQ);
 }
 
 int attn_bwd_gqa_stages(const void *Q, const void *K, const void *V, const void *O,
@@ -184,7 +251,9 @@ int attn_bwd_gqa_stages(const void *Q, const void *K, const void *V, const void 
                         void *workspace, size_t workspace_bytes,
                         const attn_gqa_params_t *p, void *hip_stream, uint32_t stages)
 {
-    return bwd_impl(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, p, hip_stream,
+    if (!p) return ATTN_ERR_NULL;
+    const attn_rect_params_t g = as_rect(*p);
+    return bwd_impl(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, &g, hip_stream,
                     stages);
 }
 
@@ -205,8 +274,8 @@ int attn_bwd_stages(const void *Q, const void *K, const void *V, const void *O, 
 {
     if (!p) return ATTN_ERR_NULL;
     const attn_gqa_params_t g = as_gqa(*p);
-    return bwd_impl(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, &g, hip_stream,
-                    stages);
+    return attn_bwd_gqa_stages(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, &g,
+                               hip_stream, stages);
 }
 
 const char *attn_status_string(int status)
@@ -214,7 +283,7 @@ const char *attn_status_string(int status)
     switch (status) {
         case ATTN_OK: return "ok";
         case ATTN_ERR_NULL: return "a required pointer is NULL";
-        case ATTN_ERR_SHAPE: return "unsupported shape (B,H,S >= 1, D in {64,128}, Hkv divides Hq, B*H*S < 2^31)";
+        case ATTN_ERR_SHAPE: return "unsupported shape (B,H,S >= 1, D in {64,128}, Hkv divides Hq, B*H*S < 2^31, causal needs Sk >= Sq)";
         case ATTN_ERR_STRIDE: return "bad stride (D contiguous, strides multiples of 8 elements, stride_s >= D)";
         case ATTN_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
         case ATTN_ERR_WORKSPACE: return "workspace missing, misaligned (256 B) or too small";
@@ -224,6 +293,6 @@ const char *attn_status_string(int status)
     }
 }
 
-int attn_version(void) { return 1001; }
+int attn_version(void) { return 1002; }
 
 }  // extern "C"

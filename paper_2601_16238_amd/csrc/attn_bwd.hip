@@ -55,14 +55,16 @@ __global__ void __launch_bounds__(256) attn_bwd_delta_kernel(const BwdArgs a)
 }
 
 // ---------------------------------------------------------------------------------------
-// 2. dK, dV.  Work-group = 8 waves = 4 producer/consumer pairs sharing a SIMD each; a pair
-// owns 32 keys and the work-group streams the head's Q and dO rows through LDS in slots of
-// 32 rows.  The K/V fragments plus two 32 x D fp32 accumulators do not fit one wave's 256
-// registers, and a wave alternating between the exp-heavy and the accumulate-heavy half
-// cannot overlap them, so the halves go to different waves:
-//   producer (waves 0-3), slot t:   S = Q K^T, dP = dO V^T, P = exp2(c S - lse2),
+// 2. dK, dV.  Work-group = 8 waves = 4 producers + 4 consumers (wave w and w+4 share a SIMD);
+// it owns 128 keys and streams the head's Q and dO rows through LDS in slots of 32 rows.
+// The K/V fragments plus two 32 x D fp32 accumulators do not fit one wave's 256 registers,
+// and a wave alternating between the exp-heavy and the accumulate-heavy half cannot overlap
+// them, so the halves go to different waves:
+//   producer p (waves 0-3), slot t: 32 keys; S = Q K^T, dP = dO V^T, P = exp2(c S - lse2),
 //                                   dS = P o (dP - delta); bf16 P and dS -> LDS exchange
-//   consumer (waves 4-7), slot t-1: dV^T += dO^T P, dK^T += Q^T dS   (transpose LDS reads)
+//   consumer (waves 4-7), slot t-1: 64 keys (two producers) and ONE output: even consumers
+//                                   dV^T += dO^T P, odd ones dK^T += Q^T dS; every transposed
+//                                   LDS fragment feeds two MFMAs (one per 32-key block)
 // Both issue 16 MFMAs per slot (D = 128); the producer's VALU work overlaps the consumer's
 // MFMAs on the shared SIMD.  One barrier per slot.
 //
@@ -119,11 +121,14 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     const int64_t base_kv = (int64_t)(bkv / Hkv) * a.kv_stride_b + (int64_t)(bkv % Hkv) * a.kv_stride_h;
     const int bh0 = (bkv / Hkv) * a.H + (bkv % Hkv) * a.group;  // first query head of the group
 
+    const int Sk = a.Sk;          // key/value rows; S is the number of query rows
+    const int coff = Sk - S;      // causal: query row i sees keys 0 .. i + coff
     const int k0 = kt * C::kBlk + pair * 32;  // first key of this pair
     const int key = k0 + r;
-    const int keyc = key < S ? key : S - 1;
+    const int keyc = key < Sk ? key : Sk - 1;
     const int n_slot = (S + C::kRows - 1) / C::kRows;
-    const int t0 = CAUSAL ? kt * (C::kBlk / C::kRows) : 0;  // first slot with a visible row
+    // first slot with a row that sees a key of this block (row >= key - coff)
+    const int t0 = CAUSAL ? max(0, kt * C::kBlk - coff) / C::kRows : 0;
 
     // chunk position swizzle: rows 0..15 get 16 distinct values (row reads of 16 lanes hit 16
     // different 16-byte bank groups) and 4 consecutive rows differ in the upper two bits (the
@@ -176,7 +181,7 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     };
     // wave-uniform: does slot t hold a real row that sees some key of the pair
     auto active = [&](int t) {
-        return t * C::kRows < S && (!CAUSAL || t * C::kRows + 31 >= k0);
+        return t * C::kRows < S && (!CAUSAL || t * C::kRows + 31 + coff >= k0);
     };
     auto ring_next = [](int x) { return x + 1 == C::kRing ? 0 : x + 1; };
 
@@ -241,9 +246,9 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
                     for (int e = 0; e < 4; ++e)
                         s[4 * g + e] = fast_exp2(__builtin_fmaf(s[4 * g + e], c, -l4[e]));
                 }
-                if ((q_lo + 32 > S) || (CAUSAL && q_lo < k0 + 31)) {
-                    // visible row offsets: >= key - q_lo (causal) and <= S - 1 - q_lo
-                    const int lo = (CAUSAL ? key - q_lo : -64) - 4 * h;
+                if ((q_lo + 32 > S) || (CAUSAL && q_lo + coff < k0 + 31)) {
+                    // visible row offsets: >= key - coff - q_lo (causal) and <= S - 1 - q_lo
+                    const int lo = (CAUSAL ? key - coff - q_lo : -64) - 4 * h;
                     const int hi = S - 1 - q_lo - 4 * h;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
@@ -290,7 +295,7 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
         }
         // wave-uniform: does slot t hold a real row that sees some key of the block at kfirst
         auto block_active = [&](int t, int kfirst) {
-            return t * C::kRows < S && (!CAUSAL || t * C::kRows + 31 >= kfirst);
+            return t * C::kRows < S && (!CAUSAL || t * C::kRows + 31 + coff >= kfirst);
         };
         const bf16x8 *const Xc = reinterpret_cast<const bf16x8 *>(smem + C::kOffXchg) +
                                  (2 * half) * 256 + kind * 128 + l;
@@ -339,7 +344,7 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
             const int okey = kA + 32 * kb + r;
-            if (okey < S) {
+            if (okey < Sk) {
                 bf16 *op = out + base_kv + (int64_t)okey * a.kv_stride_s;
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
@@ -399,8 +404,11 @@ attn_bwd_dq_kernel(const BwdArgs a)
     const int q0 = qt * C::kBlk + w * 32;
     const int q = q0 + r;
     const int qc = q < S ? q : S - 1;
+    const int Sk = a.Sk;      // key/value rows; S is the number of query rows
+    const int coff = Sk - S;  // causal: query row i sees keys 0 .. i + coff
+    const int q0e = q0 + coff;
     const int q_end = min(S, (qt + 1) * C::kBlk);
-    const int n_kt = ((CAUSAL ? q_end : S) + C::kTile - 1) / C::kTile;
+    const int n_kt = ((CAUSAL ? q_end + coff : Sk) + C::kTile - 1) / C::kTile;
 
     auto swz = [](int row) {
         return CPR == 16 ? (((row & 3) << 2) | ((row >> 2) & 3))
@@ -408,7 +416,7 @@ attn_bwd_dq_kernel(const BwdArgs a)
     };
 
     // ---- streaming of tile kt into ring position pos; rows past S-1 read as zero
-    const uint32_t head_bytes = (uint32_t)(((int64_t)(S - 1) * a.kv_stride_s + D) * 2);
+    const uint32_t head_bytes = (uint32_t)(((int64_t)(Sk - 1) * a.kv_stride_s + D) * 2);
     const desc_t Kd = make_desc(a.K + base_kv, head_bytes), Vd = make_desc(a.V + base_kv, head_bytes);
     const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2u;
     const uint32_t lds0 = lds_address(smem);
@@ -476,7 +484,7 @@ attn_bwd_dq_kernel(const BwdArgs a)
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2) {
             const int k_lo = kt * C::kTile + kb2 * 32;
-            const bool active = k_lo < S && (!CAUSAL || k_lo <= q0 + 31);  // wave-uniform
+            const bool active = k_lo < Sk && (!CAUSAL || k_lo <= q0e + 31);  // wave-uniform
             if (!active) continue;
             f32x16 s, dp;
             {
@@ -494,8 +502,8 @@ attn_bwd_dq_kernel(const BwdArgs a)
                 dp = mfma32(*(const bf16x8 *)(Vt + off), gf[ks], dp);
             }
             // register i <-> key k_lo + 8*(i/4) + 4h + i%4; this lane's query is fixed
-            const bool need_mask = (k_lo + 32 > S) || (CAUSAL && k_lo + 31 > q0);
-            const int lim = (CAUSAL ? qc : S - 1) - k_lo - 4 * h;
+            const bool need_mask = (k_lo + 32 > Sk) || (CAUSAL && k_lo + 31 > q0e);
+            const int lim = (CAUSAL ? qc + coff : Sk - 1) - k_lo - 4 * h;
 #pragma unroll
             for (int i = 0; i < 16; ++i) s[i] = fast_exp2(__builtin_fmaf(s[i], c, -lse2));
             if (need_mask) {  // wave-uniform: only blocks on the diagonal or at the ragged end
@@ -553,7 +561,7 @@ template <int D, bool CAUSAL>
 static int launch_dkdv(BwdArgs a, hipStream_t st)
 {
     using C = DkdvCfg<D>;
-    a.ntile = (a.S + C::kBlk - 1) / C::kBlk;
+    a.ntile = (a.Sk + C::kBlk - 1) / C::kBlk;
     allow_lds(attn_bwd_dkdv_kernel<D, CAUSAL>, C::kLdsBytes);
     hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL>), dim3(a.ntile * (a.BH / a.group)),
                        dim3(C::kThreads), C::kLdsBytes, st, a);
@@ -582,8 +590,10 @@ static int launch_bwd_dc(const BwdArgs &a, hipStream_t st, unsigned stages)
         if (blocks32 >= 8) return launch_dq<D, 8, CAUSAL>(a, st);
         if (blocks32 >= 4) return launch_dq<D, 4, CAUSAL>(a, st);
         if (blocks32 == 3) return launch_dq<D, 3, CAUSAL>(a, st);
-        if (blocks32 == 2) return launch_dq<D, 2, CAUSAL>(a, st);
-        return launch_dq<D, 1, CAUSAL>(a, st);
+        if (blocks32 == 2 || D == 128) return launch_dq<D, 2, CAUSAL>(a, st);
+        // one wave: only D = 64 (with D = 128 a lone wave would spill while it streams tiles)
+        if constexpr (D < 128) return launch_dq<D, 1, CAUSAL>(a, st);
+        return -1;
     }
     return 0;
 }

@@ -52,7 +52,7 @@ struct FwdCfg {
 constexpr float kOverflow = 1024.0f;
 constexpr float kMinusHuge = -1.0e30f;  // initial reference: finite, so masked -inf scores give 0
 
-template <int D, int NW, bool CAUSAL>
+template <int D, int NW, bool CAUSAL, bool SPLIT>
 __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
 attn_fwd_kernel(const FwdArgs a)
 {
@@ -76,6 +76,17 @@ attn_fwd_kernel(const FwdArgs a)
     const int64_t base_kv = (int64_t)(bh / a.H) * a.kv_stride_b +
                             (int64_t)((bh % a.H) / a.group) * a.kv_stride_h;
     const bf16 *Qp = a.Q + base, *Kp = a.K + base_kv, *Vp = a.V + base_kv;
+    // Keys seen by this work-group: all Sk of them, or one split's range (then K and V are
+    // simply re-based to the range and the causal offset moves with them).  Query row i sees
+    // key j iff j <= i + coff.
+    int Sk = a.Sk, coff = a.Sk - S;
+    if (SPLIT) {
+        const int k_begin = blockIdx.y * a.kps;  // < Sk by the launcher's plan
+        Kp += (int64_t)k_begin * a.kv_stride_s;
+        Vp += (int64_t)k_begin * a.kv_stride_s;
+        Sk = min(Sk - k_begin, a.kps);
+        coff -= k_begin;
+    }
 
     const int q0 = qt * C::kBR + w * 32;  // first query row of this wave
     const int q = q0 + r;                 // this lane's query row
@@ -89,11 +100,13 @@ attn_fwd_kernel(const FwdArgs a)
 
     // Key tiles this work-group visits.
     const int q_end = min(S, (qt + 1) * C::kBR);
-    const int n_kt = ((CAUSAL ? q_end : S) + C::kBC - 1) / C::kBC;
+    const int k_end = CAUSAL ? min(Sk, q_end + coff) : Sk;  // <= 0: nothing visible (splits only)
+    const int n_kt = k_end > 0 ? (k_end + C::kBC - 1) / C::kBC : 0;
+    const int q0e = q0 + coff;  // the wave's first row in key coordinates
 
     // ---- staging: global -> registers -> LDS.  Rows past S-1 and tiles past the last one
     // lie outside the head's buffer resource and read as zero (masked to probability 0).
-    const uint32_t head_bytes = (uint32_t)(((int64_t)(S - 1) * a.kv_stride_s + D) * 2);
+    const uint32_t head_bytes = (uint32_t)(((int64_t)(Sk - 1) * a.kv_stride_s + D) * 2);
     const rsrc_t Kr = make_rsrc(Kp, head_bytes), Vr = make_rsrc(Vp, head_bytes);
     const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2u;
     const uint32_t tile_bytes = C::kBC * row_bytes;
@@ -237,7 +250,7 @@ attn_fwd_kernel(const FwdArgs a)
         for (int i = 0; i < 16; ++i) nxt[i] = 0.f;
         if (masked) {
             // Ragged tail and causal mask: only sub-tiles that touch the end or the diagonal.
-            const int lim = (CAUSAL ? qc : S - 1) - (kt * C::kBC + 32 * u) - 4 * h;
+            const int lim = (CAUSAL ? min(qc + coff, Sk - 1) : Sk - 1) - (kt * C::kBC + 32 * u) - 4 * h;
 #pragma unroll
             for (int i = 0; i < 16; ++i)
                 if (8 * (i / 4) + (i % 4) > lim) cur[i] = -INFINITY;
@@ -317,15 +330,15 @@ attn_fwd_kernel(const FwdArgs a)
     for (int kt = 0; kt < n_kt; ++kt) {
         const int kb = kt * C::kBC;
         // wave-uniform: does the wave see any key of the sub-tile / must it mask some
-        if (!CAUSAL || kb <= q0 + 31) {
-            subtile(kt, 0, kb1, kb2, (kb + 32 > S) || (CAUSAL && kb + 31 > q0), sa, sb);
+        if (!CAUSAL || kb <= q0e + 31) {
+            subtile(kt, 0, kb1, kb2, (kb + 32 > Sk) || (CAUSAL && kb + 31 > q0e), sa, sb);
         } else {
             dma_k(kt + 2, kb2);
             store_v((kt + 1) & 1);
             load_v(kt + 2);
         }
-        if (!CAUSAL || kb + 32 <= q0 + 31)
-            subtile(kt, 1, kb1, kb2, (kb + 64 > S) || (CAUSAL && kb + 63 > q0), sb, sa);
+        if (!CAUSAL || kb + 32 <= q0e + 31)
+            subtile(kt, 1, kb1, kb2, (kb + 64 > Sk) || (CAUSAL && kb + 63 > q0e), sb, sa);
         __syncthreads();
         const int t = kb0; kb0 = kb1; kb1 = kb2; kb2 = t;
     }
@@ -333,6 +346,27 @@ attn_fwd_kernel(const FwdArgs a)
 
     // Epilogue: O = O_acc / l, LSE = ln2 * (m + log2 l).
     const float lt = xhalf_sum(lsum);
+    if (SPLIT) {
+        // normalised fp32 partial result of this key range; a row that saw no key of the
+        // range contributes O = 0 with LSE = -inf
+        const float inv = lt > 0.f ? 1.0f / lt : 0.f;
+        if (q < S) {
+            const int64_t row = ((int64_t)blockIdx.y * a.BH + bh) * S + q;
+            float *Op = a.Opart + row * D;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    f32x4 ov;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) ov[e] = o[db][4 * g + e] * inv;
+                    *(f32x4 *)(Op + 32 * db + 8 * g + 4 * h) = ov;
+                }
+            if (h == 0) a.LSEpart[row] = lt > 0.f ? (m + fast_log2(lt)) * kLn2 : -INFINITY;
+        }
+        ATTN_CYCLES_END(0);
+        return;
+    }
     const float inv = 1.0f / lt;
     if (q < S) {
         bf16 *Op = a.O + base + (int64_t)q * a.stride_s;
@@ -349,44 +383,90 @@ attn_fwd_kernel(const FwdArgs a)
     ATTN_CYCLES_END(0);
 }
 
-template <int D, int NW, bool CAUSAL>
+// Combine the per-split partial results: LSE = log sum_z exp(LSE_z), O = sum_z exp(LSE_z - LSE) O_z.
+// One thread per (row, 4 consecutive d); HBM-bound and small.
+template <int D>
+__global__ void __launch_bounds__(256) attn_fwd_merge_kernel(const FwdArgs a)
+{
+    constexpr int TPR = D / 4;  // threads per row
+    const int64_t rows = (int64_t)a.BH * a.S;
+    const int64_t row = (int64_t)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
+    if (row >= rows) return;
+    const int d0 = (threadIdx.x % TPR) * 4;
+    float mx = -INFINITY;
+    for (int z = 0; z < a.nsplit; ++z) mx = fmaxf(mx, a.LSEpart[(int64_t)z * rows + row]);
+    float den = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int z = 0; z < a.nsplit; ++z) {
+        const float wz = expf(a.LSEpart[(int64_t)z * rows + row] - mx);  // 0 for an empty split
+        const f32x4 oz = *(const f32x4 *)(a.Opart + ((int64_t)z * rows + row) * D + d0);
+        den += wz;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] += wz * oz[e];
+    }
+    const float inv = 1.0f / den;
+    const int bh = (int)(row / a.S), q = (int)(row % a.S);
+    bf16 *Op = a.O + (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h +
+               (int64_t)q * a.stride_s + d0;
+    *(bf16x4 *)Op = pack4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+    if (d0 == 0) a.LSE[row] = mx + logf(den);
+}
+
+template <int D, int NW, bool CAUSAL, bool SPLIT>
 static int launch_fwd_kernel(const FwdArgs &a, hipStream_t st)
 {
     using C = FwdCfg<D, NW>;
-    hipFuncSetAttribute((const void *)attn_fwd_kernel<D, NW, CAUSAL>,
+    hipFuncSetAttribute((const void *)attn_fwd_kernel<D, NW, CAUSAL, SPLIT>,
                         hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
-    hipLaunchKernelGGL((attn_fwd_kernel<D, NW, CAUSAL>), dim3(a.nqt * a.BH), dim3(C::kThreads),
+    hipLaunchKernelGGL((attn_fwd_kernel<D, NW, CAUSAL, SPLIT>),
+                       dim3(a.nqt * a.BH, SPLIT ? a.nsplit : 1), dim3(C::kThreads),
                        C::kLdsBytes, st, a);
-    return hipGetLastError() == hipSuccess ? 0 : -1;
+    if (hipGetLastError() != hipSuccess) return -1;
+    if (SPLIT) {
+        const int64_t rows = (int64_t)a.BH * a.S;
+        constexpr int RPB = 256 / (D / 4);
+        hipLaunchKernelGGL((attn_fwd_merge_kernel<D>), dim3((unsigned)((rows + RPB - 1) / RPB)),
+                           dim3(256), 0, st, a);
+        if (hipGetLastError() != hipSuccess) return -1;
+    }
+    return 0;
 }
 
 template <int D, int NW>
 static int launch_fwd_nw(const FwdArgs &a, bool causal, hipStream_t st)
 {
-    return causal ? launch_fwd_kernel<D, NW, true>(a, st) : launch_fwd_kernel<D, NW, false>(a, st);
+    if (a.nsplit > 1)
+        return causal ? launch_fwd_kernel<D, NW, true, true>(a, st)
+                      : launch_fwd_kernel<D, NW, false, true>(a, st);
+    return causal ? launch_fwd_kernel<D, NW, true, false>(a, st)
+                  : launch_fwd_kernel<D, NW, false, false>(a, st);
 }
 
 // Waves per work-group: 8 (256 query rows) unless the sequence is too short to fill them.
-int fwd_waves_for(int S)
+// With D = 128 at least 4: fewer waves could not hold their share of a V tile in registers
+// while staging it (waves whose rows lie past the end compute and store nothing useful, but
+// still take part in the staging).
+static int fwd_waves_for(int S, int D)
 {
     const int blocks32 = (S + 31) / 32;
     if (blocks32 >= 8) return 8;
-    if (blocks32 >= 4) return 4;
+    if (blocks32 >= 4 || D == 128) return 4;
     return blocks32;  // 1, 2 or 3
 }
 
 template <int D>
 static int launch_fwd_d(FwdArgs a, bool causal, hipStream_t st)
 {
-    const int nw = fwd_waves_for(a.S);
+    const int nw = fwd_waves_for(a.S, D);
     a.nqt = (a.S + nw * 32 - 1) / (nw * 32);
-    switch (nw) {
-        case 8: return launch_fwd_nw<D, 8>(a, causal, st);
-        case 4: return launch_fwd_nw<D, 4>(a, causal, st);
-        case 3: return launch_fwd_nw<D, 3>(a, causal, st);
-        case 2: return launch_fwd_nw<D, 2>(a, causal, st);
-        default: return launch_fwd_nw<D, 1>(a, causal, st);
+    if (nw == 8) return launch_fwd_nw<D, 8>(a, causal, st);
+    if (nw == 4) return launch_fwd_nw<D, 4>(a, causal, st);
+    if constexpr (D < 128) {
+        if (nw == 3) return launch_fwd_nw<D, 3>(a, causal, st);
+        if (nw == 2) return launch_fwd_nw<D, 2>(a, causal, st);
+        return launch_fwd_nw<D, 1>(a, causal, st);
     }
+    return -1;
 }
 
 #ifdef ATTN_CYCLES
@@ -396,6 +476,29 @@ extern "C" void attn_debug_cycles_fwd(unsigned long long *out, int reset)
     if (reset) { unsigned long long z[4][4] = {}; hipMemcpyToSymbol(HIP_SYMBOL(g_attn_cycles), z, sizeof(z)); }
 }
 #endif
+
+// Split the keys when the unsplit launch would leave compute units (256) idle.  Work-groups
+// of full 256-row query tiles are heavy, one per unit is the aim; with few rows (decoding) a
+// work-group is light and bound by the latency of its K/V stream, so about four per unit.
+// Every split keeps at least four 64-key tiles (the merge reads and writes one fp32 partial
+// result per split and row).
+int fwd_split_plan(int BH, int S, int Sk, int D, int *kps)
+{
+    const int nw = fwd_waves_for(S, D);
+    const int64_t wgs = (int64_t)BH * ((S + nw * 32 - 1) / (nw * 32));
+    const int64_t target = S >= 128 ? 256 : 1024;
+    const int tiles = (Sk + 63) / 64;
+    int nsplit = 1;
+    if (wgs < target && tiles >= 8) {
+        nsplit = (int)((target + wgs - 1) / wgs);
+        if (nsplit > tiles / 4) nsplit = tiles / 4;
+        if (nsplit > 128) nsplit = 128;
+    }
+    const int tiles_per = (tiles + nsplit - 1) / nsplit;
+    nsplit = (tiles + tiles_per - 1) / tiles_per;  // no empty split
+    if (kps) *kps = tiles_per * 64;
+    return nsplit;
+}
 
 int launch_fwd(const FwdArgs &a, int D, bool causal, hipStream_t st)
 {

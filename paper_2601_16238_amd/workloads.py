@@ -175,3 +175,57 @@ def fwd_bytes(B, H, S, D):
 def bwd_bytes(B, H, S, D):
     """Algorithmic HBM bytes backward: read Q,K,V,O,dO, write dQ,dK,dV, read LSE."""
     return 8 * B * H * S * D * 2 + B * H * S * 4
+
+
+# ---- rectangular problems: Sq query rows against Sk cached keys (decoding, chunked prefill) ----
+RectWorkload = namedtuple("RectWorkload", "name B Hq Hkv Sq Sk D causal sigma seed note")
+
+RECT_WORKLOADS = {w.name: w for w in [
+    RectWorkload("decode_cmp", 8, 32, 8, 1, 8192, 128, True, 1.0, 1009,
+                 "one new token per sequence against an 8K cache, grouped-query heads"),
+    RectWorkload("prefill_chunk", 1, 32, 8, 512, 4096, 128, True, 1.0, 1010,
+                 "small-batch chunked prefill: 512 new rows after 3584 cached ones"),
+    RectWorkload("decode_small", 2, 8, 2, 1, 300, 64, True, 1.0, 1011, "parity-size decode"),
+    RectWorkload("cross_small", 1, 4, 4, 150, 77, 64, False, 1.0, 1012,
+                 "more rows than keys, no mask"),
+]}
+
+
+def random_rect_inputs(B, Hq, Hkv, Sq, Sk, D, seed, sigma=1.0):
+    """Seeded bf16 N(0, sigma^2) tensors: Q, dO [B,Hq,Sq,D]; K, V [B,Hkv,Sk,D]."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = {}
+    for name, heads, rows in (("Q", Hq, Sq), ("K", Hkv, Sk), ("V", Hkv, Sk), ("dO", Hq, Sq)):
+        x = rng.standard_normal((B, heads, rows, D), dtype=np.float32) * np.float32(sigma)
+        out[name] = f32_to_bf16_bits(x)
+    out["scale"] = default_scale(D)
+    return out
+
+
+def make_rect_inputs(w, kv_heads=None):
+    """Draw Q, K, V, dO for rectangular workload `w` (a RectWorkload or its name), draw order
+    Q, K, V, dO.  `kv_heads` (flat b*Hkv+hkv indices) returns only those K/V heads and the
+    query heads of their groups, as [1,n*G,Sq,D] and [1,n,Sk,D] arrays drawn identically."""
+    if isinstance(w, str):
+        w = RECT_WORKLOADS[w]
+    rng = np.random.Generator(np.random.PCG64(w.seed))
+    G = w.Hq // w.Hkv
+    out = {}
+    for name, heads, rows in (("Q", w.Hq, w.Sq), ("K", w.Hkv, w.Sk), ("V", w.Hkv, w.Sk),
+                              ("dO", w.Hq, w.Sq)):
+        x = rng.standard_normal((w.B * heads, rows, w.D), dtype=np.float32)
+        if w.sigma != 1.0:
+            x *= np.float32(w.sigma)
+        if kv_heads is not None:
+            kv = np.asarray(list(kv_heads), dtype=np.int64)
+            if heads == w.Hq:
+                idx = (kv[:, None] // w.Hkv * w.Hq + kv[:, None] % w.Hkv * G +
+                       np.arange(G)[None, :]).reshape(-1)
+            else:
+                idx = kv
+            out[name] = f32_to_bf16_bits(x[idx])[None]
+        else:
+            out[name] = f32_to_bf16_bits(x).reshape(w.B, heads, rows, w.D)
+    out["scale"] = default_scale(w.D)
+    out["causal"] = bool(w.causal)
+    return out

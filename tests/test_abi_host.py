@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported_and_bound():
 
 
 def test_version_and_status_strings():
-    assert attn.attn_version() == 1001
+    assert attn.attn_version() == 1002
     seen = set()
     for code in range(0, -8, -1):
         s = attn.status_string(code)
@@ -180,3 +180,80 @@ def test_gqa_workloads_are_seeded_and_group_selection_matches():
     assert sub["Q"].shape == (1, w.Hq, w.S, w.D) and sub["K"].shape == (1, 1, w.S, w.D)
     assert np.array_equal(sub["K"][0, 0], a["K"][1, 0])
     assert np.array_equal(sub["Q"][0], a["Q"][1])
+
+
+# ---- rectangular entry points ----------------------------------------------------------------
+
+def call_fwd_rect(p, ptr=FAKE, ws=None, ws_bytes=0):
+    return attn.lib().attn_fwd_rect(ptr, ptr, ptr, ptr, ptr, ws, ws_bytes, ctypes.byref(p), None)
+
+
+def call_bwd_rect(p, ws=FAKE, ws_bytes=1 << 40):
+    return attn.lib().attn_bwd_rect(*([FAKE] * 9 + [ws, ws_bytes, ctypes.byref(p), None]))
+
+
+def test_rect_params_contiguous_and_workspace_sizes():
+    p = attn.make_rect_params(2, 8, 2, 5, 300, 64, 0.125, True)
+    assert (p.q_stride_s, p.q_stride_h, p.q_stride_b) == (64, 5 * 64, 8 * 5 * 64)
+    assert (p.kv_stride_s, p.kv_stride_h, p.kv_stride_b) == (64, 300 * 64, 2 * 300 * 64)
+    # backward: two fp32 per QUERY row, rounded up to 256 bytes
+    assert attn.attn_bwd_rect_workspace_bytes(2, 8, 2, 5, 300, 64) == 768
+    assert attn.attn_bwd_rect_workspace_bytes(4, 32, 8, 4096, 4096, 128) == \
+        attn.attn_bwd_gqa_workspace_bytes(4, 32, 8, 4096, 128)
+    # forward: nothing to split when the launch fills the chip or the keys are few ...
+    assert attn.attn_fwd_rect_workspace_bytes(4, 32, 8, 4096, 4096, 128) == 0
+    assert attn.attn_fwd_rect_workspace_bytes(2, 8, 2, 1, 300, 64) == 0
+    # ... otherwise (D+1) fp32 per split and query row; decoding 8 sequences of 32 heads
+    # against 8192 keys splits 4 ways
+    assert attn.attn_fwd_rect_workspace_bytes(8, 32, 8, 1, 8192, 128) == 4 * 256 * 129 * 4
+    assert attn.attn_fwd_rect_workspace_bytes(1, 6, 4, 1, 8192, 64) == 0      # invalid heads
+
+
+@pytest.mark.parametrize("mutate,code", [
+    (lambda p: setattr(p, "Sq", 0), binding.ATTN_ERR_SHAPE),
+    (lambda p: setattr(p, "Sk", 0), binding.ATTN_ERR_SHAPE),
+    (lambda p: (setattr(p, "Sk", 8), setattr(p, "causal", 1)), binding.ATTN_ERR_SHAPE),  # Sk < Sq
+    (lambda p: setattr(p, "Hkv", 3), binding.ATTN_ERR_SHAPE),
+    (lambda p: setattr(p, "D", 96), binding.ATTN_ERR_SHAPE),
+    (lambda p: setattr(p, "kv_stride_s", 60), binding.ATTN_ERR_STRIDE),
+    (lambda p: setattr(p, "q_stride_h", 4), binding.ATTN_ERR_STRIDE),
+    (lambda p: setattr(p, "scale", float("nan")), binding.ATTN_ERR_SCALE),
+])
+def test_rect_bad_params_rejected_before_any_launch(mutate, code):
+    p = attn.make_rect_params(1, 8, 2, 16, 128, 64, 0.125, False)
+    mutate(p)
+    assert call_fwd_rect(p) == code
+    assert call_bwd_rect(p) == code
+
+
+def test_rect_fewer_keys_than_rows_is_fine_without_a_mask():
+    p = attn.make_rect_params(1, 8, 2, 16, 8, 64, 0.125, False)
+    assert call_fwd_rect(p, ptr=None) == binding.ATTN_ERR_NULL     # got past the shape check
+    p.causal = 1
+    assert call_fwd_rect(p, ptr=None) == binding.ATTN_ERR_NULL     # NULL is checked first
+    assert call_fwd_rect(p) == binding.ATTN_ERR_SHAPE
+
+
+def test_rect_workspace_errors():
+    p = attn.make_rect_params(8, 32, 8, 1, 8192, 128, 0.0883, True)   # the plan splits
+    need = 4 * 256 * 129 * 4
+    assert call_fwd_rect(p, ws=FAKE + 16, ws_bytes=need) == binding.ATTN_ERR_WORKSPACE
+    assert call_fwd_rect(p, ws=FAKE, ws_bytes=need - 1) == binding.ATTN_ERR_WORKSPACE
+    assert call_fwd_rect(p, ptr=FAKE + 8, ws=FAKE, ws_bytes=need) == binding.ATTN_ERR_ALIGN
+    assert call_bwd_rect(p, ws=None) == binding.ATTN_ERR_WORKSPACE
+    assert call_bwd_rect(p, ws_bytes=8 * 32 * 8 - 1) == binding.ATTN_ERR_WORKSPACE
+
+
+def test_rect_workloads_are_seeded_and_group_selection_matches():
+    from paper_2601_16238_amd import workloads as wl
+    import numpy as np
+    w = wl.RECT_WORKLOADS["decode_small"]
+    a, b = wl.make_rect_inputs(w), wl.make_rect_inputs(w)
+    assert a["Q"].shape == (w.B, w.Hq, w.Sq, w.D) and a["K"].shape == (w.B, w.Hkv, w.Sk, w.D)
+    for k in ("Q", "K", "V", "dO"):
+        assert np.array_equal(a[k], b[k])
+    sub = wl.make_rect_inputs(w, kv_heads=[3])            # batch 1, K/V head 1 and its group
+    G = w.Hq // w.Hkv
+    assert sub["Q"].shape == (1, G, w.Sq, w.D) and sub["K"].shape == (1, 1, w.Sk, w.D)
+    assert np.array_equal(sub["K"][0, 0], a["K"][1, 1])
+    assert np.array_equal(sub["dO"][0], a["dO"][1, G:2 * G])

@@ -1,0 +1,165 @@
+"""GPU parity for rectangular attention (Sq query rows against Sk keys, causal mask aligned
+bottom-right) through attn_fwd_rect / attn_bwd_rect, against the fp64 oracle element by
+element: decoding (Sq = 1), chunked prefill, more rows than keys, with and without the
+forward's split over the keys; plus consistency with the square entry points."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2601_16238_amd as attn
+from paper_2601_16238_amd import workloads as wl
+from parity_util import check_bf16, check_bf16_scaled, check_lse, to_dev, to_f64
+
+pytestmark = pytest.mark.gpu
+
+# (B,Hq,Hkv,Sq,Sk,D,causal): decode rows, ragged chunks crossing the 64-key tiles and the
+# 128-key / 256-row blocks, Sk < Sq without a mask, both head dims, grouped heads
+CASES = [
+    (2, 8, 2, 1, 300, 64, True), (1, 4, 4, 1, 1, 128, True), (1, 4, 1, 1, 77, 128, False),
+    (2, 4, 2, 100, 356, 128, True), (1, 2, 2, 33, 64, 64, True), (1, 2, 1, 257, 300, 64, True),
+    (1, 4, 4, 150, 77, 64, False), (1, 2, 2, 64, 1000, 128, False), (1, 3, 3, 300, 513, 128, True),
+    (1, 2, 2, 7, 2049, 64, True), (1, 1, 1, 129, 129, 128, True),
+]
+
+
+def run(x, causal, split=True):
+    Q, K, V, dO = (to_dev(x[k]) for k in ("Q", "K", "V", "dO"))
+    O, LSE = attn.attn_fwd_rect(Q, K, V, x["scale"], causal, split=split)
+    dQ, dK, dV = attn.attn_bwd_rect(Q, K, V, O, dO, LSE, x["scale"], causal)
+    torch.cuda.synchronize()
+    return O, LSE, dQ, dK, dV
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D,causal", CASES)
+def test_rect_parity(B, Hq, Hkv, Sq, Sk, D, causal):
+    print("case rect_parity", B, Hq, Hkv, Sq, Sk, D, causal, flush=True)
+    x = wl.random_rect_inputs(B, Hq, Hkv, Sq, Sk, D, seed=1200 + Sq + Sk)
+    Oref, Lref = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], causal)
+    ref = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], causal)
+    O, LSE, dQ, dK, dV = run(x, causal)
+    assert O.shape == (B, Hq, Sq, D) and dK.shape == (B, Hkv, Sk, D) and dV.shape == dK.shape
+    check_bf16("O", to_f64(O), Oref)
+    check_lse(to_f64(LSE), Lref)
+    for name, g, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), ref):
+        if min(Sq, Sk) < 32:
+            # few terms per output: delta formed from the bf16 O dominates dS (see
+            # test_gpu_bwd); with one key the exact dQ and dK are zero
+            check_bf16(name, to_f64(g), r, floor_gate=False)
+        else:
+            check_bf16_scaled(name, to_f64(g), r)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D,causal", [
+    (1, 4, 2, 1, 4096, 128, True), (2, 2, 2, 16, 2100, 64, True), (1, 2, 1, 200, 3000, 128, True),
+    (1, 8, 8, 1, 1024, 64, False), (1, 2, 2, 300, 1500, 128, False)])
+def test_rect_forward_split_matches_unsplit_and_oracle(B, Hq, Hkv, Sq, Sk, D, causal):
+    """Shapes for which the library's plan splits the keys: the merged result must match the
+    oracle, and the one-kernel result (no workspace) as well."""
+    print("case rect_split", B, Hq, Hkv, Sq, Sk, D, causal, flush=True)
+    assert attn.attn_fwd_rect_workspace_bytes(B, Hq, Hkv, Sq, Sk, D) > 0, "plan does not split"
+    x = wl.random_rect_inputs(B, Hq, Hkv, Sq, Sk, D, seed=1300 + Sq + Sk)
+    Oref, Lref = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], causal)
+    Q, K, V = (to_dev(x[k]) for k in ("Q", "K", "V"))
+    for split in (True, False):
+        O = torch.full((B, Hq, Sq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        LSE = torch.full((B, Hq, Sq), float("nan"), dtype=torch.float32, device="cuda")
+        attn.attn_fwd_rect(Q, K, V, x["scale"], causal, O=O, LSE=LSE, split=split)
+        torch.cuda.synchronize()
+        check_bf16("O split=%s" % split, to_f64(O), Oref)
+        check_lse(to_f64(LSE), Lref)
+
+
+def test_rect_square_is_bitwise_the_gqa_call():
+    """Sq = Sk through the rectangular entry points runs the same kernels on the same data
+    as the grouped-query entry points."""
+    B, Hq, Hkv, S, D, causal = 2, 4, 2, 200, 128, True
+    print("case rect_square", B, Hq, Hkv, S, D, flush=True)
+    x = wl.random_gqa_inputs(B, Hq, Hkv, S, D, seed=1401)
+    Q, K, V, dO = (to_dev(x[k]) for k in ("Q", "K", "V", "dO"))
+    O1, L1 = attn.attn_fwd_gqa(Q, K, V, x["scale"], causal)
+    g1 = attn.attn_bwd_gqa(Q, K, V, O1, dO, L1, x["scale"], causal)
+    O2, L2 = attn.attn_fwd_rect(Q, K, V, x["scale"], causal)
+    g2 = attn.attn_bwd_rect(Q, K, V, O2, dO, L2, x["scale"], causal)
+    torch.cuda.synchronize()
+    assert torch.equal(O1.view(torch.int16), O2.view(torch.int16)) and torch.equal(L1, L2)
+    for a, b in zip(g1, g2):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_rect_causal_tail_of_square_problem():
+    """The rectangular causal result equals the last Sq rows of the square causal problem on
+    the same keys (the property that pins the oracle's mask), here on the GPU path: O, LSE
+    and dQ of those rows bit for bit (same tiles, same order), dK/dV to rounding."""
+    B, H, Sq, Sk, D = 1, 2, 256, 768, 128
+    print("case rect_tail", B, H, Sq, Sk, D, flush=True)
+    x = wl.random_rect_inputs(B, H, H, Sq, Sk, D, seed=1402)
+    Qs = np.zeros((B, H, Sk, D), np.uint16); Qs[:, :, Sk - Sq:] = x["Q"]
+    Gs = np.zeros((B, H, Sk, D), np.uint16); Gs[:, :, Sk - Sq:] = x["dO"]
+    Q, K, V, dO = (to_dev(x[k]) for k in ("Q", "K", "V", "dO"))
+    O, L = attn.attn_fwd_rect(Q, K, V, x["scale"], True, split=False)
+    dQ, dK, dV = attn.attn_bwd_rect(Q, K, V, O, dO, L, x["scale"], True)
+    Os, Ls = attn.attn_fwd(to_dev(Qs), K, V, x["scale"], True)
+    dQs, dKs, dVs = attn.attn_bwd(to_dev(Qs), K, V, Os, to_dev(Gs), Ls, x["scale"], True)
+    torch.cuda.synchronize()
+    assert torch.equal(O.view(torch.int16), Os[:, :, Sk - Sq:].contiguous().view(torch.int16))
+    assert torch.equal(L, Ls[:, :, Sk - Sq:])
+    assert torch.equal(dQ.view(torch.int16), dQs[:, :, Sk - Sq:].contiguous().view(torch.int16))
+    np.testing.assert_allclose(to_f64(dK), to_f64(dKs), rtol=0, atol=2e-2)
+    np.testing.assert_allclose(to_f64(dV), to_f64(dVs), rtol=0, atol=2e-2)
+
+
+def test_rect_strided_cache_and_poisoned_outputs():
+    """K/V taken as the first Sk rows of a longer cache allocation (row stride and head stride
+    of the cache), outputs pre-filled with NaN: every output element is written, nothing
+    beyond Sk is read into the result."""
+    B, Hq, Hkv, Sq, Sk, cap, D = 2, 4, 2, 5, 333, 512, 64
+    print("case rect_strided", B, Hq, Hkv, Sq, Sk, D, flush=True)
+    x = wl.random_rect_inputs(B, Hq, Hkv, Sq, Sk, D, seed=1403)
+    cacheK = torch.full((B, Hkv, cap, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    cacheV = torch.full((B, Hkv, cap, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    cacheK[:, :, :Sk] = to_dev(x["K"]); cacheV[:, :, :Sk] = to_dev(x["V"])
+    K, V = cacheK[:, :, :Sk], cacheV[:, :, :Sk]
+    Q, dO = to_dev(x["Q"]), to_dev(x["dO"])
+    O, LSE = attn.attn_fwd_rect(Q, K, V, x["scale"], True)
+    dK = torch.full_like(cacheK, float("nan"))[:, :, :Sk]
+    dV = torch.full_like(cacheV, float("nan"))[:, :, :Sk]
+    dQ, dK, dV = attn.attn_bwd_rect(Q, K, V, O, dO, LSE, x["scale"], True, dK=dK, dV=dV)
+    torch.cuda.synchronize()
+    Oref, Lref = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], True)
+    ref = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], True)
+    check_bf16("O", to_f64(O), Oref)
+    check_lse(to_f64(LSE), Lref)
+    for name, g, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), ref):
+        check_bf16(name, to_f64(g), r, floor_gate=False)
+
+
+def test_rect_full_size_sampled_heads():
+    """The bench shapes at full size, in the launch configuration bench.py times: sampled K/V
+    heads (with their query groups) against the oracle."""
+    for name, heads in (("decode_cmp", [0, 37, 63]), ("prefill_chunk", [5])):
+        w = wl.RECT_WORKLOADS[name]
+        print("case rect_full", name, flush=True)
+        full = wl.make_rect_inputs(w)
+        Q, K, V, dO = (to_dev(full[k]) for k in ("Q", "K", "V", "dO"))
+        O, LSE = attn.attn_fwd_rect(Q, K, V, full["scale"], w.causal)
+        dQ, dK, dV = attn.attn_bwd_rect(Q, K, V, O, dO, LSE, full["scale"], w.causal)
+        torch.cuda.synchronize()
+        G = w.Hq // w.Hkv
+        for kvh in heads:
+            sub = wl.make_rect_inputs(w, kv_heads=[kvh])
+            b, hk = kvh // w.Hkv, kvh % w.Hkv
+            qs = slice(hk * G, hk * G + G)
+            assert np.array_equal(sub["K"][0, 0], full["K"][b, hk])
+            Oref, Lref = oracle.attn_fwd(sub["Q"], sub["K"], sub["V"], sub["scale"], w.causal)
+            ref = oracle.attn_bwd(sub["Q"], sub["K"], sub["V"], sub["dO"], sub["scale"], w.causal)
+            check_bf16("O", to_f64(O[b, qs]), Oref[0])
+            check_lse(to_f64(LSE[b, qs]), Lref[0])
+            if w.Sq >= 32:
+                check_bf16_scaled("dQ", to_f64(dQ[b, qs]), ref[0][0])
+                check_bf16_scaled("dK", to_f64(dK[b, hk]), ref[1][0, 0])
+                check_bf16_scaled("dV", to_f64(dV[b, hk]), ref[2][0, 0])
+            else:
+                check_bf16("dQ", to_f64(dQ[b, qs]), ref[0][0], floor_gate=False)
+                check_bf16("dK", to_f64(dK[b, hk]), ref[1][0, 0], floor_gate=False)
+                check_bf16("dV", to_f64(dV[b, hk]), ref[2][0, 0], floor_gate=False)
