@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="long_causal",
-                    help="one of paper_2601_16238_amd.workloads.WORKLOADS or GQA_WORKLOADS")
+                    help="one of paper_2601_16238_amd.workloads.WORKLOADS, GQA_WORKLOADS or RECT_WORKLOADS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true",
                     help="also time every other workload (reported under 'other_workloads')")
@@ -127,6 +127,111 @@ def measure(torch, attn, wl, w, steps, warmup):
     return res
 
 
+def visible_pairs(Sq, Sk, causal):
+    """(query, key) pairs under the mask; causal is aligned bottom-right (needs Sk >= Sq)."""
+    return Sq * (Sk - Sq) + Sq * (Sq + 1) // 2 if causal else Sq * Sk
+
+
+def measure_rect(torch, attn, wl, w, steps, warmup):
+    """Rectangular workloads (Sq rows against Sk cached keys): forward with the library's
+    split plan, forward in one kernel, and backward.  FLOPs count the visible (query, key)
+    pairs exactly: 4*D per pair forward, 10*D backward."""
+    import numpy as np
+    x = wl.make_rect_inputs(w)
+
+    def dev(b):
+        return torch.from_numpy(b.view(np.int16)).cuda().view(torch.bfloat16)
+
+    Q, K, V, dO = (dev(x[k]) for k in ("Q", "K", "V", "dO"))
+    del x
+    scale, causal = wl.default_scale(w.D), w.causal
+    O = torch.empty_like(Q)
+    LSE = torch.empty((w.B, w.Hq, w.Sq), dtype=torch.float32, device="cuda")
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(K)
+    shape = (w.B, w.Hq, w.Hkv, w.Sq, w.Sk, w.D)
+    fws_bytes = attn.attn_fwd_rect_workspace_bytes(*shape)
+    fws = torch.empty(max(fws_bytes, 256), dtype=torch.uint8, device="cuda")
+    bws = torch.empty(attn.attn_bwd_rect_workspace_bytes(*shape), dtype=torch.uint8, device="cuda")
+
+    def fwd():
+        attn.attn_fwd_rect(Q, K, V, scale, causal, O=O, LSE=LSE, workspace=fws)
+
+    def fwd_one_kernel():
+        attn.attn_fwd_rect(Q, K, V, scale, causal, O=O, LSE=LSE, split=False)
+
+    def bwd():
+        attn.attn_bwd_rect(Q, K, V, O, dO, LSE, scale, causal, dQ=dQ, dK=dK, dV=dV, workspace=bws)
+
+    def step():
+        fwd()
+        bwd()
+
+    for _ in range(warmup):
+        step()
+        fwd_one_kernel()
+    ms = {"step": time_calls(torch, step, steps), "fwd": time_calls(torch, fwd, steps),
+          "fwd_one_kernel": time_calls(torch, fwd_one_kernel, steps),
+          "bwd": time_calls(torch, bwd, steps)}
+    pairs = w.B * w.Hq * visible_pairs(w.Sq, w.Sk, causal)
+    f_fwd, f_bwd = 4.0 * pairs * w.D, 10.0 * pairs * w.D
+    t_q, t_kv = w.B * w.Hq * w.Sq * w.D * 2, w.B * w.Hkv * w.Sk * w.D * 2
+    lse_b = w.B * w.Hq * w.Sq * 4
+    b_fwd, b_bwd = 2 * t_q + 2 * t_kv + lse_b, 4 * t_q + 4 * t_kv + lse_b
+    return {"ms": ms, "splits": fws_bytes // max(1, w.B * w.Hq * w.Sq * (w.D + 1) * 4),
+            "tflops_fwd": f_fwd / (ms["fwd"] * 1e-3) / 1e12,
+            "tflops_fwdbwd": (f_fwd + f_bwd) / (ms["step"] * 1e-3) / 1e12,
+            "gbs_fwd": b_fwd / (ms["fwd"] * 1e-3) / 1e9, "gbs_bwd": b_bwd / (ms["bwd"] * 1e-3) / 1e9,
+            "bytes_fwd": b_fwd, "flops_fwd": f_fwd, "flops_bwd": f_bwd}
+
+
+def rect_main(torch, attn, wl, w, a):
+    """The JSON line for a rectangular workload given as --workload."""
+    r = measure_rect(torch, attn, wl, w, a.steps, a.warmup)
+    hbm_bound = w.Sq < 64   # a handful of rows per K/V row read: the stream of K and V bounds it
+    roof = ({"kernel": "attn_fwd_kernel (+ merge)", "bound": "hbm", "achieved": r["gbs_fwd"],
+             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": r["gbs_fwd"] / PEAK_HBM_GBS, "traffic": None}
+            if hbm_bound else
+            {"kernel": "attn_fwd_kernel (+ merge)", "bound": "mfma", "achieved": r["tflops_fwd"],
+             "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": r["tflops_fwd"] / PEAK_BF16_TFLOPS,
+             "traffic": None})
+    out = {
+        "metric": "attention fwd+bwd TFLOP/s (FLOPs = 4*D fwd + 10*D bwd per visible query-key pair)",
+        "value": r["tflops_fwdbwd"], "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": r["ms"]["step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %s" % (w.name, " ".join(
+            "%s=%s" % (k, getattr(w, k)) for k in ("B", "Hq", "Hkv", "Sq", "Sk", "D", "causal"))),
+                   "seed": w.seed},
+        "ms": r["ms"], "key_splits": r["splits"],
+        "tflops": {"fwd": r["tflops_fwd"], "fwd_bwd": r["tflops_fwdbwd"]},
+        "algorithmic_gbs": {"fwd": r["gbs_fwd"], "bwd": r["gbs_bwd"], "hbm_peak": PEAK_HBM_GBS},
+        "roofline": roof,
+    }
+    if not a.no_cpu_baseline:
+        import oracle
+        G = w.Hq // w.Hkv
+        n_heads = w.B * w.Hkv
+
+        def run(heads):
+            x = wl.make_rect_inputs(w, kv_heads=range(heads))
+            t0 = time.perf_counter()
+            oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], w.causal)
+            oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], w.causal)
+            return time.perf_counter() - t0
+
+        heads, dt = 1, run(1)
+        more = int(min(n_heads, 15.0 // max(dt, 1e-3)))
+        if more > 1:
+            heads, dt = more, run(more)
+        flops = heads * G * 14.0 * w.D * visible_pairs(w.Sq, w.Sk, w.causal)
+        out["cpu_baseline"] = {"value": flops / dt / 1e12, "unit": "TFLOP/s",
+                               "cores": oracle.num_threads(), "kind": "oracle", "seconds": dt,
+                               "sample": "fwd+bwd of the first %d of %d K/V heads (with their query "
+                                         "groups) of %s (fp64)" % (heads, n_heads, w.name),
+                               "nproc": os.cpu_count()}
+    print(json.dumps(out))
+
+
 def cpu_baseline(wl, w):
     """The fp64 oracle, as it stands, on a bounded sample of the same workload: forward +
     backward of whole heads at full sequence length -- one head first, then as many as fit
@@ -169,6 +274,9 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     attn.lib()  # fail loudly if the HIP library is not built
+    if a.workload in wl.RECT_WORKLOADS:
+        rect_main(torch, attn, wl, wl.RECT_WORKLOADS[a.workload], a)
+        return
     w = wl.WORKLOADS[a.workload] if a.workload in wl.WORKLOADS else wl.GQA_WORKLOADS[a.workload]
     if a.calib_copy:
         src = torch.empty(CALIB_COPY_BYTES // 2, dtype=torch.bfloat16, device="cuda").normal_()
@@ -211,6 +319,15 @@ def main():
                             "gbs_fwd": o["gbs_fwd"], "gbs_bwd": o["gbs_bwd"]}
             torch.cuda.empty_cache()
         out["other_workloads"] = others
+        rect = {}
+        for name, ow in wl.RECT_WORKLOADS.items():
+            o = measure_rect(torch, attn, wl, ow, max(5, a.steps // 2), a.warmup)
+            rect[name] = {"shape": {k: getattr(ow, k) for k in ("B", "Hq", "Hkv", "Sq", "Sk", "D", "causal")},
+                          "ms": o["ms"], "key_splits": o["splits"], "tflops_fwd": o["tflops_fwd"],
+                          "tflops_fwdbwd": o["tflops_fwdbwd"], "gbs_fwd": o["gbs_fwd"],
+                          "gbs_bwd": o["gbs_bwd"]}
+            torch.cuda.empty_cache()
+        out["rect_workloads"] = rect
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, w)
         out["cpu_baseline"]["nproc"] = os.cpu_count()

@@ -64,6 +64,35 @@ attn_gqa_params_t as_gqa(const attn_params_t &p)
 
 size_t round_ws(size_t bytes) { return (bytes + kWsAlign - 1) / kWsAlign * kWsAlign; }
 
+// The forward's view of a problem: (B*H) independent heads of S query rows each.
+struct FwdView {
+    int BH, H, S, group;
+    int64_t stride_b, stride_h, stride_s;
+    bool causal;
+};
+
+// Decoding (Sq == 1) with grouped-query heads: the G query heads that share a K/V head are
+// G rows at a uniform distance (the head stride), so they are presented to the kernel as ONE
+// head of G rows.  K and V are then streamed once per K/V head instead of once per query
+// head.  A single row sees every key, so the mask drops out.  LSE [B,Hq,1] is the same
+// memory as [B,Hkv,G].
+FwdView fwd_view(const attn_rect_params_t &p)
+{
+    FwdView v;
+    const int G = p.Hq / p.Hkv;
+    if (p.Sq == 1 && G > 1 &&
+        check_strides(G, p.D, p.q_stride_b, G * p.q_stride_h, p.q_stride_h) == ATTN_OK) {
+        v.BH = p.B * p.Hkv; v.H = p.Hkv; v.S = G; v.group = 1;
+        v.stride_b = p.q_stride_b; v.stride_h = G * p.q_stride_h; v.stride_s = p.q_stride_h;
+        v.causal = false;
+    } else {
+        v.BH = p.B * p.Hq; v.H = p.Hq; v.S = p.Sq; v.group = G;
+        v.stride_b = p.q_stride_b; v.stride_h = p.q_stride_h; v.stride_s = p.q_stride_s;
+        v.causal = p.causal != 0;
+    }
+    return v;
+}
+
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 }  // namespace
@@ -112,7 +141,8 @@ void attn_rect_params_contiguous(attn_rect_params_t *p, int32_t B, int32_t Hq, i
 size_t attn_fwd_rect_workspace_bytes(const attn_rect_params_t *p)
 {
     if (check_params(p) != ATTN_OK) return 0;
-    const int nsplit = attn::fwd_split_plan(p->B * p->Hq, p->Sq, p->Sk, p->D, nullptr);
+    const FwdView v = fwd_view(*p);
+    const int nsplit = attn::fwd_split_plan(v.BH, v.S, p->Sk, p->D, nullptr);
     if (nsplit <= 1) return 0;
     const size_t rows = (size_t)p->B * p->Hq * p->Sq;
     return round_ws((size_t)nsplit * rows * (p->D + 1) * sizeof(float));
@@ -129,8 +159,9 @@ int attn_fwd_rect(const void *Q, const void *K, const void *V, void *O, float *L
         !aligned(LSE, 4))
         return ATTN_ERR_ALIGN;
     // No workspace at all: run unsplit.  A workspace that is there must be usable.
+    const FwdView v = fwd_view(*p);
     int kps = 0;
-    int nsplit = workspace ? attn::fwd_split_plan(p->B * p->Hq, p->Sq, p->Sk, p->D, &kps) : 1;
+    int nsplit = workspace ? attn::fwd_split_plan(v.BH, v.S, p->Sk, p->D, &kps) : 1;
     if (workspace && (!aligned(workspace, kWsAlign) ||
                       workspace_bytes < attn_fwd_rect_workspace_bytes(p)))
         return ATTN_ERR_WORKSPACE;
@@ -143,12 +174,12 @@ int attn_fwd_rect(const void *Q, const void *K, const void *V, void *O, float *L
     a.V = static_cast<const attn::bf16 *>(V);
     a.O = static_cast<attn::bf16 *>(O);
     a.LSE = LSE;
-    a.stride_b = p->q_stride_b; a.stride_h = p->q_stride_h; a.stride_s = p->q_stride_s;
+    a.stride_b = v.stride_b; a.stride_h = v.stride_h; a.stride_s = v.stride_s;
     a.kv_stride_b = p->kv_stride_b; a.kv_stride_h = p->kv_stride_h; a.kv_stride_s = p->kv_stride_s;
-    a.S = p->Sq; a.Sk = p->Sk; a.H = p->Hq; a.BH = p->B * p->Hq; a.group = p->Hq / p->Hkv;
+    a.S = v.S; a.Sk = p->Sk; a.H = v.H; a.BH = v.BH; a.group = v.group;
     a.nqt = 0;
     a.scale_log2e = p->scale * 1.4426950408889634f;
-    return attn::launch_fwd(a, p->D, p->causal != 0, static_cast<hipStream_t>(hip_stream)) == 0
+    return attn::launch_fwd(a, p->D, v.causal, static_cast<hipStream_t>(hip_stream)) == 0
                ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
