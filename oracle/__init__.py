@@ -4,4 +4,4 @@ Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import 
 package.  It shares nothing with the HIP library and is never a fallback for it.
 """
 from .attn_oracle import (attn_fwd, attn_bwd, attn_probs, attn_dscores, build,  # noqa: F401
-                          num_threads)
+                          f16_to_f64, num_threads)

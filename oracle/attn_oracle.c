@@ -36,7 +36,8 @@
  * Sk < Sq would leave rows without any key and is rejected.  Sq = Sk is the square form.
  *
  * Inputs are bf16 bit patterns (uint16) laid out contiguously as [B,H,S,D]; they are
- * widened exactly to double.  `scale` is the fp32 value the GPU receives, widened to
+ * widened exactly to double.  The rectangular entry points also take IEEE fp16 bit patterns
+ * (dtype 1; the paper's kernels are written for "fp16/bf16" inputs): only the widening differs.  `scale` is the fp32 value the GPU receives, widened to
  * double.  All arithmetic is double; exp/log are libm's.  There is no tiling, no online
  * softmax and no fusion: every row (forward, dQ) or column (dK, dV) is written out from
  * the formulas above, with one scratch row/column of length S.
@@ -65,12 +66,24 @@ static inline double bf16_to_f64(uint16_t h)
     return (double)f;
 }
 
-/* widen a bf16 [n] buffer to a freshly malloc'ed double buffer */
-static double *widen(const uint16_t *x, size_t n)
+/* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits; subnormals, inf, nan */
+double oracle_f16_to_f64(uint16_t h)
+{
+    const int sign = h >> 15, ex = (h >> 10) & 31, frac = h & 1023;
+    double v;
+    if (ex == 0) v = ldexp((double)frac, -24);                 /* zero and subnormals */
+    else if (ex == 31) v = frac ? NAN : INFINITY;
+    else v = ldexp(1.0 + (double)frac / 1024.0, ex - 15);
+    return sign ? -v : v;
+}
+
+/* widen a 16-bit float [n] buffer (dtype 0: bf16, 1: IEEE fp16) to a malloc'ed double buffer */
+static double *widen(const uint16_t *x, size_t n, int dtype)
 {
     double *y = (double *)malloc(n * sizeof(double));
     if (!y) return NULL;
-    for (size_t i = 0; i < n; ++i) y[i] = bf16_to_f64(x[i]);
+    if (dtype == 1) for (size_t i = 0; i < n; ++i) y[i] = oracle_f16_to_f64(x[i]);
+    else for (size_t i = 0; i < n; ++i) y[i] = bf16_to_f64(x[i]);
     return y;
 }
 
@@ -106,7 +119,7 @@ static inline int thread_id(void)
  */
 int oracle_attn_fwd_rect(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
                          int B, int H, int Hkv, int S, int Sk, int D, float scale_f32, int causal,
-                         double *O, double *LSE, double *P_out)
+                         int dtype, double *O, double *LSE, double *P_out)
 {
     /* S is the query length Sq throughout this function */
     if (B < 1 || H < 1 || Hkv < 1 || H % Hkv != 0 || S < 1 || Sk < 1 || D < 1) return -1;
@@ -114,7 +127,7 @@ int oracle_attn_fwd_rect(const uint16_t *Qb, const uint16_t *Kb, const uint16_t 
     const int G = H / Hkv; /* query heads per K/V head */
     const size_t BH = (size_t)B * H, n = BH * S * D, nkv = (size_t)B * Hkv * Sk * D;
     const double scale = (double)scale_f32;
-    double *Q = widen(Qb, n), *K = widen(Kb, nkv), *V = widen(Vb, nkv);
+    double *Q = widen(Qb, n, dtype), *K = widen(Kb, nkv, dtype), *V = widen(Vb, nkv, dtype);
     const int nt = oracle_num_threads();
     double *scratch = (double *)malloc((size_t)nt * Sk * sizeof(double)); /* one row per thread */
     const int fail = (!Q || !K || !V || !scratch);
@@ -163,7 +176,7 @@ int oracle_attn_fwd_gqa(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *
                         int B, int H, int Hkv, int S, int D, float scale_f32, int causal,
                         double *O, double *LSE, double *P_out)
 {
-    return oracle_attn_fwd_rect(Qb, Kb, Vb, B, H, Hkv, S, S, D, scale_f32, causal, O, LSE, P_out);
+    return oracle_attn_fwd_rect(Qb, Kb, Vb, B, H, Hkv, S, S, D, scale_f32, causal, 0, O, LSE, P_out);
 }
 
 int oracle_attn_fwd(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
@@ -184,7 +197,7 @@ int oracle_attn_fwd(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
 int oracle_attn_bwd_rect(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *Vb,
                          const uint16_t *dOb,
                          int B, int H, int Hkv, int S, int Sk, int D, float scale_f32, int causal,
-                         double *dQ, double *dK, double *dV, double *dS_out)
+                         int dtype, double *dQ, double *dK, double *dV, double *dS_out)
 {
     /* S is the query length Sq throughout this function */
     if (B < 1 || H < 1 || Hkv < 1 || H % Hkv != 0 || S < 1 || Sk < 1 || D < 1) return -1;
@@ -192,7 +205,8 @@ int oracle_attn_bwd_rect(const uint16_t *Qb, const uint16_t *Kb, const uint16_t 
     const int G = H / Hkv;
     const size_t BH = (size_t)B * H, n = BH * S * D, BHkv = (size_t)B * Hkv, nkv = BHkv * Sk * D;
     const double scale = (double)scale_f32;
-    double *Q = widen(Qb, n), *K = widen(Kb, nkv), *V = widen(Vb, nkv), *dO = widen(dOb, n);
+    double *Q = widen(Qb, n, dtype), *K = widen(Kb, nkv, dtype), *V = widen(Vb, nkv, dtype),
+           *dO = widen(dOb, n, dtype);
     double *LSE = (double *)malloc(BH * S * sizeof(double));
     double *delta = (double *)malloc(BH * S * sizeof(double));
     const int nt = oracle_num_threads();
@@ -285,7 +299,7 @@ int oracle_attn_bwd_gqa(const uint16_t *Qb, const uint16_t *Kb, const uint16_t *
                         int B, int H, int Hkv, int S, int D, float scale_f32, int causal,
                         double *dQ, double *dK, double *dV, double *dS_out)
 {
-    return oracle_attn_bwd_rect(Qb, Kb, Vb, dOb, B, H, Hkv, S, S, D, scale_f32, causal,
+    return oracle_attn_bwd_rect(Qb, Kb, Vb, dOb, B, H, Hkv, S, S, D, scale_f32, causal, 0,
                                 dQ, dK, dV, dS_out);
 }
 

@@ -37,11 +37,13 @@ def _load():
         f64p = ctypes.POINTER(ctypes.c_double)
         i = ctypes.c_int
         lib.oracle_attn_fwd_rect.argtypes = [u16p, u16p, u16p, i, i, i, i, i, i, ctypes.c_float, i,
-                                             f64p, f64p, f64p]
+                                             i, f64p, f64p, f64p]
         lib.oracle_attn_fwd_rect.restype = i
         lib.oracle_attn_bwd_rect.argtypes = [u16p, u16p, u16p, u16p, i, i, i, i, i, i,
-                                             ctypes.c_float, i, f64p, f64p, f64p, f64p]
+                                             ctypes.c_float, i, i, f64p, f64p, f64p, f64p]
         lib.oracle_attn_bwd_rect.restype = i
+        lib.oracle_f16_to_f64.argtypes = [ctypes.c_uint16]
+        lib.oracle_f16_to_f64.restype = ctypes.c_double
         lib.oracle_num_threads.argtypes = []
         lib.oracle_num_threads.restype = i
         _lib = lib
@@ -76,10 +78,19 @@ def _p(a, ct):
     return a.ctypes.data_as(ctypes.POINTER(ct)) if a is not None else None
 
 
-def attn_fwd(Q, K, V, scale, causal, want_probs=False):
+_DTYPES = {"bf16": 0, "f16": 1}
+
+
+def f16_to_f64(h):
+    """The oracle's own widening of one IEEE fp16 bit pattern (exposed so it can be pinned)."""
+    return float(_load().oracle_f16_to_f64(int(h)))
+
+
+def attn_fwd(Q, K, V, scale, causal, want_probs=False, dtype="bf16"):
     """O [B,H,Sq,D] f64, LSE [B,H,Sq] f64 (natural log) [, P [B,H,Sq,Sk] f64].
     K, V: [B,Hkv,Sk,D]; query head h reads K/V head h // (H // Hkv).  With causal=True and
-    Sk > Sq the mask is aligned bottom-right: row i sees keys 0 .. i + Sk - Sq."""
+    Sk > Sq the mask is aligned bottom-right: row i sees keys 0 .. i + Sk - Sq.  `dtype` says
+    how the uint16 inputs are to be read: "bf16" or "f16" (IEEE half)."""
     Q = _u16(Q); K = _kv(K, Q.shape); V = _u16(V, K.shape)
     B, H, S, D = Q.shape
     Hkv, Sk = K.shape[1], K.shape[2]
@@ -89,7 +100,7 @@ def attn_fwd(Q, K, V, scale, causal, want_probs=False):
     rc = _load().oracle_attn_fwd_rect(_p(Q, ctypes.c_uint16), _p(K, ctypes.c_uint16),
                                      _p(V, ctypes.c_uint16), B, H, Hkv, S, Sk, D,
                                      ctypes.c_float(np.float32(scale)), int(bool(causal)),
-                                     _p(O, ctypes.c_double), _p(LSE, ctypes.c_double),
+                                     _DTYPES[dtype], _p(O, ctypes.c_double), _p(LSE, ctypes.c_double),
                                      _p(P, ctypes.c_double))
     if rc != 0:
         raise RuntimeError("oracle_attn_fwd failed (rc=%d)" % rc)
@@ -101,7 +112,7 @@ def attn_probs(Q, K, V, scale, causal):
     return attn_fwd(Q, K, V, scale, causal, want_probs=True)[2]
 
 
-def attn_bwd(Q, K, V, dO, scale, causal, want_dscores=False):
+def attn_bwd(Q, K, V, dO, scale, causal, want_dscores=False, dtype="bf16"):
     """dQ [B,H,Sq,D], dK, dV [B,Hkv,Sk,D] f64 [, dS [B,H,Sq,Sk] f64] for upstream gradient dO on O."""
     Q = _u16(Q); K = _kv(K, Q.shape); V = _u16(V, K.shape); dO = _u16(dO, Q.shape)
     B, H, S, D = Q.shape
@@ -113,7 +124,7 @@ def attn_bwd(Q, K, V, dO, scale, causal, want_dscores=False):
     rc = _load().oracle_attn_bwd_rect(_p(Q, ctypes.c_uint16), _p(K, ctypes.c_uint16),
                                      _p(V, ctypes.c_uint16), _p(dO, ctypes.c_uint16),
                                      B, H, Hkv, S, Sk, D, ctypes.c_float(np.float32(scale)),
-                                     int(bool(causal)), _p(dQ, ctypes.c_double),
+                                     int(bool(causal)), _DTYPES[dtype], _p(dQ, ctypes.c_double),
                                      _p(dK, ctypes.c_double), _p(dV, ctypes.c_double),
                                      _p(dS, ctypes.c_double))
     if rc != 0:

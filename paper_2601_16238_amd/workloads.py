@@ -229,3 +229,25 @@ def make_rect_inputs(w, kv_heads=None):
     out["scale"] = default_scale(w.D)
     out["causal"] = bool(w.causal)
     return out
+
+
+# ---- IEEE fp16 inputs (the second 16-bit input type) ------------------------------------------
+
+def f32_to_f16_bits(x):
+    """Round float32 -> IEEE fp16 (round-to-nearest-even), returned as uint16 bit patterns."""
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def f16_bits_to_f32(b):
+    return np.ascontiguousarray(b, dtype=np.uint16).view(np.float16).astype(np.float32)
+
+
+def random_rect_inputs_f16(B, Hq, Hkv, Sq, Sk, D, seed, sigma=1.0):
+    """As random_rect_inputs (same draws), rounded to fp16 instead of bf16."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = {}
+    for name, heads, rows in (("Q", Hq, Sq), ("K", Hkv, Sk), ("V", Hkv, Sk), ("dO", Hq, Sq)):
+        x = rng.standard_normal((B, heads, rows, D), dtype=np.float32) * np.float32(sigma)
+        out[name] = f32_to_f16_bits(x)
+    out["scale"] = default_scale(D)
+    return out

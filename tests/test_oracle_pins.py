@@ -409,3 +409,61 @@ def test_rect_rejects_causal_with_fewer_keys():
         oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], True)
     with pytest.raises(RuntimeError):
         oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], True)
+
+
+# ---- fp16 inputs: only the widening of the inputs differs ---------------------------------------
+
+def test_f16_widening_matches_numpy_for_every_bit_pattern():
+    """The oracle's own half -> double conversion against numpy's float16 (an independent
+    implementation), for all 65536 patterns: zeros, subnormals, normals, infinities, NaNs."""
+    h = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    want = h.view(np.float16).astype(np.float64)
+    got = np.array([oracle.f16_to_f64(int(v)) for v in h])
+    nan = np.isnan(want)
+    assert (np.isnan(got) == nan).all()
+    assert (got[~nan] == want[~nan]).all()
+    assert (np.signbit(got[~nan]) == np.signbit(want[~nan])).all()
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_f16_path_equals_bf16_path_on_values_both_formats_hold(causal):
+    """Inputs with at most 8 significant bits and small exponents are exact in bf16 AND in
+    fp16, so both readings must give the same result to the last bit; this ties the fp16 path
+    to the bf16 one that everything above pins."""
+    B, Hq, Hkv, Sq, Sk, D = 1, 4, 2, 9, 21, 16
+    rng = np.random.Generator(np.random.PCG64(97))
+    vals = {}
+    for name, heads, rows in (("Q", Hq, Sq), ("K", Hkv, Sk), ("V", Hkv, Sk), ("dO", Hq, Sq)):
+        vals[name] = (rng.integers(-127, 128, size=(B, heads, rows, D)) / 64.0).astype(np.float32)
+    as_bf = {k: bits(v) for k, v in vals.items()}
+    as_h = {k: wl.f32_to_f16_bits(v) for k, v in vals.items()}
+    for k in vals:     # the premise: both encodings hold the values exactly
+        assert (f64(as_bf[k]) == vals[k]).all() and (wl.f16_bits_to_f32(as_h[k]) == vals[k]).all()
+    sc = wl.default_scale(D)
+    a = oracle.attn_fwd(as_bf["Q"], as_bf["K"], as_bf["V"], sc, causal)
+    b = oracle.attn_fwd(as_h["Q"], as_h["K"], as_h["V"], sc, causal, dtype="f16")
+    ga = oracle.attn_bwd(as_bf["Q"], as_bf["K"], as_bf["V"], as_bf["dO"], sc, causal)
+    gb = oracle.attn_bwd(as_h["Q"], as_h["K"], as_h["V"], as_h["dO"], sc, causal, dtype="f16")
+    for x, y in zip(a + ga, b + gb):
+        assert np.array_equal(x, y)
+
+
+def test_f16_against_torch_fp64_on_fp16_inputs():
+    """fp16 inputs that are NOT representable in bf16 (11 significant bits), against torch."""
+    x = wl.random_rect_inputs_f16(1, 2, 1, 5, 12, 8, seed=98)
+    assert (bits(wl.f16_bits_to_f32(x["Q"])) != 0).any()
+    assert not np.array_equal(f64(bits(wl.f16_bits_to_f32(x["Q"]))),
+                              wl.f16_bits_to_f32(x["Q"]).astype(np.float64))
+    t = {k: torch.tensor(wl.f16_bits_to_f32(x[k]).astype(np.float64), requires_grad=(k != "dO"))
+         for k in ("Q", "K", "V", "dO")}
+    Kt, Vt = t["K"].repeat_interleave(2, dim=1), t["V"].repeat_interleave(2, dim=1)
+    s = (t["Q"] @ Kt.transpose(-1, -2)) * float(np.float32(x["scale"]))
+    o_t = torch.softmax(s, dim=-1) @ Vt
+    gq, gk, gv = torch.autograd.grad(o_t, (t["Q"], t["K"], t["V"]), grad_outputs=t["dO"])
+    O, LSE = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], False, dtype="f16")
+    dQ, dK, dV = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], False, dtype="f16")
+    np.testing.assert_allclose(O, o_t.detach().numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(LSE, torch.logsumexp(s, dim=-1).detach().numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dQ, gq.numpy(), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(dK, gk.numpy(), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(dV, gv.numpy(), rtol=0, atol=1e-11)
