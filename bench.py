@@ -328,6 +328,24 @@ def main():
                           "gbs_bwd": o["gbs_bwd"]}
             torch.cuda.empty_cache()
         out["rect_workloads"] = rect
+        # the fp16 build of the kernels on the main shape (through the rectangular entry points)
+        g = torch.Generator(device="cuda"); g.manual_seed(w.seed)
+        H = w.Hq if hasattr(w, "Hq") else w.H
+        q16, k16, v16, do16 = (torch.randn((w.B, H, w.S, w.D), device="cuda", generator=g)
+                               .to(torch.float16) for _ in range(4))
+        sc = wl.default_scale(w.D)
+        o16, l16 = attn.attn_fwd_rect(q16, k16, v16, sc, w.causal)
+        bufs = [torch.empty_like(q16) for _ in range(3)]
+        ws16 = torch.empty(attn.attn_bwd_rect_workspace_bytes(w.B, H, H, w.S, w.S, w.D),
+                           dtype=torch.uint8, device="cuda")
+        f16_fwd = time_calls(torch, lambda: attn.attn_fwd_rect(q16, k16, v16, sc, w.causal, O=o16, LSE=l16), 10)
+        f16_bwd = time_calls(torch, lambda: attn.attn_bwd_rect(q16, k16, v16, o16, do16, l16, sc, w.causal,
+                                                                dQ=bufs[0], dK=bufs[1], dV=bufs[2],
+                                                                workspace=ws16), 10)
+        ff = wl.fwd_flops(w.B, H, w.S, w.D, w.causal)
+        out["f16_same_shape"] = {"ms": {"fwd": f16_fwd, "bwd": f16_bwd},
+                                 "tflops_fwd": ff / (f16_fwd * 1e-3) / 1e12,
+                                 "tflops_fwdbwd": 3.5 * ff / ((f16_fwd + f16_bwd) * 1e-3) / 1e12}
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, w)
         out["cpu_baseline"]["nproc"] = os.cpu_count()

@@ -206,6 +206,22 @@ int attn_bwd_rect(const void *Q, const void *K, const void *V, const void *O, co
                   void *workspace, size_t workspace_bytes,
                   const attn_rect_params_t *p, void *hip_stream);
 
+/*
+ * IEEE fp16 variant of the rectangular entry points (the paper's kernels are written for
+ * fp16/bf16 inputs): Q, K, V, O, dO, dQ, dK, dV hold fp16 instead of bf16; LSE, the
+ * workspaces (same sizes, same *_workspace_bytes functions), parameters, errors and stream
+ * semantics are unchanged.  Accumulation is fp32; P and dS are rounded to fp16 for the
+ * second matrix product of each stage.
+ */
+int attn_fwd_rect_f16(const void *Q, const void *K, const void *V, void *O, float *LSE,
+                      void *workspace, size_t workspace_bytes,
+                      const attn_rect_params_t *p, void *hip_stream);
+
+int attn_bwd_rect_f16(const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                      const float *LSE, void *dQ, void *dK, void *dV,
+                      void *workspace, size_t workspace_bytes,
+                      const attn_rect_params_t *p, void *hip_stream);
+
 /* Static, NUL-terminated description of a status code.  Never NULL. */
 const char *attn_status_string(int status);
 

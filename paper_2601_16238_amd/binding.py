@@ -24,8 +24,8 @@ EXPORTS = ("attn_params_contiguous", "attn_fwd", "attn_bwd_workspace_bytes", "at
            "attn_bwd_stages", "attn_gqa_params_contiguous", "attn_fwd_gqa",
            "attn_bwd_gqa_workspace_bytes", "attn_bwd_gqa", "attn_bwd_gqa_stages",
            "attn_rect_params_contiguous", "attn_fwd_rect_workspace_bytes", "attn_fwd_rect",
-           "attn_bwd_rect_workspace_bytes", "attn_bwd_rect",
-           "attn_status_string", "attn_version")
+           "attn_bwd_rect_workspace_bytes", "attn_bwd_rect", "attn_fwd_rect_f16",
+           "attn_bwd_rect_f16", "attn_status_string", "attn_version")
 STAGE_DELTA, STAGE_DKDV, STAGE_DQ = 1, 2, 4
 STAGE_ALL = 7
 
@@ -113,6 +113,10 @@ def lib():
         L.attn_bwd_rect_workspace_bytes.restype = ctypes.c_size_t
         L.attn_bwd_rect.argtypes = [vp] * 9 + [vp, ctypes.c_size_t, rp, vp]
         L.attn_bwd_rect.restype = ctypes.c_int
+        L.attn_fwd_rect_f16.argtypes = L.attn_fwd_rect.argtypes
+        L.attn_fwd_rect_f16.restype = ctypes.c_int
+        L.attn_bwd_rect_f16.argtypes = L.attn_bwd_rect.argtypes
+        L.attn_bwd_rect_f16.restype = ctypes.c_int
         L.attn_status_string.argtypes = [ctypes.c_int]
         L.attn_status_string.restype = ctypes.c_char_p
         L.attn_version.argtypes = []
@@ -352,10 +356,11 @@ def attn_fwd_rect(Q, K, V, scale, causal, O=None, LSE=None, workspace=None, spli
                   stream=None):
     """O [B,Hq,Sq,D], LSE [B,Hq,Sq]; K, V: [B,Hkv,Sk,D].  `split=False` passes no workspace,
     which keeps the forward in one kernel; otherwise a workspace is allocated when the
-    library's plan asks for one."""
+    library's plan asks for one.  bf16 or fp16 tensors (all of one type)."""
     import torch
-    if Q.dtype != torch.bfloat16 or not Q.is_cuda:
-        raise ValueError("Q,K,V must be bf16 tensors on the GPU")
+    if Q.dtype not in (torch.bfloat16, torch.float16) or not Q.is_cuda:
+        raise ValueError("Q,K,V must be bf16 or fp16 tensors on the GPU")
+    entry = lib().attn_fwd_rect if Q.dtype == torch.bfloat16 else lib().attn_fwd_rect_f16
     _same_layout(K, V)
     if O is None:
         O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
@@ -374,9 +379,8 @@ def attn_fwd_rect(Q, K, V, scale, causal, O=None, LSE=None, workspace=None, spli
             workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
         if workspace is not None:
             ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
-    rc = lib().attn_fwd_rect(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
-                             LSE.data_ptr(), ws_ptr, ws_bytes, ctypes.byref(p),
-                             _stream_ptr(torch, stream))
+    rc = entry(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+               LSE.data_ptr(), ws_ptr, ws_bytes, ctypes.byref(p), _stream_ptr(torch, stream))
     if rc != ATTN_OK:
         raise AttnError(rc, "attn_fwd_rect")
     return O, LSE
@@ -389,10 +393,11 @@ def attn_bwd_rect_workspace_bytes(B, Hq, Hkv, Sq, Sk, D):
 
 def attn_bwd_rect(Q, K, V, O, dO, LSE, scale, causal, dQ=None, dK=None, dV=None, workspace=None,
                   stream=None):
-    """dQ [B,Hq,Sq,D], dK, dV [B,Hkv,Sk,D] = rectangular attention backward."""
+    """dQ [B,Hq,Sq,D], dK, dV [B,Hkv,Sk,D] = rectangular attention backward (bf16 or fp16)."""
     import torch
-    if Q.dtype != torch.bfloat16 or not Q.is_cuda:
-        raise ValueError("tensors must be bf16 on the GPU")
+    if Q.dtype not in (torch.bfloat16, torch.float16) or not Q.is_cuda:
+        raise ValueError("tensors must be bf16 or fp16 on the GPU")
+    entry = lib().attn_bwd_rect if Q.dtype == torch.bfloat16 else lib().attn_bwd_rect_f16
     _same_layout(Q, O, dO)
     _same_layout(K, V)
     if dQ is None:
@@ -414,11 +419,11 @@ def attn_bwd_rect(Q, K, V, O, dO, LSE, scale, causal, dQ=None, dK=None, dV=None,
     need = int(lib().attn_bwd_rect_workspace_bytes(ctypes.byref(p)))
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
-    rc = lib().attn_bwd_rect(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
-                             dO.data_ptr(), LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(),
-                             dV.data_ptr(), workspace.data_ptr(),
-                             workspace.numel() * workspace.element_size(), ctypes.byref(p),
-                             _stream_ptr(torch, stream))
+    rc = entry(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+               dO.data_ptr(), LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(),
+               dV.data_ptr(), workspace.data_ptr(),
+               workspace.numel() * workspace.element_size(), ctypes.byref(p),
+               _stream_ptr(torch, stream))
     if rc != ATTN_OK:
         raise AttnError(rc, "attn_bwd_rect")
     return dQ, dK, dV

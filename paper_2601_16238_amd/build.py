@@ -8,7 +8,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libmi355attn.so")
-SOURCES = ["attn_api.hip", "attn_fwd.hip", "attn_bwd.hip"]
+# (source, extra flags, object): the kernel sources are built once per element type
+SOURCES = [("attn_api.hip", [], "attn_api.o"),
+           ("attn_fwd.hip", [], "attn_fwd.o"), ("attn_bwd.hip", [], "attn_bwd.o"),
+           ("attn_fwd.hip", ["-DATTN_F16"], "attn_fwd_f16.o"),
+           ("attn_bwd.hip", ["-DATTN_F16"], "attn_bwd_f16.o")]
 # -packed-fp32-ops: never let the compiler form v_pk_*_f32 instructions.
 # -fno-honor-nans (device only): fmaxf lowers to bare v_max/v_max3 without canonicalising
 # moves; the kernels never produce or test NaNs.
@@ -30,9 +34,10 @@ def build(verbose=False, resource_usage=False):
     os.makedirs(OBJ, exist_ok=True)
     cc = _hipcc()
 
-    def one(src):
-        obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-        cmd = [cc] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+    def one(job):
+        src, extra, objname = job
+        obj = os.path.join(OBJ, objname)
+        cmd = [cc] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", obj]
         if resource_usage:
             cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
         res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

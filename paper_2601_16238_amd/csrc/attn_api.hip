@@ -97,6 +97,82 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 
 }  // namespace
 
+// E: element type of Q, K, V, O (__bf16 or _Float16)
+template <typename E>
+static int fwd_impl(const void *Q, const void *K, const void *V, void *O, float *LSE,
+                    void *workspace, size_t workspace_bytes,
+                    const attn_rect_params_t *p, void *hip_stream)
+{
+    if (!Q || !K || !V || !O || !LSE) return ATTN_ERR_NULL;
+    const int rc = check_params(p);
+    if (rc != ATTN_OK) return rc;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) ||
+        !aligned(LSE, 4))
+        return ATTN_ERR_ALIGN;
+    // No workspace at all: run unsplit.  A workspace that is there must be usable.
+    const FwdView v = fwd_view(*p);
+    int kps = 0;
+    int nsplit = workspace ? attn::fwd_split_plan(v.BH, v.S, p->Sk, p->D, &kps) : 1;
+    if (workspace && (!aligned(workspace, kWsAlign) ||
+                      workspace_bytes < attn_fwd_rect_workspace_bytes(p)))
+        return ATTN_ERR_WORKSPACE;
+    attn::FwdArgsT<E> a;
+    a.nsplit = nsplit; a.kps = kps;
+    a.Opart = static_cast<float *>(workspace);
+    a.LSEpart = a.Opart ? a.Opart + (size_t)nsplit * p->B * p->Hq * p->Sq * p->D : nullptr;
+    a.Q = static_cast<const E *>(Q);
+    a.K = static_cast<const E *>(K);
+    a.V = static_cast<const E *>(V);
+    a.O = static_cast<E *>(O);
+    a.LSE = LSE;
+    a.stride_b = v.stride_b; a.stride_h = v.stride_h; a.stride_s = v.stride_s;
+    a.kv_stride_b = p->kv_stride_b; a.kv_stride_h = p->kv_stride_h; a.kv_stride_s = p->kv_stride_s;
+    a.S = v.S; a.Sk = p->Sk; a.H = v.H; a.BH = v.BH; a.group = v.group;
+    a.nqt = 0;
+    a.scale_log2e = p->scale * 1.4426950408889634f;
+    return attn::launch_fwd(a, p->D, v.causal, static_cast<hipStream_t>(hip_stream)) == 0
+               ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+template <typename E>
+static int bwd_impl(const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                    const float *LSE, void *dQ, void *dK, void *dV,
+                    void *workspace, size_t workspace_bytes,
+                    const attn_rect_params_t *p, void *hip_stream, uint32_t stages)
+{
+    if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_NULL;
+    const int rc = check_params(p);
+    if (rc != ATTN_OK) return rc;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) ||
+        !aligned(dO, 16) || !aligned(dQ, 16) || !aligned(dK, 16) || !aligned(dV, 16) ||
+        !aligned(LSE, 4))
+        return ATTN_ERR_ALIGN;
+    if (!workspace || !aligned(workspace, kWsAlign) ||
+        workspace_bytes < attn_bwd_rect_workspace_bytes(p))
+        return ATTN_ERR_WORKSPACE;
+    if (stages == 0 || (stages & ~7u)) return ATTN_ERR_SHAPE;
+    attn::BwdArgsT<E> a;
+    a.Q = static_cast<const E *>(Q);
+    a.K = static_cast<const E *>(K);
+    a.V = static_cast<const E *>(V);
+    a.O = static_cast<const E *>(O);
+    a.dO = static_cast<const E *>(dO);
+    a.LSE = LSE;
+    a.delta = static_cast<float *>(workspace);
+    a.dQ = static_cast<E *>(dQ);
+    a.dK = static_cast<E *>(dK);
+    a.dV = static_cast<E *>(dV);
+    a.stride_b = p->q_stride_b; a.stride_h = p->q_stride_h; a.stride_s = p->q_stride_s;
+    a.kv_stride_b = p->kv_stride_b; a.kv_stride_h = p->kv_stride_h; a.kv_stride_s = p->kv_stride_s;
+    a.S = p->Sq; a.Sk = p->Sk; a.H = p->Hq; a.BH = p->B * p->Hq; a.group = p->Hq / p->Hkv;
+    a.ntile = 0;
+    a.scale = p->scale;
+    a.scale_log2e = p->scale * 1.4426950408889634f;
+    return attn::launch_bwd(a, p->D, p->causal != 0, static_cast<hipStream_t>(hip_stream),
+                            stages) == 0
+               ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
 extern "C" {
 
 void attn_params_contiguous(attn_params_t *p, int32_t B, int32_t H, int32_t S, int32_t D,
@@ -152,35 +228,14 @@ int attn_fwd_rect(const void *Q, const void *K, const void *V, void *O, float *L
                   void *workspace, size_t workspace_bytes,
                   const attn_rect_params_t *p, void *hip_stream)
 {
-    if (!Q || !K || !V || !O || !LSE) return ATTN_ERR_NULL;
-    const int rc = check_params(p);
-    if (rc != ATTN_OK) return rc;
-    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) ||
-        !aligned(LSE, 4))
-        return ATTN_ERR_ALIGN;
-    // No workspace at all: run unsplit.  A workspace that is there must be usable.
-    const FwdView v = fwd_view(*p);
-    int kps = 0;
-    int nsplit = workspace ? attn::fwd_split_plan(v.BH, v.S, p->Sk, p->D, &kps) : 1;
-    if (workspace && (!aligned(workspace, kWsAlign) ||
-                      workspace_bytes < attn_fwd_rect_workspace_bytes(p)))
-        return ATTN_ERR_WORKSPACE;
-    attn::FwdArgs a;
-    a.nsplit = nsplit; a.kps = kps;
-    a.Opart = static_cast<float *>(workspace);
-    a.LSEpart = a.Opart ? a.Opart + (size_t)nsplit * p->B * p->Hq * p->Sq * p->D : nullptr;
-    a.Q = static_cast<const attn::bf16 *>(Q);
-    a.K = static_cast<const attn::bf16 *>(K);
-    a.V = static_cast<const attn::bf16 *>(V);
-    a.O = static_cast<attn::bf16 *>(O);
-    a.LSE = LSE;
-    a.stride_b = v.stride_b; a.stride_h = v.stride_h; a.stride_s = v.stride_s;
-    a.kv_stride_b = p->kv_stride_b; a.kv_stride_h = p->kv_stride_h; a.kv_stride_s = p->kv_stride_s;
-    a.S = v.S; a.Sk = p->Sk; a.H = v.H; a.BH = v.BH; a.group = v.group;
-    a.nqt = 0;
-    a.scale_log2e = p->scale * 1.4426950408889634f;
-    return attn::launch_fwd(a, p->D, v.causal, static_cast<hipStream_t>(hip_stream)) == 0
-               ? ATTN_OK : ATTN_ERR_LAUNCH;
+    return fwd_impl<__bf16>(Q, K, V, O, LSE, workspace, workspace_bytes, p, hip_stream);
+}
+
+int attn_fwd_rect_f16(const void *Q, const void *K, const void *V, void *O, float *LSE,
+                      void *workspace, size_t workspace_bytes,
+                      const attn_rect_params_t *p, void *hip_stream)
+{
+    return fwd_impl<_Float16>(Q, K, V, O, LSE, workspace, workspace_bytes, p, hip_stream);
 }
 
 int attn_fwd_gqa(const void *Q, const void *K, const void *V, void *O, float *LSE,
@@ -220,51 +275,24 @@ size_t attn_bwd_workspace_bytes(const attn_params_t *p)
     return attn_bwd_gqa_workspace_bytes(&g);
 }
 
-static int bwd_impl(const void *Q, const void *K, const void *V, const void *O, const void *dO,
-                    const float *LSE, void *dQ, void *dK, void *dV,
-                    void *workspace, size_t workspace_bytes,
-                    const attn_rect_params_t *p, void *hip_stream, uint32_t stages)
-{
-    if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_NULL;
-    const int rc = check_params(p);
-    if (rc != ATTN_OK) return rc;
-    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) ||
-        !aligned(dO, 16) || !aligned(dQ, 16) || !aligned(dK, 16) || !aligned(dV, 16) ||
-        !aligned(LSE, 4))
-        return ATTN_ERR_ALIGN;
-    if (!workspace || !aligned(workspace, kWsAlign) ||
-        workspace_bytes < attn_bwd_rect_workspace_bytes(p))
-        return ATTN_ERR_WORKSPACE;
-    if (stages == 0 || (stages & ~7u)) return ATTN_ERR_SHAPE;
-    attn::BwdArgs a;
-    a.Q = static_cast<const attn::bf16 *>(Q);
-    a.K = static_cast<const attn::bf16 *>(K);
-    a.V = static_cast<const attn::bf16 *>(V);
-    a.O = static_cast<const attn::bf16 *>(O);
-    a.dO = static_cast<const attn::bf16 *>(dO);
-    a.LSE = LSE;
-    a.delta = static_cast<float *>(workspace);
-    a.dQ = static_cast<attn::bf16 *>(dQ);
-    a.dK = static_cast<attn::bf16 *>(dK);
-    a.dV = static_cast<attn::bf16 *>(dV);
-    a.stride_b = p->q_stride_b; a.stride_h = p->q_stride_h; a.stride_s = p->q_stride_s;
-    a.kv_stride_b = p->kv_stride_b; a.kv_stride_h = p->kv_stride_h; a.kv_stride_s = p->kv_stride_s;
-    a.S = p->Sq; a.Sk = p->Sk; a.H = p->Hq; a.BH = p->B * p->Hq; a.group = p->Hq / p->Hkv;
-    a.ntile = 0;
-    a.scale = p->scale;
-    a.scale_log2e = p->scale * 1.4426950408889634f;
-    return attn::launch_bwd(a, p->D, p->causal != 0, static_cast<hipStream_t>(hip_stream),
-                            stages) == 0
-               ? ATTN_OK : ATTN_ERR_LAUNCH;
-}
-
 int attn_bwd_rect(const void *Q, const void *K, const void *V, const void *O, const void *dO,
                   const float *LSE, void *dQ, void *dK, void *dV,
                   void *workspace, size_t workspace_bytes,
                   const attn_rect_params_t *p, void *hip_stream)
 {
-    return bwd_impl(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, p, hip_stream,
-                    ATTN_BWD_STAGE_DELTA | ATTN_BWD_STAGE_DKDV | ATTN_BWD_STAGE_DQ);
+    return bwd_impl<__bf16>(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, p,
+                            hip_stream,
+                            ATTN_BWD_STAGE_DELTA | ATTN_BWD_STAGE_DKDV | ATTN_BWD_STAGE_DQ);
+}
+
+int attn_bwd_rect_f16(const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                      const float *LSE, void *dQ, void *dK, void *dV,
+                      void *workspace, size_t workspace_bytes,
+                      const attn_rect_params_t *p, void *hip_stream)
+{
+    return bwd_impl<_Float16>(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, p,
+                              hip_stream,
+                              ATTN_BWD_STAGE_DELTA | ATTN_BWD_STAGE_DKDV | ATTN_BWD_STAGE_DQ);
 }
 
 int attn_bwd_gqa(const void *Q, const void *K, const void *V, const void *O, const void *dO,
@@ -284,8 +312,8 @@ int attn_bwd_gqa_stages(const void *Q, const void *K, const void *V, const void 
 {
     if (!p) return ATTN_ERR_NULL;
     const attn_rect_params_t g = as_rect(*p);
-    return bwd_impl(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, &g, hip_stream,
-                    stages);
+    return bwd_impl<__bf16>(Q, K, V, O, dO, LSE, dQ, dK, dV, workspace, workspace_bytes, &g,
+                            hip_stream, stages);
 }
 
 int attn_bwd(const void *Q, const void *K, const void *V, const void *O, const void *dO,
@@ -324,6 +352,6 @@ const char *attn_status_string(int status)
     }
 }
 
-int attn_version(void) { return 1002; }
+int attn_version(void) { return 1003; }
 
 }  // extern "C"

@@ -40,8 +40,8 @@ __global__ void __launch_bounds__(256) attn_bwd_delta_kernel(const BwdArgs a)
         const int bh = (int)(row / a.S), i = (int)(row % a.S);
         const int64_t off = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h +
                             (int64_t)i * a.stride_s + sub * 8;
-        const bf16x8 o = as_bf16x8(ld_global16(a.O + off));
-        const bf16x8 g = as_bf16x8(ld_global16(a.dO + off));
+        const elem8 o = as_elem8(ld_global16(a.O + off));
+        const elem8 g = as_elem8(ld_global16(a.dO + off));
 #pragma unroll
         for (int t = 0; t < 8; ++t) acc += (float)o[t] * (float)g[t];
     }
@@ -61,7 +61,7 @@ __global__ void __launch_bounds__(256) attn_bwd_delta_kernel(const BwdArgs a)
 // and a wave alternating between the exp-heavy and the accumulate-heavy half cannot overlap
 // them, so the halves go to different waves:
 //   producer p (waves 0-3), slot t: 32 keys; S = Q K^T, dP = dO V^T, P = exp2(c S - lse2),
-//                                   dS = P o (dP - delta); bf16 P and dS -> LDS exchange
+//                                   dS = P o (dP - delta); elem P and dS -> LDS exchange
 //   consumer (waves 4-7), slot t-1: 64 keys (two producers) and ONE output: even consumers
 //                                   dV^T += dO^T P, odd ones dK^T += Q^T dS; every transposed
 //                                   LDS fragment feeds two MFMAs (one per 32-key block)
@@ -185,15 +185,15 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     };
     auto ring_next = [](int x) { return x + 1 == C::kRing ? 0 : x + 1; };
 
-    bf16x8 *const Xs = reinterpret_cast<bf16x8 *>(smem + C::kOffXchg) + pair * 256 + l;
+    elem8 *const Xs = reinterpret_cast<elem8 *>(smem + C::kOffXchg) + pair * 256 + l;
 
     if (producer) {
         // K and V fragments (B operands): lane holds K[key][16ks + 8h .. +7].
-        bf16x8 kf[KS], vf[KS];
+        elem8 kf[KS], vf[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            kf[ks] = as_bf16x8(ld_global16(a.K + base_kv + (int64_t)keyc * a.kv_stride_s + ks * 16 + 8 * h));
-            vf[ks] = as_bf16x8(ld_global16(a.V + base_kv + (int64_t)keyc * a.kv_stride_s + ks * 16 + 8 * h));
+            kf[ks] = as_elem8(ld_global16(a.K + base_kv + (int64_t)keyc * a.kv_stride_s + ks * 16 + 8 * h));
+            vf[ks] = as_elem8(ld_global16(a.V + base_kv + (int64_t)keyc * a.kv_stride_s + ks * 16 + 8 * h));
         }
         // make sure no register load is counted among the streamed transfers any more
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -229,14 +229,14 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
                     }
 #pragma unroll
                     for (int i = 0; i < 16; ++i) zero[i] = 0.f;
-                    s = mfma32(*(const bf16x8 *)(Qt + lane_off), kf[0], zero);
-                    dp = mfma32(*(const bf16x8 *)(Qt + C::kTensorBytes + lane_off), vf[0], nd);
+                    s = mfma32(*(const elem8 *)(Qt + lane_off), kf[0], zero);
+                    dp = mfma32(*(const elem8 *)(Qt + C::kTensorBytes + lane_off), vf[0], nd);
                 }
 #pragma unroll
                 for (int ks = 1; ks < KS; ++ks) {
                     const int off = lane_off ^ (ks * 32);
-                    s = mfma32(*(const bf16x8 *)(Qt + off), kf[ks], s);
-                    dp = mfma32(*(const bf16x8 *)(Qt + C::kTensorBytes + off), vf[ks], dp);
+                    s = mfma32(*(const elem8 *)(Qt + off), kf[ks], s);
+                    dp = mfma32(*(const elem8 *)(Qt + C::kTensorBytes + off), vf[ks], dp);
                 }
                 // the lane's key is fixed; P = exp2(c S - lse2) per row
 #pragma unroll
@@ -258,7 +258,7 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
                 }
 #pragma unroll
                 for (int i = 0; i < 16; ++i) dp[i] *= s[i];  // dS = P o (dP - delta)
-                bf16x8 *x = Xs + (t & 1) * (C::kPairs * 256);
+                elem8 *x = Xs + (t & 1) * (C::kPairs * 256);
                 x[0] = pack8(s[0], s[1], s[2], s[3], s[4], s[5], s[6], s[7]);
                 x[64] = pack8(s[8], s[9], s[10], s[11], s[12], s[13], s[14], s[15]);
                 x[128] = pack8(dp[0], dp[1], dp[2], dp[3], dp[4], dp[5], dp[6], dp[7]);
@@ -297,18 +297,18 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
         auto block_active = [&](int t, int kfirst) {
             return t * C::kRows < S && (!CAUSAL || t * C::kRows + 31 + coff >= kfirst);
         };
-        const bf16x8 *const Xc = reinterpret_cast<const bf16x8 *>(smem + C::kOffXchg) +
+        const elem8 *const Xc = reinterpret_cast<const elem8 *>(smem + C::kOffXchg) +
                                  (2 * half) * 256 + kind * 128 + l;
         auto consume = [&](int t, int rs) {
             const bool actA = block_active(t, kA), actB = block_active(t, kB);
             if (!actA) return;  // kA < kB: then the second block is not active either
             const char *Tt = smem + rs * C::kSlotBytes + (kind ? 0 : C::kTensorBytes);
-            const bf16x8 *x = Xc + (t & 1) * (C::kPairs * 256);
-            const bf16x8 opA[2] = {x[0], x[64]};
+            const elem8 *x = Xc + (t & 1) * (C::kPairs * 256);
+            const elem8 opA[2] = {x[0], x[64]};
             // Slots above the diagonal of the second key block: its producer wrote nothing,
             // so the block gets zero operands (a second code path without its MFMAs makes
             // the compiler spill the accumulators).
-            bf16x8 opB[2];
+            elem8 opB[2];
 #pragma unroll
             for (int i = 0; i < 8; ++i) opB[0][i] = opB[1][i] = 0;
             if (actB) { opB[0] = x[256]; opB[1] = x[256 + 64]; }
@@ -319,8 +319,8 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
                     // d block db = chunks 4db..4db+3: flips bits 6.. of the swizzled offset
                     const int o0 = (tr_off[0] ^ (db << 6)) + cc * 16 * RB;
                     const int o1 = (tr_off[1] ^ (db << 6)) + cc * 16 * RB;
-                    const bf16x8 T = join8(lds_read_tr((const bf16 *)(Tt + o0)),
-                                           lds_read_tr((const bf16 *)(Tt + o1)));
+                    const elem8 T = join8(lds_read_tr((const elem *)(Tt + o0)),
+                                           lds_read_tr((const elem *)(Tt + o1)));
                     acc[0][db] = mfma32(T, opA[cc], acc[0][db]);
                     acc[1][db] = mfma32(T, opB[cc], acc[1][db]);
                 }
@@ -339,18 +339,18 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
         if (n_slot > t0) consume(n_slot - 1, rs == 0 ? C::kRing - 1 : rs - 1);
         }
 
-        bf16 *const out = kind ? a.dK : a.dV;
+        elem *const out = kind ? a.dK : a.dV;
         const float sc = kind ? a.scale : 1.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
             const int okey = kA + 32 * kb + r;
             if (okey < Sk) {
-                bf16 *op = out + base_kv + (int64_t)okey * a.kv_stride_s;
+                elem *op = out + base_kv + (int64_t)okey * a.kv_stride_s;
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
                     for (int g = 0; g < 4; ++g)
-                        *(bf16x4 *)(op + 32 * db + 8 * g + 4 * h) =
+                        *(elem4 *)(op + 32 * db + 8 * g + 4 * h) =
                             pack4(acc[kb][db][4 * g] * sc, acc[kb][db][4 * g + 1] * sc,
                                   acc[kb][db][4 * g + 2] * sc, acc[kb][db][4 * g + 3] * sc);
             }
@@ -436,11 +436,11 @@ attn_bwd_dq_kernel(const BwdArgs a)
     dma_tile(0, 0);
     if (n_kt > 1) dma_tile(1, 1);
 
-    bf16x8 qf[KS], gf[KS];
+    elem8 qf[KS], gf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-        qf[ks] = as_bf16x8(ld_global16(a.Q + base + (int64_t)qc * a.stride_s + ks * 16 + 8 * h));
-        gf[ks] = as_bf16x8(ld_global16(a.dO + base + (int64_t)qc * a.stride_s + ks * 16 + 8 * h));
+        qf[ks] = as_elem8(ld_global16(a.Q + base + (int64_t)qc * a.stride_s + ks * 16 + 8 * h));
+        gf[ks] = as_elem8(ld_global16(a.dO + base + (int64_t)qc * a.stride_s + ks * 16 + 8 * h));
     }
     const float lse2 = a.delta[(int64_t)bh * 2 * S + S + qc];
     // -delta of this lane's query, replicated: the dP accumulators start from it
@@ -492,14 +492,14 @@ attn_bwd_dq_kernel(const BwdArgs a)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) zero[i] = 0.f;
                 const int off = kb2 * 32 * RB + lane_off;
-                s = mfma32(*(const bf16x8 *)(Kt + off), qf[0], zero);
-                dp = mfma32(*(const bf16x8 *)(Vt + off), gf[0], nd);  // ends as dP - delta
+                s = mfma32(*(const elem8 *)(Kt + off), qf[0], zero);
+                dp = mfma32(*(const elem8 *)(Vt + off), gf[0], nd);  // ends as dP - delta
             }
 #pragma unroll
             for (int ks = 1; ks < KS; ++ks) {
                 const int off = kb2 * 32 * RB + (lane_off ^ (ks * 32));
-                s = mfma32(*(const bf16x8 *)(Kt + off), qf[ks], s);
-                dp = mfma32(*(const bf16x8 *)(Vt + off), gf[ks], dp);
+                s = mfma32(*(const elem8 *)(Kt + off), qf[ks], s);
+                dp = mfma32(*(const elem8 *)(Vt + off), gf[ks], dp);
             }
             // register i <-> key k_lo + 8*(i/4) + 4h + i%4; this lane's query is fixed
             const bool need_mask = (k_lo + 32 > Sk) || (CAUSAL && k_lo + 31 > q0e);
@@ -513,7 +513,7 @@ attn_bwd_dq_kernel(const BwdArgs a)
             }
 #pragma unroll
             for (int i = 0; i < 16; ++i) dp[i] *= s[i];  // dS = P o (dP - delta)
-            bf16x8 sb[2];
+            elem8 sb[2];
             sb[0] = pack8(dp[0], dp[1], dp[2], dp[3], dp[4], dp[5], dp[6], dp[7]);
             sb[1] = pack8(dp[8], dp[9], dp[10], dp[11], dp[12], dp[13], dp[14], dp[15]);
 #pragma unroll
@@ -523,8 +523,8 @@ attn_bwd_dq_kernel(const BwdArgs a)
                     // d block db = chunks 4db..4db+3: flips bits 6.. of the swizzled offset
                     const int o0 = (tr_off[0] ^ (db << 6)) + (kb2 * 32 + cc * 16) * RB;
                     const int o1 = (tr_off[1] ^ (db << 6)) + (kb2 * 32 + cc * 16) * RB;
-                    const bf16x8 kT = join8(lds_read_tr((const bf16 *)(Kt + o0)),
-                                            lds_read_tr((const bf16 *)(Kt + o1)));
+                    const elem8 kT = join8(lds_read_tr((const elem *)(Kt + o0)),
+                                            lds_read_tr((const elem *)(Kt + o1)));
                     dq[db] = mfma32(kT, sb[cc], dq[db]);
                 }
             }
@@ -535,13 +535,13 @@ attn_bwd_dq_kernel(const BwdArgs a)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     if (q < S) {
-        bf16 *dQp = a.dQ + base + (int64_t)q * a.stride_s;
+        elem *dQp = a.dQ + base + (int64_t)q * a.stride_s;
         const float sc = a.scale;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int g = 0; g < 4; ++g)
-                *(bf16x4 *)(dQp + 32 * db + 8 * g + 4 * h) =
+                *(elem4 *)(dQp + 32 * db + 8 * g + 4 * h) =
                     pack4(dq[db][4 * g] * sc, dq[db][4 * g + 1] * sc,
                           dq[db][4 * g + 2] * sc, dq[db][4 * g + 3] * sc);
     }
@@ -612,7 +612,7 @@ static int launch_bwd_d(const BwdArgs &a, bool causal, hipStream_t st, unsigned 
     return causal ? launch_bwd_dc<D, true>(a, st, stages) : launch_bwd_dc<D, false>(a, st, stages);
 }
 
-#ifdef ATTN_CYCLES
+#if defined(ATTN_CYCLES) && !defined(ATTN_F16)
 extern "C" void attn_debug_cycles_bwd(unsigned long long *out, int reset)
 {
     hipMemcpyFromSymbol(out, HIP_SYMBOL(g_attn_cycles), sizeof(g_attn_cycles));

@@ -1,15 +1,16 @@
 // Device-side building blocks shared by the forward and backward attention kernels
-// (gfx950 / CDNA4 only: wave64, bf16 MFMA 32x32x16, LDS transpose reads).
+// (gfx950 / CDNA4 only: wave64, 16-bit MFMA 32x32x16, LDS transpose reads).  `elem` is the
+// 16-bit element type of this build of the kernels: bf16, or IEEE fp16 with -DATTN_F16.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include "attn_launch.hpp"
 
 namespace attn {
 
-typedef __bf16 bf16;
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef elem elem8 __attribute__((ext_vector_type(8)));
+typedef elem elem4 __attribute__((ext_vector_type(4)));
+typedef elem elem2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -21,12 +22,16 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-// D = A(32x16) * B(16x32) + C, bf16 in, fp32 accumulate.
+// D = A(32x16) * B(16x32) + C, 16-bit elements in, fp32 accumulate.
 // Lane l holds A[l%32][8*(l/32)..+7], B[8*(l/32)..+7][l%32] and, in C/D register i,
 // element [8*(i/4) + 4*(l/32) + i%4][l%32].
-__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
+__device__ __forceinline__ f32x16 mfma32(elem8 a, elem8 b, f32x16 c)
 {
+#ifdef ATTN_F16
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+#else
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+#endif
 }
 
 // Row of a 32x32 accumulator block held in register i by a lane of half h = lane/32.
@@ -48,38 +53,38 @@ __device__ __forceinline__ float xhalf_sum(float x)
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
-// Eight fp32 -> bf16x8 (round to nearest even; v_cvt_pk_bf16_f32 on gfx950).
-__device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3,
+// Eight fp32 -> elem8 (round to nearest even; v_cvt_pk_bf16_f32 / v_cvt_pk_f16_f32 on gfx950).
+__device__ __forceinline__ elem8 pack8(float a0, float a1, float a2, float a3,
                                         float a4, float a5, float a6, float a7)
 {
     typedef float f32x8 __attribute__((ext_vector_type(8)));
     f32x8 v = {a0, a1, a2, a3, a4, a5, a6, a7};
-    return __builtin_convertvector(v, bf16x8);
+    return __builtin_convertvector(v, elem8);
 }
-__device__ __forceinline__ bf16x4 pack4(float a0, float a1, float a2, float a3)
+__device__ __forceinline__ elem4 pack4(float a0, float a1, float a2, float a3)
 {
     f32x4 v = {a0, a1, a2, a3};
-    return __builtin_convertvector(v, bf16x4);
+    return __builtin_convertvector(v, elem4);
 }
 
 // LDS transpose read (ds_read_b64_tr_b16).  Within each group of 16 lanes, source lane
 // s = 4*e + c points at 4 consecutive 16-bit elements ("row e, chunk c"); result lane i
 // receives, in element e, element i%4 of the chunk addressed by source lane 4*e + i/4.
 // I.e. the group reads a 4-row x 16-column tile and every lane gets one column.
-__device__ __forceinline__ s16x4 lds_read_tr(const bf16 *p)
+__device__ __forceinline__ s16x4 lds_read_tr(const elem *p)
 {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
         (s16x4 __attribute__((address_space(3))) *)(p));
 }
-__device__ __forceinline__ bf16x8 join8(s16x4 lo, s16x4 hi)
+__device__ __forceinline__ elem8 join8(s16x4 lo, s16x4 hi)
 {
     s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, v);
+    return __builtin_bit_cast(elem8, v);
 }
 
-// 16-byte global load / LDS access of 8 bf16.
-__device__ __forceinline__ u32x4 ld_global16(const bf16 *p) { return *(const u32x4 *)p; }
-__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+// 16-byte global load / LDS access of 8 elem.
+__device__ __forceinline__ u32x4 ld_global16(const elem *p) { return *(const u32x4 *)p; }
+__device__ __forceinline__ elem8 as_elem8(u32x4 v) { return __builtin_bit_cast(elem8, v); }
 
 // Raw buffer loads: byte offset = per-lane voff + wave-uniform soff into a resource that
 // covers `bytes` bytes from `p`; reads past the end return 0 instead of faulting, which is

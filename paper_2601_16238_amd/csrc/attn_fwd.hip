@@ -6,11 +6,11 @@
 //   work-group = NW waves, one tile of BR = 32*NW query rows of one (batch, head);
 //   wave       = 32 query rows; loops over key tiles of BC = 64 rows staged in LDS.
 // The score tile is computed TRANSPOSED, S^T = K Q^T (keys x queries), with the
-// 32x32x16 bf16 MFMA.  Its accumulator layout puts one query per lane (column l%32) and
+// 32x32x16 elem MFMA.  Its accumulator layout puts one query per lane (column l%32) and
 // 16 keys per lane and 32-key block, so
 //   - row max / row sum are in-lane reductions plus ONE exchange with lane l^32,
 //   - the rescale factor alpha is a per-lane scalar,
-//   - bf16(P^T) is already in the B-operand layout of the second MFMA,
+//   - elem(P^T) is already in the B-operand layout of the second MFMA,
 //     O^T = V^T P^T (d x queries), once the contraction index is enumerated in the order
 //     the accumulator holds it (key = 8*(t/4) + 4*(l/32) + t%4 within 16 keys).
 // V is transposed once per work-group while it is staged into LDS (4x4 register
@@ -60,8 +60,8 @@ attn_fwd_kernel(const FwdArgs a)
     constexpr int KS = D / 16;  // contraction steps of K Q^T
     constexpr int DB = D / 32;  // 32-row blocks of O^T
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16 *Ks = reinterpret_cast<bf16 *>(smem);  // [3][64][D] swizzled
-    bf16 *Vs = Ks + 3 * C::kKTile;              // [2][D][kLdV]
+    elem *Ks = reinterpret_cast<elem *>(smem);  // [3][64][D] swizzled
+    elem *Vs = Ks + 3 * C::kKTile;              // [2][D][kLdV]
 
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, r = l & 31, h = l >> 5;
     const int S = a.S;
@@ -75,7 +75,7 @@ attn_fwd_kernel(const FwdArgs a)
     // grouped-query heads: query head h reads K/V head h / group
     const int64_t base_kv = (int64_t)(bh / a.H) * a.kv_stride_b +
                             (int64_t)((bh % a.H) / a.group) * a.kv_stride_h;
-    const bf16 *Qp = a.Q + base, *Kp = a.K + base_kv, *Vp = a.V + base_kv;
+    const elem *Qp = a.Q + base, *Kp = a.K + base_kv, *Vp = a.V + base_kv;
     // Keys seen by this work-group: all Sk of them, or one split's range (then K and V are
     // simply re-based to the range and the causal offset moves with them).  Query row i sees
     // key j iff j <= i + coff.
@@ -93,10 +93,10 @@ attn_fwd_kernel(const FwdArgs a)
     const int qc = q < S ? q : S - 1;     // clamped for loads; rows >= S are never stored
 
     // Q fragments, B operand of K Q^T: lane holds Q[q][16*ks + 8h .. +7].
-    bf16x8 qf[KS];
+    elem8 qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-        qf[ks] = as_bf16x8(ld_global16(Qp + (int64_t)qc * a.stride_s + ks * 16 + 8 * h));
+        qf[ks] = as_elem8(ld_global16(Qp + (int64_t)qc * a.stride_s + ks * 16 + 8 * h));
 
     // Key tiles this work-group visits.
     const int q_end = min(S, (qt + 1) * C::kBR);
@@ -159,7 +159,7 @@ attn_fwd_kernel(const FwdArgs a)
                 // position of key0 (a multiple of 4) in the MFMA contraction order:
                 // key = 16cc + 8u + 4hh + e  ->  16cc + 8hh + 4u + e
                 const int kpos = (key0 & ~15) | ((key0 & 4) << 1) | ((key0 & 8) >> 1);
-                bf16 *dst = Vs + buf * C::kVTile + d0 * C::kLdV + kpos;
+                elem *dst = Vs + buf * C::kVTile + d0 * C::kLdV + kpos;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     // column d0+j of the 4x4 micro-tile: keys key0..key0+3
@@ -193,27 +193,27 @@ attn_fwd_kernel(const FwdArgs a)
     int koff[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) koff[ks] = r * D + (((2 * ks + h) ^ swz(r)) * 8);
-    auto ld_k = [&](const bf16 *Kt, int kq, bf16x8 (&f)[4]) {
+    auto ld_k = [&](const elem *Kt, int kq, elem8 (&f)[4]) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) f[t] = *(const bf16x8 *)(Kt + koff[4 * kq + t]);
+        for (int t = 0; t < 4; ++t) f[t] = *(const elem8 *)(Kt + koff[4 * kq + t]);
     };
-    auto mm_k = [&](int kq, const bf16x8 (&f)[4], f32x16 &t0) {
+    auto mm_k = [&](int kq, const elem8 (&f)[4], f32x16 &t0) {
 #pragma unroll
         for (int t = 0; t < 4; ++t) t0 = mfma32(f[t], qf[4 * kq + t], t0);
     };
     // V^T fragment: lane (d = 32*db + l%32, half h) holds the 8 keys of contraction step cc
     // that its half owns, contiguous in the staged order.
-    auto ld_v = [&](const bf16 *Vt, int cc, bf16x8 (&f)[4]) {
+    auto ld_v = [&](const elem *Vt, int cc, elem8 (&f)[4]) {
 #pragma unroll
         for (int db = 0; db < DB; ++db)
-            f[db] = *(const bf16x8 *)(Vt + (32 * db + r) * C::kLdV + 16 * cc + 8 * h);
+            f[db] = *(const elem8 *)(Vt + (32 * db + r) * C::kLdV + 16 * cc + 8 * h);
     };
-    auto mm_v = [&](const bf16x8 (&f)[4], bf16x8 p) {
+    auto mm_v = [&](const elem8 (&f)[4], elem8 p) {
 #pragma unroll
         for (int db = 0; db < DB; ++db) o[db] = mfma32(f[db], p, o[db]);
     };
-    // exp2 of eight scores against the reference max, fp32 row-sum, and bf16 pack
-    auto softmax8 = [&](const f32x16 &t, int i0, float &psum) -> bf16x8 {
+    // exp2 of eight scores against the reference max, fp32 row-sum, and elem pack
+    auto softmax8 = [&](const f32x16 &t, int i0, float &psum) -> elem8 {
         float e[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -230,11 +230,11 @@ attn_fwd_kernel(const FwdArgs a)
     //   K0 (f0), K1 (f1): S^T(g+1) += K Q^T      V0 (f2), V1 (f3): O^T += V^T P^T(g)
     // and every set is fetched two steps before it is consumed; the K fragments of sub-tile
     // g+2 (tile kt+1, resident since the previous iteration) are fetched during V0/V1.
-    bf16x8 f0[4], f1[4], f2[4], f3[4];
+    elem8 f0[4], f1[4], f2[4], f3[4];
     auto subtile = [&](int kt, int u, int kbuf_next, int kbuf_fill, bool masked, f32x16 &cur,
                        f32x16 &nxt) {
-        const bf16 *Kn = Ks + kbuf_next * C::kKTile + u * 32 * D;  // rows of sub-tile g+2
-        const bf16 *Vt = Vs + (kt & 1) * C::kVTile + 32 * u;
+        const elem *Kn = Ks + kbuf_next * C::kKTile + u * 32 * D;  // rows of sub-tile g+2
+        const elem *Vt = Vs + (kt & 1) * C::kVTile + 32 * u;
         // The two waves that share a SIMD (w and w+4) take turns at the higher issue
         // priority, one sub-tile each; otherwise the older wave always wins arbitration,
         // runs ahead, and then idles at the tile barrier while the younger one catches up.
@@ -256,7 +256,7 @@ attn_fwd_kernel(const FwdArgs a)
                 if (8 * (i / 4) + (i % 4) > lim) cur[i] = -INFINITY;
         }
         float psum = 0.f;
-        bf16x8 p0 = softmax8(cur, 0, psum);
+        elem8 p0 = softmax8(cur, 0, psum);
         mm_k(0, f0, nxt);
         ATTN_FENCE();
         // ---- K1
@@ -264,7 +264,7 @@ attn_fwd_kernel(const FwdArgs a)
             ld_v(Vt, 1, f3);
             mm_k(1, f1, nxt);
         }
-        bf16x8 p1 = softmax8(cur, 8, psum);
+        elem8 p1 = softmax8(cur, 8, psum);
         // Rare path: some probability outgrew 2^10 relative to the reference max (always so
         // for a wave's first sub-tile).  Move the reference to the true running max, rescale
         // what has been accumulated, and redo this sub-tile's probabilities.
@@ -369,14 +369,14 @@ attn_fwd_kernel(const FwdArgs a)
     }
     const float inv = 1.0f / lt;
     if (q < S) {
-        bf16 *Op = a.O + base + (int64_t)q * a.stride_s;
+        elem *Op = a.O + base + (int64_t)q * a.stride_s;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const bf16x4 ov = pack4(o[db][4 * g] * inv, o[db][4 * g + 1] * inv,
+                const elem4 ov = pack4(o[db][4 * g] * inv, o[db][4 * g + 1] * inv,
                                         o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
-                *(bf16x4 *)(Op + 32 * db + 8 * g + 4 * h) = ov;
+                *(elem4 *)(Op + 32 * db + 8 * g + 4 * h) = ov;
             }
         if (h == 0) a.LSE[(int64_t)bh * S + q] = (m + fast_log2(lt)) * kLn2;
     }
@@ -406,9 +406,9 @@ __global__ void __launch_bounds__(256) attn_fwd_merge_kernel(const FwdArgs a)
     }
     const float inv = 1.0f / den;
     const int bh = (int)(row / a.S), q = (int)(row % a.S);
-    bf16 *Op = a.O + (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h +
+    elem *Op = a.O + (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h +
                (int64_t)q * a.stride_s + d0;
-    *(bf16x4 *)Op = pack4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+    *(elem4 *)Op = pack4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
     if (d0 == 0) a.LSE[row] = mx + logf(den);
 }
 
@@ -469,7 +469,7 @@ static int launch_fwd_d(FwdArgs a, bool causal, hipStream_t st)
     return -1;
 }
 
-#ifdef ATTN_CYCLES
+#if defined(ATTN_CYCLES) && !defined(ATTN_F16)
 extern "C" void attn_debug_cycles_fwd(unsigned long long *out, int reset)
 {
     hipMemcpyFromSymbol(out, HIP_SYMBOL(g_attn_cycles), sizeof(g_attn_cycles));
@@ -482,6 +482,7 @@ extern "C" void attn_debug_cycles_fwd(unsigned long long *out, int reset)
 // work-group is light and bound by the latency of its K/V stream, so about four per unit.
 // Every split keeps at least four 64-key tiles (the merge reads and writes one fp32 partial
 // result per split and row).
+#ifndef ATTN_F16  // a function of the shape only: defined once, by the bf16 build
 int fwd_split_plan(int BH, int S, int Sk, int D, int *kps)
 {
     const int nw = fwd_waves_for(S, D);
@@ -499,6 +500,7 @@ int fwd_split_plan(int BH, int S, int Sk, int D, int *kps)
     if (kps) *kps = tiles_per * 64;
     return nsplit;
 }
+#endif
 
 int launch_fwd(const FwdArgs &a, int D, bool causal, hipStream_t st)
 {

@@ -5,7 +5,15 @@
 
 namespace attn {
 
-typedef __bf16 bf16;
+// The library is built twice from the same kernel sources: once with bf16 elements (the
+// default) and once with IEEE fp16 (-DATTN_F16).  `elem` is the element type of the
+// translation unit; the argument blocks are templates so that both builds can live in one
+// library (kernels and launchers are distinguished by their argument type).
+#ifdef ATTN_F16
+typedef _Float16 elem;
+#else
+typedef __bf16 elem;
+#endif
 
 // One small block of arguments per kernel, passed by value: no per-tensor stride lists
 // (the paper's debugging table records a crash from too many explicit stride arguments).
@@ -13,9 +21,10 @@ typedef __bf16 bf16;
 // heads, Sk rows and the strides kv_stride_* (grouped-query attention; group == 1 is
 // multi-head attention; Sk == S is the square problem).  With a causal mask query row i sees
 // keys 0 .. i + Sk - S (aligned to the bottom-right corner).
-struct FwdArgs {
-    const bf16 *Q, *K, *V;
-    bf16 *O;
+template <typename E>
+struct FwdArgsT {
+    const E *Q, *K, *V;
+    E *O;
     float *LSE;
     int64_t stride_b, stride_h, stride_s;
     int64_t kv_stride_b, kv_stride_h, kv_stride_s;
@@ -32,11 +41,12 @@ struct FwdArgs {
     float *LSEpart;     // [nsplit][B*H][S]
 };
 
-struct BwdArgs {
-    const bf16 *Q, *K, *V, *O, *dO;
+template <typename E>
+struct BwdArgsT {
+    const E *Q, *K, *V, *O, *dO;
     const float *LSE;
     float *delta;       // workspace [B*H][2][S]: -delta, then LSE * log2(e)
-    bf16 *dQ, *dK, *dV;
+    E *dQ, *dK, *dV;
     int64_t stride_b, stride_h, stride_s;
     int64_t kv_stride_b, kv_stride_h, kv_stride_s;
     int S, H, BH;
@@ -46,12 +56,18 @@ struct BwdArgs {
     float scale, scale_log2e;
 };
 
-// Each returns 0 on success, -1 if the HIP runtime reported a launch error.
-int launch_fwd(const FwdArgs &a, int D, bool causal, hipStream_t st);
+typedef FwdArgsT<elem> FwdArgs;
+typedef BwdArgsT<elem> BwdArgs;
+
+// Each returns 0 on success, -1 if the HIP runtime reported a launch error.  One overload per
+// element type; each is defined by the build of the kernel sources for that type.
+int launch_fwd(const FwdArgsT<__bf16> &a, int D, bool causal, hipStream_t st);
+int launch_fwd(const FwdArgsT<_Float16> &a, int D, bool causal, hipStream_t st);
 // Number of key splits the forward would use for this problem (1: none), and the keys per
 // split; a pure host function of the shape.
 int fwd_split_plan(int BH, int S, int Sk, int D, int *kps);
 // `stages`: bit 0 delta, bit 1 dK/dV, bit 2 dQ.
-int launch_bwd(const BwdArgs &a, int D, bool causal, hipStream_t st, unsigned stages);
+int launch_bwd(const BwdArgsT<__bf16> &a, int D, bool causal, hipStream_t st, unsigned stages);
+int launch_bwd(const BwdArgsT<_Float16> &a, int D, bool causal, hipStream_t st, unsigned stages);
 
 }  // namespace attn

@@ -24,18 +24,29 @@ def bf16_round(x):
     return wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(x.astype(np.float32))).astype(np.float64)
 
 
+def f16_round(x):
+    """fp64 -> nearest IEEE fp16 -> fp64: the rounding floor of an fp16 output."""
+    return x.astype(np.float32).astype(np.float16).astype(np.float64)
+
+
+def to_dev_f16(bits):
+    """uint16 fp16 bit patterns (numpy) -> fp16 torch tensor on cuda:0 (same bytes)."""
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.float16)
+
+
 def errs(got, ref):
     d = np.abs(got - ref)
     return float(d.max()), float(d.mean())
 
 
-def check_bf16(name, got, ref, tol_max=TOL_MAX, tol_mean=TOL_MEAN, floor_gate=True):
+def check_bf16(name, got, ref, tol_max=TOL_MAX, tol_mean=TOL_MEAN, floor_gate=True,
+               rnd=bf16_round):
     """Assert a bf16 output is within the stated tolerance of the oracle and, as a tighter
     internal gate, within a small multiple of the error that rounding the exact result to
     bf16 already makes (so a real bug cannot hide inside the loose official bound)."""
     assert np.isfinite(got).all(), "%s has non-finite values" % name
     emax, emean = errs(got, ref)
-    fmax, fmean = errs(bf16_round(ref), ref)
+    fmax, fmean = errs(rnd(ref), ref)
     msg = "%s: max %.3e mean %.3e (floor max %.3e mean %.3e)" % (name, emax, emean, fmax, fmean)
     assert emax <= tol_max and emean <= tol_mean, msg
     if floor_gate:

@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported_and_bound():
 
 
 def test_version_and_status_strings():
-    assert attn.attn_version() == 1002
+    assert attn.attn_version() == 1003
     seen = set()
     for code in range(0, -8, -1):
         s = attn.status_string(code)
@@ -258,3 +258,17 @@ def test_rect_workloads_are_seeded_and_group_selection_matches():
     assert sub["Q"].shape == (1, G, w.Sq, w.D) and sub["K"].shape == (1, 1, w.Sk, w.D)
     assert np.array_equal(sub["K"][0, 0], a["K"][1, 1])
     assert np.array_equal(sub["dO"][0], a["dO"][1, G:2 * G])
+
+
+def test_f16_entry_points_validate_like_the_bf16_ones():
+    p = attn.make_rect_params(1, 8, 2, 16, 128, 64, 0.125, True)
+    L = attn.lib()
+    assert L.attn_fwd_rect_f16(FAKE, FAKE, FAKE, FAKE, None, None, 0, ctypes.byref(p), None) == \
+        binding.ATTN_ERR_NULL
+    assert L.attn_fwd_rect_f16(FAKE, FAKE + 2, FAKE, FAKE, FAKE, None, 0, ctypes.byref(p), None) == \
+        binding.ATTN_ERR_ALIGN
+    assert L.attn_bwd_rect_f16(*([FAKE] * 9 + [None, 0, ctypes.byref(p), None])) == \
+        binding.ATTN_ERR_WORKSPACE
+    p.D = 96
+    assert L.attn_fwd_rect_f16(FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, ctypes.byref(p), None) == \
+        binding.ATTN_ERR_SHAPE
