@@ -15,7 +15,8 @@ int check_strides(int32_t S, int32_t D, int64_t sb, int64_t sh, int64_t ss)
     if (ss % 8 || sh % 8 || sb % 8) return ATTN_ERR_STRIDE;
     // One head's rows (plus the look-ahead tiles the kernels fetch past the end, which read
     // as zero) are addressed with 32-bit byte offsets.
-    if (((int64_t)S + 512) * ss * 2 >= ((int64_t)1 << 32)) return ATTN_ERR_STRIDE;
+    // (half the 32-bit range: an offset one resource length past a row must not wrap either)
+    if (((int64_t)S + 512) * ss * 2 >= ((int64_t)1 << 31)) return ATTN_ERR_STRIDE;
     return ATTN_OK;
 }
 
@@ -25,7 +26,7 @@ int check_params(const attn_rect_params_t *p)
     if (!p) return ATTN_ERR_NULL;
     if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->Sq < 1 || p->Sk < 1) return ATTN_ERR_SHAPE;
     if (p->Hq % p->Hkv != 0) return ATTN_ERR_SHAPE;
-    if (p->D != 64 && p->D != 128) return ATTN_ERR_SHAPE;
+    if (p->D < 8 || p->D > 128 || p->D % 8 != 0) return ATTN_ERR_SHAPE;
     // the causal mask is aligned bottom-right: with fewer keys than rows some rows see none
     if (p->causal && p->Sk < p->Sq) return ATTN_ERR_SHAPE;
     // B*Hq*Sq and B*Hkv*Sk rows must be indexable with int32 (LSE / workspace offsets, grids).
@@ -61,6 +62,10 @@ attn_gqa_params_t as_gqa(const attn_params_t &p)
     g.scale = p.scale; g.causal = p.causal;
     return g;
 }
+
+// The kernels exist for D = 64 and D = 128; other head dimensions (multiples of 8) run in the
+// next larger one with the missing columns read as zeros.
+int kernel_d(int D) { return D <= 64 ? 64 : 128; }
 
 size_t round_ws(size_t bytes) { return (bytes + kWsAlign - 1) / kWsAlign * kWsAlign; }
 
@@ -112,14 +117,14 @@ static int fwd_impl(const void *Q, const void *K, const void *V, void *O, float 
     // No workspace at all: run unsplit.  A workspace that is there must be usable.
     const FwdView v = fwd_view(*p);
     int kps = 0;
-    int nsplit = workspace ? attn::fwd_split_plan(v.BH, v.S, p->Sk, p->D, &kps) : 1;
+    int nsplit = workspace ? attn::fwd_split_plan(v.BH, v.S, p->Sk, kernel_d(p->D), &kps) : 1;
     if (workspace && (!aligned(workspace, kWsAlign) ||
                       workspace_bytes < attn_fwd_rect_workspace_bytes(p)))
         return ATTN_ERR_WORKSPACE;
     attn::FwdArgsT<E> a;
     a.nsplit = nsplit; a.kps = kps;
     a.Opart = static_cast<float *>(workspace);
-    a.LSEpart = a.Opart ? a.Opart + (size_t)nsplit * p->B * p->Hq * p->Sq * p->D : nullptr;
+    a.LSEpart = a.Opart ? a.Opart + (size_t)nsplit * p->B * p->Hq * p->Sq * kernel_d(p->D) : nullptr;
     a.Q = static_cast<const E *>(Q);
     a.K = static_cast<const E *>(K);
     a.V = static_cast<const E *>(V);
@@ -128,9 +133,10 @@ static int fwd_impl(const void *Q, const void *K, const void *V, void *O, float 
     a.stride_b = v.stride_b; a.stride_h = v.stride_h; a.stride_s = v.stride_s;
     a.kv_stride_b = p->kv_stride_b; a.kv_stride_h = p->kv_stride_h; a.kv_stride_s = p->kv_stride_s;
     a.S = v.S; a.Sk = p->Sk; a.H = v.H; a.BH = v.BH; a.group = v.group;
+    a.Dr = p->D;
     a.nqt = 0;
     a.scale_log2e = p->scale * 1.4426950408889634f;
-    return attn::launch_fwd(a, p->D, v.causal, static_cast<hipStream_t>(hip_stream)) == 0
+    return attn::launch_fwd(a, kernel_d(p->D), v.causal, static_cast<hipStream_t>(hip_stream)) == 0
                ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
 
@@ -165,10 +171,11 @@ static int bwd_impl(const void *Q, const void *K, const void *V, const void *O, 
     a.stride_b = p->q_stride_b; a.stride_h = p->q_stride_h; a.stride_s = p->q_stride_s;
     a.kv_stride_b = p->kv_stride_b; a.kv_stride_h = p->kv_stride_h; a.kv_stride_s = p->kv_stride_s;
     a.S = p->Sq; a.Sk = p->Sk; a.H = p->Hq; a.BH = p->B * p->Hq; a.group = p->Hq / p->Hkv;
+    a.Dr = p->D;
     a.ntile = 0;
     a.scale = p->scale;
     a.scale_log2e = p->scale * 1.4426950408889634f;
-    return attn::launch_bwd(a, p->D, p->causal != 0, static_cast<hipStream_t>(hip_stream),
+    return attn::launch_bwd(a, kernel_d(p->D), p->causal != 0, static_cast<hipStream_t>(hip_stream),
                             stages) == 0
                ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
@@ -218,10 +225,10 @@ size_t attn_fwd_rect_workspace_bytes(const attn_rect_params_t *p)
 {
     if (check_params(p) != ATTN_OK) return 0;
     const FwdView v = fwd_view(*p);
-    const int nsplit = attn::fwd_split_plan(v.BH, v.S, p->Sk, p->D, nullptr);
+    const int nsplit = attn::fwd_split_plan(v.BH, v.S, p->Sk, kernel_d(p->D), nullptr);
     if (nsplit <= 1) return 0;
     const size_t rows = (size_t)p->B * p->Hq * p->Sq;
-    return round_ws((size_t)nsplit * rows * (p->D + 1) * sizeof(float));
+    return round_ws((size_t)nsplit * rows * (kernel_d(p->D) + 1) * sizeof(float));
 }
 
 int attn_fwd_rect(const void *Q, const void *K, const void *V, void *O, float *LSE,
@@ -342,7 +349,7 @@ const char *attn_status_string(int status)
     switch (status) {
         case ATTN_OK: return "ok";
         case ATTN_ERR_NULL: return "a required pointer is NULL";
-        case ATTN_ERR_SHAPE: return "unsupported shape (B,H,S >= 1, D in {64,128}, Hkv divides Hq, B*H*S < 2^31, causal needs Sk >= Sq)";
+        case ATTN_ERR_SHAPE: return "unsupported shape (B,H,S >= 1, D a multiple of 8 up to 128, Hkv divides Hq, B*H*S < 2^31, causal needs Sk >= Sq)";
         case ATTN_ERR_STRIDE: return "bad stride (D contiguous, strides multiples of 8 elements, stride_s >= D)";
         case ATTN_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
         case ATTN_ERR_WORKSPACE: return "workspace missing, misaligned (256 B) or too small";
@@ -352,6 +359,6 @@ const char *attn_status_string(int status)
     }
 }
 
-int attn_version(void) { return 1003; }
+int attn_version(void) { return 1004; }
 
 }  // extern "C"

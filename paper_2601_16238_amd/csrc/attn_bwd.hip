@@ -40,10 +40,12 @@ __global__ void __launch_bounds__(256) attn_bwd_delta_kernel(const BwdArgs a)
         const int bh = (int)(row / a.S), i = (int)(row % a.S);
         const int64_t off = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h +
                             (int64_t)i * a.stride_s + sub * 8;
-        const elem8 o = as_elem8(ld_global16(a.O + off));
-        const elem8 g = as_elem8(ld_global16(a.dO + off));
+        if (sub * 8 < a.Dr) {  // lanes past the tensors' head dimension add nothing
+            const elem8 o = as_elem8(ld_global16(a.O + off));
+            const elem8 g = as_elem8(ld_global16(a.dO + off));
 #pragma unroll
-        for (int t = 0; t < 8; ++t) acc += (float)o[t] * (float)g[t];
+            for (int t = 0; t < 8; ++t) acc += (float)o[t] * (float)g[t];
+        }
     }
 #pragma unroll
     for (int s = LPR / 2; s >= 1; s >>= 1) acc += __shfl_xor(acc, s);
@@ -140,7 +142,10 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
 
     // ---- global -> LDS streaming of slot t into ring position rs.  Rows past S-1 lie
     // outside the head's buffer resource and read as zero.
-    const uint32_t head_bytes = (uint32_t)(((int64_t)(S - 1) * a.stride_s + D) * 2);
+    // Columns Dr..D-1 (head dimensions below the kernel's D) are fetched at an offset past
+    // the end of the resource, so they read as zero like everything else outside it.
+    const int Dr = a.Dr;
+    const uint32_t head_bytes = (uint32_t)(((int64_t)(S - 1) * a.stride_s + Dr) * 2);
     rsrc_t Qr, Gr, Wr;  // Q, dO and row statistics of the current query head
     auto set_head = [&](int bh) {
         const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
@@ -154,7 +159,8 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     for (int n = 0; n < C::kDmaPerWave; ++n) {
         const int grp = pair + (n % (C::kDmaPerWave / 2)) * C::kPairs;
         const int row = grp * (64 / CPR) + l / CPR;
-        dma_voff[n] = row * row_bytes + (((l % CPR) ^ swz(row)) << 4);
+        const int chunk = (l % CPR) ^ swz(row);
+        dma_voff[n] = chunk * 8 < Dr ? row * row_bytes + (chunk << 4) : head_bytes;
     }
     // stats: lanes 0-31 fetch lse2 (second half of the head's workspace), 32-63 delta
     const uint32_t stat_voff = (uint32_t)(h ? r : S + r) * 4u;
@@ -192,8 +198,8 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
         elem8 kf[KS], vf[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            kf[ks] = as_elem8(ld_global16(a.K + base_kv + (int64_t)keyc * a.kv_stride_s + ks * 16 + 8 * h));
-            vf[ks] = as_elem8(ld_global16(a.V + base_kv + (int64_t)keyc * a.kv_stride_s + ks * 16 + 8 * h));
+            kf[ks] = as_elem8(ld_row16(a.K + base_kv + (int64_t)keyc * a.kv_stride_s, ks * 16 + 8 * h, Dr));
+            vf[ks] = as_elem8(ld_row16(a.V + base_kv + (int64_t)keyc * a.kv_stride_s, ks * 16 + 8 * h, Dr));
         }
         // make sure no register load is counted among the streamed transfers any more
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -350,9 +356,10 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
                     for (int g = 0; g < 4; ++g)
-                        *(elem4 *)(op + 32 * db + 8 * g + 4 * h) =
-                            pack4(acc[kb][db][4 * g] * sc, acc[kb][db][4 * g + 1] * sc,
-                                  acc[kb][db][4 * g + 2] * sc, acc[kb][db][4 * g + 3] * sc);
+                        if (32 * db + 8 * g + 4 * h < Dr)
+                            *(elem4 *)(op + 32 * db + 8 * g + 4 * h) =
+                                pack4(acc[kb][db][4 * g] * sc, acc[kb][db][4 * g + 1] * sc,
+                                      acc[kb][db][4 * g + 2] * sc, acc[kb][db][4 * g + 3] * sc);
             }
         }
     }
@@ -416,7 +423,8 @@ attn_bwd_dq_kernel(const BwdArgs a)
     };
 
     // ---- streaming of tile kt into ring position pos; rows past S-1 read as zero
-    const uint32_t head_bytes = (uint32_t)(((int64_t)(Sk - 1) * a.kv_stride_s + D) * 2);
+    const int Dr = a.Dr;  // columns Dr..D-1 read as zero (offset past the end of the resource)
+    const uint32_t head_bytes = (uint32_t)(((int64_t)(Sk - 1) * a.kv_stride_s + Dr) * 2);
     const desc_t Kd = make_desc(a.K + base_kv, head_bytes), Vd = make_desc(a.V + base_kv, head_bytes);
     const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2u;
     const uint32_t lds0 = lds_address(smem);
@@ -428,7 +436,8 @@ attn_bwd_dq_kernel(const BwdArgs a)
             const int i = (w + n * NW) % C::kDmaPerTile;
             const int tensor = i / (C::kDmaPerTile / 2), grp = i % (C::kDmaPerTile / 2);
             const int row = grp * (64 / CPR) + l / CPR;
-            const uint32_t voff = row * row_bytes + (((l % CPR) ^ swz(row)) << 4);
+            const int chunk = (l % CPR) ^ swz(row);
+            const uint32_t voff = chunk * 8 < Dr ? row * row_bytes + (chunk << 4) : head_bytes;
             dma16(tensor ? Vd : Kd, lds0 + pos * C::kTileBytes + tensor * C::kTensorBytes + grp * 1024,
                   voff, kt * C::kTile * row_bytes);
         }
@@ -439,8 +448,8 @@ attn_bwd_dq_kernel(const BwdArgs a)
     elem8 qf[KS], gf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-        qf[ks] = as_elem8(ld_global16(a.Q + base + (int64_t)qc * a.stride_s + ks * 16 + 8 * h));
-        gf[ks] = as_elem8(ld_global16(a.dO + base + (int64_t)qc * a.stride_s + ks * 16 + 8 * h));
+        qf[ks] = as_elem8(ld_row16(a.Q + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
+        gf[ks] = as_elem8(ld_row16(a.dO + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
     }
     const float lse2 = a.delta[(int64_t)bh * 2 * S + S + qc];
     // -delta of this lane's query, replicated: the dP accumulators start from it
@@ -541,9 +550,10 @@ attn_bwd_dq_kernel(const BwdArgs a)
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int g = 0; g < 4; ++g)
-                *(elem4 *)(dQp + 32 * db + 8 * g + 4 * h) =
-                    pack4(dq[db][4 * g] * sc, dq[db][4 * g + 1] * sc,
-                          dq[db][4 * g + 2] * sc, dq[db][4 * g + 3] * sc);
+                if (32 * db + 8 * g + 4 * h < Dr)
+                    *(elem4 *)(dQp + 32 * db + 8 * g + 4 * h) =
+                        pack4(dq[db][4 * g] * sc, dq[db][4 * g + 1] * sc,
+                              dq[db][4 * g + 2] * sc, dq[db][4 * g + 3] * sc);
     }
     ATTN_CYCLES_END(2);
 }

@@ -84,6 +84,12 @@ __device__ __forceinline__ elem8 join8(s16x4 lo, s16x4 hi)
 
 // 16-byte global load / LDS access of 8 elem.
 __device__ __forceinline__ u32x4 ld_global16(const elem *p) { return *(const u32x4 *)p; }
+// The same for columns col..col+7 of a row with only dr real columns: zeros past the end.
+__device__ __forceinline__ u32x4 ld_row16(const elem *row, int col, int dr)
+{
+    u32x4 z = {0u, 0u, 0u, 0u};
+    return col < dr ? *(const u32x4 *)(row + col) : z;
+}
 __device__ __forceinline__ elem8 as_elem8(u32x4 v) { return __builtin_bit_cast(elem8, v); }
 
 // Raw buffer loads: byte offset = per-lane voff + wave-uniform soff into a resource that

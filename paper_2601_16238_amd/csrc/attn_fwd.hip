@@ -64,7 +64,7 @@ attn_fwd_kernel(const FwdArgs a)
     elem *Vs = Ks + 3 * C::kKTile;              // [2][D][kLdV]
 
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, r = l & 31, h = l >> 5;
-    const int S = a.S;
+    const int S = a.S, Dr = a.Dr;
     ATTN_CYCLES_BEGIN();
 
     // (head, query tile) of this work-group; causal tiles are issued heaviest first.
@@ -96,7 +96,7 @@ attn_fwd_kernel(const FwdArgs a)
     elem8 qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-        qf[ks] = as_elem8(ld_global16(Qp + (int64_t)qc * a.stride_s + ks * 16 + 8 * h));
+        qf[ks] = as_elem8(ld_row16(Qp + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
 
     // Key tiles this work-group visits.
     const int q_end = min(S, (qt + 1) * C::kBR);
@@ -106,7 +106,9 @@ attn_fwd_kernel(const FwdArgs a)
 
     // ---- staging: global -> registers -> LDS.  Rows past S-1 and tiles past the last one
     // lie outside the head's buffer resource and read as zero (masked to probability 0).
-    const uint32_t head_bytes = (uint32_t)(((int64_t)(Sk - 1) * a.kv_stride_s + D) * 2);
+    // Columns Dr..D-1 (head dimensions below the kernel's D) are fetched at an offset past the
+    // end of the resource, so they read as zero like everything else outside it.
+    const uint32_t head_bytes = (uint32_t)(((int64_t)(Sk - 1) * a.kv_stride_s + Dr) * 2);
     const rsrc_t Kr = make_rsrc(Kp, head_bytes), Vr = make_rsrc(Vp, head_bytes);
     const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2u;
     const uint32_t tile_bytes = C::kBC * row_bytes;
@@ -124,9 +126,10 @@ attn_fwd_kernel(const FwdArgs a)
             if (C::kKDmas % NW == 0 || ii < C::kKDmas) {
                 const int row = ii * C::kKRowsPerDma + l / CPR;
                 const int chunk = (l % CPR) ^ swz(row);
+                const uint32_t voff = chunk * 8 < Dr ? row * row_bytes + chunk * 16 : head_bytes;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
                     Kr, (void __attribute__((address_space(3))) *)(Ks + buf * C::kKTile + ii * 512),
-                    16, row * row_bytes + chunk * 16, kt * tile_bytes, 0, 0);
+                    16, (int)voff, kt * tile_bytes, 0, 0);
             }
         }
     };
@@ -145,7 +148,8 @@ attn_fwd_kernel(const FwdArgs a)
                 v_coords(mt, key0, d0);
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    vreg[n][i] = buf_load8(Vr, (key0 + i) * row_bytes + d0 * 2, kt * tile_bytes);
+                    vreg[n][i] = buf_load8(Vr, d0 < Dr ? (key0 + i) * row_bytes + d0 * 2 : head_bytes,
+                                           kt * tile_bytes);
             }
         }
     };
@@ -376,7 +380,7 @@ attn_fwd_kernel(const FwdArgs a)
             for (int g = 0; g < 4; ++g) {
                 const elem4 ov = pack4(o[db][4 * g] * inv, o[db][4 * g + 1] * inv,
                                         o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
-                *(elem4 *)(Op + 32 * db + 8 * g + 4 * h) = ov;
+                if (32 * db + 8 * g + 4 * h < Dr) *(elem4 *)(Op + 32 * db + 8 * g + 4 * h) = ov;
             }
         if (h == 0) a.LSE[(int64_t)bh * S + q] = (m + fast_log2(lt)) * kLn2;
     }
@@ -408,7 +412,7 @@ __global__ void __launch_bounds__(256) attn_fwd_merge_kernel(const FwdArgs a)
     const int bh = (int)(row / a.S), q = (int)(row % a.S);
     elem *Op = a.O + (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h +
                (int64_t)q * a.stride_s + d0;
-    *(elem4 *)Op = pack4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+    if (d0 < a.Dr) *(elem4 *)Op = pack4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
     if (d0 == 0) a.LSE[row] = mx + logf(den);
 }
 

@@ -30,6 +30,8 @@ struct FwdArgsT {
     int64_t kv_stride_b, kv_stride_h, kv_stride_s;
     int S, H, BH;
     int Sk;             // key/value rows
+    int Dr;             // head dimension of the tensors (a multiple of 8); the kernels run at
+                        // D = 64 or 128 and treat columns Dr..D-1 as zeros
     int group;          // query heads per K/V head
     int nqt;            // query tiles per head (set by the launcher)
     float scale_log2e;  // scale * log2(e): the softmax runs on exp2
@@ -51,6 +53,7 @@ struct BwdArgsT {
     int64_t kv_stride_b, kv_stride_h, kv_stride_s;
     int S, H, BH;
     int Sk;             // key/value rows
+    int Dr;             // head dimension of the tensors; columns Dr..D-1 are zeros (see FwdArgsT)
     int group;          // query heads per K/V head
     int ntile;          // tiles per head of the launched kernel (set by the launcher)
     float scale, scale_log2e;

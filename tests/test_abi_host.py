@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported_and_bound():
 
 
 def test_version_and_status_strings():
-    assert attn.attn_version() == 1003
+    assert attn.attn_version() == 1004
     seen = set()
     for code in range(0, -8, -1):
         s = attn.status_string(code)
@@ -43,7 +43,7 @@ def test_params_contiguous_and_workspace_size():
     assert (p.stride_s, p.stride_h, p.stride_b) == (128, 4096 * 128, 32 * 4096 * 128)
     assert attn.attn_bwd_workspace_bytes(4, 32, 4096, 128) == 2 * 4 * 32 * 4096 * 4
     assert attn.attn_bwd_workspace_bytes(1, 1, 1, 64) == 256          # rounded up
-    assert attn.attn_bwd_workspace_bytes(1, 1, 1, 96) == 0            # invalid D
+    assert attn.attn_bwd_workspace_bytes(1, 1, 1, 100) == 0           # invalid D
 
 
 FAKE = 0x1000  # a non-NULL, 16-byte aligned address; never dereferenced on the host
@@ -63,7 +63,7 @@ def call_bwd(p, ws=FAKE, ws_bytes=1 << 40, ptr=FAKE, stages=None):
 @pytest.mark.parametrize("mutate,code", [
     (lambda p: setattr(p, "B", 0), binding.ATTN_ERR_SHAPE),
     (lambda p: setattr(p, "S", 0), binding.ATTN_ERR_SHAPE),
-    (lambda p: setattr(p, "D", 96), binding.ATTN_ERR_SHAPE),
+    (lambda p: setattr(p, "D", 100), binding.ATTN_ERR_SHAPE),
     (lambda p: setattr(p, "stride_s", 60), binding.ATTN_ERR_STRIDE),
     (lambda p: setattr(p, "stride_h", 132), binding.ATTN_ERR_STRIDE),
     (lambda p: setattr(p, "scale", 0.0), binding.ATTN_ERR_SCALE),
@@ -144,7 +144,7 @@ def test_gqa_params_contiguous_and_workspace_size():
     (lambda p: setattr(p, "Hkv", 3), binding.ATTN_ERR_SHAPE),           # 3 does not divide 8
     (lambda p: setattr(p, "Hkv", 0), binding.ATTN_ERR_SHAPE),
     (lambda p: setattr(p, "Hkv", 16), binding.ATTN_ERR_SHAPE),          # more K/V than query heads
-    (lambda p: setattr(p, "D", 32), binding.ATTN_ERR_SHAPE),
+    (lambda p: setattr(p, "D", 136), binding.ATTN_ERR_SHAPE),
     (lambda p: setattr(p, "kv_stride_s", 60), binding.ATTN_ERR_STRIDE),
     (lambda p: setattr(p, "kv_stride_h", 132), binding.ATTN_ERR_STRIDE),
     (lambda p: setattr(p, "q_stride_b", 4), binding.ATTN_ERR_STRIDE),
@@ -215,7 +215,7 @@ def test_rect_params_contiguous_and_workspace_sizes():
     (lambda p: setattr(p, "Sk", 0), binding.ATTN_ERR_SHAPE),
     (lambda p: (setattr(p, "Sk", 8), setattr(p, "causal", 1)), binding.ATTN_ERR_SHAPE),  # Sk < Sq
     (lambda p: setattr(p, "Hkv", 3), binding.ATTN_ERR_SHAPE),
-    (lambda p: setattr(p, "D", 96), binding.ATTN_ERR_SHAPE),
+    (lambda p: setattr(p, "D", 100), binding.ATTN_ERR_SHAPE),
     (lambda p: setattr(p, "kv_stride_s", 60), binding.ATTN_ERR_STRIDE),
     (lambda p: setattr(p, "q_stride_h", 4), binding.ATTN_ERR_STRIDE),
     (lambda p: setattr(p, "scale", float("nan")), binding.ATTN_ERR_SCALE),
@@ -269,6 +269,6 @@ def test_f16_entry_points_validate_like_the_bf16_ones():
         binding.ATTN_ERR_ALIGN
     assert L.attn_bwd_rect_f16(*([FAKE] * 9 + [None, 0, ctypes.byref(p), None])) == \
         binding.ATTN_ERR_WORKSPACE
-    p.D = 96
+    p.D = 100
     assert L.attn_fwd_rect_f16(FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, ctypes.byref(p), None) == \
         binding.ATTN_ERR_SHAPE
