@@ -205,8 +205,8 @@ def test_rect_params_contiguous_and_workspace_sizes():
     assert attn.attn_fwd_rect_workspace_bytes(2, 8, 2, 1, 300, 64) == 0
     # ... otherwise (D+1) fp32 per split and query row; decoding 8 sequences of 32 heads
     # against 8192 keys: the 4 query heads of a group are packed into one head of 4 rows (64
-    # work-groups), which splits 16 ways
-    assert attn.attn_fwd_rect_workspace_bytes(8, 32, 8, 1, 8192, 128) == 16 * 256 * 129 * 4
+    # work-groups), which splits 4 ways: one work-group per compute unit
+    assert attn.attn_fwd_rect_workspace_bytes(8, 32, 8, 1, 8192, 128) == 4 * 256 * 129 * 4
     assert attn.attn_fwd_rect_workspace_bytes(1, 6, 4, 1, 8192, 64) == 0      # invalid heads
 
 
@@ -237,7 +237,7 @@ def test_rect_fewer_keys_than_rows_is_fine_without_a_mask():
 
 def test_rect_workspace_errors():
     p = attn.make_rect_params(8, 32, 8, 1, 8192, 128, 0.0883, True)   # the plan splits
-    need = 16 * 256 * 129 * 4
+    need = 4 * 256 * 129 * 4
     assert call_fwd_rect(p, ws=FAKE + 16, ws_bytes=need) == binding.ATTN_ERR_WORKSPACE
     assert call_fwd_rect(p, ws=FAKE, ws_bytes=need - 1) == binding.ATTN_ERR_WORKSPACE
     assert call_fwd_rect(p, ptr=FAKE + 8, ws=FAKE, ws_bytes=need) == binding.ATTN_ERR_ALIGN
