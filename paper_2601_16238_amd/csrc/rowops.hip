@@ -1,0 +1,394 @@
+// Row-wise neighbours of attention for gfx950: RMSNorm forward, LayerNorm forward and
+// backward, rotary forward.  All are bound by HBM traffic: every activation element is read
+// once and written once, a whole row lives in the registers of one work-group between the
+// reduction and the normalisation, 16-byte accesses throughout.
+#include "../../include/attn.h"
+#include "../../include/rowops.h"
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rowops {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;          // one work-group per row
+constexpr int kWaves = kThreads / 64;
+constexpr int kMaxCols = 16384;        // 8 vectors of 8 elements per thread
+constexpr int kBwdGroups = 512;        // work-groups of the LayerNorm backward (two per unit)
+
+__device__ __forceinline__ bf16x8 load8(const __bf16 *p)
+{
+    return __builtin_bit_cast(bf16x8, *(const u32x4 *)p);
+}
+__device__ __forceinline__ void store8(__bf16 *p, const float (&v)[8])
+{
+    typedef float f32x8 __attribute__((ext_vector_type(8)));
+    f32x8 f = {v[0], v[1], v[2], v[3], v[4], v[5], v[6], v[7]};
+    *(u32x4 *)p = __builtin_bit_cast(u32x4, __builtin_convertvector(f, bf16x8));
+}
+__device__ __forceinline__ void load8f(const float *p, float (&v)[8])
+{
+    const f32x4 a = *(const f32x4 *)p, b = *(const f32x4 *)(p + 4);
+    v[0] = a[0]; v[1] = a[1]; v[2] = a[2]; v[3] = a[3];
+    v[4] = b[0]; v[5] = b[1]; v[6] = b[2]; v[7] = b[3];
+}
+
+// Sum of N values per thread over the work-group; every thread gets the result.  `red` is
+// LDS scratch of kWaves * N floats; the trailing barrier makes it reusable at once.
+template <int N>
+__device__ __forceinline__ void block_sum(float (&v)[N], float *red)
+{
+#pragma unroll
+    for (int n = 0; n < N; ++n)
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) v[n] += __shfl_xor(v[n], s);
+    const int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0)
+#pragma unroll
+        for (int n = 0; n < N; ++n) red[w * N + n] = v[n];
+    __syncthreads();
+#pragma unroll
+    for (int n = 0; n < N; ++n) {
+        float t = 0.f;
+#pragma unroll
+        for (int i = 0; i < kWaves; ++i) t += red[i * N + n];
+        v[n] = t;
+    }
+    __syncthreads();
+}
+
+// Thread t owns vectors t, t + 256, ... (V of them) of 8 consecutive columns each.
+template <int V>
+__device__ __forceinline__ void load_row(const __bf16 *row, int cols, float (&x)[V][8])
+{
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int c = (threadIdx.x + v * kThreads) * 8;
+        if (c < cols) {
+            const bf16x8 b = load8(row + c);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[v][e] = (float)b[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[v][e] = 0.f;
+        }
+    }
+}
+
+template <int V>
+__global__ void __launch_bounds__(kThreads)
+rmsnorm_fwd_kernel(const __bf16 *x, const float *w, __bf16 *y, int cols, int64_t xs, int64_t ys,
+                   float eps)
+{
+    __shared__ float red[kWaves];
+    const int64_t i = blockIdx.x;
+    float xv[V][8];
+    load_row<V>(x + i * xs, cols, xv);
+    float ss[1] = {0.f};
+#pragma unroll
+    for (int v = 0; v < V; ++v)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss[0] += xv[v][e] * xv[v][e];
+    block_sum<1>(ss, red);
+    const float r = 1.0f / sqrtf(ss[0] / (float)cols + eps);
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int c = (threadIdx.x + v * kThreads) * 8;
+        if (c < cols) {
+            float wv[8], o[8];
+            load8f(w + c, wv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = xv[v][e] * r * wv[e];
+            store8(y + i * ys + c, o);
+        }
+    }
+}
+
+template <int V>
+__global__ void __launch_bounds__(kThreads)
+layernorm_fwd_kernel(const __bf16 *x, const float *w, const float *b, __bf16 *y, float *mean,
+                     float *rstd, int cols, int64_t xs, int64_t ys, float eps)
+{
+    __shared__ float red[kWaves];
+    const int64_t i = blockIdx.x;
+    float xv[V][8];
+    load_row<V>(x + i * xs, cols, xv);
+    float s[1] = {0.f};
+#pragma unroll
+    for (int v = 0; v < V; ++v)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s[0] += xv[v][e];
+    block_sum<1>(s, red);
+    const float mu = s[0] / (float)cols;
+    // second pass over the registers: the variance of the centred values
+    float q[1] = {0.f};
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int c = (threadIdx.x + v * kThreads) * 8;
+        if (c < cols)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                xv[v][e] -= mu;
+                q[0] += xv[v][e] * xv[v][e];
+            }
+    }
+    block_sum<1>(q, red);
+    const float r = 1.0f / sqrtf(q[0] / (float)cols + eps);
+    if (threadIdx.x == 0) {
+        mean[i] = mu;
+        rstd[i] = r;
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int c = (threadIdx.x + v * kThreads) * 8;
+        if (c < cols) {
+            float wv[8], bv[8], o[8];
+            load8f(w + c, wv);
+            load8f(b + c, bv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = xv[v][e] * r * wv[e] + bv[e];
+            store8(y + i * ys + c, o);
+        }
+    }
+}
+
+// Backward, rows i = group, group + G, ...: dx of each row, and the work-group's partial column
+// sums of dw and db, kept in registers across its rows and written once: part[g][0][cols] = dw,
+// part[g][1][cols] = db.
+template <int V>
+__global__ void __launch_bounds__(kThreads)
+layernorm_bwd_rows_kernel(const __bf16 *dy, const __bf16 *x, const float *w, const float *mean,
+                          const float *rstd, __bf16 *dx, float *part, int64_t rows, int cols,
+                          int64_t dys, int64_t xs, int64_t dxs)
+{
+    __shared__ float red[kWaves * 2];
+    float wv[V][8], dwp[V][8], dbp[V][8];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int c = (threadIdx.x + v * kThreads) * 8;
+        if (c < cols) load8f(w + c, wv[v]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { dwp[v][e] = 0.f; dbp[v][e] = 0.f; }
+    }
+    for (int64_t i = blockIdx.x; i < rows; i += gridDim.x) {
+        float xv[V][8], gv[V][8];
+        load_row<V>(x + i * xs, cols, xv);
+        load_row<V>(dy + i * dys, cols, gv);
+        const float mu = mean[i], r = rstd[i];
+        float s[2] = {0.f, 0.f};  // sum g, sum g*xhat with g = dy*w
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const int c = (threadIdx.x + v * kThreads) * 8;
+            if (c < cols)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    xv[v][e] = (xv[v][e] - mu) * r;  // xhat
+                    dwp[v][e] += gv[v][e] * xv[v][e];
+                    dbp[v][e] += gv[v][e];
+                    gv[v][e] *= wv[v][e];            // g
+                    s[0] += gv[v][e];
+                    s[1] += gv[v][e] * xv[v][e];
+                }
+        }
+        block_sum<2>(s, red);
+        const float mg = s[0] / (float)cols, mgx = s[1] / (float)cols;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const int c = (threadIdx.x + v * kThreads) * 8;
+            if (c < cols) {
+                float o[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = r * (gv[v][e] - mg - xv[v][e] * mgx);
+                store8(dx + i * dxs + c, o);
+            }
+        }
+    }
+    float *pw = part + (int64_t)blockIdx.x * 2 * cols, *pb = pw + cols;
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int c = (threadIdx.x + v * kThreads) * 8;
+        if (c < cols)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                f32x4 a, b;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { a[e] = dwp[v][4 * h + e]; b[e] = dbp[v][4 * h + e]; }
+                *(f32x4 *)(pw + c + 4 * h) = a;
+                *(f32x4 *)(pb + c + 4 * h) = b;
+            }
+    }
+}
+
+// Column reduction of the partial sums: thread = (which of dw/db, 4 consecutive columns).
+__global__ void __launch_bounds__(256)
+layernorm_bwd_cols_kernel(const float *part, float *dw, float *db, int groups, int cols)
+{
+    const int t = blockIdx.x * 256 + threadIdx.x;  // over 2 * cols / 4
+    const int per = cols / 4;
+    if (t >= 2 * per) return;
+    const int which = t / per, c = (t % per) * 4;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int g = 0; g < groups; ++g)
+        acc += *(const f32x4 *)(part + ((int64_t)g * 2 + which) * cols + c);
+    *(f32x4 *)((which ? db : dw) + c) = acc;
+}
+
+// Rotary: one thread per 8 pairs (d..d+7, d+hd..d+hd+7) of one (b, h, s) row.
+__global__ void __launch_bounds__(256)
+rotary_fwd_kernel(const __bf16 *x, const float *cosv, const float *sinv, __bf16 *y, int H, int S,
+                  int D, int64_t rows, int64_t xsb, int64_t xsh, int64_t xss, int64_t ysb,
+                  int64_t ysh, int64_t yss)
+{
+    const int hd = D / 2, tpr = hd / 8;  // threads per row
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t row = t / tpr;
+    if (row >= rows) return;
+    const int d = (int)(t % tpr) * 8;
+    const int s = (int)(row % S), h = (int)((row / S) % H);
+    const int64_t b = row / ((int64_t)S * H);
+    const __bf16 *xr = x + b * xsb + h * xsh + (int64_t)s * xss;
+    __bf16 *yr = y + b * ysb + h * ysh + (int64_t)s * yss;
+    const bf16x8 lo = load8(xr + d), hi = load8(xr + d + hd);
+    float c[8], sn[8], o1[8], o2[8];
+    load8f(cosv + (int64_t)s * hd + d, c);
+    load8f(sinv + (int64_t)s * hd + d, sn);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float a = (float)lo[e], bb = (float)hi[e];
+        o1[e] = a * c[e] - bb * sn[e];
+        o2[e] = bb * c[e] + a * sn[e];
+    }
+    store8(yr + d, o1);
+    store8(yr + d + hd, o2);
+}
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int check_rows(int64_t rows, int32_t cols, std::initializer_list<int64_t> strides)
+{
+    if (rows < 1 || rows > 0x7fffffffLL || cols < 8 || cols > kMaxCols || cols % 8) return ATTN_ERR_SHAPE;
+    for (int64_t s : strides)
+        if (s < cols || s % 8) return ATTN_ERR_STRIDE;
+    return ATTN_OK;
+}
+
+int bwd_groups(int64_t rows) { return (int)(rows < kBwdGroups ? rows : kBwdGroups); }
+
+// vectors per thread: 1, 2, 4 or 8
+int vectors_for(int cols)
+{
+    const int v = (cols / 8 + kThreads - 1) / kThreads;
+    return v <= 1 ? 1 : v <= 2 ? 2 : v <= 4 ? 4 : 8;
+}
+
+#define ROWOPS_DISPATCH(V, CALL)            \
+    switch (V) {                            \
+        case 1: { constexpr int kV = 1; CALL; } break; \
+        case 2: { constexpr int kV = 2; CALL; } break; \
+        case 4: { constexpr int kV = 4; CALL; } break; \
+        default: { constexpr int kV = 8; CALL; } break; \
+    }
+
+}  // namespace rowops
+
+using namespace rowops;
+
+extern "C" {
+
+int rowops_rmsnorm_fwd(const void *x, const float *w, void *y, int64_t rows, int32_t cols,
+                       int64_t x_row_stride, int64_t y_row_stride, float eps, void *hip_stream)
+{
+    if (!x || !w || !y) return ATTN_ERR_NULL;
+    const int rc = check_rows(rows, cols, {x_row_stride, y_row_stride});
+    if (rc != ATTN_OK) return rc;
+    if (!aligned(x, 16) || !aligned(w, 16) || !aligned(y, 16)) return ATTN_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    ROWOPS_DISPATCH(vectors_for(cols),
+        hipLaunchKernelGGL((rmsnorm_fwd_kernel<kV>), dim3((unsigned)rows), dim3(kThreads), 0, st,
+                           static_cast<const __bf16 *>(x), w, static_cast<__bf16 *>(y), cols,
+                           x_row_stride, y_row_stride, eps));
+    return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+int rowops_layernorm_fwd(const void *x, const float *w, const float *b, void *y, float *mean,
+                         float *rstd, int64_t rows, int32_t cols, int64_t x_row_stride,
+                         int64_t y_row_stride, float eps, void *hip_stream)
+{
+    if (!x || !w || !b || !y || !mean || !rstd) return ATTN_ERR_NULL;
+    const int rc = check_rows(rows, cols, {x_row_stride, y_row_stride});
+    if (rc != ATTN_OK) return rc;
+    if (!aligned(x, 16) || !aligned(w, 16) || !aligned(b, 16) || !aligned(y, 16) ||
+        !aligned(mean, 4) || !aligned(rstd, 4))
+        return ATTN_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    ROWOPS_DISPATCH(vectors_for(cols),
+        hipLaunchKernelGGL((layernorm_fwd_kernel<kV>), dim3((unsigned)rows), dim3(kThreads), 0, st,
+                           static_cast<const __bf16 *>(x), w, b, static_cast<__bf16 *>(y), mean,
+                           rstd, cols, x_row_stride, y_row_stride, eps));
+    return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+size_t rowops_layernorm_bwd_workspace_bytes(int64_t rows, int32_t cols)
+{
+    if (check_rows(rows, cols, {}) != ATTN_OK) return 0;
+    const size_t bytes = (size_t)bwd_groups(rows) * 2 * cols * sizeof(float);
+    return (bytes + 255) / 256 * 256;
+}
+
+int rowops_layernorm_bwd(const void *dy, const void *x, const float *w, const float *mean,
+                         const float *rstd, void *dx, float *dw, float *db,
+                         void *workspace, size_t workspace_bytes, int64_t rows, int32_t cols,
+                         int64_t dy_row_stride, int64_t x_row_stride, int64_t dx_row_stride,
+                         void *hip_stream)
+{
+    if (!dy || !x || !w || !mean || !rstd || !dx || !dw || !db) return ATTN_ERR_NULL;
+    const int rc = check_rows(rows, cols, {dy_row_stride, x_row_stride, dx_row_stride});
+    if (rc != ATTN_OK) return rc;
+    if (!aligned(dy, 16) || !aligned(x, 16) || !aligned(w, 16) || !aligned(dx, 16) ||
+        !aligned(dw, 16) || !aligned(db, 16) || !aligned(mean, 4) || !aligned(rstd, 4))
+        return ATTN_ERR_ALIGN;
+    if (!workspace || !aligned(workspace, 256) ||
+        workspace_bytes < rowops_layernorm_bwd_workspace_bytes(rows, cols))
+        return ATTN_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int groups = bwd_groups(rows);
+    float *part = static_cast<float *>(workspace);
+    ROWOPS_DISPATCH(vectors_for(cols),
+        hipLaunchKernelGGL((layernorm_bwd_rows_kernel<kV>), dim3(groups), dim3(kThreads), 0, st,
+                           static_cast<const __bf16 *>(dy), static_cast<const __bf16 *>(x), w, mean,
+                           rstd, static_cast<__bf16 *>(dx), part, rows, cols, dy_row_stride,
+                           x_row_stride, dx_row_stride));
+    if (hipGetLastError() != hipSuccess) return ATTN_ERR_LAUNCH;
+    const int threads = 2 * cols / 4;
+    hipLaunchKernelGGL(layernorm_bwd_cols_kernel, dim3((threads + 255) / 256), dim3(256), 0, st,
+                       part, dw, db, groups, cols);
+    return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+int rowops_rotary_fwd(const void *x, const float *cos_table, const float *sin_table, void *y,
+                      int32_t B, int32_t H, int32_t S, int32_t D,
+                      int64_t x_stride_b, int64_t x_stride_h, int64_t x_stride_s,
+                      int64_t y_stride_b, int64_t y_stride_h, int64_t y_stride_s,
+                      void *hip_stream)
+{
+    if (!x || !cos_table || !sin_table || !y) return ATTN_ERR_NULL;
+    if (B < 1 || H < 1 || S < 1 || D < 16 || D > 512 || D % 16) return ATTN_ERR_SHAPE;
+    const int64_t rows = (int64_t)B * H * S;
+    if (rows * (D / 16) > 0x7fffffffLL * 256) return ATTN_ERR_SHAPE;
+    for (int64_t s : {x_stride_b, x_stride_h, x_stride_s, y_stride_b, y_stride_h, y_stride_s})
+        if (s < 1 || s % 8) return ATTN_ERR_STRIDE;
+    if (x_stride_s < D || y_stride_s < D) return ATTN_ERR_STRIDE;
+    if (!aligned(x, 16) || !aligned(y, 16) || !aligned(cos_table, 16) || !aligned(sin_table, 16))
+        return ATTN_ERR_ALIGN;
+    const int64_t threads = rows * (D / 16);
+    hipLaunchKernelGGL(rotary_fwd_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), static_cast<const __bf16 *>(x),
+                       cos_table, sin_table, static_cast<__bf16 *>(y), H, S, D, rows, x_stride_b,
+                       x_stride_h, x_stride_s, y_stride_b, y_stride_h, y_stride_s);
+    return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -272,3 +272,41 @@ def test_f16_entry_points_validate_like_the_bf16_ones():
     p.D = 100
     assert L.attn_fwd_rect_f16(FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, ctypes.byref(p), None) == \
         binding.ATTN_ERR_SHAPE
+
+
+# ---- row-wise entry points (include/rowops.h) ---------------------------------------------------
+
+def test_every_rowops_symbol_is_exported_and_bound():
+    from paper_2601_16238_amd import rowops
+    src = open(os.path.join(ROOT, "include", "rowops.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = sorted(set(re.findall(r"\b(rowops_\w+)\s*\(", src)))
+    assert len(names) == 5 and sorted(rowops.EXPORTS) == names
+    for n in names:
+        assert getattr(attn.lib(), n) is not None
+
+
+def test_rowops_validation_without_a_gpu():
+    from paper_2601_16238_amd import rowops
+    L = rowops._lib()
+    ok_args = dict(rows=16, cols=256, xs=256, ys=256)
+    call = lambda x=FAKE, w=FAKE, y=FAKE, rows=16, cols=256, xs=256, ys=256: \
+        L.rowops_rmsnorm_fwd(x, w, y, rows, cols, xs, ys, 1e-6, None)
+    assert call(x=None) == binding.ATTN_ERR_NULL
+    assert call(cols=12) == binding.ATTN_ERR_SHAPE            # not a multiple of 8
+    assert call(cols=16392, xs=16392, ys=16392) == binding.ATTN_ERR_SHAPE   # above the row budget
+    assert call(rows=0) == binding.ATTN_ERR_SHAPE
+    assert call(xs=128) == binding.ATTN_ERR_STRIDE            # row stride below cols
+    assert call(ys=260) == binding.ATTN_ERR_STRIDE            # not a multiple of 8
+    assert call(w=FAKE + 4) == binding.ATTN_ERR_ALIGN
+    assert rowops.layernorm_bwd_workspace_bytes(4096, 8192) == 512 * 2 * 8192 * 4
+    assert rowops.layernorm_bwd_workspace_bytes(3, 64) == 3 * 2 * 64 * 4
+    assert rowops.layernorm_bwd_workspace_bytes(3, 60) == 0
+    bwd = lambda ws=FAKE, nbytes=1 << 30: L.rowops_layernorm_bwd(
+        FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ws, nbytes, 16, 256, 256, 256, 256, None)
+    assert bwd(ws=None) == binding.ATTN_ERR_WORKSPACE
+    assert bwd(nbytes=16 * 2 * 256 * 4 - 1) == binding.ATTN_ERR_WORKSPACE
+    rot = lambda D=128, ss=128: L.rowops_rotary_fwd(FAKE, FAKE, FAKE, FAKE, 2, 4, 64, D,
+                                                   4 * 64 * 128, 64 * 128, ss, 4 * 64 * 128, 64 * 128, 128, None)
+    assert rot(D=24) == binding.ATTN_ERR_SHAPE                # halves must be multiples of 8
+    assert rot(ss=64) == binding.ATTN_ERR_STRIDE
