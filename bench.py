@@ -35,7 +35,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="long_causal",
-                    help="one of paper_2601_16238_amd.workloads.WORKLOADS, GQA_WORKLOADS or RECT_WORKLOADS")
+                    help="one of paper_2601_16238_amd.workloads.WORKLOADS, GQA_WORKLOADS or RECT_WORKLOADS, "
+                         "or 'rowops' (the row-wise kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true",
                     help="also time every other workload (reported under 'other_workloads')")
@@ -232,6 +233,101 @@ def rect_main(torch, attn, wl, w, a):
     print(json.dumps(out))
 
 
+def measure_rowops(torch, steps, warmup):
+    """The row-wise kernels on the shapes of the paper's kernel table: (4096, 8192) bf16 for the
+    norms, (4, 8, 2048, 128) for rotary.  Algorithmic bytes: every activation read once and
+    written once (parameters, statistics and tables are negligible)."""
+    from paper_2601_16238_amd import rowops
+    rows, cols = 4096, 8192
+    g = torch.Generator(device="cuda"); g.manual_seed(1013)
+    x = torch.randn((rows, cols), device="cuda", generator=g).to(torch.bfloat16)
+    dy = torch.randn((rows, cols), device="cuda", generator=g).to(torch.bfloat16)
+    w = torch.randn(cols, device="cuda", generator=g) * 0.5 + 1.0
+    b = torch.randn(cols, device="cuda", generator=g) * 0.3
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    mean, rstd = (torch.empty(rows, dtype=torch.float32, device="cuda") for _ in range(2))
+    dw, db = (torch.empty(cols, dtype=torch.float32, device="cuda") for _ in range(2))
+    ws = torch.empty(rowops.layernorm_bwd_workspace_bytes(rows, cols), dtype=torch.uint8, device="cuda")
+    B, H, S, D = 4, 8, 2048, 128
+    xr = torch.randn((B, H, S, D), device="cuda", generator=g).to(torch.bfloat16)
+    yr = torch.empty_like(xr)
+    ang = torch.arange(S, device="cuda", dtype=torch.float32)[:, None] * \
+        (10000.0 ** (-torch.arange(0, D, 2, device="cuda", dtype=torch.float32) / D))[None, :]
+    cos, sin = torch.cos(ang).contiguous(), torch.sin(ang).contiguous()
+    act = rows * cols * 2
+    cases = {
+        "rmsnorm_fwd": (lambda: rowops.rmsnorm_fwd(x, w, 1e-6, y=y), 2 * act),
+        "layernorm_fwd": (lambda: rowops.layernorm_fwd(x, w, b, 1e-5, y=y, mean=mean, rstd=rstd), 2 * act),
+        "layernorm_bwd": (lambda: rowops.layernorm_bwd(dy, x, w, mean, rstd, dx=dx, dw=dw, db=db,
+                                                       workspace=ws), 3 * act),
+        "rotary_fwd": (lambda: rowops.rotary_fwd(xr, cos, sin, y=yr), 2 * xr.numel() * 2),
+    }
+    out = {}
+    n = max(steps, 20)
+    for name, (fn, nbytes) in cases.items():
+        for _ in range(warmup):
+            fn()
+        ms_eager = time_calls(torch, fn, n)
+        # These kernels take 5-50 us, less than issuing a launch from Python costs: the figure
+        # that says something about the kernel is taken from n launches recorded into one HIP
+        # graph and replayed (events around the replay on the replaying stream).
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            fn()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(n):
+                    fn()
+        torch.cuda.synchronize()
+        graph.replay()
+        ms = time_calls(torch, graph.replay, 3) / n
+        out[name] = {"ms": ms, "ms_eager_python_launch": ms_eager, "algorithmic_bytes": nbytes,
+                     "gbs": nbytes / (ms * 1e-3) / 1e9,
+                     "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+        del graph
+    out["layernorm_fwd_bwd_ms"] = out["layernorm_fwd"]["ms"] + out["layernorm_bwd"]["ms"]
+    out["shapes"] = {"norms": [rows, cols], "rotary": [B, H, S, D]}
+    return out
+
+
+def rowops_main(torch, a):
+    """The JSON line for --workload rowops."""
+    r = measure_rowops(torch, a.steps, a.warmup)
+    names = ("rmsnorm_fwd", "layernorm_fwd", "layernorm_bwd", "rotary_fwd")
+    total_b = sum(r[k]["algorithmic_bytes"] for k in names)
+    total_ms = sum(r[k]["ms"] for k in names)
+    dom = max(names, key=lambda k: r[k]["ms"])
+    out = {
+        "metric": "row-wise kernels (RMSNorm fwd, LayerNorm fwd+bwd, rotary fwd): algorithmic GB/s",
+        "value": total_b / (total_ms * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": total_ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "rowops: norms (4096, 8192), rotary (4, 8, 2048, 128), the paper's table shapes"},
+        "kernels": r,
+        "roofline": {"kernel": dom, "bound": "hbm", "achieved": r[dom]["gbs"], "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": r[dom]["frac_hbm_peak"], "traffic": None},
+    }
+    if not a.no_cpu_baseline:
+        import numpy as np
+        import oracle
+        rows, cols = 512, 8192
+        rng = np.random.Generator(np.random.PCG64(1013))
+        from paper_2601_16238_amd import workloads as wl
+        xb = wl.f32_to_bf16_bits(rng.standard_normal((rows, cols), dtype=np.float32))
+        w = np.ones(cols, np.float32)
+        t0 = time.perf_counter()
+        oracle.rowops.rmsnorm_fwd(xb, w, 1e-6)
+        oracle.rowops.layernorm_fwd(xb, w, w, 1e-5)
+        oracle.rowops.layernorm_bwd(xb, xb, w, 1e-5)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 7 * rows * cols * 2 / dt / 1e9, "unit": "GB/s",
+                               "cores": oracle.num_threads(), "kind": "oracle", "seconds": dt,
+                               "sample": "RMSNorm fwd, LayerNorm fwd and bwd on 512 of the 4096 rows (fp64)"}
+    print(json.dumps(out))
+
+
 def cpu_baseline(wl, w):
     """The fp64 oracle, as it stands, on a bounded sample of the same workload: forward +
     backward of whole heads at full sequence length -- one head first, then as many as fit
@@ -274,6 +370,9 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     attn.lib()  # fail loudly if the HIP library is not built
+    if a.workload == "rowops":
+        rowops_main(torch, a)
+        return
     if a.workload in wl.RECT_WORKLOADS:
         rect_main(torch, attn, wl, wl.RECT_WORKLOADS[a.workload], a)
         return
@@ -328,6 +427,7 @@ def main():
                           "gbs_bwd": o["gbs_bwd"]}
             torch.cuda.empty_cache()
         out["rect_workloads"] = rect
+        out["row_kernels"] = measure_rowops(torch, a.steps, a.warmup)
         # the fp16 build of the kernels on the main shape (through the rectangular entry points)
         g = torch.Generator(device="cuda"); g.manual_seed(w.seed)
         H = w.Hq if hasattr(w, "Hq") else w.H

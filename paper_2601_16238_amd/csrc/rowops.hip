@@ -222,18 +222,29 @@ layernorm_bwd_rows_kernel(const __bf16 *dy, const __bf16 *x, const float *w, con
     }
 }
 
-// Column reduction of the partial sums: thread = (which of dw/db, 4 consecutive columns).
+// Column reduction of the partial sums.  The rows of `part` are [group][dw | db][cols], i.e.
+// 2 * cols floats per group.  A work-group owns 32 consecutive floats of that row (8 lanes x 4)
+// and splits the groups over 32 slices, so that enough loads are in flight to cover HBM
+// latency; the slices are then summed through LDS in a fixed order (deterministic).
 __global__ void __launch_bounds__(256)
 layernorm_bwd_cols_kernel(const float *part, float *dw, float *db, int groups, int cols)
 {
-    const int t = blockIdx.x * 256 + threadIdx.x;  // over 2 * cols / 4
-    const int per = cols / 4;
-    if (t >= 2 * per) return;
-    const int which = t / per, c = (t % per) * 4;
+    __shared__ f32x4 red[32][8];
+    const int q = threadIdx.x & 7, slice = threadIdx.x >> 3;
+    const int c = blockIdx.x * 32 + q * 4;   // position within the 2 * cols floats of a group
+    const bool in_range = c < 2 * cols;      // the last work-group may be ragged
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int g = 0; g < groups; ++g)
-        acc += *(const f32x4 *)(part + ((int64_t)g * 2 + which) * cols + c);
-    *(f32x4 *)((which ? db : dw) + c) = acc;
+    if (in_range)
+        for (int g = slice; g < groups; g += 32)
+            acc += *(const f32x4 *)(part + (int64_t)g * 2 * cols + c);
+    red[slice][q] = acc;
+    __syncthreads();
+    if (slice == 0 && in_range) {
+        f32x4 t = red[0][q];
+#pragma unroll
+        for (int i = 1; i < 32; ++i) t += red[i][q];
+        *(f32x4 *)((c < cols ? dw : db - cols) + c) = t;
+    }
 }
 
 // Rotary: one thread per 8 pairs (d..d+7, d+hd..d+hd+7) of one (b, h, s) row.
@@ -362,8 +373,8 @@ int rowops_layernorm_bwd(const void *dy, const void *x, const float *w, const fl
                            rstd, static_cast<__bf16 *>(dx), part, rows, cols, dy_row_stride,
                            x_row_stride, dx_row_stride));
     if (hipGetLastError() != hipSuccess) return ATTN_ERR_LAUNCH;
-    const int threads = 2 * cols / 4;
-    hipLaunchKernelGGL(layernorm_bwd_cols_kernel, dim3((threads + 255) / 256), dim3(256), 0, st,
+    // 2 * cols floats per group, 32 per work-group
+    hipLaunchKernelGGL(layernorm_bwd_cols_kernel, dim3((2 * cols + 31) / 32), dim3(256), 0, st,
                        part, dw, db, groups, cols);
     return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
