@@ -76,6 +76,11 @@ def lib():
                 "libmi355attn.so is not built (%s missing): run "
                 "`python -c 'import __graft_entry__ as g; g.build()'` first; "
                 "there is no fallback path" % LIB_PATH)
+        # torch ships its own copy of the HIP runtime.  If this library were loaded first it
+        # would bring in the system copy, and kernels registered with one runtime cannot be
+        # launched on the streams of the other (the launch fails).  Importing torch first
+        # makes its copy the one both use; the tensors and streams come from torch anyway.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, pp = ctypes.c_void_p, ctypes.POINTER(AttnParams)
         L.attn_params_contiguous.argtypes = [pp] + [ctypes.c_int32] * 4 + [ctypes.c_float,
