@@ -597,7 +597,10 @@ static int launch_bwd_dc(const BwdArgs &a, hipStream_t st, unsigned stages)
         if (launch_dkdv<D, CAUSAL>(a, st)) return -1;
     }
     if (stages & 4u) {
-        if (blocks32 >= 8) return launch_dq<D, 8, CAUSAL>(a, st);
+        // 256-row work-groups unless they would leave compute units (256) idle while 128-row
+        // ones would not (few heads and rows against many keys, e.g. chunked prefill)
+        const int64_t wgs8 = (int64_t)a.BH * ((a.S + 255) / 256);
+        if (blocks32 >= 8 && wgs8 >= 256) return launch_dq<D, 8, CAUSAL>(a, st);
         if (blocks32 >= 4) return launch_dq<D, 4, CAUSAL>(a, st);
         if (blocks32 == 3) return launch_dq<D, 3, CAUSAL>(a, st);
         if (blocks32 == 2 || D == 128) return launch_dq<D, 2, CAUSAL>(a, st);
