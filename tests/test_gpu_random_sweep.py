@@ -1,0 +1,76 @@
+"""Seeded random sweep over the whole argument space of the rectangular entry points
+(lengths, head counts and groups, head dimensions, mask, element type, split or not) against
+the fp64 oracle.  The fixed cases elsewhere pick the known tile boundaries; this sweep is
+there for the combinations nobody thought of."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2601_16238_amd as attn
+from paper_2601_16238_amd import workloads as wl
+from parity_util import bf16_round, check_lse, f16_round, to_dev, to_dev_f16, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def draw_cases(n, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    cases = []
+    while len(cases) < n:
+        Hkv = int(rng.integers(1, 4)); G = int(rng.choice([1, 1, 2, 4, 6]))
+        D = int(rng.choice([8, 16, 32, 40, 64, 64, 96, 128, 128, 120]))
+        kind = rng.choice(["square", "decode", "chunk", "cross", "long_keys"])
+        if kind == "square":
+            Sq = Sk = int(rng.integers(1, 700))
+        elif kind == "decode":
+            Sq, Sk = int(rng.integers(1, 5)), int(rng.integers(1, 3000))
+        elif kind == "chunk":
+            Sq = int(rng.integers(2, 400)); Sk = Sq + int(rng.integers(0, 900))
+        elif kind == "cross":
+            Sq, Sk = int(rng.integers(1, 500)), int(rng.integers(1, 500))
+        else:
+            Sq, Sk = int(rng.integers(1, 130)), int(rng.integers(2000, 5000))
+        causal = bool(rng.integers(0, 2)) and Sk >= Sq
+        B = int(rng.integers(1, 3))
+        if B * Hkv * G * Sq * Sk * D > 6e8:      # keep the oracle within a second or two
+            continue
+        cases.append((B, Hkv * G, Hkv, Sq, Sk, D, causal, bool(rng.integers(0, 2)),
+                      bool(rng.integers(0, 4) == 0), int(rng.integers(1 << 30))))
+    return cases
+
+
+# 64 cases by default; ATTN_SWEEP_CASES / ATTN_SWEEP_SEED widen or move the sweep for a soak run
+CASES = draw_cases(int(os.environ.get("ATTN_SWEEP_CASES", "64")),
+                   seed=int(os.environ.get("ATTN_SWEEP_SEED", "20260116")))
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D,causal,split,f16,seed", CASES)
+def test_random_case(B, Hq, Hkv, Sq, Sk, D, causal, split, f16, seed):
+    print("case sweep", B, Hq, Hkv, Sq, Sk, D, causal, split, f16, seed, flush=True)
+    gen = wl.random_rect_inputs_f16 if f16 else wl.random_rect_inputs
+    x = gen(B, Hq, Hkv, Sq, Sk, D, seed=seed)
+    dt = "f16" if f16 else "bf16"
+    Oref, Lref = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], causal, dtype=dt)
+    ref = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], causal, dtype=dt)
+    dev = to_dev_f16 if f16 else to_dev
+    Q, K, V, dO = (dev(x[k]) for k in ("Q", "K", "V", "dO"))
+    O, LSE = attn.attn_fwd_rect(Q, K, V, x["scale"], causal, split=split)
+    dQ, dK, dV = attn.attn_bwd_rect(Q, K, V, O, dO, LSE, x["scale"], causal)
+    torch.cuda.synchronize()
+    check_lse(to_f64(LSE), Lref)
+    rnd = f16_round if f16 else bf16_round
+    for name, got, r in (("O", O, Oref), ("dQ", dQ, ref[0]), ("dK", dK, ref[1]), ("dV", dV, ref[2])):
+        g = to_f64(got)
+        assert np.isfinite(g).all(), name
+        e = np.abs(g - r)
+        scale = max(1.0, float(np.abs(r).max()))
+        floor = float(np.abs(rnd(r) - r).max())
+        # the stated tolerance, scale-aware for gradients that outgrow 1 ...
+        assert e.max() <= 2e-2 * scale and e.mean() <= 2e-3 * scale, \
+            "%s: max %.3e mean %.3e (scale %.3g)" % (name, e.max(), e.mean(), scale)
+        # ... and, for the forward output, the tight gate against the rounding floor
+        if name == "O":
+            assert e.max() <= 4.0 * floor + 1e-6, "O: max %.3e floor %.3e" % (e.max(), floor)
