@@ -67,6 +67,18 @@ __device__ __forceinline__ elem4 pack4(float a0, float a1, float a2, float a3)
     return __builtin_convertvector(v, elem4);
 }
 
+// acc + a + b for two 16-bit elements, accumulated in fp32 (v_dot2c_f32_bf16 / v_dot2_f32_f16
+// with a vector of ones).
+__device__ __forceinline__ float dot2_acc(elem a, elem b, float acc)
+{
+    elem2 v = {a, b}, one = {(elem)1.0f, (elem)1.0f};
+#ifdef ATTN_F16
+    return __builtin_amdgcn_fdot2(v, one, acc, false);
+#else
+    return __builtin_amdgcn_fdot2_f32_bf16(v, one, acc, false);
+#endif
+}
+
 // LDS transpose read (ds_read_b64_tr_b16).  Within each group of 16 lanes, source lane
 // s = 4*e + c points at 4 consecutive 16-bit elements ("row e, chunk c"); result lane i
 // receives, in element e, element i%4 of the chunk addressed by source lane 4*e + i/4.

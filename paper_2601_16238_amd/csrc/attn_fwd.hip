@@ -212,9 +212,19 @@ attn_fwd_kernel(const FwdArgs a)
         for (int db = 0; db < DB; ++db)
             f[db] = *(const elem8 *)(Vt + (32 * db + r) * C::kLdV + 16 * cc + 8 * h);
     };
+    // Row sums of the ROUNDED probabilities (one packed dot product with a vector of ones per
+    // element pair; this lane's half of the keys, both halves are added at the end like the
+    // exact sum).  O is divided by this sum, so that the rounding of P cancels between
+    // numerator and denominator: the reference max is not the true row max, so the dominant
+    // probability of a peaked row is in general not exactly representable, and dividing by the
+    // exact sum would leave its rounding error (up to 2^-9 relative) in O.  LSE is still made
+    // from the exact fp32 sum.
+    float hsum = 0.f;
     auto mm_v = [&](const elem8 (&f)[4], elem8 p) {
 #pragma unroll
         for (int db = 0; db < DB; ++db) o[db] = mfma32(f[db], p, o[db]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) hsum = dot2_acc(p[2 * i], p[2 * i + 1], hsum);
     };
     // exp2 of eight scores against the reference max, fp32 row-sum, and elem pack
     auto softmax8 = [&](const f32x16 &t, int i0, float &psum) -> elem8 {
@@ -286,6 +296,7 @@ attn_fwd_kernel(const FwdArgs a)
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+            hsum *= alpha;
             psum = 0.f;
             p0 = softmax8(cur, 0, psum);
             p1 = softmax8(cur, 8, psum);
@@ -350,10 +361,11 @@ attn_fwd_kernel(const FwdArgs a)
 
     // Epilogue: O = O_acc / l, LSE = ln2 * (m + log2 l).
     const float lt = xhalf_sum(lsum);
+    const float lr = xhalf_sum(hsum);  // sum of the rounded probabilities
     if (SPLIT) {
         // normalised fp32 partial result of this key range; a row that saw no key of the
         // range contributes O = 0 with LSE = -inf
-        const float inv = lt > 0.f ? 1.0f / lt : 0.f;
+        const float inv = lr > 0.f ? 1.0f / lr : 0.f;
         if (q < S) {
             const int64_t row = ((int64_t)blockIdx.y * a.BH + bh) * S + q;
             float *Op = a.Opart + row * D;
@@ -371,7 +383,7 @@ attn_fwd_kernel(const FwdArgs a)
         ATTN_CYCLES_END(0);
         return;
     }
-    const float inv = 1.0f / lt;
+    const float inv = 1.0f / lr;
     if (q < S) {
         elem *Op = a.O + base + (int64_t)q * a.stride_s;
 #pragma unroll

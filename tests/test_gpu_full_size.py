@@ -68,3 +68,25 @@ def test_long_causal_sampled_head():
     # every head: finite, and rows of the whole tensor are what the sampled head saw
     for t in (O, LSE, dQ, dK, dV):
         assert torch.isfinite(t.float()).all()
+
+
+def test_long_causal_forward_every_head_meets_the_literal_tolerance():
+    """The forward output of the long-sequence workload against the oracle on ALL sixteen
+    heads.  |O| reaches 4.2 on its outlier rows, where rounding to bf16 alone errs by up to
+    1.56e-2, so the literal max-abs 2e-2 leaves little room: it is met because O is divided by
+    the sum of the rounded probabilities (dividing by the exact sum left up to 2.7e-2 on half
+    of the heads)."""
+    print("case full_size long_causal forward all heads", flush=True)
+    w = wl.WORKLOADS["long_causal"]
+    x = wl.make_inputs(w)
+    Q, K, V = (to_dev(x[k]) for k in ("Q", "K", "V"))
+    O, LSE = attn.attn_fwd(Q, K, V, x["scale"], True)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for bh in range(w.B * w.H):
+        sub = {k: np.ascontiguousarray(x[k][:, bh:bh + 1]) for k in ("Q", "K", "V")}
+        Oref, Lref = oracle.attn_fwd(sub["Q"], sub["K"], sub["V"], x["scale"], True)
+        emax, emean, fmax, fmean = check_bf16("O head %d" % bh, head(O, w, bh), Oref[0, 0])
+        check_lse_allclose(head(LSE, w, bh), Lref[0, 0])
+        worst = max(worst, emax)
+    print("worst max-abs over the heads: %.3e" % worst, flush=True)
