@@ -246,7 +246,7 @@ attn_fwd_kernel(const FwdArgs a)
     // g+2 (tile kt+1, resident since the previous iteration) are fetched during V0/V1.
     elem8 f0[4], f1[4], f2[4], f3[4];
     auto subtile = [&](int kt, int u, int kbuf_next, int kbuf_fill, bool masked, f32x16 &cur,
-                       f32x16 &nxt) {
+                       f32x16 &nxt) __attribute__((always_inline)) {
         const elem *Kn = Ks + kbuf_next * C::kKTile + u * 32 * D;  // rows of sub-tile g+2
         const elem *Vt = Vs + (kt & 1) * C::kVTile + 32 * u;
         // The two waves that share a SIMD (w and w+4) take turns at the higher issue
@@ -341,8 +341,10 @@ attn_fwd_kernel(const FwdArgs a)
     // half) and K(kt+1) (first half), so K is triple-buffered and K(kt+2) streams into the
     // third buffer; V(kt+1) replaces V(kt-1), whose last readers finished before the
     // previous barrier.
-    int kb1 = 1, kb2 = 2, kb0 = 0;  // buffers of K(kt+1), K(kt+2), K(kt)
-    for (int kt = 0; kt < n_kt; ++kt) {
+    // With 8 waves the loop is unrolled three times so that the K buffer of every access is a
+    // compile-time constant: the LDS addresses of the K fragments are then a loop-invariant register plus
+    // an immediate offset (one vector instruction per fragment less on the issue port).
+    auto tile = [&](int kt, int kb1, int kb2) __attribute__((always_inline)) {  // K(kt+1), K(kt+2)
         const int kb = kt * C::kBC;
         // wave-uniform: does the wave see any key of the sub-tile / must it mask some
         if (!CAUSAL || kb <= q0e + 31) {
@@ -355,7 +357,31 @@ attn_fwd_kernel(const FwdArgs a)
         if (!CAUSAL || kb + 32 <= q0e + 31)
             subtile(kt, 1, kb1, kb2, (kb + 64 > Sk) || (CAUSAL && kb + 63 > q0e), sb, sa);
         __syncthreads();
-        const int t = kb0; kb0 = kb1; kb1 = kb2; kb2 = t;
+    };
+    if constexpr (NW == 8) {
+        for (int kt = 0; kt < n_kt; kt += 3) {  // n_kt is the same for every wave of the work-group
+            tile(kt, 1, 2);
+            if (kt + 1 < n_kt) tile(kt + 1, 2, 0);
+            if (kt + 2 < n_kt) tile(kt + 2, 0, 1);
+        }
+    } else {
+        // fewer waves stage more of each tile per wave and have no registers to spare for the
+        // unrolled form: the buffer indices rotate at run time
+        int kb1 = 1, kb2 = 2, kb0 = 0;  // buffers of K(kt+1), K(kt+2), K(kt)
+        for (int kt = 0; kt < n_kt; ++kt) {
+            const int kb = kt * C::kBC;
+            if (!CAUSAL || kb <= q0e + 31) {
+                subtile(kt, 0, kb1, kb2, (kb + 32 > Sk) || (CAUSAL && kb + 31 > q0e), sa, sb);
+            } else {
+                dma_k(kt + 2, kb2);
+                store_v((kt + 1) & 1);
+                load_v(kt + 2);
+            }
+            if (!CAUSAL || kb + 32 <= q0e + 31)
+                subtile(kt, 1, kb1, kb2, (kb + 64 > Sk) || (CAUSAL && kb + 63 > q0e), sb, sa);
+            __syncthreads();
+            const int t = kb0; kb0 = kb1; kb1 = kb2; kb2 = t;
+        }
     }
 #undef ATTN_FENCE
 
