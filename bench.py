@@ -128,6 +128,55 @@ def measure(torch, attn, wl, w, steps, warmup):
     return res
 
 
+def measure_mfma_peak(torch, attn):
+    """What the matrix pipes of this GPU sustain on nothing but bf16 32x32x16 MFMAs (the
+    library's measurement kernel: 1024 work-groups of 8 waves, ~30 ms per launch), to print
+    beside the nominal peak every fraction here is quoted against."""
+    wgs, iters = 1024, 16384
+    sink = torch.empty(wgs * 512, dtype=torch.float32, device="cuda")
+    flop = attn.attn_probe_mfma_bf16(wgs, iters, sink)   # warm-up launch
+    ms = time_calls(torch, lambda: attn.attn_probe_mfma_bf16(wgs, iters, sink), 3)
+    tf = flop / (ms * 1e-3) / 1e12
+    return {"tflops": tf, "frac_of_nominal": tf / PEAK_BF16_TFLOPS, "ms_per_launch": ms,
+            "kernel": "MFMA-only loop, 2 waves per SIMD, 4 independent accumulator chains"}
+
+
+def measure_cold(torch, attn, wl, w, steps):
+    """Cold-cache timing of a small workload: every call works on its own set of tensors, and
+    the sets together exceed the 256 MiB last-level cache several times over, so no call finds
+    its inputs cached.  (Each call is still issued from Python, which costs some microseconds
+    that the smallest shapes cannot hide.)"""
+    g = torch.Generator(device="cuda"); g.manual_seed(w.seed)
+    per_set = 9 * w.B * w.H * w.S * w.D * 2
+    nsets = int(max(4, min(4096, (1 << 30) // per_set)))
+    mk = lambda: torch.randn((nsets, w.B, w.H, w.S, w.D), device="cuda", generator=g).to(torch.bfloat16)
+    Q, K, V, dO = mk(), mk(), mk(), mk()
+    O, dQ, dK, dV = (torch.empty_like(Q) for _ in range(4))
+    LSE = torch.empty((nsets, w.B, w.H, w.S), dtype=torch.float32, device="cuda")
+    ws = torch.empty(attn.attn_bwd_workspace_bytes(w.B, w.H, w.S, w.D), dtype=torch.uint8, device="cuda")
+    scale = wl.default_scale(w.D)
+    state = {"i": 0}
+
+    def fwd():
+        i = state["i"] = (state["i"] + 1) % nsets
+        attn.attn_fwd(Q[i], K[i], V[i], scale, w.causal, O=O[i], LSE=LSE[i])
+
+    def bwd():
+        i = state["i"] = (state["i"] + 1) % nsets
+        attn.attn_bwd(Q[i], K[i], V[i], O[i], dO[i], LSE[i], scale, w.causal, dQ=dQ[i], dK=dK[i],
+                      dV=dV[i], workspace=ws)
+
+    for _ in range(nsets):   # every O and LSE the backward will read is a forward result
+        fwd()
+    n = max(steps, min(nsets, 200))
+    return {"sets": nsets, "bytes_per_set": per_set, "fwd_ms": time_calls(torch, fwd, n),
+            "bwd_ms": time_calls(torch, bwd, n)}
+
+
+def per_tensor_bytes(w):
+    return w.B * (w.Hq if hasattr(w, "Hq") else w.H) * w.S * w.D * 2
+
+
 def visible_pairs(Sq, Sk, causal):
     """(query, key) pairs under the mask; causal is aligned bottom-right (needs Sk >= Sq)."""
     return Sq * (Sk - Sq) + Sq * (Sq + 1) // 2 if causal else Sq * Sk
@@ -404,6 +453,11 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom))},
         "roofline_all": r["kernels"],
     }
+    probe = measure_mfma_peak(torch, attn)
+    out["mfma_probe"] = probe
+    out["roofline"]["frac_of_measured_peak"] = out["roofline"]["achieved"] / probe["tflops"]
+    out["frac_of_measured_mfma_peak"] = {"fwd": r["tflops_fwd"] / probe["tflops"],
+                                         "fwd_bwd": r["tflops_fwdbwd"] / probe["tflops"]}
     if a.all:
         others = {}
         for name, ow in list(wl.WORKLOADS.items()) + list(wl.GQA_WORKLOADS.items()):
@@ -416,6 +470,8 @@ def main():
                             "frac_fwd": o["tflops_fwd"] / PEAK_BF16_TFLOPS,
                             "frac_fwdbwd": o["tflops_fwdbwd"] / PEAK_BF16_TFLOPS,
                             "gbs_fwd": o["gbs_fwd"], "gbs_bwd": o["gbs_bwd"]}
+            if per_tensor_bytes(ow) <= (16 << 20) and not hasattr(ow, "Hq"):
+                others[name]["cold"] = measure_cold(torch, attn, wl, ow, max(5, a.steps // 2))
             torch.cuda.empty_cache()
         out["other_workloads"] = others
         rect = {}

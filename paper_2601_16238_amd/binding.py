@@ -25,7 +25,7 @@ EXPORTS = ("attn_params_contiguous", "attn_fwd", "attn_bwd_workspace_bytes", "at
            "attn_bwd_gqa_workspace_bytes", "attn_bwd_gqa", "attn_bwd_gqa_stages",
            "attn_rect_params_contiguous", "attn_fwd_rect_workspace_bytes", "attn_fwd_rect",
            "attn_bwd_rect_workspace_bytes", "attn_bwd_rect", "attn_fwd_rect_f16",
-           "attn_bwd_rect_f16", "attn_status_string", "attn_version")
+           "attn_bwd_rect_f16", "attn_probe_mfma_bf16", "attn_status_string", "attn_version")
 STAGE_DELTA, STAGE_DKDV, STAGE_DQ = 1, 2, 4
 STAGE_ALL = 7
 
@@ -122,6 +122,9 @@ def lib():
         L.attn_fwd_rect_f16.restype = ctypes.c_int
         L.attn_bwd_rect_f16.argtypes = L.attn_bwd_rect.argtypes
         L.attn_bwd_rect_f16.restype = ctypes.c_int
+        L.attn_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t,
+                                           ctypes.POINTER(ctypes.c_double), vp]
+        L.attn_probe_mfma_bf16.restype = ctypes.c_int
         L.attn_status_string.argtypes = [ctypes.c_int]
         L.attn_status_string.restype = ctypes.c_char_p
         L.attn_version.argtypes = []
@@ -136,6 +139,20 @@ def status_string(status):
 
 def attn_version():
     return int(lib().attn_version())
+
+
+def attn_probe_mfma_bf16(workgroups, iters, sink, stream=None):
+    """Enqueue the MFMA-only measurement kernel; returns the floating-point operations one
+    launch executes.  `sink`: fp32 CUDA tensor of at least workgroups * 512 elements."""
+    import torch
+    assert sink.is_cuda and sink.dtype == torch.float32 and sink.is_contiguous()
+    st = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    flop = ctypes.c_double(0.0)
+    rc = lib().attn_probe_mfma_bf16(int(workgroups), int(iters), sink.data_ptr(), sink.numel(),
+                                    ctypes.byref(flop), ctypes.c_void_p(st))
+    if rc != 0:
+        raise AttnError(rc, "attn_probe_mfma_bf16")
+    return flop.value
 
 
 def make_params(B, H, S, D, scale, causal, strides=None):

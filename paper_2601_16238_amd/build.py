@@ -13,7 +13,7 @@ SOURCES = [("attn_api.hip", [], "attn_api.o"),
            ("attn_fwd.hip", [], "attn_fwd.o"), ("attn_bwd.hip", [], "attn_bwd.o"),
            ("attn_fwd.hip", ["-DATTN_F16"], "attn_fwd_f16.o"),
            ("attn_bwd.hip", ["-DATTN_F16"], "attn_bwd_f16.o"),
-           ("rowops.hip", [], "rowops.o")]
+           ("rowops.hip", [], "rowops.o"), ("probe.hip", [], "probe.o")]
 # -packed-fp32-ops: never let the compiler form v_pk_*_f32 instructions.
 # -fno-honor-nans (device only): fmaxf lowers to bare v_max/v_max3 without canonicalising
 # moves; the kernels never produce or test NaNs.

@@ -274,6 +274,15 @@ def test_f16_entry_points_validate_like_the_bf16_ones():
         binding.ATTN_ERR_SHAPE
 
 
+def test_mfma_probe_validates_its_arguments():
+    L = attn.lib()
+    assert L.attn_probe_mfma_bf16(4, 10, None, 4 * 512, None, None) == binding.ATTN_ERR_NULL
+    assert L.attn_probe_mfma_bf16(0, 10, FAKE, 4 * 512, None, None) == binding.ATTN_ERR_SHAPE
+    assert L.attn_probe_mfma_bf16(4, 0, FAKE, 4 * 512, None, None) == binding.ATTN_ERR_SHAPE
+    assert L.attn_probe_mfma_bf16(4, 10, FAKE, 4 * 512 - 1, None, None) == binding.ATTN_ERR_WORKSPACE
+    assert L.attn_probe_mfma_bf16(4, 10, FAKE + 2, 4 * 512, None, None) == binding.ATTN_ERR_ALIGN
+
+
 # ---- row-wise entry points (include/rowops.h) ---------------------------------------------------
 
 def test_every_rowops_symbol_is_exported_and_bound():

@@ -1,0 +1,35 @@
+"""The MFMA-only measurement kernel really executes the work its flop count claims: with
+operands that are small integers times 2^-10 every product and partial sum is exact in fp32,
+so the grand total of a wave's accumulators has a closed form."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2601_16238_amd as attn
+
+pytestmark = pytest.mark.gpu
+
+
+def test_probe_total_matches_the_closed_form_and_the_flop_count():
+    wgs, iters = 3, 5
+    sink = torch.full((wgs * 512,), -1.0, dtype=torch.float32, device="cuda")
+    flop = attn.attn_probe_mfma_bf16(wgs, iters, sink)
+    torch.cuda.synchronize()
+    assert flop == wgs * 8 * iters * 16 * 32768.0
+    got = sink.cpu().numpy().astype(np.float64).reshape(wgs * 8, 64)
+    # operand layout of the 32x32x16 MFMA: lane l holds A[l % 32][8 * (l // 32) + i] and
+    # B[8 * (l // 32) + i][l % 32], i = 0..7
+    lanes = np.arange(64)
+    A = np.zeros((32, 16)); B = np.zeros((16, 32))
+    for i in range(8):
+        A[lanes % 32, 8 * (lanes // 32) + i] = (1 + ((lanes + i) & 15)) / 1024.0
+        B[8 * (lanes // 32) + i, lanes % 32] = (1 + ((lanes * 3 + i) & 15)) / 1024.0
+    total = (A @ B).sum() * iters * 16        # 16 MFMAs per iteration, all accumulated
+    np.testing.assert_allclose(got.sum(axis=1), total, rtol=1e-6)
+    assert np.array_equal(got[0], got[-1])    # every wave does the same work
+
+
+def test_probe_rejects_a_small_sink():
+    sink = torch.empty(511, dtype=torch.float32, device="cuda")
+    with pytest.raises(attn.AttnError):
+        attn.attn_probe_mfma_bf16(1, 1, sink)
