@@ -61,6 +61,24 @@ def time_calls(torch, fn, n):
     return e0.elapsed_time(e1) / n
 
 
+def graph_ms(torch, fn, n):
+    """Milliseconds per call of fn when n calls are recorded into one HIP graph and replayed
+    (events around the replay on the replaying stream): the device time of kernels that take
+    less than issuing a launch from Python costs.  The library's calls only enqueue kernels."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        fn()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(n):
+                fn()
+    torch.cuda.synchronize()
+    graph.replay()
+    return time_calls(torch, graph.replay, 3) / n
+
+
 def measure(torch, attn, wl, w, steps, warmup):
     import numpy as np
     from paper_2601_16238_amd import binding
@@ -103,6 +121,10 @@ def measure(torch, attn, wl, w, steps, warmup):
           "bwd_delta": time_calls(torch, lambda: bwd(binding.STAGE_DELTA), n),
           "bwd_dkdv": time_calls(torch, lambda: bwd(binding.STAGE_DKDV), n),
           "bwd_dq": time_calls(torch, lambda: bwd(binding.STAGE_DQ), n)}
+    if w.B * H * w.S * w.D * 2 <= (16 << 20):
+        # small shapes: a call takes less than issuing it from Python costs
+        ms["fwd_graph_replay"] = graph_ms(torch, fwd, 20)
+        ms["bwd_graph_replay"] = graph_ms(torch, bwd, 20)
     f_fwd = wl.fwd_flops(w.B, H, w.S, w.D, causal)
     f_bwd = wl.bwd_flops(w.B, H, w.S, w.D, causal)
     # algorithmic bytes: Q-shaped tensors have H heads, K/V-shaped ones Hkv
@@ -320,22 +342,10 @@ def measure_rowops(torch, steps, warmup):
         # These kernels take 5-50 us, less than issuing a launch from Python costs: the figure
         # that says something about the kernel is taken from n launches recorded into one HIP
         # graph and replayed (events around the replay on the replaying stream).
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            fn()
-            side.synchronize()
-            with torch.cuda.graph(graph, stream=side):
-                for _ in range(n):
-                    fn()
-        torch.cuda.synchronize()
-        graph.replay()
-        ms = time_calls(torch, graph.replay, 3) / n
+        ms = graph_ms(torch, fn, n)
         out[name] = {"ms": ms, "ms_eager_python_launch": ms_eager, "algorithmic_bytes": nbytes,
                      "gbs": nbytes / (ms * 1e-3) / 1e9,
                      "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
-        del graph
     out["layernorm_fwd_bwd_ms"] = out["layernorm_fwd"]["ms"] + out["layernorm_bwd"]["ms"]
     out["shapes"] = {"norms": [rows, cols], "rotary": [B, H, S, D]}
     return out

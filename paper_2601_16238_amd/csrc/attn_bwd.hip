@@ -562,9 +562,10 @@ attn_bwd_dq_kernel(const BwdArgs a)
 // Launch
 // ---------------------------------------------------------------------------------------
 template <typename K>
-static void allow_lds(K kernel, int bytes)
+static bool allow_lds(K kernel, int bytes)
 {
-    hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    return hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               bytes) == hipSuccess;
 }
 
 template <int D, bool CAUSAL>
@@ -572,7 +573,7 @@ static int launch_dkdv(BwdArgs a, hipStream_t st)
 {
     using C = DkdvCfg<D>;
     a.ntile = (a.Sk + C::kBlk - 1) / C::kBlk;
-    allow_lds(attn_bwd_dkdv_kernel<D, CAUSAL>, C::kLdsBytes);
+    if (!allow_lds(attn_bwd_dkdv_kernel<D, CAUSAL>, C::kLdsBytes)) return -1;
     hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, CAUSAL>), dim3(a.ntile * (a.BH / a.group)),
                        dim3(C::kThreads), C::kLdsBytes, st, a);
     return hipGetLastError() == hipSuccess ? 0 : -1;
@@ -583,7 +584,7 @@ static int launch_dq(BwdArgs a, hipStream_t st)
 {
     using C = DqCfg<D, NW>;
     a.ntile = (a.S + C::kBlk - 1) / C::kBlk;
-    allow_lds(attn_bwd_dq_kernel<D, NW, CAUSAL>, C::kLdsBytes);
+    if (!allow_lds(attn_bwd_dq_kernel<D, NW, CAUSAL>, C::kLdsBytes)) return -1;
     hipLaunchKernelGGL((attn_bwd_dq_kernel<D, NW, CAUSAL>), dim3(a.ntile * a.BH),
                        dim3(C::kThreads), C::kLdsBytes, st, a);
     return hipGetLastError() == hipSuccess ? 0 : -1;

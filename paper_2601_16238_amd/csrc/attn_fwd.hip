@@ -458,8 +458,9 @@ template <int D, int NW, bool CAUSAL, bool SPLIT>
 static int launch_fwd_kernel(const FwdArgs &a, hipStream_t st)
 {
     using C = FwdCfg<D, NW>;
-    hipFuncSetAttribute((const void *)attn_fwd_kernel<D, NW, CAUSAL, SPLIT>,
-                        hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes);
+    if (hipFuncSetAttribute((const void *)attn_fwd_kernel<D, NW, CAUSAL, SPLIT>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes) != hipSuccess)
+        return -1;
     hipLaunchKernelGGL((attn_fwd_kernel<D, NW, CAUSAL, SPLIT>),
                        dim3(a.nqt * a.BH, SPLIT ? a.nsplit : 1), dim3(C::kThreads),
                        C::kLdsBytes, st, a);
