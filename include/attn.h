@@ -230,12 +230,15 @@ int attn_bwd_rect_f16(const void *Q, const void *K, const void *V, const void *O
  * section quotes its kernels against the peak of the device they ran on, and this gives the
  * figure the matrix pipes of THIS device sustain, to print beside the nominal peak).
  * `workgroups` work-groups of 512 threads each run `iters` iterations of 16 MFMAs per wave.
+ * random_operands: 0 = the same small constant operands at every step; non-zero = operands
+ * with random signs and mantissas that change from step to step, as real data does (the
+ * clock a GPU sustains depends on how much the operand buses toggle).
  * sink: DEVICE, at least workgroups * 512 floats (sink_floats = its size), fully overwritten;
  * flop: HOST, optional; receives the floating-point operations one launch executes.
  * Errors: ATTN_ERR_NULL (sink), ATTN_ERR_SHAPE (workgroups or iters < 1, workgroups > 2^20),
  * ATTN_ERR_WORKSPACE (sink too small), ATTN_ERR_ALIGN, ATTN_ERR_LAUNCH.  Asynchronous. */
-int attn_probe_mfma_bf16(int workgroups, int iters, float *sink, size_t sink_floats,
-                         double *flop, void *hip_stream);
+int attn_probe_mfma_bf16(int workgroups, int iters, int random_operands, float *sink,
+                         size_t sink_floats, double *flop, void *hip_stream);
 
 /* Static, NUL-terminated description of a status code.  Never NULL. */
 const char *attn_status_string(int status);

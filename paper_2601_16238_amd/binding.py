@@ -122,7 +122,7 @@ def lib():
         L.attn_fwd_rect_f16.restype = ctypes.c_int
         L.attn_bwd_rect_f16.argtypes = L.attn_bwd_rect.argtypes
         L.attn_bwd_rect_f16.restype = ctypes.c_int
-        L.attn_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t,
+        L.attn_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t,
                                            ctypes.POINTER(ctypes.c_double), vp]
         L.attn_probe_mfma_bf16.restype = ctypes.c_int
         L.attn_status_string.argtypes = [ctypes.c_int]
@@ -141,14 +141,15 @@ def attn_version():
     return int(lib().attn_version())
 
 
-def attn_probe_mfma_bf16(workgroups, iters, sink, stream=None):
+def attn_probe_mfma_bf16(workgroups, iters, sink, random_operands=False, stream=None):
     """Enqueue the MFMA-only measurement kernel; returns the floating-point operations one
     launch executes.  `sink`: fp32 CUDA tensor of at least workgroups * 512 elements."""
     import torch
     assert sink.is_cuda and sink.dtype == torch.float32 and sink.is_contiguous()
     st = torch.cuda.current_stream().cuda_stream if stream is None else stream
     flop = ctypes.c_double(0.0)
-    rc = lib().attn_probe_mfma_bf16(int(workgroups), int(iters), sink.data_ptr(), sink.numel(),
+    rc = lib().attn_probe_mfma_bf16(int(workgroups), int(iters), int(bool(random_operands)),
+                                    sink.data_ptr(), sink.numel(),
                                     ctypes.byref(flop), ctypes.c_void_p(st))
     if rc != 0:
         raise AttnError(rc, "attn_probe_mfma_bf16")

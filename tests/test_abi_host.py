@@ -276,11 +276,11 @@ def test_f16_entry_points_validate_like_the_bf16_ones():
 
 def test_mfma_probe_validates_its_arguments():
     L = attn.lib()
-    assert L.attn_probe_mfma_bf16(4, 10, None, 4 * 512, None, None) == binding.ATTN_ERR_NULL
-    assert L.attn_probe_mfma_bf16(0, 10, FAKE, 4 * 512, None, None) == binding.ATTN_ERR_SHAPE
-    assert L.attn_probe_mfma_bf16(4, 0, FAKE, 4 * 512, None, None) == binding.ATTN_ERR_SHAPE
-    assert L.attn_probe_mfma_bf16(4, 10, FAKE, 4 * 512 - 1, None, None) == binding.ATTN_ERR_WORKSPACE
-    assert L.attn_probe_mfma_bf16(4, 10, FAKE + 2, 4 * 512, None, None) == binding.ATTN_ERR_ALIGN
+    assert L.attn_probe_mfma_bf16(4, 10, 0, None, 4 * 512, None, None) == binding.ATTN_ERR_NULL
+    assert L.attn_probe_mfma_bf16(0, 10, 0, FAKE, 4 * 512, None, None) == binding.ATTN_ERR_SHAPE
+    assert L.attn_probe_mfma_bf16(4, 0, 1, FAKE, 4 * 512, None, None) == binding.ATTN_ERR_SHAPE
+    assert L.attn_probe_mfma_bf16(4, 10, 1, FAKE, 4 * 512 - 1, None, None) == binding.ATTN_ERR_WORKSPACE
+    assert L.attn_probe_mfma_bf16(4, 10, 0, FAKE + 2, 4 * 512, None, None) == binding.ATTN_ERR_ALIGN
 
 
 # ---- row-wise entry points (include/rowops.h) ---------------------------------------------------

@@ -29,6 +29,33 @@ def test_probe_total_matches_the_closed_form_and_the_flop_count():
     assert np.array_equal(got[0], got[-1])    # every wave does the same work
 
 
+def test_probe_with_random_operands_matches_numpy():
+    wgs, iters = 2, 3
+    sink = torch.empty(wgs * 512, dtype=torch.float32, device="cuda")
+    flop = attn.attn_probe_mfma_bf16(wgs, iters, sink, random_operands=True)
+    torch.cuda.synchronize()
+    assert flop == wgs * 8 * iters * 16 * 32768.0
+    got = sink.cpu().numpy().astype(np.float64).reshape(wgs * 8, 64)
+    lanes = np.arange(64, dtype=np.uint64)
+    A = np.zeros((4, 32, 16)); B = np.zeros((4, 16, 32))
+    M = np.uint64(0xFFFFFFFF)
+    for s in range(4):
+        for i in range(8):
+            x = ((lanes * np.uint64(64) + np.uint64(s * 8 + i)) * np.uint64(2654435761)) & M
+            x ^= x >> np.uint64(15); x = (x * np.uint64(2246822519)) & M; x ^= x >> np.uint64(13)
+            ua = (0x3F000000 | ((x & np.uint64(0x7F)) << np.uint64(16)) | ((x & np.uint64(0x80)) << np.uint64(24))) & M
+            ub = (0x3F000000 | ((x & np.uint64(0x7F00)) << np.uint64(8)) | ((x & np.uint64(0x8000)) << np.uint64(16))) & M
+            fa = ua.astype(np.uint32).view(np.float32).astype(np.float64)
+            fb = ub.astype(np.uint32).view(np.float32).astype(np.float64)
+            assert np.all((np.abs(fa) >= 0.5) & (np.abs(fa) < 1.0))
+            li = lanes.astype(np.int64)
+            A[s, li % 32, 8 * (li // 32) + i] = fa
+            B[s, 8 * (li // 32) + i, li % 32] = fb
+    total = iters * sum((A[(s + j) & 3] @ B[s]).sum() for s in range(4) for j in range(4))
+    np.testing.assert_allclose(got.sum(axis=1), total, rtol=0, atol=2e-3)
+    assert np.array_equal(got[0], got[-1])
+
+
 def test_probe_rejects_a_small_sink():
     sink = torch.empty(511, dtype=torch.float32, device="cuda")
     with pytest.raises(attn.AttnError):
