@@ -5,6 +5,7 @@ HIP kernels for gfx950).  `workloads` holds the seeded synthetic inputs.
 """
 from . import workloads  # noqa: F401
 from . import rowops  # noqa: F401
+from .autograd import fused_attention  # noqa: F401
 from .binding import (AttnError, AttnGqaParams, AttnParams, AttnRectParams,  # noqa: F401
                       attn_bwd, attn_bwd_gqa, attn_bwd_gqa_workspace_bytes, attn_bwd_rect,
                       attn_bwd_rect_workspace_bytes, attn_bwd_workspace_bytes, attn_fwd,
