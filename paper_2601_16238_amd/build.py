@@ -30,15 +30,17 @@ def _hipcc():
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose=False, resource_usage=False):
-    """Compile every HIP source and link the shared library.  Always recompiles."""
+def build(verbose=False, resource_usage=False, extra_flags=(), lib_path=LIB):
+    """Compile every HIP source and link the shared library.  Always recompiles.
+    `extra_flags` (e.g. a -D switch of an experiment) and `lib_path` serve development builds
+    that must not replace the in-tree library."""
     os.makedirs(OBJ, exist_ok=True)
     cc = _hipcc()
 
     def one(job):
         src, extra, objname = job
         obj = os.path.join(OBJ, objname)
-        cmd = [cc] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [cc] + FLAGS + list(extra_flags) + extra + ["-c", os.path.join(CSRC, src), "-o", obj]
         if resource_usage:
             cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
         res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -52,10 +54,10 @@ def build(verbose=False, resource_usage=False):
 
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
         objs = list(ex.map(one, SOURCES))
-    tmp = LIB + ".tmp%d" % os.getpid()
+    tmp = lib_path + ".tmp%d" % os.getpid()
     subprocess.check_call([cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib_path)
+    return lib_path
 
 
 if __name__ == "__main__":

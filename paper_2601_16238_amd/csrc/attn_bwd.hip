@@ -119,7 +119,7 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     // read it (grouped-query attention; group == 1 is multi-head attention).
     const int Hkv = a.H / a.group;
     int bkv, kt;  // causal: key block 0 is the heaviest
-    xcd_heavy_first(blockIdx.x, a.ntile, a.BH / a.group, bkv, kt);
+    xcd_tile_order<CAUSAL>(blockIdx.x, a.ntile, a.BH / a.group, bkv, kt);
     const int64_t base_kv = (int64_t)(bkv / Hkv) * a.kv_stride_b + (int64_t)(bkv % Hkv) * a.kv_stride_h;
     const int bh0 = (bkv / Hkv) * a.H + (bkv % Hkv) * a.group;  // first query head of the group
 
@@ -401,7 +401,7 @@ attn_bwd_dq_kernel(const BwdArgs a)
     const int S = a.S;
     ATTN_CYCLES_BEGIN();
     int bh, rank;
-    xcd_heavy_first(blockIdx.x, a.ntile, a.BH, bh, rank);
+    xcd_tile_order<CAUSAL>(blockIdx.x, a.ntile, a.BH, bh, rank);
     const int qt = CAUSAL ? a.ntile - 1 - rank : rank;  // heaviest first
     const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
     // grouped-query heads: query head h reads K/V head h / group

@@ -69,7 +69,7 @@ attn_fwd_kernel(const FwdArgs a)
 
     // (head, query tile) of this work-group; causal tiles are issued heaviest first.
     int bh, rank;
-    xcd_heavy_first(blockIdx.x, a.nqt, a.BH, bh, rank);
+    xcd_tile_order<CAUSAL>(blockIdx.x, a.nqt, a.BH, bh, rank);
     const int qt = CAUSAL ? a.nqt - 1 - rank : rank;
     const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
     // grouped-query heads: query head h reads K/V head h / group

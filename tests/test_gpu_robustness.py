@@ -111,3 +111,29 @@ def test_large_scores_do_not_overflow():
     assert np.isfinite(got).all() and (np.abs(got - Lref) <= 1e-5 + 1e-5 * np.abs(Lref)).all()
     d = np.abs(to_f64(O) - Oref)
     assert d.max() <= 2e-2 * max(1.0, np.abs(Oref).max()) and np.isfinite(d).all()
+
+
+@pytest.mark.parametrize("B,H,S,D,causal", [(5, 8, 600, 64, True), (3, 8, 520, 64, False),
+                                            (1, 24, 300, 128, True), (9, 8, 130, 64, True)])
+def test_work_group_order_covers_every_head_and_tile(B, H, S, D, causal):
+    """The work-groups walk the heads of an XCD in small groups; with B*H = 40, 24 or 72 the
+    heads per XCD (5, 3, 9) are no multiple of the group size, so the last group is a smaller
+    one.  Every (head, tile) must still be computed exactly once: outputs are poisoned first
+    and all of them are compared with the oracle."""
+    print("case tile_order", B, H, S, D, causal, flush=True)
+    x = wl.random_inputs(B, H, S, D, seed=900 + B * H)
+    Q, K, V, dO = (to_dev(x[k]) for k in ("Q", "K", "V", "dO"))
+    O = torch.empty_like(Q)
+    LSE = torch.empty((B, H, S), dtype=torch.float32, device="cuda")
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
+    ws = torch.empty(attn.attn_bwd_workspace_bytes(B, H, S, D), dtype=torch.uint8, device="cuda")
+    poison(O, LSE, dQ, dK, dV, ws)
+    attn.attn_fwd(Q, K, V, x["scale"], causal, O=O, LSE=LSE)
+    attn.attn_bwd(Q, K, V, O, dO, LSE, x["scale"], causal, dQ=dQ, dK=dK, dV=dV, workspace=ws)
+    torch.cuda.synchronize()
+    Oref, Lref = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], causal)
+    gref = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], causal)
+    check_bf16("O", to_f64(O), Oref)
+    check_lse(to_f64(LSE), Lref)
+    for nm, t, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), gref):
+        check_bf16(nm, to_f64(t), r)
