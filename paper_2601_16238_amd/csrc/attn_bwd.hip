@@ -369,9 +369,21 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
 // ---------------------------------------------------------------------------------------
 // 3. dQ.  Work-group = NW waves, wave = 32 queries (Q, dO fragments and the 32 x D fp32
 // accumulator in registers), loop over key tiles of 64 rows.  K and V tiles go global -> LDS
-// directly, two tiles ahead, into a ring of three; rows are stored unpadded with the 16-byte
-// chunk index XOR-swizzled by the row (same swizzle as kernel 2) so that the row reads for
-// S^T = K Q^T, dP^T = V dO^T and the transpose reads for dQ^T += K^T dS^T are conflict free.
+// directly, two tiles ahead, into a ring of three.
+//
+// LDS layout of a tile tensor.  One wave-wide transfer fills 1 KB in lane order, and a lane
+// may fetch any 16-byte chunk, so within such a piece (P rows of a tile: 4 at D = 128, 8 at
+// D = 64) the chunks are stored chunk-major: chunk c of row r sits at 16 * (c * P + r % P),
+// and consecutive pieces are P * 16 bytes apart more than their size.  Then
+//  - the address of a fragment is a per-lane constant plus compile-time terms for the
+//    contraction step, the d block, the sub-tile and the ring position: with the loop unrolled
+//    over the ring positions every LDS access is one register plus an immediate offset and the
+//    loop has no vector instruction for addressing (it had 16 per sub-tile with a row-major,
+//    XOR-swizzled tile);
+//  - 16 consecutive rows at a fixed chunk fall into 16 different 16-byte bank groups (the row
+//    reads for S^T = K Q^T and dP^T = V dO^T), and the 64 lanes of a transpose read (4 rows x
+//    4 chunks x 2 halves per half-wave, for dQ^T += K^T dS^T) cover 512 contiguous bytes:
+//    both are conflict free.
 // ---------------------------------------------------------------------------------------
 template <int D, int NW>
 struct DqCfg {
@@ -380,11 +392,17 @@ struct DqCfg {
     static constexpr int kTile = 64;                 // keys per tile
     static constexpr int kRing = 3;
     static constexpr int kRowBytes = D * 2;
-    static constexpr int kTensorBytes = kTile * kRowBytes;   // K part of a tile; V follows
+    static constexpr int kPieceRows = 1024 / kRowBytes;       // rows one 1 KB transfer fills
+    static constexpr int kPieceBytes = 1024 + kPieceRows * 16;
+    static constexpr int kPieces = kTile / kPieceRows;        // per tensor
+    static constexpr int kTensorBytes = kPieces * kPieceBytes;   // K part of a tile; V follows
     static constexpr int kTileBytes = 2 * kTensorBytes;
     static constexpr int kLdsBytes = kRing * kTileBytes;
-    static constexpr int kDmaPerTile = kTileBytes / 1024;     // wave-wide 1 KB transfers
+    static constexpr int kDmaPerTile = 2 * kPieces;           // wave-wide 1 KB transfers
     static constexpr int kDmaPerWave = (kDmaPerTile + NW - 1) / NW;
+    static constexpr int kChunkStep = kPieceRows * 16;        // next 16-byte chunk of a row
+    static constexpr int kRows16 = (16 / kPieceRows) * kPieceBytes;  // 16 rows further
+    static_assert(16 % kPieceRows == 0, "sub-tiles start at piece boundaries");
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 CU exceeded");
 };
 
@@ -393,7 +411,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2)
 attn_bwd_dq_kernel(const BwdArgs a)
 {
     using C = DqCfg<D, NW>;
-    constexpr int KS = D / 16, DB = D / 32, CPR = D / 8, RB = C::kRowBytes;
+    constexpr int KS = D / 16, DB = D / 32, PR = C::kPieceRows;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     const int tid = threadIdx.x, l = tid & 63, r = l & 31, h = l >> 5;
@@ -417,33 +435,37 @@ attn_bwd_dq_kernel(const BwdArgs a)
     const int q_end = min(S, (qt + 1) * C::kBlk);
     const int n_kt = ((CAUSAL ? q_end + coff : Sk) + C::kTile - 1) / C::kTile;
 
-    auto swz = [](int row) {
-        return CPR == 16 ? (((row & 3) << 2) | ((row >> 2) & 3))
-                         : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+    // byte offset of 16-byte chunk `chunk` of row `row` within a tile tensor
+    auto at = [](int row, int chunk) {
+        return (row / PR) * C::kPieceBytes + (chunk * PR + row % PR) * 16;
     };
 
     // ---- streaming of tile kt into ring position pos; rows past S-1 read as zero
     const int Dr = a.Dr;  // columns Dr..D-1 read as zero (offset past the end of the resource)
     const uint32_t head_bytes = (uint32_t)(((int64_t)(Sk - 1) * a.kv_stride_s + Dr) * 2);
-    const desc_t Kd = make_desc(a.K + base_kv, head_bytes), Vd = make_desc(a.V + base_kv, head_bytes);
+    const desc_t Kd0 = make_desc(a.K + base_kv, head_bytes), Vd0 = make_desc(a.V + base_kv, head_bytes);
     const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2u;
     const uint32_t lds0 = lds_address(smem);
-    auto dma_tile = [&](int kt, int pos) {
+    // (the descriptors are passed by value: captured by reference through two levels of
+    // lambdas the compiler no longer proves them wave-uniform)
+    // lane l lands at byte 16 * l of a piece: chunk l / PR of the piece's row l % PR.  The
+    // piece's first row goes into the scalar offset (which takes part in the range check like
+    // the per-lane one), so one per-lane offset serves every transfer.
+    const uint32_t voff = (l / PR) * 8 < Dr ? (l % PR) * row_bytes + ((l / PR) << 4) : head_bytes;
+    auto dma_tile = [&](int kt, int pos, desc_t Kd, desc_t Vd) __attribute__((always_inline)) {
 #pragma unroll
         for (int n = 0; n < C::kDmaPerWave; ++n) {
             // wave-uniform 1 KB piece; a wave with nothing left repeats an earlier piece so
             // that every wave has the same number of transfers in flight
             const int i = (w + n * NW) % C::kDmaPerTile;
-            const int tensor = i / (C::kDmaPerTile / 2), grp = i % (C::kDmaPerTile / 2);
-            const int row = grp * (64 / CPR) + l / CPR;
-            const int chunk = (l % CPR) ^ swz(row);
-            const uint32_t voff = chunk * 8 < Dr ? row * row_bytes + (chunk << 4) : head_bytes;
-            dma16(tensor ? Vd : Kd, lds0 + pos * C::kTileBytes + tensor * C::kTensorBytes + grp * 1024,
-                  voff, kt * C::kTile * row_bytes);
+            const int tensor = i / C::kPieces, piece = i % C::kPieces;
+            dma16(tensor ? Vd : Kd,
+                  lds0 + pos * C::kTileBytes + tensor * C::kTensorBytes + piece * C::kPieceBytes,
+                  voff, (kt * C::kTile + piece * PR) * row_bytes);
         }
     };
-    dma_tile(0, 0);
-    if (n_kt > 1) dma_tile(1, 1);
+    dma_tile(0, 0, Kd0, Vd0);
+    if (n_kt > 1) dma_tile(1, 1, Kd0, Vd0);
 
     elem8 qf[KS], gf[KS];
 #pragma unroll
@@ -467,28 +489,35 @@ attn_bwd_dq_kernel(const BwdArgs a)
         for (int i = 0; i < 16; ++i) dq[db][i] = 0.f;
 
     const float c = a.scale_log2e;
-    const int lane_off = r * RB + ((h ^ swz(r)) << 4);  // chunk 2ks+h of row r: ^ (ks*32)
-    int tr_off[2];  // transpose reads: rows 4h+e (+8), 64 bytes of d block 0 per row
+    // Per-lane LDS addresses within ring position 0 (lo) and 2 (hi): row fragment = chunk h of
+    // row r (contraction step ks: 2 ks chunks further); transpose reads = rows 4h+e (+8), the
+    // 64 bytes of d block 0 of each row (d block db: 4 db chunks further).  Everything else --
+    // ring position, tensor, sub-tile, 16-row step -- is a compile-time offset.  Position 2
+    // gets registers of its own because an LDS instruction's immediate reaches 64 KB and the
+    // ring is longer than that at D = 128.  The values are made opaque so that the compiler
+    // keeps exactly these six registers instead of re-deriving addresses in the loop.
+    int row_lo = at(r, h), tr_lo[2];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int row = 8 * j + 4 * h + ((l & 15) >> 2);
-        const int chunk = 2 * ((l >> 4) & 1) + ((l >> 1) & 1);
-        tr_off[j] = row * RB + ((chunk ^ swz(row)) << 4) + (l & 1) * 8;
-    }
+    for (int j = 0; j < 2; ++j)
+        tr_lo[j] = at(8 * j + 4 * h + ((l & 15) >> 2), 2 * ((l >> 4) & 1) + ((l >> 1) & 1)) + (l & 1) * 8;
+    int row_hi = row_lo + 2 * C::kTileBytes, tr_hi[2] = {tr_lo[0] + 2 * C::kTileBytes,
+                                                          tr_lo[1] + 2 * C::kTileBytes};
+    asm volatile("" : "+v"(row_lo), "+v"(tr_lo[0]), "+v"(tr_lo[1]));
+    if (NW == 8) asm volatile("" : "+v"(row_hi), "+v"(tr_hi[0]), "+v"(tr_hi[1]));
 
     // All register loads above must be complete before the loop: the compiler would otherwise
     // place its own vmcnt waits for them at their first use inside the loop, where they would
     // also wait for the tile transfers (which it does not see) in every iteration.
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 
-    int pos = 0;
-    for (int kt = 0; kt < n_kt; ++kt) {
+    // One tile of 64 keys at ring position `pos`; Kt + rowa / tra0 / tra1 address its K tensor.
+    auto tile = [&](int kt, int pos, const char *Kt, int rowa, int tra0, int tra1, desc_t Kd,
+                    desc_t Vd) __attribute__((always_inline)) {
         // tile kt must have landed; tile kt+1 (if any) may stay in flight
         if (kt + 1 < n_kt) wait_vm_and_barrier<C::kDmaPerWave>();
         else wait_vm_and_barrier<0>();
-        if (kt + 2 < n_kt) dma_tile(kt + 2, pos == 0 ? 2 : pos - 1);  // the tile freed by the barrier
+        if (kt + 2 < n_kt) dma_tile(kt + 2, pos == 0 ? 2 : pos - 1, Kd, Vd);  // the tile freed by the barrier
 
-        const char *Kt = smem + pos * C::kTileBytes;
         const char *Vt = Kt + C::kTensorBytes;
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2) {
@@ -500,15 +529,15 @@ attn_bwd_dq_kernel(const BwdArgs a)
                 f32x16 zero;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) zero[i] = 0.f;
-                const int off = kb2 * 32 * RB + lane_off;
-                s = mfma32(*(const elem8 *)(Kt + off), qf[0], zero);
-                dp = mfma32(*(const elem8 *)(Vt + off), gf[0], nd);  // ends as dP - delta
+                const int off = kb2 * 2 * C::kRows16;
+                s = mfma32(*(const elem8 *)(Kt + off + rowa), qf[0], zero);
+                dp = mfma32(*(const elem8 *)(Vt + off + rowa), gf[0], nd);  // ends as dP - delta
             }
 #pragma unroll
             for (int ks = 1; ks < KS; ++ks) {
-                const int off = kb2 * 32 * RB + (lane_off ^ (ks * 32));
-                s = mfma32(*(const elem8 *)(Kt + off), qf[ks], s);
-                dp = mfma32(*(const elem8 *)(Vt + off), gf[ks], dp);
+                const int off = kb2 * 2 * C::kRows16 + ks * 2 * C::kChunkStep;
+                s = mfma32(*(const elem8 *)(Kt + off + rowa), qf[ks], s);
+                dp = mfma32(*(const elem8 *)(Vt + off + rowa), gf[ks], dp);
             }
             // register i <-> key k_lo + 8*(i/4) + 4h + i%4; this lane's query is fixed
             const bool need_mask = (k_lo + 32 > Sk) || (CAUSAL && k_lo + 31 > q0e);
@@ -529,16 +558,32 @@ attn_bwd_dq_kernel(const BwdArgs a)
             for (int cc = 0; cc < 2; ++cc) {
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    // d block db = chunks 4db..4db+3: flips bits 6.. of the swizzled offset
-                    const int o0 = (tr_off[0] ^ (db << 6)) + (kb2 * 32 + cc * 16) * RB;
-                    const int o1 = (tr_off[1] ^ (db << 6)) + (kb2 * 32 + cc * 16) * RB;
-                    const elem8 kT = join8(lds_read_tr((const elem *)(Kt + o0)),
-                                            lds_read_tr((const elem *)(Kt + o1)));
+                    const int off = (kb2 * 2 + cc) * C::kRows16 + db * 4 * C::kChunkStep;
+                    const elem8 kT = join8(lds_read_tr((const elem *)(Kt + off + tra0)),
+                                           lds_read_tr((const elem *)(Kt + off + tra1)));
                     dq[db] = mfma32(kT, sb[cc], dq[db]);
                 }
             }
         }
-        pos = pos == 2 ? 0 : pos + 1;
+    };
+    if constexpr (NW == 8) {
+        // unrolled over the three ring positions, which makes them compile-time constants;
+        // n_kt is the same for every wave of the work-group
+        for (int kt = 0; kt < n_kt; kt += 3) {
+            tile(kt, 0, smem, row_lo, tr_lo[0], tr_lo[1], Kd0, Vd0);
+            if (kt + 1 < n_kt)
+                tile(kt + 1, 1, smem + C::kTileBytes, row_lo, tr_lo[0], tr_lo[1], Kd0, Vd0);
+            if (kt + 2 < n_kt) tile(kt + 2, 2, smem, row_hi, tr_hi[0], tr_hi[1], Kd0, Vd0);
+        }
+    } else {
+        // fewer waves issue more transfers each and have no registers to spare for the unrolled
+        // form: the ring position advances at run time (three additions per tile)
+        int pos = 0;
+        for (int kt = 0; kt < n_kt; ++kt) {
+            const int o = pos * C::kTileBytes;
+            tile(kt, pos, smem, row_lo + o, tr_lo[0] + o, tr_lo[1] + o, Kd0, Vd0);
+            pos = pos == 2 ? 0 : pos + 1;
+        }
     }
     // no transfer may still be in flight when the work-group's LDS is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
