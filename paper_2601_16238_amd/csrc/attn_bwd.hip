@@ -511,6 +511,56 @@ attn_bwd_dq_kernel(const BwdArgs a)
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 
     // One tile of 64 keys at ring position `pos`; Kt + rowa / tra0 / tra1 address its K tensor.
+    // The steps of one 32-key sub-tile kb2 of the tile whose K tensor Kt + rowa / tra0 / tra1
+    // address; register i of s and dp <-> key k_lo + 8*(i/4) + 4h + i%4 (this lane's query is
+    // fixed).
+    auto step_s = [&](const char *Kt, int rowa, int kb2, f32x16 &s) __attribute__((always_inline)) {
+        f32x16 zero;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+        s = mfma32(*(const elem8 *)(Kt + kb2 * 2 * C::kRows16 + rowa), qf[0], zero);
+#pragma unroll
+        for (int ks = 1; ks < KS; ++ks)
+            s = mfma32(*(const elem8 *)(Kt + kb2 * 2 * C::kRows16 + ks * 2 * C::kChunkStep + rowa), qf[ks], s);
+    };
+    auto step_dp = [&](const char *Kt, int rowa, int kb2, f32x16 &dp) __attribute__((always_inline)) {
+        const char *Vt = Kt + C::kTensorBytes;
+        dp = mfma32(*(const elem8 *)(Vt + kb2 * 2 * C::kRows16 + rowa), gf[0], nd);  // ends as dP - delta
+#pragma unroll
+        for (int ks = 1; ks < KS; ++ks)
+            dp = mfma32(*(const elem8 *)(Vt + kb2 * 2 * C::kRows16 + ks * 2 * C::kChunkStep + rowa), gf[ks], dp);
+    };
+    auto step_p = [&](int k_lo, f32x16 &s) __attribute__((always_inline)) {  // S -> P
+        const bool need_mask = (k_lo + 32 > Sk) || (CAUSAL && k_lo + 31 > q0e);
+        const int lim = (CAUSAL ? qc + coff : Sk - 1) - k_lo - 4 * h;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[i] = fast_exp2(__builtin_fmaf(s[i], c, -lse2));
+        if (need_mask) {  // wave-uniform: only blocks on the diagonal or at the ragged end
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (8 * (i / 4) + (i % 4) > lim) s[i] = 0.f;
+        }
+    };
+    auto step_ds = [&](const f32x16 &s, f32x16 &dp, elem8 (&sb)[2]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dp[i] *= s[i];  // dS = P o (dP - delta)
+        sb[0] = pack8(dp[0], dp[1], dp[2], dp[3], dp[4], dp[5], dp[6], dp[7]);
+        sb[1] = pack8(dp[8], dp[9], dp[10], dp[11], dp[12], dp[13], dp[14], dp[15]);
+    };
+    auto step_dq = [&](const char *Kt, int tra0, int tra1, int kb2, const elem8 (&sb)[2])
+                       __attribute__((always_inline)) {
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const int off = (kb2 * 2 + cc) * C::kRows16 + db * 4 * C::kChunkStep;
+                const elem8 kT = join8(lds_read_tr((const elem *)(Kt + off + tra0)),
+                                       lds_read_tr((const elem *)(Kt + off + tra1)));
+                dq[db] = mfma32(kT, sb[cc], dq[db]);
+            }
+        }
+    };
+    // One tile of 64 keys at ring position `pos`.
     auto tile = [&](int kt, int pos, const char *Kt, int rowa, int tra0, int tra1, desc_t Kd,
                     desc_t Vd) __attribute__((always_inline)) {
         // tile kt must have landed; tile kt+1 (if any) may stay in flight
@@ -518,52 +568,20 @@ attn_bwd_dq_kernel(const BwdArgs a)
         else wait_vm_and_barrier<0>();
         if (kt + 2 < n_kt) dma_tile(kt + 2, pos == 0 ? 2 : pos - 1, Kd, Vd);  // the tile freed by the barrier
 
-        const char *Vt = Kt + C::kTensorBytes;
+        const int k0 = kt * C::kTile;
+        // wave-uniform: does this wave see any key of the first / second sub-tile
+        const bool act0 = k0 < Sk && (!CAUSAL || k0 <= q0e + 31);
+        const bool act1 = k0 + 32 < Sk && (!CAUSAL || k0 + 32 <= q0e + 31);
 #pragma unroll
         for (int kb2 = 0; kb2 < 2; ++kb2) {
-            const int k_lo = kt * C::kTile + kb2 * 32;
-            const bool active = k_lo < Sk && (!CAUSAL || k_lo <= q0e + 31);  // wave-uniform
-            if (!active) continue;
+            if (!(kb2 ? act1 : act0)) continue;
             f32x16 s, dp;
-            {
-                f32x16 zero;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) zero[i] = 0.f;
-                const int off = kb2 * 2 * C::kRows16;
-                s = mfma32(*(const elem8 *)(Kt + off + rowa), qf[0], zero);
-                dp = mfma32(*(const elem8 *)(Vt + off + rowa), gf[0], nd);  // ends as dP - delta
-            }
-#pragma unroll
-            for (int ks = 1; ks < KS; ++ks) {
-                const int off = kb2 * 2 * C::kRows16 + ks * 2 * C::kChunkStep;
-                s = mfma32(*(const elem8 *)(Kt + off + rowa), qf[ks], s);
-                dp = mfma32(*(const elem8 *)(Vt + off + rowa), gf[ks], dp);
-            }
-            // register i <-> key k_lo + 8*(i/4) + 4h + i%4; this lane's query is fixed
-            const bool need_mask = (k_lo + 32 > Sk) || (CAUSAL && k_lo + 31 > q0e);
-            const int lim = (CAUSAL ? qc + coff : Sk - 1) - k_lo - 4 * h;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) s[i] = fast_exp2(__builtin_fmaf(s[i], c, -lse2));
-            if (need_mask) {  // wave-uniform: only blocks on the diagonal or at the ragged end
-#pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    if (8 * (i / 4) + (i % 4) > lim) s[i] = 0.f;
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) dp[i] *= s[i];  // dS = P o (dP - delta)
             elem8 sb[2];
-            sb[0] = pack8(dp[0], dp[1], dp[2], dp[3], dp[4], dp[5], dp[6], dp[7]);
-            sb[1] = pack8(dp[8], dp[9], dp[10], dp[11], dp[12], dp[13], dp[14], dp[15]);
-#pragma unroll
-            for (int cc = 0; cc < 2; ++cc) {
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const int off = (kb2 * 2 + cc) * C::kRows16 + db * 4 * C::kChunkStep;
-                    const elem8 kT = join8(lds_read_tr((const elem *)(Kt + off + tra0)),
-                                           lds_read_tr((const elem *)(Kt + off + tra1)));
-                    dq[db] = mfma32(kT, sb[cc], dq[db]);
-                }
-            }
+            step_s(Kt, rowa, kb2, s);
+            step_dp(Kt, rowa, kb2, dp);
+            step_p(k0 + kb2 * 32, s);
+            step_ds(s, dp, sb);
+            step_dq(Kt, tra0, tra1, kb2, sb);
         }
     };
     if constexpr (NW == 8) {
