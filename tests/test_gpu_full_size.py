@@ -131,3 +131,59 @@ def test_full_size_closed_forms_on_every_head(name):
     assert err_lse <= 2e-5
     assert err_o <= 2e-2 and err_dv <= 2e-2 and err_dq <= 2e-2
     assert torch.isfinite(dK.float()).all()
+
+
+@pytest.mark.parametrize("name", ["long_causal", "sdpa_cmp"])
+def test_full_size_closed_forms_with_equal_query_rows(name):
+    """The counterpart for dK: with all query rows of a head equal to one vector q0 the score
+    of key j is the same number s_j in every row, so with e_j = exp(s_j - max s) and
+    Z_i = sum of e_j over the keys row i sees,
+        LSE_i = max s + ln Z_i,   O_i = sum_j e_j V_j / Z_i,   delta_i = dO_i . O_i,
+        dV_j = e_j A_j,   dK_j = scale q0 e_j (A_j . V_j - b_j),
+    where A_j and b_j are the sums of dO_i / Z_i and delta_i / Z_i over the rows i that see
+    key j: prefix and suffix sums along the sequence, done in fp64 with torch."""
+    print("case full_size closed forms, equal queries", name, flush=True)
+    w = wl.WORKLOADS[name]
+    B, H, S, D, causal = w.B, w.H, w.S, w.D, w.causal
+    g = torch.Generator(device="cuda"); g.manual_seed(w.seed + 1)
+    rnd = lambda *shape: torch.randn(shape, device="cuda", generator=g).to(torch.bfloat16)
+    K, V, dO = rnd(B, H, S, D), rnd(B, H, S, D), rnd(B, H, S, D)
+    q0 = rnd(B, H, 1, D)
+    Q = q0.expand(B, H, S, D).contiguous()
+    scale = wl.default_scale(D)
+    O, LSE = attn.attn_fwd(Q, K, V, scale, causal)
+    dQ, dK, dV = attn.attn_bwd(Q, K, V, O, dO, LSE, scale, causal)
+    torch.cuda.synchronize()
+    f64 = lambda t: t.to(torch.float64)
+    sc = float(np.float32(scale))
+    s = sc * (f64(K) * f64(q0)).sum(-1)                        # [B,H,S]
+    m = s.max(dim=-1, keepdim=True).values
+    e = torch.exp(s - m)
+    suffix = lambda t: torch.flip(torch.cumsum(torch.flip(t, dims=[2]), dim=2), dims=[2])
+    if causal:
+        Z = torch.cumsum(e, dim=-1)
+        Oref = torch.cumsum(e[..., None] * f64(V), dim=2) / Z[..., None]
+    else:
+        Z = e.sum(-1, keepdim=True).expand(B, H, S)
+        Oref = ((e[..., None] * f64(V)).sum(dim=2, keepdim=True) / Z[..., :1, None]).expand(B, H, S, D)
+    delta = (f64(dO) * Oref).sum(-1)
+    a_terms, b_terms = f64(dO) / Z[..., None], delta / Z
+    if causal:
+        A, b = suffix(a_terms), suffix(b_terms[..., None])[..., 0]
+    else:
+        A = a_terms.sum(dim=2, keepdim=True).expand(B, H, S, D)
+        b = b_terms.sum(dim=-1, keepdim=True).expand(B, H, S)
+    dVref = e[..., None] * A
+    dKref = sc * f64(q0) * (e * ((A * f64(V)).sum(-1) - b))[..., None]
+    errs = {"LSE": (f64(LSE) - (m + torch.log(Z))).abs().max().item(),
+            "O": (f64(O) - Oref).abs().max().item(),
+            "dV": (f64(dV) - dVref).abs().max().item(),
+            "dK": (f64(dK) - dKref).abs().max().item()}
+    mags = {"O": Oref.abs().max().item(), "dV": dVref.abs().max().item(), "dK": dKref.abs().max().item()}
+    print("max errors", {k: "%.3g" % v for k, v in errs.items()}, "max |ref|",
+          {k: "%.3g" % v for k, v in mags.items()}, flush=True)
+    assert errs["LSE"] <= 2e-5
+    for k in ("O", "dV", "dK"):
+        # absolute bound of the benchmark, widened by the bf16 spacing where |ref| exceeds 1
+        assert errs[k] <= 2e-2 * max(1.0, mags[k]), (k, errs[k], mags[k])
+    assert torch.isfinite(dQ.float()).all()
