@@ -187,3 +187,53 @@ def test_full_size_closed_forms_with_equal_query_rows(name):
         # absolute bound of the benchmark, widened by the bf16 spacing where |ref| exceeds 1
         assert errs[k] <= 2e-2 * max(1.0, mags[k]), (k, errs[k], mags[k])
     assert torch.isfinite(dQ.float()).all()
+
+
+@pytest.mark.parametrize("name", ["long_causal", "sdpa_cmp"])
+def test_full_size_closed_forms_with_two_alternating_keys(name):
+    """The counterpart for dQ: even key rows all equal k_a, odd ones k_b, so a row has two
+    score values s_a, s_b and, with e_t = exp(s_t - max), n_t = visible keys of type t,
+    V_t = sum of the visible V rows of type t and Z = n_a e_a + n_b e_b,
+        LSE = max + ln Z,   O = (e_a V_a + e_b V_b) / Z,   delta = dO . O,
+        dQ = scale sum_t k_t (e_t / Z) (dO . V_t - n_t delta)."""
+    print("case full_size closed forms, two keys", name, flush=True)
+    w = wl.WORKLOADS[name]
+    B, H, S, D, causal = w.B, w.H, w.S, w.D, w.causal
+    g = torch.Generator(device="cuda"); g.manual_seed(w.seed + 2)
+    rnd = lambda *shape: torch.randn(shape, device="cuda", generator=g).to(torch.bfloat16)
+    Q, V, dO = rnd(B, H, S, D), rnd(B, H, S, D), rnd(B, H, S, D)
+    kab = rnd(B, H, 2, D)
+    K = kab.repeat(1, 1, S // 2, 1).contiguous()              # rows a, b, a, b, ...
+    scale = wl.default_scale(D)
+    O, LSE = attn.attn_fwd(Q, K, V, scale, causal)
+    dQ, dK, dV = attn.attn_bwd(Q, K, V, O, dO, LSE, scale, causal)
+    torch.cuda.synchronize()
+    f64 = lambda t: t.to(torch.float64)
+    sc = float(np.float32(scale))
+    s = sc * torch.einsum("bhsd,bhtd->bhst", f64(Q), f64(kab))  # [B,H,S,2]
+    m = s.max(dim=-1, keepdim=True).values
+    e = torch.exp(s - m)
+    typ = (torch.arange(S, device="cuda") % 2)
+    mask = torch.stack([(typ == 0), (typ == 1)], dim=-1).to(torch.float64)       # [S,2]
+    if causal:
+        n = torch.cumsum(mask, dim=0)                                            # [S,2]
+        Vt = torch.stack([torch.cumsum(f64(V) * mask[:, t, None], dim=2) for t in (0, 1)], dim=3)
+    else:
+        n = mask.sum(dim=0, keepdim=True).expand(S, 2)
+        Vt = torch.stack([(f64(V) * mask[:, t, None]).sum(dim=2, keepdim=True).expand(B, H, S, D)
+                          for t in (0, 1)], dim=3)                               # [B,H,S,2,D]
+    Z = (n * e).sum(-1)                                                          # [B,H,S]
+    Oref = (e[..., None] * Vt).sum(dim=3) / Z[..., None]
+    delta = (f64(dO) * Oref).sum(-1)
+    coef = (e / Z[..., None]) * (torch.einsum("bhsd,bhstd->bhst", f64(dO), Vt) - n * delta[..., None])
+    dQref = sc * torch.einsum("bhst,bhtd->bhsd", coef, f64(kab))
+    errs = {"LSE": (f64(LSE) - (m[..., 0] + torch.log(Z))).abs().max().item(),
+            "O": (f64(O) - Oref).abs().max().item(),
+            "dQ": (f64(dQ) - dQref).abs().max().item()}
+    mags = {"O": Oref.abs().max().item(), "dQ": dQref.abs().max().item()}
+    print("max errors", {k: "%.3g" % v for k, v in errs.items()}, "max |ref|",
+          {k: "%.3g" % v for k, v in mags.items()}, flush=True)
+    assert errs["LSE"] <= 2e-5
+    for k in ("O", "dQ"):
+        assert errs[k] <= 2e-2 * max(1.0, mags[k]), (k, errs[k], mags[k])
+    assert torch.isfinite(dK.float()).all() and torch.isfinite(dV.float()).all()
