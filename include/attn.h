@@ -98,7 +98,8 @@ size_t attn_bwd_workspace_bytes(const attn_params_t *p);
  *   workspace  : device scratch of at least attn_bwd_workspace_bytes(p) bytes, 256-byte
  *                aligned; contents undefined on entry and on exit (the library initialises
  *                everything it reads)
- * Enqueues three kernels on hip_stream: row statistics (delta, rescaled LSE), dK/dV, dQ.
+ * Enqueues two kernels on hip_stream: dQ (which also forms the row statistics delta and
+ * rescaled LSE and stores them in the workspace), then dK/dV (which reads them).
  */
 int attn_bwd(const void *Q, const void *K, const void *V, const void *O, const void *dO,
              const float *LSE, void *dQ, void *dK, void *dV,
@@ -106,12 +107,13 @@ int attn_bwd(const void *Q, const void *K, const void *V, const void *O, const v
              const attn_params_t *p, void *hip_stream);
 
 /*
- * Profiling aid: attn_bwd restricted to a subset of its three kernels, so that each can be
- * timed on its own with events on the caller's stream.  `stages` is a bit mask of
- * ATTN_BWD_STAGE_*; attn_bwd is attn_bwd_stages with all three bits.  The dK/dV and dQ
- * stages read the row statistics from the workspace, so it must hold the delta stage's result of an
- * earlier call on the same problem.  Validation and errors as attn_bwd; stages == 0 or
- * unknown bits give ATTN_ERR_SHAPE.
+ * Profiling aid: attn_bwd restricted to a subset of its stages, so that each can be timed
+ * on its own with events on the caller's stream.  `stages` is a bit mask of
+ * ATTN_BWD_STAGE_*; attn_bwd is attn_bwd_stages with all three bits.  With DELTA and DQ
+ * together the dQ kernel forms the row statistics itself, as in attn_bwd; DELTA without DQ
+ * runs a separate kernel for them.  DKDV, and DQ without DELTA, read the statistics from the
+ * workspace, so it must hold those of an earlier call on the same problem.  Validation and
+ * errors as attn_bwd; stages == 0 or unknown bits give ATTN_ERR_SHAPE.
  */
 #define ATTN_BWD_STAGE_DELTA 1u
 #define ATTN_BWD_STAGE_DKDV 2u

@@ -473,14 +473,33 @@ attn_bwd_dq_kernel(const BwdArgs a)
         qf[ks] = as_elem8(ld_row16(a.Q + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
         gf[ks] = as_elem8(ld_row16(a.dO + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
     }
-    const float lse2 = a.delta[(int64_t)bh * 2 * S + S + qc];
-    // -delta of this lane's query, replicated: the dP accumulators start from it
-    f32x16 nd;
-    {
-        const float ndelta = a.delta[(int64_t)bh * 2 * S + qc];
+    // Row statistics of this lane's query: lse2 = LSE * log2(e) and -delta = -rowsum(dO * O).
+    // In a full backward this kernel runs first and forms them itself (the dO row is in
+    // registers anyway; lanes l and l^32 hold the two halves of a row) and stores them for the
+    // dK/dV kernel, which saves the separate kernel's launch; called alone it reads them.
+    float lse2, ndelta;
+    if (a.stats_in_dq) {
+        float acc = 0.f;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) nd[i] = ndelta;
+        for (int ks = 0; ks < KS; ++ks) {
+            const elem8 of = as_elem8(ld_row16(a.O + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
+#pragma unroll
+            for (int t = 0; t < 8; ++t) acc += (float)of[t] * (float)gf[ks][t];
+        }
+        ndelta = -xhalf_sum(acc);
+        lse2 = a.LSE[(int64_t)bh * S + qc] * kLog2e;
+        if (q < S && h == 0) {
+            a.delta[(int64_t)bh * 2 * S + q] = ndelta;
+            a.delta[(int64_t)bh * 2 * S + S + q] = lse2;
+        }
+    } else {
+        lse2 = a.delta[(int64_t)bh * 2 * S + S + qc];
+        ndelta = a.delta[(int64_t)bh * 2 * S + qc];
     }
+    // -delta replicated: the dP accumulators start from it
+    f32x16 nd;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) nd[i] = ndelta;
 
     f32x16 dq[DB];
 #pragma unroll
@@ -654,39 +673,39 @@ static int launch_dq(BwdArgs a, hipStream_t st)
 }
 
 template <int D, bool CAUSAL>
-static int launch_bwd_dc(const BwdArgs &a, hipStream_t st, unsigned stages)
+static int launch_dq_for(const BwdArgs &a, hipStream_t st)
 {
     const int blocks32 = (a.S + 31) / 32;
-    if (stages & 2u) {
-        if (launch_dkdv<D, CAUSAL>(a, st)) return -1;
-    }
-    if (stages & 4u) {
-        // 256-row work-groups unless they would leave compute units (256) idle while 128-row
-        // ones would not (few heads and rows against many keys, e.g. chunked prefill)
-        const int64_t wgs8 = (int64_t)a.BH * ((a.S + 255) / 256);
-        if (blocks32 >= 8 && wgs8 >= 256) return launch_dq<D, 8, CAUSAL>(a, st);
-        if (blocks32 >= 4) return launch_dq<D, 4, CAUSAL>(a, st);
-        if (blocks32 == 3) return launch_dq<D, 3, CAUSAL>(a, st);
-        if (blocks32 == 2 || D == 128) return launch_dq<D, 2, CAUSAL>(a, st);
-        // one wave: only D = 64 (with D = 128 a lone wave would spill while it streams tiles)
-        if constexpr (D < 128) return launch_dq<D, 1, CAUSAL>(a, st);
-        return -1;
-    }
-    return 0;
+    // 256-row work-groups unless they would leave compute units (256) idle while 128-row
+    // ones would not (few heads and rows against many keys, e.g. chunked prefill)
+    const int64_t wgs8 = (int64_t)a.BH * ((a.S + 255) / 256);
+    if (blocks32 >= 8 && wgs8 >= 256) return launch_dq<D, 8, CAUSAL>(a, st);
+    if (blocks32 >= 4) return launch_dq<D, 4, CAUSAL>(a, st);
+    if (blocks32 == 3) return launch_dq<D, 3, CAUSAL>(a, st);
+    if (blocks32 == 2 || D == 128) return launch_dq<D, 2, CAUSAL>(a, st);
+    // one wave: only D = 64 (with D = 128 a lone wave would spill while it streams tiles)
+    if constexpr (D < 128) return launch_dq<D, 1, CAUSAL>(a, st);
+    return -1;
 }
 
+// Order of a full backward: dQ (which also forms the row statistics and stores them), then
+// dK/dV (which reads them).  The separate statistics kernel runs only when they are asked for
+// without dQ.
 template <int D>
-static int launch_bwd_d(const BwdArgs &a, bool causal, hipStream_t st, unsigned stages)
+static int launch_bwd_d(BwdArgs a, bool causal, hipStream_t st, unsigned stages)
 {
-    if (stages & 1u) {
+    a.stats_in_dq = (stages & 5u) == 5u;
+    if (stages & 4u) {
+        if (causal ? launch_dq_for<D, true>(a, st) : launch_dq_for<D, false>(a, st)) return -1;
+    } else if (stages & 1u) {
         constexpr int RPB = 256 / (D / 8);
         const int64_t rows = (int64_t)a.BH * a.S;
         hipLaunchKernelGGL((attn_bwd_delta_kernel<D>), dim3((unsigned)((rows + RPB - 1) / RPB)),
                            dim3(256), 0, st, a);
         if (hipGetLastError() != hipSuccess) return -1;
     }
-    if (!(stages & 6u)) return 0;
-    return causal ? launch_bwd_dc<D, true>(a, st, stages) : launch_bwd_dc<D, false>(a, st, stages);
+    if (stages & 2u) return causal ? launch_dkdv<D, true>(a, st) : launch_dkdv<D, false>(a, st);
+    return 0;
 }
 
 #if defined(ATTN_CYCLES) && !defined(ATTN_F16)

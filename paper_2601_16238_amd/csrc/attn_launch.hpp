@@ -56,6 +56,8 @@ struct BwdArgsT {
     int Dr;             // head dimension of the tensors; columns Dr..D-1 are zeros (see FwdArgsT)
     int group;          // query heads per K/V head
     int ntile;          // tiles per head of the launched kernel (set by the launcher)
+    int stats_in_dq;    // the dQ kernel forms the row statistics itself and stores them to
+                        // `delta` for the dK/dV kernel (set by the launcher)
     float scale, scale_log2e;
 };
 
@@ -69,7 +71,8 @@ int launch_fwd(const FwdArgsT<_Float16> &a, int D, bool causal, hipStream_t st);
 // Number of key splits the forward would use for this problem (1: none), and the keys per
 // split; a pure host function of the shape.
 int fwd_split_plan(int BH, int S, int Sk, int D, int *kps);
-// `stages`: bit 0 delta, bit 1 dK/dV, bit 2 dQ.
+// `stages`: bit 0 row statistics, bit 1 dK/dV, bit 2 dQ.  With bits 0 and 2 the dQ kernel
+// forms the statistics (and runs first); bit 0 without bit 2 runs the separate kernel.
 int launch_bwd(const BwdArgsT<__bf16> &a, int D, bool causal, hipStream_t st, unsigned stages);
 int launch_bwd(const BwdArgsT<_Float16> &a, int D, bool causal, hipStream_t st, unsigned stages);
 

@@ -137,3 +137,37 @@ def test_work_group_order_covers_every_head_and_tile(B, H, S, D, causal):
     check_lse(to_f64(LSE), Lref)
     for nm, t, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), gref):
         check_bf16(nm, to_f64(t), r)
+
+
+@pytest.mark.parametrize("B,H,S,D,causal", [(2, 3, 333, 128, True), (1, 8, 96, 64, False)])
+def test_stage_wise_backward_equals_the_full_call(B, H, S, D, causal):
+    """attn_bwd forms the row statistics inside the dQ kernel; called stage by stage (separate
+    statistics kernel, then dK/dV and dQ reading them from the workspace) the gradients must be
+    the same.  The statistics of the two paths may differ in the last bit (other summation
+    order), so dK/dV of the stage-wise path are compared within one bf16 ulp; dQ from the
+    separately computed statistics likewise."""
+    from paper_2601_16238_amd import binding
+    print("case stage_wise", B, H, S, D, causal, flush=True)
+    x = wl.random_inputs(B, H, S, D, seed=1300 + S)
+    Q, K, V, dO = (to_dev(x[k]) for k in ("Q", "K", "V", "dO"))
+    O, LSE = attn.attn_fwd(Q, K, V, x["scale"], causal)
+    ws = torch.empty(attn.attn_bwd_workspace_bytes(B, H, S, D), dtype=torch.uint8, device="cuda")
+    full = attn.attn_bwd(Q, K, V, O, dO, LSE, x["scale"], causal, workspace=ws)
+    torch.cuda.synchronize()
+    stats_full = ws.clone()
+    outs = [torch.full_like(Q, float("nan")) for _ in range(3)]
+    ws.fill_(0x7F)
+    for st in (binding.STAGE_DELTA, binding.STAGE_DKDV, binding.STAGE_DQ):
+        attn.attn_bwd(Q, K, V, O, dO, LSE, x["scale"], causal, dQ=outs[0], dK=outs[1], dV=outs[2],
+                      workspace=ws, stages=st)
+    torch.cuda.synchronize()
+    a, b = stats_full.view(torch.float32), ws.view(torch.float32)
+    n = B * H * 2 * S
+    assert torch.allclose(a[:n], b[:n], rtol=1e-5, atol=1e-5)
+    for nm, f, s in zip(("dQ", "dK", "dV"), full, outs):
+        d = (f.double() - s.double()).abs()
+        tol = 2.0 ** -7 * torch.maximum(f.double().abs(), torch.tensor(2.0 ** -6, device="cuda", dtype=torch.float64))
+        assert bool((d <= tol).all()), (nm, d.max().item())
+    gref = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], causal)
+    for nm, t, r in zip(("dQ", "dK", "dV"), outs, gref):
+        check_bf16(nm, to_f64(t), r)
