@@ -369,9 +369,10 @@ def _rect_params_for(q, k, scale, causal):
                             q.stride()[:3], k.stride()[:3])
 
 
-def attn_fwd_rect_workspace_bytes(B, Hq, Hkv, Sq, Sk, D):
-    """Bytes attn_fwd_rect needs to split this problem over the keys (0: it would not split)."""
-    p = make_rect_params(B, Hq, Hkv, Sq, Sk, D, 1.0, False)
+def attn_fwd_rect_workspace_bytes(B, Hq, Hkv, Sq, Sk, D, causal=False):
+    """Bytes attn_fwd_rect needs to split this problem over the keys (0: it would not split).
+    The plan may use fewer splits under a causal mask, never more."""
+    p = make_rect_params(B, Hq, Hkv, Sq, Sk, D, 1.0, causal)
     return int(lib().attn_fwd_rect_workspace_bytes(ctypes.byref(p)))
 
 

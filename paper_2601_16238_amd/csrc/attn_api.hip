@@ -117,7 +117,7 @@ static int fwd_impl(const void *Q, const void *K, const void *V, void *O, float 
     // No workspace at all: run unsplit.  A workspace that is there must be usable.
     const FwdView v = fwd_view(*p);
     int kps = 0;
-    int nsplit = workspace ? attn::fwd_split_plan(v.BH, v.S, p->Sk, kernel_d(p->D), &kps) : 1;
+    int nsplit = workspace ? attn::fwd_split_plan(v.BH, v.S, p->Sk, kernel_d(p->D), v.causal, &kps) : 1;
     if (workspace && (!aligned(workspace, kWsAlign) ||
                       workspace_bytes < attn_fwd_rect_workspace_bytes(p)))
         return ATTN_ERR_WORKSPACE;
@@ -225,7 +225,7 @@ size_t attn_fwd_rect_workspace_bytes(const attn_rect_params_t *p)
 {
     if (check_params(p) != ATTN_OK) return 0;
     const FwdView v = fwd_view(*p);
-    const int nsplit = attn::fwd_split_plan(v.BH, v.S, p->Sk, kernel_d(p->D), nullptr);
+    const int nsplit = attn::fwd_split_plan(v.BH, v.S, p->Sk, kernel_d(p->D), v.causal, nullptr);
     if (nsplit <= 1) return 0;
     const size_t rows = (size_t)p->B * p->Hq * p->Sq;
     return round_ws((size_t)nsplit * rows * (kernel_d(p->D) + 1) * sizeof(float));

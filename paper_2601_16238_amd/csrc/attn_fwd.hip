@@ -489,9 +489,14 @@ static int launch_fwd_nw(const FwdArgs &a, bool causal, hipStream_t st)
 // With D = 128 at least 4: fewer waves could not hold their share of a V tile in registers
 // while staging it (waves whose rows lie past the end compute and store nothing useful, but
 // still take part in the staging).
-static int fwd_waves_for(int S, int D)
+static int fwd_waves_for(int S, int D, int BH, bool causal)
 {
     const int blocks32 = (S + 31) / 32;
+    // D = 64 under a causal mask with fewer than four 256-row work-groups per compute unit:
+    // 128-row work-groups (three fit a compute unit at D = 64) balance the unequal tiles
+    // better.  Measured: B=8 H=8 S=1024 26.5 -> 24.3 us, B=16 H=16 S=512 29.5 -> 27.6 us; not
+    // so without a mask (+5 %), at D = 128 (+4..33 % on mid-size shapes) or on large problems.
+    if (blocks32 >= 8 && D == 64 && causal && (int64_t)BH * ((S + 255) / 256) < 1024) return 4;
     if (blocks32 >= 8) return 8;
     if (blocks32 >= 4 || D == 128) return 4;
     return blocks32;  // 1, 2 or 3
@@ -500,7 +505,7 @@ static int fwd_waves_for(int S, int D)
 template <int D>
 static int launch_fwd_d(FwdArgs a, bool causal, hipStream_t st)
 {
-    const int nw = fwd_waves_for(a.S, D);
+    const int nw = fwd_waves_for(a.S, D, a.BH, causal);
     a.nqt = (a.S + nw * 32 - 1) / (nw * 32);
     if (nw == 8) return launch_fwd_nw<D, 8>(a, causal, st);
     if (nw == 4) return launch_fwd_nw<D, 4>(a, causal, st);
@@ -527,9 +532,9 @@ extern "C" void attn_debug_cycles_fwd(unsigned long long *out, int reset)
 // prologues.)  Every split keeps at least four 64-key tiles (the merge reads and writes one
 // fp32 partial result per split and row).
 #ifndef ATTN_F16  // a function of the shape only: defined once, by the bf16 build
-int fwd_split_plan(int BH, int S, int Sk, int D, int *kps)
+int fwd_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps)
 {
-    const int nw = fwd_waves_for(S, D);
+    const int nw = fwd_waves_for(S, D, BH, causal);
     const int64_t wgs = (int64_t)BH * ((S + nw * 32 - 1) / (nw * 32));
     const int64_t target = 256;
     const int tiles = (Sk + 63) / 64;

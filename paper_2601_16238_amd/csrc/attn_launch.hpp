@@ -70,7 +70,7 @@ int launch_fwd(const FwdArgsT<__bf16> &a, int D, bool causal, hipStream_t st);
 int launch_fwd(const FwdArgsT<_Float16> &a, int D, bool causal, hipStream_t st);
 // Number of key splits the forward would use for this problem (1: none), and the keys per
 // split; a pure host function of the shape.
-int fwd_split_plan(int BH, int S, int Sk, int D, int *kps);
+int fwd_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps);
 // `stages`: bit 0 row statistics, bit 1 dK/dV, bit 2 dQ.  With bits 0 and 2 the dQ kernel
 // forms the statistics (and runs first); bit 0 without bit 2 runs the separate kernel.
 int launch_bwd(const BwdArgsT<__bf16> &a, int D, bool causal, hipStream_t st, unsigned stages);
