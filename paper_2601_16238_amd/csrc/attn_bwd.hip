@@ -677,9 +677,15 @@ static int launch_dq_for(const BwdArgs &a, hipStream_t st)
 {
     const int blocks32 = (a.S + 31) / 32;
     // 256-row work-groups unless they would leave compute units (256) idle while 128-row
-    // ones would not (few heads and rows against many keys, e.g. chunked prefill)
+    // ones would not (few heads and rows against many keys, e.g. chunked prefill).  Under a
+    // causal mask 128-row work-groups also balance the unequal tiles better as long as the
+    // launch is small: at D = 128 (one work-group per compute unit either way) up to one
+    // 256-row work-group per unit (B=1 H=16 S=4096: 135 -> 117 us, B=1 H=8 S=8192: 256 -> 220 us;
+    // with 1.25 per unit already 15 % slower), at D = 64 (two fit a unit) up to four
+    // (B=8 H=8 S=1024: 28.9 -> 26.6 us, B=4 H=8 S=2048: 45.4 -> 42.0 us).
     const int64_t wgs8 = (int64_t)a.BH * ((a.S + 255) / 256);
-    if (blocks32 >= 8 && wgs8 >= 256) return launch_dq<D, 8, CAUSAL>(a, st);
+    const bool prefer4 = CAUSAL && (D == 64 ? wgs8 < 1024 : wgs8 <= 256);
+    if (blocks32 >= 8 && wgs8 >= 256 && !prefer4) return launch_dq<D, 8, CAUSAL>(a, st);
     if (blocks32 >= 4) return launch_dq<D, 4, CAUSAL>(a, st);
     if (blocks32 == 3) return launch_dq<D, 3, CAUSAL>(a, st);
     if (blocks32 == 2 || D == 128) return launch_dq<D, 2, CAUSAL>(a, st);
