@@ -116,6 +116,16 @@ layernorm_fwd_kernel(const __bf16 *x, const float *w, const float *b, __bf16 *y,
     const int64_t i = blockIdx.x;
     float xv[V][8];
     load_row<V>(x + i * xs, cols, xv);
+    // the parameters are requested now, so that their latency overlaps the two reductions
+    float wv[V][8], bv[V][8];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int c = (threadIdx.x + v * kThreads) * 8;
+        if (c < cols) {
+            load8f(w + c, wv[v]);
+            load8f(b + c, bv[v]);
+        }
+    }
     float s[1] = {0.f};
 #pragma unroll
     for (int v = 0; v < V; ++v)
@@ -145,11 +155,9 @@ layernorm_fwd_kernel(const __bf16 *x, const float *w, const float *b, __bf16 *y,
     for (int v = 0; v < V; ++v) {
         const int c = (threadIdx.x + v * kThreads) * 8;
         if (c < cols) {
-            float wv[8], bv[8], o[8];
-            load8f(w + c, wv);
-            load8f(b + c, bv);
+            float o[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = xv[v][e] * r * wv[e] + bv[e];
+            for (int e = 0; e < 8; ++e) o[e] = xv[v][e] * r * wv[v][e] + bv[v][e];
             store8(y + i * ys + c, o);
         }
     }
@@ -173,11 +181,38 @@ layernorm_bwd_rows_kernel(const __bf16 *dy, const __bf16 *x, const float *w, con
 #pragma unroll
         for (int e = 0; e < 8; ++e) { dwp[v][e] = 0.f; dbp[v][e] = 0.f; }
     }
+    // The work-group walks its rows one after the other, so the next row is fetched (as raw
+    // 16-byte vectors) before the current one is worked on: its HBM latency then overlaps the
+    // arithmetic, the two block reductions and the stores of the current row.
+    u32x4 nx[V], ng[V];
+    float nmu = 0.f, nr = 0.f;
+    auto fetch = [&](int64_t i) __attribute__((always_inline)) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const int c = (threadIdx.x + v * kThreads) * 8;
+            if (c < cols) {
+                nx[v] = *(const u32x4 *)(x + i * xs + c);
+                ng[v] = *(const u32x4 *)(dy + i * dys + c);
+            }
+        }
+        nmu = mean[i];
+        nr = rstd[i];
+    };
+    if ((int64_t)blockIdx.x < rows) fetch(blockIdx.x);
     for (int64_t i = blockIdx.x; i < rows; i += gridDim.x) {
         float xv[V][8], gv[V][8];
-        load_row<V>(x + i * xs, cols, xv);
-        load_row<V>(dy + i * dys, cols, gv);
-        const float mu = mean[i], r = rstd[i];
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const int c = (threadIdx.x + v * kThreads) * 8;
+            const bf16x8 bx = __builtin_bit_cast(bf16x8, nx[v]), bg = __builtin_bit_cast(bf16x8, ng[v]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                xv[v][e] = c < cols ? (float)bx[e] : 0.f;
+                gv[v][e] = c < cols ? (float)bg[e] : 0.f;
+            }
+        }
+        const float mu = nmu, r = nr;
+        if (i + gridDim.x < rows) fetch(i + gridDim.x);
         float s[2] = {0.f, 0.f};  // sum g, sum g*xhat with g = dy*w
 #pragma unroll
         for (int v = 0; v < V; ++v) {
