@@ -138,6 +138,11 @@ def measure(torch, attn, wl, w, steps, warmup):
         "gbs_fwd": b_fwd / (ms["fwd"] * 1e-3) / 1e9,
         "gbs_bwd": b_bwd / (ms["bwd"] * 1e-3) / 1e9,
     }
+    if "fwd_graph_replay" in ms:   # small shapes: the device-time figures
+        res["gbs_fwd_graph_replay"] = b_fwd / (ms["fwd_graph_replay"] * 1e-3) / 1e9
+        res["gbs_bwd_graph_replay"] = b_bwd / (ms["bwd_graph_replay"] * 1e-3) / 1e9
+        res["tflops_fwdbwd_graph_replay"] = (f_fwd + f_bwd) / (
+            (ms["fwd_graph_replay"] + ms["bwd_graph_replay"]) * 1e-3) / 1e12
     # Algorithmic FLOPs per launch of each MFMA kernel (GEMM = 2*N_s*D flops, N_s = S^2 or
     # S^2/2): forward 2 GEMMs; dK/dV kernel 4 (S, dP, dV, dK); dQ kernel 1 (dQ -- its
     # recomputed S and dP are overhead, not algorithmic work).
@@ -485,6 +490,9 @@ def main():
                             "frac_fwd": o["tflops_fwd"] / PEAK_BF16_TFLOPS,
                             "frac_fwdbwd": o["tflops_fwdbwd"] / PEAK_BF16_TFLOPS,
                             "gbs_fwd": o["gbs_fwd"], "gbs_bwd": o["gbs_bwd"]}
+            for k in ("gbs_fwd_graph_replay", "gbs_bwd_graph_replay", "tflops_fwdbwd_graph_replay"):
+                if k in o:
+                    others[name][k] = o[k]
             if per_tensor_bytes(ow) <= (16 << 20) and not hasattr(ow, "Hq"):
                 others[name]["cold"] = measure_cold(torch, attn, wl, ow, max(5, a.steps // 2))
             torch.cuda.empty_cache()
