@@ -33,7 +33,7 @@ def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="long_causal",
                     help="one of paper_2601_16238_amd.workloads.WORKLOADS, GQA_WORKLOADS or RECT_WORKLOADS, "
                          "or 'rowops' (the row-wise kernels)")
