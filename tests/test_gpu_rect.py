@@ -163,3 +163,17 @@ def test_rect_full_size_sampled_heads():
                 check_bf16("dQ", to_f64(dQ[b, qs]), ref[0][0], floor_gate=False)
                 check_bf16("dK", to_f64(dK[b, hk]), ref[1][0, 0], floor_gate=False)
                 check_bf16("dV", to_f64(dV[b, hk]), ref[2][0, 0], floor_gate=False)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D,causal", [
+    (8, 32, 32, 300, 300, 128, True),     # 256 heads x 2 key blocks of 192: ragged second block
+    (4, 64, 64, 200, 450, 96, True),      # rectangular, head dimension below the kernel's 128
+    (16, 64, 16, 130, 385, 128, False),   # grouped heads: 256 K/V heads x 3 blocks, group loop
+    (2, 128, 128, 64, 1000, 72, True),    # few rows against many keys
+])
+def test_backward_with_192_key_work_groups(B, Hq, Hkv, Sq, Sk, D, causal):
+    """At D > 64 launches of at least 512 dK/dV work-groups use work-groups of six producer and
+    six consumer waves that own 192 keys; these shapes reach that path with ragged last blocks,
+    padded head dimensions, grouped heads and rectangular problems."""
+    assert (B * Hkv) * ((Sk + 191) // 192) >= 512
+    test_rect_parity(B, Hq, Hkv, Sq, Sk, D, causal)
