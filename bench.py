@@ -23,9 +23,9 @@ CALIB_COPY_BYTES = 256 * 1024 * 1024   # --calib-copy reads this many bytes and 
 # rocprofv3 --pmc passes summarised in profiles/ (None until measured for a workload).
 MEASURED_TRAFFIC_BYTES = {
     # profiles/long_causal_hbm_traffic_pmc.txt: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (KiB)
-    ("long_causal", "attn_bwd_dkdv_kernel"): int((356991.0 * 2.0 + 131072.0) * 1024),
-    ("long_causal", "attn_fwd_kernel"): int((227867.6 * 2.0 + 66588.5) * 1024),
-    ("long_causal", "attn_bwd_dq_kernel"): int((324138.4 * 2.0 + 66901.3) * 1024),
+    ("long_causal", "attn_bwd_dkdv_kernel"): int((280343.5 * 2.0 + 131130.7) * 1024),
+    ("long_causal", "attn_fwd_kernel"): int((225755.4 * 2.0 + 66585.0) * 1024),
+    ("long_causal", "attn_bwd_dq_kernel"): int((316631.2 * 2.0 + 66901.3) * 1024),
 }
 
 
