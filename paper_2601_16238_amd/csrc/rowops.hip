@@ -17,7 +17,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kThreads = 256;          // one work-group per row
 constexpr int kWaves = kThreads / 64;
 constexpr int kMaxCols = 16384;        // 8 vectors of 8 elements per thread
-constexpr int kBwdGroups = 512;        // work-groups of the LayerNorm backward (two per unit)
+constexpr int kBwdTeams = 512;         // rows above which the LayerNorm backward pairs teams at V = 4
 
 __device__ __forceinline__ bf16x8 load8(const __bf16 *p)
 {
@@ -80,20 +80,20 @@ __device__ __forceinline__ void load_row(const __bf16 *row, int cols, float (&x)
 
 // Raw 16-byte vectors of a row, fetched one row ahead by the kernels that walk several rows.
 template <int V>
-__device__ __forceinline__ void fetch_row(const __bf16 *row, int cols, u32x4 (&raw)[V])
+__device__ __forceinline__ void fetch_row(const __bf16 *row, int cols, u32x4 (&raw)[V], int t)
 {
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-        const int c = (threadIdx.x + v * kThreads) * 8;
+        const int c = (t + v * kThreads) * 8;
         if (c < cols) raw[v] = *(const u32x4 *)(row + c);
     }
 }
 template <int V>
-__device__ __forceinline__ void unpack_row(const u32x4 (&raw)[V], int cols, float (&x)[V][8])
+__device__ __forceinline__ void unpack_row(const u32x4 (&raw)[V], int cols, float (&x)[V][8], int t)
 {
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-        const int c = (threadIdx.x + v * kThreads) * 8;
+        const int c = (t + v * kThreads) * 8;
         const bf16x8 b = __builtin_bit_cast(bf16x8, raw[v]);
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[v][e] = c < cols ? (float)b[e] : 0.f;
@@ -116,11 +116,11 @@ rmsnorm_fwd_kernel(const __bf16 *x, const float *w, __bf16 *y, int64_t rows, int
         if (c < cols) load8f(w + c, wv[v]);
     }
     u32x4 nx[V];
-    if ((int64_t)blockIdx.x < rows) fetch_row<V>(x + blockIdx.x * xs, cols, nx);
+    if ((int64_t)blockIdx.x < rows) fetch_row<V>(x + blockIdx.x * xs, cols, nx, threadIdx.x);
     for (int64_t i = blockIdx.x; i < rows; i += gridDim.x) {
         float xv[V][8];
-        unpack_row<V>(nx, cols, xv);
-        if (i + gridDim.x < rows) fetch_row<V>(x + (i + gridDim.x) * xs, cols, nx);
+        unpack_row<V>(nx, cols, xv, threadIdx.x);
+        if (i + gridDim.x < rows) fetch_row<V>(x + (i + gridDim.x) * xs, cols, nx, threadIdx.x);
         float ss[1] = {0.f};
 #pragma unroll
         for (int v = 0; v < V; ++v)
@@ -157,11 +157,11 @@ layernorm_fwd_kernel(const __bf16 *x, const float *w, const float *b, __bf16 *y,
         }
     }
     u32x4 nx[V];
-    if ((int64_t)blockIdx.x < rows) fetch_row<V>(x + blockIdx.x * xs, cols, nx);
+    if ((int64_t)blockIdx.x < rows) fetch_row<V>(x + blockIdx.x * xs, cols, nx, threadIdx.x);
     for (int64_t i = blockIdx.x; i < rows; i += gridDim.x) {
         float xv[V][8];
-        unpack_row<V>(nx, cols, xv);
-        if (i + gridDim.x < rows) fetch_row<V>(x + (i + gridDim.x) * xs, cols, nx);
+        unpack_row<V>(nx, cols, xv, threadIdx.x);
+        if (i + gridDim.x < rows) fetch_row<V>(x + (i + gridDim.x) * xs, cols, nx, threadIdx.x);
         float s[1] = {0.f};
 #pragma unroll
         for (int v = 0; v < V; ++v)
@@ -200,74 +200,139 @@ layernorm_fwd_kernel(const __bf16 *x, const float *w, const float *b, __bf16 *y,
     }
 }
 
-// Backward, rows i = group, group + G, ...: dx of each row, and the work-group's partial column
-// sums of dw and db, kept in registers across its rows and written once: part[g][0][cols] = dw,
-// part[g][1][cols] = db.
-template <int V>
-__global__ void __launch_bounds__(kThreads)
+// Backward.  A work-group is T teams of kThreads threads; each team takes one row at a time
+// (round j of the work-group covers rows (j * G + group) * T + team) and computes its dx.  The
+// column sums of dw and db stay in registers across a team's rows; at the end the teams add
+// theirs together through LDS, in team order, and the work-group writes one partial row:
+// part[g][0][cols] = dw, part[g][1][cols] = db.  More teams per work-group mean fewer partial
+// rows to write here and to read in the column kernel, at the same number of waves per unit.
+template <int V, int T>
+__global__ void __launch_bounds__(kThreads * T)
 layernorm_bwd_rows_kernel(const __bf16 *dy, const __bf16 *x, const float *w, const float *mean,
                           const float *rstd, __bf16 *dx, float *part, int64_t rows, int cols,
                           int64_t dys, int64_t xs, int64_t dxs)
 {
-    __shared__ float red[kWaves * 2];
+    __shared__ float red[T * kWaves * 2];
+    __shared__ float comb[T > 1 ? 16 * kThreads : 1];
+    const int t = threadIdx.x % kThreads, team = threadIdx.x / kThreads;
     float wv[V][8], dwp[V][8], dbp[V][8];
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-        const int c = (threadIdx.x + v * kThreads) * 8;
+        const int c = (t + v * kThreads) * 8;
         if (c < cols) load8f(w + c, wv[v]);
 #pragma unroll
         for (int e = 0; e < 8; ++e) { dwp[v][e] = 0.f; dbp[v][e] = 0.f; }
     }
-    // The work-group walks its rows one after the other, so the next row is fetched (as raw
-    // 16-byte vectors) before the current one is worked on: its HBM latency then overlaps the
-    // arithmetic, the two block reductions and the stores of the current row.
-    u32x4 nx[V], ng[V];
+    // A team walks its rows one after the other, so the next row is fetched (as raw 16-byte
+    // vectors) before the current one is worked on: its HBM latency then overlaps the
+    // arithmetic, the two reductions and the stores of the current row.
+    u32x4 nx[V] = {}, ng[V] = {};
     float nmu = 0.f, nr = 0.f;
+    // (vectors past the row's end re-read its first one, so that every thread issues the same
+    // loads and the wait for them can be counted; unpack_row zeroes those vectors)
     auto fetch = [&](int64_t i) __attribute__((always_inline)) {
-        fetch_row<V>(x + i * xs, cols, nx);
-        fetch_row<V>(dy + i * dys, cols, ng);
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const int c = (t + v * kThreads) * 8;
+            nx[v] = *(const u32x4 *)(x + i * xs + (c < cols ? c : 0));
+            ng[v] = *(const u32x4 *)(dy + i * dys + (c < cols ? c : 0));
+        }
         nmu = mean[i];
         nr = rstd[i];
     };
-    if ((int64_t)blockIdx.x < rows) fetch(blockIdx.x);
-    for (int64_t i = blockIdx.x; i < rows; i += gridDim.x) {
+    const int64_t step = (int64_t)gridDim.x * T;
+    if ((int64_t)blockIdx.x * T + team < rows) fetch((int64_t)blockIdx.x * T + team);
+    // `base` is the same for every thread of the work-group, so all of them reach the barriers
+    // of every round; a team whose row lies past the end contributes zeros and stores nothing.
+    for (int64_t base = (int64_t)blockIdx.x * T; base < rows; base += step) {
+        const int64_t i = base + team;
+        const bool live = i < rows;
         float xv[V][8], gv[V][8];
-        unpack_row<V>(nx, cols, xv);
-        unpack_row<V>(ng, cols, gv);
-        const float mu = nmu, r = nr;
-        if (i + gridDim.x < rows) fetch(i + gridDim.x);
         float s[2] = {0.f, 0.f};  // sum g, sum g*xhat with g = dy*w
+        // (the fetch stands outside the `live` branch so that its registers are not merged
+        // with another path at the branch's end, which would make the wave wait for them there)
+        unpack_row<V>(nx, cols, xv, t);
+        unpack_row<V>(ng, cols, gv, t);
+        const float mu = nmu, r = nr;
+        // the row is unpacked here, before the raw registers are loaded again
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-            const int c = (threadIdx.x + v * kThreads) * 8;
-            if (c < cols)
+        for (int v = 0; v < V; ++v)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    xv[v][e] = (xv[v][e] - mu) * r;  // xhat
-                    dwp[v][e] += gv[v][e] * xv[v][e];
-                    dbp[v][e] += gv[v][e];
-                    gv[v][e] *= wv[v][e];            // g
-                    s[0] += gv[v][e];
-                    s[1] += gv[v][e] * xv[v][e];
-                }
+            for (int e = 0; e < 8; ++e) asm volatile("" : "+v"(xv[v][e]), "+v"(gv[v][e]));
+        if (i + step < rows) fetch(i + step);
+        if (live) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const int c = (t + v * kThreads) * 8;
+                if (c < cols)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        xv[v][e] = (xv[v][e] - mu) * r;  // xhat
+                        dwp[v][e] += gv[v][e] * xv[v][e];
+                        dbp[v][e] += gv[v][e];
+                        gv[v][e] *= wv[v][e];            // g
+                        s[0] += gv[v][e];
+                        s[1] += gv[v][e] * xv[v][e];
+                    }
+            }
         }
-        block_sum<2>(s, red);
-        const float mg = s[0] / (float)cols, mgx = s[1] / (float)cols;
+        // sums over the team
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-            const int c = (threadIdx.x + v * kThreads) * 8;
-            if (c < cols) {
-                float o[8];
+        for (int n = 0; n < 2; ++n)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) o[e] = r * (gv[v][e] - mg - xv[v][e] * mgx);
-                store8(dx + i * dxs + c, o);
+            for (int m = 32; m >= 1; m >>= 1) s[n] += __shfl_xor(s[n], m);
+        if ((threadIdx.x & 63) == 0) {
+            red[(threadIdx.x >> 6) * 2 + 0] = s[0];
+            red[(threadIdx.x >> 6) * 2 + 1] = s[1];
+        }
+        __syncthreads();
+        s[0] = s[1] = 0.f;
+#pragma unroll
+        for (int k = 0; k < kWaves; ++k) {
+            s[0] += red[(team * kWaves + k) * 2 + 0];
+            s[1] += red[(team * kWaves + k) * 2 + 1];
+        }
+        __syncthreads();
+        if (live) {
+            const float mg = s[0] / (float)cols, mgx = s[1] / (float)cols;
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const int c = (t + v * kThreads) * 8;
+                if (c < cols) {
+                    float o[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] = r * (gv[v][e] - mg - xv[v][e] * mgx);
+                    store8(dx + i * dxs + c, o);
+                }
             }
         }
     }
+    // teams 1 .. T-1 hand their column sums to team 0, one vector slot at a time
+    if (T > 1) {
+#pragma unroll
+        for (int v = 0; v < V; ++v)
+            for (int k = 1; k < T; ++k) {
+                if (team == k)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        comb[e * kThreads + t] = dwp[v][e];
+                        comb[(8 + e) * kThreads + t] = dbp[v][e];
+                    }
+                __syncthreads();
+                if (team == 0)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        dwp[v][e] += comb[e * kThreads + t];
+                        dbp[v][e] += comb[(8 + e) * kThreads + t];
+                    }
+                __syncthreads();
+            }
+    }
+    if (team != 0) return;
     float *pw = part + (int64_t)blockIdx.x * 2 * cols, *pb = pw + cols;
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-        const int c = (threadIdx.x + v * kThreads) * 8;
+        const int c = (t + v * kThreads) * 8;
         if (c < cols)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
@@ -344,7 +409,20 @@ int check_rows(int64_t rows, int32_t cols, std::initializer_list<int64_t> stride
     return ATTN_OK;
 }
 
-int bwd_groups(int64_t rows) { return (int)(rows < kBwdGroups ? rows : kBwdGroups); }
+// LayerNorm backward: row teams per work-group, and work-groups.  The launch is one round of
+// resident work-groups.  At V = 4 the kernel's registers allow one 256-thread work-group per
+// unit or one 512-thread one, so two teams share a work-group there (on (4096, 8192): 40.5 us
+// against 44.4 us, with half the partial rows).  Work-groups per unit otherwise, measured on
+// (16384, 1024), (8192, 4096), (2048, 16384): V = 1: 4 (38.3 us; 44.8 with 2, 39.1 with 3),
+// V = 2: 2 (41.4 us; 44.7 with 3), V = 8: 1 (50.3 us; 63.4 with 2).
+int bwd_teams(int64_t rows, int V) { return rows > kBwdTeams && V == 4 ? 2 : 1; }
+int bwd_groups(int64_t rows, int V)
+{
+    const int T = bwd_teams(rows, V);
+    const int per_cu = V == 1 ? 4 : V == 8 ? 1 : 2 / T;
+    const int64_t g = (rows + T - 1) / T, cap = 256 * per_cu;
+    return (int)(g < cap ? g : cap);
+}
 // Work-groups of the forward kernels: as many as are resident at once on the 256 compute units
 // for the kernel's register use at V vectors per thread (8 waves per SIMD at most), so that
 // the launch is a single round.  Measured on (4096, 8192): LayerNorm 28.1 us with one
@@ -413,7 +491,7 @@ int rowops_layernorm_fwd(const void *x, const float *w, const float *b, void *y,
 size_t rowops_layernorm_bwd_workspace_bytes(int64_t rows, int32_t cols)
 {
     if (check_rows(rows, cols, {}) != ATTN_OK) return 0;
-    const size_t bytes = (size_t)bwd_groups(rows) * 2 * cols * sizeof(float);
+    const size_t bytes = (size_t)bwd_groups(rows, vectors_for(cols)) * 2 * cols * sizeof(float);
     return (bytes + 255) / 256 * 256;
 }
 
@@ -433,13 +511,20 @@ int rowops_layernorm_bwd(const void *dy, const void *x, const float *w, const fl
         workspace_bytes < rowops_layernorm_bwd_workspace_bytes(rows, cols))
         return ATTN_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const int groups = bwd_groups(rows);
+    const int V = vectors_for(cols), groups = bwd_groups(rows, V);
     float *part = static_cast<float *>(workspace);
-    ROWOPS_DISPATCH(vectors_for(cols),
-        hipLaunchKernelGGL((layernorm_bwd_rows_kernel<kV>), dim3(groups), dim3(kThreads), 0, st,
-                           static_cast<const __bf16 *>(dy), static_cast<const __bf16 *>(x), w, mean,
-                           rstd, static_cast<__bf16 *>(dx), part, rows, cols, dy_row_stride,
-                           x_row_stride, dx_row_stride));
+#define ROWOPS_LN_BWD(T)                                                                          \
+    hipLaunchKernelGGL((layernorm_bwd_rows_kernel<kV, T>), dim3(groups), dim3(kThreads * T), 0,   \
+                       st, static_cast<const __bf16 *>(dy), static_cast<const __bf16 *>(x), w,    \
+                       mean, rstd, static_cast<__bf16 *>(dx), part, rows, cols, dy_row_stride,    \
+                       x_row_stride, dx_row_stride)
+    if (bwd_teams(rows, V) == 2) {
+        constexpr int kV = 4;
+        ROWOPS_LN_BWD(2);
+    } else {
+        ROWOPS_DISPATCH(V, ROWOPS_LN_BWD(1));
+    }
+#undef ROWOPS_LN_BWD
     if (hipGetLastError() != hipSuccess) return ATTN_ERR_LAUNCH;
     // 2 * cols floats per group, 32 per work-group
     hipLaunchKernelGGL(layernorm_bwd_cols_kernel, dim3((2 * cols + 31) / 32), dim3(256), 0, st,

@@ -34,6 +34,9 @@ def close_bf16(name, got, ref):
 # rows x cols: the paper's benchmark width, ragged widths for every vectors-per-thread variant
 # (1, 2, 4, 8), a single row, the maximum width
 SHAPES = [(64, 8192), (5, 8), (3, 264), (7, 2048), (4, 2056), (9, 4096), (2, 5000), (3, 16384), (1, 1024), (1030, 512)]
+# more than 512 rows: the LayerNorm backward pairs two rows per work-group (odd counts leave the last
+# pair half empty; 16384 columns keep one row per work-group)
+LN_SHAPES = SHAPES + [(1027, 2056), (513, 4104), (1539, 8192), (515, 16384)]
 
 
 @pytest.mark.parametrize("rows,cols", SHAPES)
@@ -45,7 +48,7 @@ def test_rmsnorm_fwd(rows, cols):
     close_bf16("y", to_f64(y), ro.rmsnorm_fwd(x, w, 1e-6))
 
 
-@pytest.mark.parametrize("rows,cols", SHAPES)
+@pytest.mark.parametrize("rows,cols", LN_SHAPES)
 def test_layernorm_fwd_bwd(rows, cols):
     print("case layernorm", rows, cols, flush=True)
     x, dy, w, b = inputs(rows, cols, 2100 + cols, sigma=2.0)
