@@ -14,7 +14,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;          // one work-group per row
+constexpr int kThreads = 256;          // threads that share one row
 constexpr int kWaves = kThreads / 64;
 constexpr int kMaxCols = 16384;        // 8 vectors of 8 elements per thread
 constexpr int kBwdTeams = 512;         // rows above which the LayerNorm backward pairs teams at V = 4
