@@ -69,9 +69,10 @@ def test_layernorm_fwd_bwd(rows, cols):
     np.testing.assert_allclose(to_f64(db), dbr, rtol=0, atol=tol)
 
 
-def test_layernorm_bwd_is_deterministic_and_handles_strided_rows():
-    rows, cols, pitch = 600, 1024, 1032
-    print("case layernorm_strided", flush=True)
+# one row team per work-group, and two (more than 512 rows of 8192 columns)
+@pytest.mark.parametrize("rows,cols,pitch", [(600, 1024, 1032), (1301, 8192, 8200)])
+def test_layernorm_bwd_is_deterministic_and_handles_strided_rows(rows, cols, pitch):
+    print("case layernorm_strided", rows, cols, pitch, flush=True)
     x, dy, w, b = inputs(rows, cols, 2201)
     wd, bd = torch.from_numpy(w).cuda(), torch.from_numpy(b).cuda()
 
