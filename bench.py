@@ -26,6 +26,11 @@ MEASURED_TRAFFIC_BYTES = {
     ("long_causal", "attn_bwd_dkdv_kernel"): int((280343.5 * 2.0 + 131130.7) * 1024),
     ("long_causal", "attn_fwd_kernel"): int((225755.4 * 2.0 + 66585.0) * 1024),
     ("long_causal", "attn_bwd_dq_kernel"): int((316631.2 * 2.0 + 66901.3) * 1024),
+    # profiles/rowops_hbm_traffic_pmc.txt (for the backward: rows kernel + column kernel)
+    ("rowops", "rmsnorm_fwd"): int((32927.1 * 2.0 + 65536.0) * 1024),
+    ("rowops", "layernorm_fwd"): int((33062.6 * 2.0 + 65792.4) * 1024),
+    ("rowops", "layernorm_bwd"): int(((65853.2 + 8210.1) * 2.0 + 81920.0 + 64.0) * 1024),
+    ("rowops", "rotary_fwd"): int((8741.5 * 2.0 + 16384.0) * 1024),
 }
 
 
@@ -376,7 +381,8 @@ def rowops_main(torch, a):
         "config": {"workload": "rowops: norms (4096, 8192), rotary (4, 8, 2048, 128), the paper's table shapes"},
         "kernels": r,
         "roofline": {"kernel": dom, "bound": "hbm", "achieved": r[dom]["gbs"], "peak": PEAK_HBM_GBS,
-                     "unit": "GB/s", "frac": r[dom]["frac_hbm_peak"], "traffic": None},
+                     "unit": "GB/s", "frac": r[dom]["frac_hbm_peak"],
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(("rowops", dom))},
     }
     if not a.no_cpu_baseline:
         import numpy as np
@@ -439,6 +445,12 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     attn.lib()  # fail loudly if the HIP library is not built
+    if a.calib_copy:
+        src = torch.empty(CALIB_COPY_BYTES // 2, dtype=torch.bfloat16, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if a.workload == "rowops":
         rowops_main(torch, a)
         return
@@ -446,12 +458,6 @@ def main():
         rect_main(torch, attn, wl, wl.RECT_WORKLOADS[a.workload], a)
         return
     w = wl.WORKLOADS[a.workload] if a.workload in wl.WORKLOADS else wl.GQA_WORKLOADS[a.workload]
-    if a.calib_copy:
-        src = torch.empty(CALIB_COPY_BYTES // 2, dtype=torch.bfloat16, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
     r = measure(torch, attn, wl, w, a.steps, a.warmup)
     dom = max(r["kernels"], key=lambda k: r["kernels"][k]["ms"])
     out = {
