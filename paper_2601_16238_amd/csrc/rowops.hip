@@ -17,7 +17,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kThreads = 256;          // threads that share one row
 constexpr int kWaves = kThreads / 64;
 constexpr int kMaxCols = 16384;        // 8 vectors of 8 elements per thread
-constexpr int kBwdTeams = 512;         // rows above which the LayerNorm backward pairs teams at V = 4
+constexpr int kBwdTeams = 512;         // rows above which the LayerNorm backward pairs its row teams
 
 __device__ __forceinline__ bf16x8 load8(const __bf16 *p)
 {
@@ -412,17 +412,19 @@ int check_rows(int64_t rows, int32_t cols, std::initializer_list<int64_t> stride
 }
 
 // LayerNorm backward: row teams per work-group, and work-groups.  The launch is one round of
-// resident work-groups.  At V = 4 the kernel's registers allow one 256-thread work-group per
-// unit or one 512-thread one, so two teams share a work-group there (on (4096, 8192): 40.5 us
-// against 44.4 us, with half the partial rows).  Work-groups per unit otherwise, measured on
-// (16384, 1024), (8192, 4096), (2048, 16384): V = 1: 4 (38.3 us; 44.8 with 2, 39.1 with 3),
-// V = 2: 2 (41.4 us; 44.7 with 3), V = 8: 1 (50.3 us; 63.4 with 2).
-int bwd_teams(int64_t rows, int V) { return rows > kBwdTeams && V == 4 ? 2 : 1; }
+// resident work-groups.  Up to 4 vectors per thread a work-group is two teams once there are
+// rows for more than 512 teams: the same waves per unit in half the work-groups, so half the
+// partial rows to write and to sum.  Teams per unit (more cost partial rows, fewer leave
+// latency uncovered), measured on (16384, 1024), (8192, 4096), (4096, 8192), (2048, 16384):
+// V = 1: 4 (33.7 us; 44.8 with 2, 39.1 with 3), V = 2: 2 (38.3 us; 44.7 with 3; 41.3 as
+// single-team work-groups), V = 4: 2, all its registers allow (40.3 us; 44.4 as single-team
+// work-groups in two rounds), V = 8: 1 (50.3 us; 63.4 with 2).
+int bwd_teams(int64_t rows, int V) { return rows > kBwdTeams && V <= 4 ? 2 : 1; }
 int bwd_groups(int64_t rows, int V)
 {
     const int T = bwd_teams(rows, V);
-    const int per_cu = V == 1 ? 4 : V == 8 ? 1 : 2 / T;
-    const int64_t g = (rows + T - 1) / T, cap = 256 * per_cu;
+    const int teams_per_cu = V == 1 ? 4 : V == 8 ? 1 : 2;
+    const int64_t g = (rows + T - 1) / T, cap = 256 * teams_per_cu / T;
     return (int)(g < cap ? g : cap);
 }
 // Work-groups of the forward kernels: as many as are resident at once on the 256 compute units
@@ -521,8 +523,11 @@ int rowops_layernorm_bwd(const void *dy, const void *x, const float *w, const fl
                        mean, rstd, static_cast<__bf16 *>(dx), part, rows, cols, dy_row_stride,    \
                        x_row_stride, dx_row_stride)
     if (bwd_teams(rows, V) == 2) {
-        constexpr int kV = 4;
-        ROWOPS_LN_BWD(2);
+        switch (V) {
+            case 1: { constexpr int kV = 1; ROWOPS_LN_BWD(2); } break;
+            case 2: { constexpr int kV = 2; ROWOPS_LN_BWD(2); } break;
+            default: { constexpr int kV = 4; ROWOPS_LN_BWD(2); } break;
+        }
     } else {
         ROWOPS_DISPATCH(V, ROWOPS_LN_BWD(1));
     }

@@ -308,12 +308,12 @@ def test_rowops_validation_without_a_gpu():
     assert call(xs=128) == binding.ATTN_ERR_STRIDE            # row stride below cols
     assert call(ys=260) == binding.ATTN_ERR_STRIDE            # not a multiple of 8
     assert call(w=FAKE + 4) == binding.ATTN_ERR_ALIGN
-    # one pair of fp32 rows per work-group: 256 two-team groups at 8192 columns, up to 1024 at <= 2048,
-    # 256 at 16384, 512 otherwise, never more than there are rows
+    # one pair of fp32 rows per work-group; above 512 rows: 256 two-team groups, 512 at <= 2048 columns,
+    # 256 one-team groups at 16384 columns; never more groups than rows
     assert rowops.layernorm_bwd_workspace_bytes(4096, 8192) == 256 * 2 * 8192 * 4
     assert rowops.layernorm_bwd_workspace_bytes(400, 8192) == 400 * 2 * 8192 * 4
-    assert rowops.layernorm_bwd_workspace_bytes(4096, 2048) == 1024 * 2 * 2048 * 4
-    assert rowops.layernorm_bwd_workspace_bytes(4096, 4096) == 512 * 2 * 4096 * 4
+    assert rowops.layernorm_bwd_workspace_bytes(4096, 2048) == 512 * 2 * 2048 * 4
+    assert rowops.layernorm_bwd_workspace_bytes(4096, 4096) == 256 * 2 * 4096 * 4
     assert rowops.layernorm_bwd_workspace_bytes(4096, 16384) == 256 * 2 * 16384 * 4
     assert rowops.layernorm_bwd_workspace_bytes(3, 64) == 3 * 2 * 64 * 4
     assert rowops.layernorm_bwd_workspace_bytes(3, 60) == 0
