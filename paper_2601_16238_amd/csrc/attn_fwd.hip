@@ -498,8 +498,13 @@ static int fwd_waves_for(int S, int D, int BH, bool causal)
     // so without a mask (+5 %), at D = 128 (+4..33 % on mid-size shapes) or on large problems.
     if (blocks32 >= 8 && D == 64 && causal && (int64_t)BH * ((S + 255) / 256) < 1024) return 4;
     if (blocks32 >= 8) return 8;
-    if (blocks32 >= 4 || D == 128) return 4;
-    return blocks32;  // 1, 2 or 3
+    // Three 32-row blocks also take four waves: the three-wave kernel needs 177 registers at
+    // D = 64, which leaves two waves per SIMD and two work-groups per compute unit, where the
+    // four-wave kernel (150 registers) fits three.  Measured at B=128 H=6 S=65: 13.6 -> 10.4 us,
+    // S=96: 15.4 -> 12.5 us.  (Four waves for two blocks change nothing; forcing the small
+    // kernels to 168 registers spills and is slower.)
+    if (blocks32 >= 3 || D == 128) return 4;
+    return blocks32;  // 1 or 2
 }
 
 template <int D>
@@ -510,7 +515,6 @@ static int launch_fwd_d(FwdArgs a, bool causal, hipStream_t st)
     if (nw == 8) return launch_fwd_nw<D, 8>(a, causal, st);
     if (nw == 4) return launch_fwd_nw<D, 4>(a, causal, st);
     if constexpr (D < 128) {
-        if (nw == 3) return launch_fwd_nw<D, 3>(a, causal, st);
         if (nw == 2) return launch_fwd_nw<D, 2>(a, causal, st);
         return launch_fwd_nw<D, 1>(a, causal, st);
     }
