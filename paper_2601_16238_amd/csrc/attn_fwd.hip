@@ -498,11 +498,12 @@ static int fwd_waves_for(int S, int D, int BH, bool causal)
     // so without a mask (+5 %), at D = 128 (+4..33 % on mid-size shapes) or on large problems.
     if (blocks32 >= 8 && D == 64 && causal && (int64_t)BH * ((S + 255) / 256) < 1024) return 4;
     if (blocks32 >= 8) return 8;
-    // Three 32-row blocks also take four waves: the three-wave kernel needs 177 registers at
-    // D = 64, which leaves two waves per SIMD and two work-groups per compute unit, where the
-    // four-wave kernel (150 registers) fits three.  Measured at B=128 H=6 S=65: 13.6 -> 10.4 us,
-    // S=96: 15.4 -> 12.5 us.  (Four waves for two blocks change nothing; forcing the small
-    // kernels to 168 registers spills and is slower.)
+    // Three 32-row blocks also take four waves; the fourth has no rows and only stages K and V.
+    // Measured at B=128 H=6 S=65: 13.6 -> 10.4 us, S=96: 15.4 -> 12.5 us.  The three-wave
+    // kernel needs 177 registers at D = 64 (two waves per SIMD, two work-groups per compute
+    // unit) against 150 for four waves (three work-groups), but capping it at 168 registers
+    // (with 48 bytes of spills) did not make it faster, so the shorter staging per wave counts
+    // as well.  Four waves for two blocks change nothing.
     if (blocks32 >= 3 || D == 128) return 4;
     return blocks32;  // 1 or 2
 }
