@@ -174,8 +174,11 @@ def _params_for(t, scale, causal):
 
 
 def _same_layout(ref, *ts):
+    # (the stride of an axis of length 1 is never used and may be anything)
+    def strides(t):
+        return tuple(st for n, st in zip(t.shape, t.stride()) if n > 1)
     for t in ts:
-        if t.shape != ref.shape or t.stride() != ref.stride() or t.dtype != ref.dtype \
+        if t.shape != ref.shape or strides(t) != strides(ref) or t.dtype != ref.dtype \
                 or t.device != ref.device:
             raise ValueError("all bf16 tensors must share shape, strides, dtype and device")
 
@@ -185,28 +188,101 @@ def _stream_ptr(torch, stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
+def _on_stream(torch, stream):
+    """Context in which tensors this binding allocates itself belong to the stream the kernels
+    are enqueued on: torch's caching allocator ties a block to the stream that was current when
+    it was allocated, and would otherwise hand a dropped workspace to other work of the
+    current stream while kernels on `stream` still use it."""
+    import contextlib
+    return contextlib.nullcontext() if stream is None else torch.cuda.stream(stream)
+
+
+
+def _elem_types(torch):
+    return (torch.bfloat16, torch.float16)
+
+
+def _check_lse(torch, LSE, shape):
+    if LSE.dtype != torch.float32 or not LSE.is_contiguous() or tuple(LSE.shape) != tuple(shape):
+        raise ValueError("LSE must be a contiguous fp32 [B,Hq,Sq] tensor")
+
+
+def _forward(where, entry, params, ws_bytes_fn, Q, K, V, O, LSE, workspace, split, stream,
+             dtypes):
+    """Shared marshalling of the three forward entry points: checks, output allocation and the
+    call `entry(Q, K, V, O, LSE, [workspace, bytes,] params, stream)`."""
+    import torch
+    if Q.dtype not in dtypes or not Q.is_cuda:
+        raise ValueError("Q,K,V must be %s tensors on the GPU" % " or ".join(str(d) for d in dtypes))
+    _same_layout(K, V)
+    if K.dtype != Q.dtype or K.device != Q.device:
+        raise ValueError("all tensors must share dtype and device")
+    B, H, S, D = Q.shape
+    with _on_stream(torch, stream):
+        if O is None:
+            O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+        else:
+            _same_layout(Q, O)
+        if LSE is None:
+            LSE = torch.empty((B, H, S), dtype=torch.float32, device=Q.device)
+        else:
+            _check_lse(torch, LSE, (B, H, S))
+        args = [Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr()]
+        if ws_bytes_fn is not None:  # the rectangular form takes an optional workspace
+            ws_ptr, ws_bytes = None, 0
+            if split:
+                need = int(ws_bytes_fn(ctypes.byref(params)))
+                if workspace is None and need:
+                    workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+                if workspace is not None:
+                    ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+            args += [ws_ptr, ws_bytes]
+    rc = entry(*args, ctypes.byref(params), _stream_ptr(torch, stream))
+    if rc != ATTN_OK:
+        raise AttnError(rc, where)
+    return O, LSE
+
+
+def _backward(where, entry, params, ws_bytes_fn, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace,
+              stream, dtypes, extra=()):
+    """Shared marshalling of the backward entry points."""
+    import torch
+    if Q.dtype not in dtypes or not Q.is_cuda:
+        raise ValueError("tensors must be %s on the GPU" % " or ".join(str(d) for d in dtypes))
+    _same_layout(Q, O, dO)
+    _same_layout(K, V)
+    if K.dtype != Q.dtype or K.device != Q.device:
+        raise ValueError("all tensors must share dtype and device")
+    B, H, S, D = Q.shape
+    _check_lse(torch, LSE, (B, H, S))
+    with _on_stream(torch, stream):
+        outs = []
+        for t, like in ((dQ, Q), (dK, K), (dV, K)):
+            if t is None:
+                t = torch.empty_strided(like.shape, like.stride(), dtype=like.dtype, device=like.device)
+            else:
+                _same_layout(like, t)
+            outs.append(t)
+        dQ, dK, dV = outs
+        if workspace is None:
+            workspace = torch.empty(int(ws_bytes_fn(ctypes.byref(params))), dtype=torch.uint8,
+                                    device=Q.device)
+    rc = entry(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(),
+               LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), workspace.data_ptr(),
+               workspace.numel() * workspace.element_size(), ctypes.byref(params),
+               _stream_ptr(torch, stream), *extra)
+    if rc != ATTN_OK:
+        raise AttnError(rc, where)
+    return dQ, dK, dV
+
+
 def attn_fwd(Q, K, V, scale, causal, O=None, LSE=None, stream=None):
     """O, LSE = attention forward.  Q,K,V: bf16 device tensors [B,H,S,D] with equal strides.
     Enqueues on `stream` (default: torch's current stream); does not synchronise."""
     import torch
-    if Q.dtype != torch.bfloat16 or not Q.is_cuda:
-        raise ValueError("Q,K,V must be bf16 tensors on the GPU")
     _same_layout(Q, K, V)
-    if O is None:
-        O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
-    else:
-        _same_layout(Q, O)
-    B, H, S, D = Q.shape
-    if LSE is None:
-        LSE = torch.empty((B, H, S), dtype=torch.float32, device=Q.device)
-    elif LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != (B, H, S):
-        raise ValueError("LSE must be a contiguous fp32 [B,H,S] tensor")
-    p = _params_for(Q, scale, causal)
-    rc = lib().attn_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(),
-                        ctypes.byref(p), _stream_ptr(torch, stream))
-    if rc != ATTN_OK:
-        raise AttnError(rc, "attn_fwd")
-    return O, LSE
+    return _forward("attn_fwd", lib().attn_fwd, _params_for(Q, scale, causal), None, Q, K, V, O,
+                    LSE, None, False, stream, (torch.bfloat16,))
 
 
 def attn_bwd_workspace_bytes(B, H, S, D):
@@ -220,35 +296,11 @@ def attn_bwd(Q, K, V, O, dO, LSE, scale, causal, dQ=None, dK=None, dV=None, work
     `stages` (profiling aid) restricts the call to a subset of its kernels through
     attn_bwd_stages; None calls attn_bwd."""
     import torch
-    if Q.dtype != torch.bfloat16 or not Q.is_cuda:
-        raise ValueError("tensors must be bf16 on the GPU")
-    _same_layout(Q, K, V, O, dO)
-    outs = []
-    for t in (dQ, dK, dV):
-        if t is None:
-            t = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
-        else:
-            _same_layout(Q, t)
-        outs.append(t)
-    dQ, dK, dV = outs
-    B, H, S, D = Q.shape
-    if LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != (B, H, S):
-        raise ValueError("LSE must be a contiguous fp32 [B,H,S] tensor")
-    p = _params_for(Q, scale, causal)
-    need = int(lib().attn_bwd_workspace_bytes(ctypes.byref(p)))
-    if workspace is None:
-        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
-    args = (Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(),
-            LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
-            workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-            ctypes.byref(p), _stream_ptr(torch, stream))
-    if stages is None:
-        rc = lib().attn_bwd(*args)
-    else:
-        rc = lib().attn_bwd_stages(*args, int(stages))
-    if rc != ATTN_OK:
-        raise AttnError(rc, "attn_bwd")
-    return dQ, dK, dV
+    _same_layout(Q, K, V)
+    entry, extra = (lib().attn_bwd, ()) if stages is None else (lib().attn_bwd_stages, (int(stages),))
+    return _backward("attn_bwd", entry, _params_for(Q, scale, causal),
+                     lib().attn_bwd_workspace_bytes, Q, K, V, O, dO, LSE, dQ, dK, dV, workspace,
+                     stream, (torch.bfloat16,), extra)
 
 
 # ---- grouped-query heads: Q, O, dO, dQ are [B,Hq,S,D]; K, V, dK, dV are [B,Hkv,S,D] ----------
@@ -278,24 +330,8 @@ def _gqa_params_for(q, k, scale, causal):
 def attn_fwd_gqa(Q, K, V, scale, causal, O=None, LSE=None, stream=None):
     """O [B,Hq,S,D], LSE [B,Hq,S] = grouped-query attention forward; K, V: [B,Hkv,S,D]."""
     import torch
-    if Q.dtype != torch.bfloat16 or not Q.is_cuda:
-        raise ValueError("Q,K,V must be bf16 tensors on the GPU")
-    _same_layout(K, V)
-    if O is None:
-        O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
-    else:
-        _same_layout(Q, O)
-    B, H, S, D = Q.shape
-    if LSE is None:
-        LSE = torch.empty((B, H, S), dtype=torch.float32, device=Q.device)
-    elif LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != (B, H, S):
-        raise ValueError("LSE must be a contiguous fp32 [B,Hq,S] tensor")
-    p = _gqa_params_for(Q, K, scale, causal)
-    rc = lib().attn_fwd_gqa(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
-                            LSE.data_ptr(), ctypes.byref(p), _stream_ptr(torch, stream))
-    if rc != ATTN_OK:
-        raise AttnError(rc, "attn_fwd_gqa")
-    return O, LSE
+    return _forward("attn_fwd_gqa", lib().attn_fwd_gqa, _gqa_params_for(Q, K, scale, causal), None,
+                    Q, K, V, O, LSE, None, False, stream, (torch.bfloat16,))
 
 
 def attn_bwd_gqa_workspace_bytes(B, Hq, Hkv, S, D):
@@ -307,40 +343,11 @@ def attn_bwd_gqa(Q, K, V, O, dO, LSE, scale, causal, dQ=None, dK=None, dV=None, 
                  stream=None, stages=None):
     """dQ [B,Hq,S,D], dK, dV [B,Hkv,S,D] = grouped-query attention backward."""
     import torch
-    if Q.dtype != torch.bfloat16 or not Q.is_cuda:
-        raise ValueError("tensors must be bf16 on the GPU")
-    _same_layout(Q, O, dO)
-    _same_layout(K, V)
-    if dQ is None:
-        dQ = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
-    else:
-        _same_layout(Q, dQ)
-    outs = []
-    for t in (dK, dV):
-        if t is None:
-            t = torch.empty_strided(K.shape, K.stride(), dtype=K.dtype, device=K.device)
-        else:
-            _same_layout(K, t)
-        outs.append(t)
-    dK, dV = outs
-    B, H, S, D = Q.shape
-    if LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != (B, H, S):
-        raise ValueError("LSE must be a contiguous fp32 [B,Hq,S] tensor")
-    p = _gqa_params_for(Q, K, scale, causal)
-    need = int(lib().attn_bwd_gqa_workspace_bytes(ctypes.byref(p)))
-    if workspace is None:
-        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
-    args = (Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(),
-            LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(),
-            workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-            ctypes.byref(p), _stream_ptr(torch, stream))
-    if stages is None:
-        rc = lib().attn_bwd_gqa(*args)
-    else:
-        rc = lib().attn_bwd_gqa_stages(*args, int(stages))
-    if rc != ATTN_OK:
-        raise AttnError(rc, "attn_bwd_gqa")
-    return dQ, dK, dV
+    entry, extra = ((lib().attn_bwd_gqa, ()) if stages is None
+                    else (lib().attn_bwd_gqa_stages, (int(stages),)))
+    return _backward("attn_bwd_gqa", entry, _gqa_params_for(Q, K, scale, causal),
+                     lib().attn_bwd_gqa_workspace_bytes, Q, K, V, O, dO, LSE, dQ, dK, dV,
+                     workspace, stream, (torch.bfloat16,), extra)
 
 
 # ---- rectangular: Q, O, dO, dQ are [B,Hq,Sq,D]; K, V, dK, dV are [B,Hkv,Sk,D]; a causal mask
@@ -382,32 +389,10 @@ def attn_fwd_rect(Q, K, V, scale, causal, O=None, LSE=None, workspace=None, spli
     which keeps the forward in one kernel; otherwise a workspace is allocated when the
     library's plan asks for one.  bf16 or fp16 tensors (all of one type)."""
     import torch
-    if Q.dtype not in (torch.bfloat16, torch.float16) or not Q.is_cuda:
-        raise ValueError("Q,K,V must be bf16 or fp16 tensors on the GPU")
-    entry = lib().attn_fwd_rect if Q.dtype == torch.bfloat16 else lib().attn_fwd_rect_f16
-    _same_layout(K, V)
-    if O is None:
-        O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
-    else:
-        _same_layout(Q, O)
-    B, H, S, D = Q.shape
-    if LSE is None:
-        LSE = torch.empty((B, H, S), dtype=torch.float32, device=Q.device)
-    elif LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != (B, H, S):
-        raise ValueError("LSE must be a contiguous fp32 [B,Hq,Sq] tensor")
-    p = _rect_params_for(Q, K, scale, causal)
-    ws_ptr, ws_bytes = None, 0
-    if split:
-        need = int(lib().attn_fwd_rect_workspace_bytes(ctypes.byref(p)))
-        if workspace is None and need:
-            workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
-        if workspace is not None:
-            ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
-    rc = entry(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
-               LSE.data_ptr(), ws_ptr, ws_bytes, ctypes.byref(p), _stream_ptr(torch, stream))
-    if rc != ATTN_OK:
-        raise AttnError(rc, "attn_fwd_rect")
-    return O, LSE
+    entry = lib().attn_fwd_rect_f16 if Q.dtype == torch.float16 else lib().attn_fwd_rect
+    return _forward("attn_fwd_rect", entry, _rect_params_for(Q, K, scale, causal),
+                    lib().attn_fwd_rect_workspace_bytes, Q, K, V, O, LSE, workspace, split, stream,
+                    _elem_types(torch))
 
 
 def attn_bwd_rect_workspace_bytes(B, Hq, Hkv, Sq, Sk, D):
@@ -419,35 +404,7 @@ def attn_bwd_rect(Q, K, V, O, dO, LSE, scale, causal, dQ=None, dK=None, dV=None,
                   stream=None):
     """dQ [B,Hq,Sq,D], dK, dV [B,Hkv,Sk,D] = rectangular attention backward (bf16 or fp16)."""
     import torch
-    if Q.dtype not in (torch.bfloat16, torch.float16) or not Q.is_cuda:
-        raise ValueError("tensors must be bf16 or fp16 on the GPU")
-    entry = lib().attn_bwd_rect if Q.dtype == torch.bfloat16 else lib().attn_bwd_rect_f16
-    _same_layout(Q, O, dO)
-    _same_layout(K, V)
-    if dQ is None:
-        dQ = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
-    else:
-        _same_layout(Q, dQ)
-    outs = []
-    for t in (dK, dV):
-        if t is None:
-            t = torch.empty_strided(K.shape, K.stride(), dtype=K.dtype, device=K.device)
-        else:
-            _same_layout(K, t)
-        outs.append(t)
-    dK, dV = outs
-    B, H, S, D = Q.shape
-    if LSE.dtype != torch.float32 or not LSE.is_contiguous() or LSE.shape != (B, H, S):
-        raise ValueError("LSE must be a contiguous fp32 [B,Hq,Sq] tensor")
-    p = _rect_params_for(Q, K, scale, causal)
-    need = int(lib().attn_bwd_rect_workspace_bytes(ctypes.byref(p)))
-    if workspace is None:
-        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
-    rc = entry(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
-               dO.data_ptr(), LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(),
-               dV.data_ptr(), workspace.data_ptr(),
-               workspace.numel() * workspace.element_size(), ctypes.byref(p),
-               _stream_ptr(torch, stream))
-    if rc != ATTN_OK:
-        raise AttnError(rc, "attn_bwd_rect")
-    return dQ, dK, dV
+    entry = lib().attn_bwd_rect_f16 if Q.dtype == torch.float16 else lib().attn_bwd_rect
+    return _backward("attn_bwd_rect", entry, _rect_params_for(Q, K, scale, causal),
+                     lib().attn_bwd_rect_workspace_bytes, Q, K, V, O, dO, LSE, dQ, dK, dV,
+                     workspace, stream, _elem_types(torch))

@@ -113,7 +113,6 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     const bool producer = w < C::kPairs;
     const int pair = w < C::kPairs ? w : w - C::kPairs;
     const int S = a.S;
-    ATTN_CYCLES_BEGIN();
     // The work-group owns 128 keys of one K/V head and sums over the `group` query heads that
     // read it (grouped-query attention; group == 1 is multi-head attention).
     const int Hkv = a.H / a.group;
@@ -363,7 +362,6 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
             }
         }
     }
-    ATTN_CYCLES_END(1);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -417,7 +415,6 @@ attn_bwd_dq_kernel(const BwdArgs a)
     const int tid = threadIdx.x, l = tid & 63, r = l & 31, h = l >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int S = a.S;
-    ATTN_CYCLES_BEGIN();
     int bh, rank;
     xcd_tile_order<CAUSAL>(blockIdx.x, a.ntile, a.BH, bh, rank);
     const int qt = CAUSAL ? a.ntile - 1 - rank : rank;  // heaviest first
@@ -637,7 +634,6 @@ attn_bwd_dq_kernel(const BwdArgs a)
                         pack4(dq[db][4 * g] * sc, dq[db][4 * g + 1] * sc,
                               dq[db][4 * g + 2] * sc, dq[db][4 * g + 3] * sc);
     }
-    ATTN_CYCLES_END(2);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -728,14 +724,6 @@ static int launch_bwd_d(BwdArgs a, bool causal, hipStream_t st, unsigned stages)
     if (stages & 2u) return causal ? launch_dkdv<D, true>(a, st) : launch_dkdv<D, false>(a, st);
     return 0;
 }
-
-#if defined(ATTN_CYCLES) && !defined(ATTN_F16)
-extern "C" void attn_debug_cycles_bwd(unsigned long long *out, int reset)
-{
-    hipMemcpyFromSymbol(out, HIP_SYMBOL(g_attn_cycles), sizeof(g_attn_cycles));
-    if (reset) { unsigned long long z[4][4] = {}; hipMemcpyToSymbol(HIP_SYMBOL(g_attn_cycles), z, sizeof(z)); }
-}
-#endif
 
 int launch_bwd(const BwdArgs &a, int D, bool causal, hipStream_t st, unsigned stages)
 {

@@ -128,6 +128,10 @@ __device__ __forceinline__ u32x2 buf_load8(rsrc_t r, uint32_t voff, uint32_t sof
 // wait for ALL of its outstanding transfers before any later transpose read of LDS.  The
 // caller orders transfers and reads itself (s_waitcnt vmcnt + barrier) and must wait for
 // vmcnt(0) before the work-group ends.
+// (m0 is named as clobbered so that the compiler does not assume a value it put there earlier
+// survives; it answers that with a warning about reserved registers, silenced here)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 typedef u32x4 desc_t;
 __device__ __forceinline__ desc_t make_desc(const void *p, uint32_t bytes)
 {
@@ -149,15 +153,17 @@ __device__ __forceinline__ void dma16(desc_t desc, uint32_t lds_addr, uint32_t v
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  ::"s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(desc),
                  "s"(__builtin_amdgcn_readfirstlane(soff))
-                 : "memory");
+                 : "memory", "m0");
 }
 // Same with 4 bytes per lane: lane i lands at lds_addr + 4 i.
 __device__ __forceinline__ void dma4(desc_t desc, uint32_t lds_addr, uint32_t voff, uint32_t soff)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
-                 ::"s"(lds_addr), "v"(voff), "s"(desc), "s"(soff)
-                 : "memory");
+                 ::"s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(desc),
+                 "s"(__builtin_amdgcn_readfirstlane(soff))
+                 : "memory", "m0");
 }
+#pragma clang diagnostic pop
 // Wait until at most N of this wave's vector-memory operations are outstanding and all its
 // LDS operations are done, then join the work-group barrier.  Unlike __syncthreads this
 // leaves the newest global -> LDS transfers in flight across the barrier.
@@ -185,51 +191,6 @@ __device__ __forceinline__ float pin_scalar(float x)
     return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, x)));
 }
 __device__ __forceinline__ int pin_scalar(int x) { return __builtin_amdgcn_readfirstlane(x); }
-
-// Cycle accounting for development builds (-DATTN_CYCLES): every work-group adds its
-// elapsed shader cycles and 100 MHz wall ticks to a per-kernel slot, so that a change can be
-// judged in cycles although the shader clock floats with load.  Not compiled into the
-// product library.
-#ifdef ATTN_CYCLES
-static __device__ unsigned long long g_attn_cycles[4][4];  // [slot][cycles, wall ticks, work-groups]
-#define ATTN_CYCLES_BEGIN() \
-    const long long attn_c0_ = __builtin_readcyclecounter(), attn_r0_ = wall_clock64()
-#define ATTN_CYCLES_END(slot)                                                                  \
-    do {                                                                                       \
-        if (threadIdx.x == 0) {                                                                \
-            atomicAdd(&g_attn_cycles[slot][0], (unsigned long long)(__builtin_readcyclecounter() - attn_c0_)); \
-            atomicAdd(&g_attn_cycles[slot][1], (unsigned long long)(wall_clock64() - attn_r0_));             \
-            atomicAdd(&g_attn_cycles[slot][2], 1ull);                                          \
-        }                                                                                      \
-    } while (0)
-#else
-#define ATTN_CYCLES_BEGIN() ((void)0)
-#define ATTN_CYCLES_END(slot) ((void)0)
-#endif
-// Finer split for development builds (-DATTN_CYCLES -DATTN_PHASES): a wave accumulates the
-// cycles between successive ATTN_PHASE(n) marks into bucket n; thread `tid0` of every
-// work-group adds its buckets to slot 3, starting at entry `first`.
-#if defined(ATTN_CYCLES) && defined(ATTN_PHASES)
-#define ATTN_PHASE_INIT() \
-    long long attn_pt_ = __builtin_readcyclecounter(); unsigned long long attn_pa_[4] = {0, 0, 0, 0}
-#define ATTN_PHASE(n)                                                  \
-    do {                                                               \
-        const long long t_ = __builtin_readcyclecounter();             \
-        attn_pa_[n] += (unsigned long long)(t_ - attn_pt_);            \
-        attn_pt_ = t_;                                                 \
-    } while (0)
-#define ATTN_PHASE_END(tid0, first)                                    \
-    do {                                                               \
-        if ((int)threadIdx.x == (tid0)) {                              \
-            for (int n_ = 0; n_ + (first) < 4; ++n_)                   \
-                atomicAdd(&g_attn_cycles[3][(first) + n_], attn_pa_[n_]); \
-        }                                                              \
-    } while (0)
-#else
-#define ATTN_PHASE_INIT() ((void)0)
-#define ATTN_PHASE(n) ((void)0)
-#define ATTN_PHASE_END(tid0, first) ((void)0)
-#endif
 
 // Work-group id -> position in a virtual order in which consecutive positions land on the
 // same XCD.  Work-groups are handed to the 8 XCDs round-robin by linear id, each XCD has

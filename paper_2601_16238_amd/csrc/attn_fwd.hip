@@ -35,15 +35,31 @@ struct FwdCfg {
     static constexpr int kThreads = NW * 64;
     static constexpr int kBR = NW * 32;
     static constexpr int kBC = 64;
-    static constexpr int kKTile = kBC * D;          // K tile [key][d], 16-byte chunks XOR-swizzled
+    // K tile: one wave-wide transfer of 16 B per lane fills a 1 KB piece of kKRowsPerDma
+    // rows; within a piece the 16-byte chunks are stored chunk-major (chunk c of row r at
+    // 16 * (c * rows + r % rows)) and consecutive pieces lie 16 * rows bytes further apart than
+    // their size.  The fragment a lane needs for contraction step ks is then at a per-lane
+    // constant plus ks * kKStep -- one address register instead of one per step -- and the 16
+    // rows that one quarter of a wave reads at a fixed chunk fall into 16 different 16-byte
+    // bank groups.
     static constexpr int kKRowsPerDma = 1024 / (D * 2);        // rows one wave-wide 16 B/lane load fills
+    static constexpr int kKPieceBytes = 1024 + kKRowsPerDma * 16;
     static constexpr int kKDmas = kBC / kKRowsPerDma;          // such loads per tile
+    static constexpr int kKTile = kKDmas * kKPieceBytes / 2;   // in elements
+    static constexpr int kKHalf = kKTile / 2;                  // 32 rows further
+    static constexpr int kKStep = 2 * kKRowsPerDma * 16 / 2;   // next contraction step, in elements
     static constexpr int kKDmaPerWave = (kKDmas + NW - 1) / NW;
     static constexpr int kLdV = kBC + 8;            // V^T tile [d][key order], rows skewed
     static constexpr int kVTile = D * kLdV;
-    static constexpr int kLdsBytes = (3 * kKTile + 2 * kVTile) * 2;   // K x3, V^T x2
     static constexpr int kVMicro = (kBC / 4) * (D / 4);   // 4 keys x 4 d micro-tiles of a V tile
     static constexpr int kVPerThread = (kVMicro + kThreads - 1) / kThreads;
+    // V^T tiles: two, or three for the eight-wave kernel, whose main loop multiplies P of a
+    // sub-tile by V one sub-tile later and therefore still reads tile kt-1 while tile kt+1 is
+    // being stored
+    static constexpr int kVBufs = NW == 8 ? 3 : 2;
+    static constexpr int kLdsBytes = (3 * kKTile + kVBufs * kVTile) * 2;
+    // register loads of V that a thread issues per tile (after the K transfers of that tile)
+    static constexpr int kVLoads = 4 * kVPerThread;
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 CU exceeded");
 };
 
@@ -61,11 +77,11 @@ attn_fwd_kernel(const FwdArgs a)
     constexpr int DB = D / 32;  // 32-row blocks of O^T
     extern __shared__ __attribute__((aligned(16))) char smem[];
     elem *Ks = reinterpret_cast<elem *>(smem);  // [3][64][D] swizzled
-    elem *Vs = Ks + 3 * C::kKTile;              // [2][D][kLdV]
+    elem *Vs = Ks + 3 * C::kKTile;              // [kVBufs][D][kLdV]
 
-    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, r = l & 31, h = l >> 5;
+    const int tid = threadIdx.x, l = tid & 63, r = l & 31, h = l >> 5;
+    const int w = tid >> 6;
     const int S = a.S, Dr = a.Dr;
-    ATTN_CYCLES_BEGIN();
 
     // (head, query tile) of this work-group; causal tiles are issued heaviest first.
     int bh, rank;
@@ -113,24 +129,22 @@ attn_fwd_kernel(const FwdArgs a)
     const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2u;
     const uint32_t tile_bytes = C::kBC * row_bytes;
     // K goes global -> LDS directly (no registers): one wave-wide load of 16 B per lane fills
-    // 1 KB of LDS in lane order, so the tile is stored unpadded and bank conflicts are avoided
-    // by XOR-swizzling the 16-byte chunk index with the row: a lane fetches the chunk that
-    // belongs at its LDS position.  Chunk c of row k sits at chunk position c ^ swz(k).
-    constexpr int CPR = D / 8;  // 16-byte chunks per row
-    auto swz = [](int row) { return CPR == 16 ? (row & 15) : ((row >> 1) & 7); };
+    // 1 KB of LDS in lane order; lane l fetches the chunk that belongs at its position of the
+    // piece, chunk l / rows of row l % rows.  The piece's first row goes into the scalar
+    // offset (which takes part in the range check like the per-lane one).
+    constexpr int PR = C::kKRowsPerDma;
     u32x2 vreg[C::kVPerThread][4];
+    const uint32_t k_voff = (l / PR) * 8 < Dr ? (l % PR) * row_bytes + ((l / PR) << 4) : head_bytes;
     auto dma_k = [&](int kt, int buf) {
 #pragma unroll
         for (int n = 0; n < C::kKDmaPerWave; ++n) {
-            const int ii = w + n * NW;  // which 1 KB piece of the tile (wave-uniform)
-            if (C::kKDmas % NW == 0 || ii < C::kKDmas) {
-                const int row = ii * C::kKRowsPerDma + l / CPR;
-                const int chunk = (l % CPR) ^ swz(row);
-                const uint32_t voff = chunk * 8 < Dr ? row * row_bytes + chunk * 16 : head_bytes;
+            // which 1 KB piece of the tile: wave-uniform, and said so, because it goes into the
+            // transfer's scalar offset and LDS base
+            const int ii = __builtin_amdgcn_readfirstlane(w) + n * NW;
+            if (C::kKDmas % NW == 0 || ii < C::kKDmas)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                    Kr, (void __attribute__((address_space(3))) *)(Ks + buf * C::kKTile + ii * 512),
-                    16, (int)voff, kt * tile_bytes, 0, 0);
-            }
+                    Kr, (void __attribute__((address_space(3))) *)(Ks + buf * C::kKTile + ii * (C::kKPieceBytes / 2)),
+                    16, (int)k_voff, kt * tile_bytes + ii * PR * row_bytes, 0, 0);
         }
     };
     // V micro-tile mt: a wave covers 32 keys x 32 d as 8 key groups x 8 d groups.
@@ -153,17 +167,25 @@ attn_fwd_kernel(const FwdArgs a)
             }
         }
     };
+    // byte address within V buffer 0 of this thread's micro-tile(s): one opaque register each,
+    // so that the buffer and the column are immediate offsets of the LDS writes
+    int vst_lane[C::kVPerThread];
+#pragma unroll
+    for (int n = 0; n < C::kVPerThread; ++n) {
+        int key0, d0;
+        v_coords(tid + n * C::kThreads, key0, d0);
+        // position of key0 (a multiple of 4) in the MFMA contraction order:
+        // key = 16cc + 8u + 4hh + e  ->  16cc + 8hh + 4u + e
+        const int kpos = (key0 & ~15) | ((key0 & 4) << 1) | ((key0 & 8) >> 1);
+        vst_lane[n] = (3 * C::kKTile + d0 * C::kLdV + kpos) * 2;
+        asm volatile("" : "+v"(vst_lane[n]));
+    }
     auto store_v = [&](int buf) {
 #pragma unroll
         for (int n = 0; n < C::kVPerThread; ++n) {
             const int mt = tid + n * C::kThreads;
             if (C::kVMicro % C::kThreads == 0 || mt < C::kVMicro) {
-                int key0, d0;
-                v_coords(mt, key0, d0);
-                // position of key0 (a multiple of 4) in the MFMA contraction order:
-                // key = 16cc + 8u + 4hh + e  ->  16cc + 8hh + 4u + e
-                const int kpos = (key0 & ~15) | ((key0 & 4) << 1) | ((key0 & 8) >> 1);
-                elem *dst = Vs + buf * C::kVTile + d0 * C::kLdV + kpos;
+                elem *dst = reinterpret_cast<elem *>(smem + buf * (C::kVTile * 2) + vst_lane[n]);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     // column d0+j of the 4x4 micro-tile: keys key0..key0+3
@@ -192,14 +214,20 @@ attn_fwd_kernel(const FwdArgs a)
     // are fetched a step ahead into the other of two fragment sets, so the LDS latency hides
     // behind the previous step's MFMAs.
     constexpr int NKQ = KS / 4;  // K Q^T steps per sub-tile, four contraction steps each
-    // element offset of this lane's fragment for contraction step ks within a 32-row half
-    // tile (rows r and 32+r have the same swizzle)
-    int koff[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) koff[ks] = r * D + (((2 * ks + h) ^ swz(r)) * 8);
+    // element offset of this lane's fragment for contraction step 0 within a 32-row half
+    // tile: chunk h of row r
+    // The per-lane parts of the LDS addresses are kept in one register each and made opaque to
+    // the compiler, so that buffer, sub-tile and step are folded into the 16-bit immediate
+    // offset of the LDS instruction instead of into further address registers.  (The V region
+    // starts beyond what an immediate reaches from zero, so its registers include its base.)
+    int k_lane = ((r / PR) * (C::kKPieceBytes / 2) + (h * PR + r % PR) * 8) * 2;
+    int v_lane = (3 * C::kKTile + r * C::kLdV + 8 * h) * 2;
+    asm volatile("" : "+v"(k_lane), "+v"(v_lane));
+    const elem *const L0 = reinterpret_cast<const elem *>(smem);  // V fragment reads: tile offsets from here
     auto ld_k = [&](const elem *Kt, int kq, elem8 (&f)[4]) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) f[t] = *(const elem8 *)(Kt + koff[4 * kq + t]);
+        for (int t = 0; t < 4; ++t)
+            f[t] = *(const elem8 *)((const char *)(Kt + (4 * kq + t) * C::kKStep) + k_lane);
     };
     auto mm_k = [&](int kq, const elem8 (&f)[4], f32x16 &t0) {
 #pragma unroll
@@ -207,10 +235,10 @@ attn_fwd_kernel(const FwdArgs a)
     };
     // V^T fragment: lane (d = 32*db + l%32, half h) holds the 8 keys of contraction step cc
     // that its half owns, contiguous in the staged order.
-    auto ld_v = [&](const elem *Vt, int cc, elem8 (&f)[4]) {
+    auto ld_v = [&](const elem *Vt, int cc, elem8 (&f)[4]) {  // Vt: tile and sub-tile, from L0
 #pragma unroll
         for (int db = 0; db < DB; ++db)
-            f[db] = *(const elem8 *)(Vt + (32 * db + r) * C::kLdV + 16 * cc + 8 * h);
+            f[db] = *(const elem8 *)((const char *)(Vt + 32 * db * C::kLdV + 16 * cc) + v_lane);
     };
     // Row sums of the ROUNDED probabilities (one packed dot product with a vector of ones per
     // element pair; this lane's half of the keys, both halves are added at the end like the
@@ -245,17 +273,33 @@ attn_fwd_kernel(const FwdArgs a)
     // and every set is fetched two steps before it is consumed; the K fragments of sub-tile
     // g+2 (tile kt+1, resident since the previous iteration) are fetched during V0/V1.
     elem8 f0[4], f1[4], f2[4], f3[4];
-    auto subtile = [&](int kt, int u, int kbuf_next, int kbuf_fill, bool masked, f32x16 &cur,
-                       f32x16 &nxt) __attribute__((always_inline)) {
-        const elem *Kn = Ks + kbuf_next * C::kKTile + u * 32 * D;  // rows of sub-tile g+2
-        const elem *Vt = Vs + (kt & 1) * C::kVTile + 32 * u;
-        // The two waves that share a SIMD (w and w+4) take turns at the higher issue
-        // priority, one sub-tile each; otherwise the older wave always wins arbitration,
-        // runs ahead, and then idles at the tile barrier while the younger one catches up.
-        if (NW == 8) {
-            if (((w >> 2) ^ u) & 1) __builtin_amdgcn_s_setprio(0);
-            else __builtin_amdgcn_s_setprio(2);
-        }
+    // The reference max moves to the true running max: rescale what has been accumulated and
+    // redo the probabilities of the sub-tile whose scores are in cur.
+    auto move_reference = [&](const f32x16 &cur, elem8 &p0, elem8 &p1, float &psum)
+                              __attribute__((always_inline)) {
+        float mx = cur[0];
+#pragma unroll
+        for (int i = 1; i < 16; i += 3)
+            mx = fmaxf(mx, fmaxf(cur[i], fmaxf(cur[i + 1], cur[i + 2])));
+        mx = xhalf_max(mx) * c;
+        const float m_new = fmaxf(m, mx);
+        const float alpha = fast_exp2(m - m_new);
+        m = m_new;
+        lsum *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+        hsum *= alpha;
+        psum = 0.f;
+        p0 = softmax8(cur, 0, psum);
+        p1 = softmax8(cur, 8, psum);
+    };
+    // vb: buffer of V(kt); vb_fill: buffer that takes V(kt+1)
+    auto subtile = [&](int kt, int u, int kbuf_next, int kbuf_fill, int vb, int vb_fill, bool masked,
+                       f32x16 &cur, f32x16 &nxt) __attribute__((always_inline)) {
+        const elem *Kn = Ks + kbuf_next * C::kKTile + u * C::kKHalf;  // rows of sub-tile g+2
+        const elem *Vt = L0 + vb * C::kVTile + 32 * u;
         // ---- K0
         ld_v(Vt, 0, f2);
         if (NKQ == 1) ld_v(Vt, 1, f3);
@@ -282,30 +326,12 @@ attn_fwd_kernel(const FwdArgs a)
         // Rare path: some probability outgrew 2^10 relative to the reference max (always so
         // for a wave's first sub-tile).  Move the reference to the true running max, rescale
         // what has been accumulated, and redo this sub-tile's probabilities.
-        if (__builtin_amdgcn_ballot_w64(psum > kOverflow) != 0) {
-            float mx = cur[0];
-#pragma unroll
-            for (int i = 1; i < 16; i += 3)
-                mx = fmaxf(mx, fmaxf(cur[i], fmaxf(cur[i + 1], cur[i + 2])));
-            mx = xhalf_max(mx) * c;
-            const float m_new = fmaxf(m, mx);
-            const float alpha = fast_exp2(m - m_new);
-            m = m_new;
-            lsum *= alpha;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-            hsum *= alpha;
-            psum = 0.f;
-            p0 = softmax8(cur, 0, psum);
-            p1 = softmax8(cur, 8, psum);
-        }
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(psum > kOverflow) != 0, 0)) move_reference(cur, p0, p1, psum);
         ATTN_FENCE();
         // ---- V0 (first sub-tile: V(kt+1), fetched an iteration ago, is transposed into LDS)
         ld_k(Kn, 0, f0);
         mm_v(f2, p0);
-        if (u == 0) store_v((kt + 1) & 1);
+        if (u == 0) store_v(vb_fill);
         ATTN_FENCE();
         // ---- V1 (first sub-tile: start fetching V(kt+2))
         if (NKQ > 1) ld_k(Kn, 1, f1);
@@ -322,6 +348,13 @@ attn_fwd_kernel(const FwdArgs a)
     load_v(0);
     store_v(0);
     load_v(1);
+    if constexpr (NW == 8) {
+        // The main loop's first iteration multiplies an all-zero P by the second half of V
+        // buffer 2, which nothing has written yet: give it finite contents.
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        for (int i = tid; i < C::kVTile / 8; i += C::kThreads)
+            *(u32x4 *)(Vs + 2 * C::kVTile + 8 * i) = z;
+    }
     __syncthreads();
     f32x16 sa, sb;
     {
@@ -332,54 +365,160 @@ attn_fwd_kernel(const FwdArgs a)
         mm_k(0, f0, sa);
         if (NKQ > 1) mm_k(1, f1, sa);
         ATTN_FENCE();
-        ld_k(Ks + 32 * D, 0, f0);
-        if (NKQ > 1) ld_k(Ks + 32 * D, 1, f1);
+        ld_k(Ks + C::kKHalf, 0, f0);
+        if (NKQ > 1) ld_k(Ks + C::kKHalf, 1, f1);
     }
+
+    // Main-loop form of a sub-tile (eight-wave kernel, sub-tiles that the wave sees in full):
+    // the probabilities of sub-tile g are multiplied by V one sub-tile LATER.  The iteration
+    // then holds three independent pieces of work -- S^T(g+1) = K Q^T, the softmax arithmetic
+    // of g, and O^T += V^T P^T(g-1) -- in one basic block with nothing to mask, and the test
+    // whether the reference max must move sits at its end instead of between the softmax and
+    // the second MFMA phase, where it made every wave wait for its last exp2 before it could
+    // issue the next MFMA (measured: the same arithmetic without that branch in the middle
+    // runs 15 % faster).  pp0/pp1 carry P(g-1) into the iteration; vprev is the buffer that
+    // holds the V rows of sub-tile g-1 (tile kt-1 for u == 0, tile kt for u == 1).
+    elem8 pp0, pp1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) pp0[i] = pp1[i] = (elem)0.f;
+    auto subtile_main = [&](int kt, int u, int kbuf_next, int kbuf_fill, int vprev, int vb_fill,
+                            f32x16 &cur, f32x16 &nxt) __attribute__((always_inline)) {
+        const elem *Kn = Ks + kbuf_next * C::kKTile + u * C::kKHalf;  // rows of sub-tile g+2
+        const elem *Vt = L0 + vprev * C::kVTile + 32 * (1 - u);     // rows of sub-tile g-1
+        // The softmax arithmetic of g is spread evenly over the four MFMA steps (four scores
+        // each), so that every step has about three quarters as many vector-ALU cycles as
+        // matrix-pipe cycles.
+        float e[16], psum = 0.f;
+        auto exp4 = [&](int i0) __attribute__((always_inline)) {
+#pragma unroll
+            for (int i = i0; i < i0 + 4; ++i) {
+                e[i] = fast_exp2(__builtin_fmaf(cur[i], c, -m));
+                psum += e[i];
+            }
+        };
+        auto hsum4 = [&](elem8 p) __attribute__((always_inline)) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) hsum = dot2_acc(p[2 * i], p[2 * i + 1], hsum);
+        };
+        auto mm_o = [&](const elem8 (&f)[4], elem8 p) __attribute__((always_inline)) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db) o[db] = mfma32(f[db], p, o[db]);
+        };
+        // ---- K0
+        ld_v(Vt, 0, f2);
+        if (NKQ == 1) ld_v(Vt, 1, f3);
+        if (u == 0) dma_k(kt + 2, kbuf_fill);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) nxt[i] = 0.f;
+        exp4(0);
+        hsum4(pp0);
+        mm_k(0, f0, nxt);
+        ATTN_FENCE();
+        // ---- K1
+        if (NKQ > 1) {
+            ld_v(Vt, 1, f3);
+            mm_k(1, f1, nxt);
+        }
+        exp4(4);
+        hsum4(pp1);
+        elem8 p0 = pack8(e[0], e[1], e[2], e[3], e[4], e[5], e[6], e[7]);
+        ATTN_FENCE();
+        // ---- V0
+        ld_k(Kn, 0, f0);
+        mm_o(f2, pp0);
+        exp4(8);
+        if (u == 0) store_v(vb_fill);
+        ATTN_FENCE();
+        // ---- V1
+        if (NKQ > 1) ld_k(Kn, 1, f1);
+        mm_o(f3, pp1);
+        exp4(12);
+        elem8 p1 = pack8(e[8], e[9], e[10], e[11], e[12], e[13], e[14], e[15]);
+        if (u == 0) load_v(kt + 2);
+        ATTN_FENCE();
+        // rare: some probability of g outgrew 2^10 (always so for a wave's first sub-tile);
+        // what has been accumulated (up to g-1) is rescaled, P(g) redone
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(psum > kOverflow) != 0, 0)) move_reference(cur, p0, p1, psum);
+        lsum += psum;
+        pp0 = p0;
+        pp1 = p1;
+    };
+    // The K transfers of a tile are issued before the V register loads of the same tile, so
+    // "at most kVLoads vector-memory operations outstanding" means that this wave's piece of
+    // K(kt+2) has landed in LDS; only then may the other waves be let past the barrier to
+    // read it.  (When some threads have no V micro-tile the count is not uniform: wait for all.)
+    auto tile_barrier = [&]() {
+        if (C::kVMicro % C::kThreads == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::kVLoads) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    };
 
     // One loop iteration = one staged tile of 64 keys = two sub-tiles.  Staging is folded
     // into the first sub-tile's steps.  During iteration kt the waves read K(kt) (second
     // half) and K(kt+1) (first half), so K is triple-buffered and K(kt+2) streams into the
-    // third buffer; V(kt+1) replaces V(kt-1), whose last readers finished before the
+    // third buffer; V(kt+1) replaces the oldest V tile, whose last readers finished before the
     // previous barrier.
-    // With 8 waves the loop is unrolled three times so that the K buffer of every access is a
-    // compile-time constant: the LDS addresses of the K fragments are then a loop-invariant register plus
-    // an immediate offset (one vector instruction per fragment less on the issue port).
-    auto tile = [&](int kt, int kb1, int kb2) __attribute__((always_inline)) {  // K(kt+1), K(kt+2)
+    int kt0 = 0;  // first tile of the generic loop below
+    if constexpr (NW == 8) {
+        // Tiles that this wave sees in full (no key past the end, none above its diagonal), in
+        // whole groups of three: the loop is unrolled over the three K (and V) buffers so that
+        // the buffer of every access is a compile-time constant and the LDS addresses of the
+        // fragments are a loop-invariant register plus an immediate offset.
+        const int seen = CAUSAL ? min(Sk, q0e + 1) : Sk;  // keys 0 .. seen-1 are visible to every row of the wave
+        // (rows past S: never more than n_kt; the same in every lane of the wave, and said so,
+        // so that the loop is controlled by scalar registers)
+        const int n_main = __builtin_amdgcn_readfirstlane(min(max(seen, 0) / C::kBC, n_kt) / 3 * 3);
+        for (int kt = 0; kt < n_main; kt += 3) {
+            subtile_main(kt, 0, 1, 2, 2, 1, sa, sb);
+            subtile_main(kt, 1, 1, 2, 0, 1, sb, sa);
+            tile_barrier();
+            subtile_main(kt + 1, 0, 2, 0, 0, 2, sa, sb);
+            subtile_main(kt + 1, 1, 2, 0, 1, 2, sb, sa);
+            tile_barrier();
+            subtile_main(kt + 2, 0, 0, 1, 1, 0, sa, sb);
+            subtile_main(kt + 2, 1, 0, 1, 2, 0, sb, sa);
+            tile_barrier();
+        }
+        if (n_main > 0) {
+            // the last sub-tile's P V is still owed: second half of V(n_main - 1), buffer 2
+            const elem *Vt = L0 + 2 * C::kVTile + 32;
+            ld_v(Vt, 0, f2);
+            ld_v(Vt, 1, f3);
+            mm_v(f2, pp0);
+            mm_v(f3, pp1);
+        }
+        kt0 = n_main;  // a multiple of three: K(kt0) and V(kt0) are in buffer 0 again
+    }
+    // Generic form of a tile (the tiles at the diagonal and the ragged end of the eight-wave
+    // kernel; every tile with fewer waves).  kb1, kb2: buffers of K(kt+1), K(kt+2); vb, vb1:
+    // buffers of V(kt), V(kt+1).
+    auto tile = [&](int kt, int kb1, int kb2, int vb, int vb1) __attribute__((always_inline)) {
         const int kb = kt * C::kBC;
         // wave-uniform: does the wave see any key of the sub-tile / must it mask some
         if (!CAUSAL || kb <= q0e + 31) {
-            subtile(kt, 0, kb1, kb2, (kb + 32 > Sk) || (CAUSAL && kb + 31 > q0e), sa, sb);
+            subtile(kt, 0, kb1, kb2, vb, vb1, (kb + 32 > Sk) || (CAUSAL && kb + 31 > q0e), sa, sb);
         } else {
             dma_k(kt + 2, kb2);
-            store_v((kt + 1) & 1);
+            store_v(vb1);
             load_v(kt + 2);
         }
         if (!CAUSAL || kb + 32 <= q0e + 31)
-            subtile(kt, 1, kb1, kb2, (kb + 64 > Sk) || (CAUSAL && kb + 63 > q0e), sb, sa);
-        __syncthreads();
+            subtile(kt, 1, kb1, kb2, vb, vb1, (kb + 64 > Sk) || (CAUSAL && kb + 63 > q0e), sb, sa);
+        tile_barrier();
     };
     if constexpr (NW == 8) {
-        for (int kt = 0; kt < n_kt; kt += 3) {  // n_kt is the same for every wave of the work-group
-            tile(kt, 1, 2);
-            if (kt + 1 < n_kt) tile(kt + 1, 2, 0);
-            if (kt + 2 < n_kt) tile(kt + 2, 0, 1);
+        // unrolled over the three buffers like the main loop (kt0 is a multiple of three)
+        for (int kt = kt0; kt < n_kt; kt += 3) {  // n_kt is the same for every wave of the work-group
+            tile(kt, 1, 2, 0, 1);
+            if (kt + 1 < n_kt) tile(kt + 1, 2, 0, 1, 2);
+            if (kt + 2 < n_kt) tile(kt + 2, 0, 1, 2, 0);
         }
     } else {
         // fewer waves stage more of each tile per wave and have no registers to spare for the
         // unrolled form: the buffer indices rotate at run time
-        int kb1 = 1, kb2 = 2, kb0 = 0;  // buffers of K(kt+1), K(kt+2), K(kt)
-        for (int kt = 0; kt < n_kt; ++kt) {
-            const int kb = kt * C::kBC;
-            if (!CAUSAL || kb <= q0e + 31) {
-                subtile(kt, 0, kb1, kb2, (kb + 32 > Sk) || (CAUSAL && kb + 31 > q0e), sa, sb);
-            } else {
-                dma_k(kt + 2, kb2);
-                store_v((kt + 1) & 1);
-                load_v(kt + 2);
-            }
-            if (!CAUSAL || kb + 32 <= q0e + 31)
-                subtile(kt, 1, kb1, kb2, (kb + 64 > Sk) || (CAUSAL && kb + 63 > q0e), sb, sa);
-            __syncthreads();
+        int kb1 = 1, kb2 = 2, kb0 = 0;
+        for (int kt = kt0; kt < n_kt; ++kt) {
+            tile(kt, kb1, kb2, kt & 1, (kt + 1) & 1);
             const int t = kb0; kb0 = kb1; kb1 = kb2; kb2 = t;
         }
     }
@@ -406,7 +545,6 @@ attn_fwd_kernel(const FwdArgs a)
                 }
             if (h == 0) a.LSEpart[row] = lt > 0.f ? (m + fast_log2(lt)) * kLn2 : -INFINITY;
         }
-        ATTN_CYCLES_END(0);
         return;
     }
     const float inv = 1.0f / lr;
@@ -422,7 +560,6 @@ attn_fwd_kernel(const FwdArgs a)
             }
         if (h == 0) a.LSE[(int64_t)bh * S + q] = (m + fast_log2(lt)) * kLn2;
     }
-    ATTN_CYCLES_END(0);
 }
 
 // Combine the per-split partial results: LSE = log sum_z exp(LSE_z), O = sum_z exp(LSE_z - LSE) O_z.
@@ -521,14 +658,6 @@ static int launch_fwd_d(FwdArgs a, bool causal, hipStream_t st)
     }
     return -1;
 }
-
-#if defined(ATTN_CYCLES) && !defined(ATTN_F16)
-extern "C" void attn_debug_cycles_fwd(unsigned long long *out, int reset)
-{
-    hipMemcpyFromSymbol(out, HIP_SYMBOL(g_attn_cycles), sizeof(g_attn_cycles));
-    if (reset) { unsigned long long z[4][4] = {}; hipMemcpyToSymbol(HIP_SYMBOL(g_attn_cycles), z, sizeof(z)); }
-}
-#endif
 
 // Split the keys when the unsplit launch would leave compute units (256) idle: aim at one
 // work-group per unit.  (Measured on the decode shape: 256 work-groups with long key ranges

@@ -9,7 +9,7 @@ import torch
 import oracle
 import paper_2601_16238_amd as attn
 from paper_2601_16238_amd import workloads as wl
-from parity_util import check_bf16, check_bf16_scaled, check_lse, to_dev, to_f64
+from parity_util import check_bf16, check_grad, check_lse, to_dev, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -54,7 +54,7 @@ def test_headdim_parity_in_padded_poisoned_buffers(B, Hq, Hkv, Sq, Sk, D, causal
         if min(Sq, Sk) < 32 or D < 32:
             check_bf16(name, to_f64(g), r, floor_gate=False)
         else:
-            check_bf16_scaled(name, to_f64(g), r)
+            check_grad(name, to_f64(g), r)
 
 
 def test_headdim_96_equals_zero_padded_128_bitwise():

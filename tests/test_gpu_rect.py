@@ -9,7 +9,7 @@ import torch
 import oracle
 import paper_2601_16238_amd as attn
 from paper_2601_16238_amd import workloads as wl
-from parity_util import check_bf16, check_bf16_scaled, check_lse, to_dev, to_f64
+from parity_util import check_bf16, check_grad, check_lse, to_dev, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -47,7 +47,7 @@ def test_rect_parity(B, Hq, Hkv, Sq, Sk, D, causal):
             # test_gpu_bwd); with one key the exact dQ and dK are zero
             check_bf16(name, to_f64(g), r, floor_gate=False)
         else:
-            check_bf16_scaled(name, to_f64(g), r)
+            check_grad(name, to_f64(g), r)
 
 
 @pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D,causal", [
@@ -156,9 +156,9 @@ def test_rect_full_size_sampled_heads():
             check_bf16("O", to_f64(O[b, qs]), Oref[0])
             check_lse(to_f64(LSE[b, qs]), Lref[0])
             if w.Sq >= 32:
-                check_bf16_scaled("dQ", to_f64(dQ[b, qs]), ref[0][0])
-                check_bf16_scaled("dK", to_f64(dK[b, hk]), ref[1][0, 0])
-                check_bf16_scaled("dV", to_f64(dV[b, hk]), ref[2][0, 0])
+                check_grad("dQ", to_f64(dQ[b, qs]), ref[0][0])
+                check_grad("dK", to_f64(dK[b, hk]), ref[1][0, 0])
+                check_grad("dV", to_f64(dV[b, hk]), ref[2][0, 0])
             else:
                 check_bf16("dQ", to_f64(dQ[b, qs]), ref[0][0], floor_gate=False)
                 check_bf16("dK", to_f64(dK[b, hk]), ref[1][0, 0], floor_gate=False)

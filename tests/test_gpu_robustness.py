@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_2601_16238_amd as attn
 from paper_2601_16238_amd import workloads as wl
-from parity_util import check_bf16, check_lse, to_dev, to_f64
+from parity_util import check_bf16, check_grad, check_lse, to_dev, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -78,6 +78,38 @@ def test_bshd_strides_and_side_stream():
     check_lse(to_f64(LSE), Lref)
     for nm, t, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), ref):
         check_bf16(nm, to_f64(t), r)
+
+
+def test_explicit_stream_without_stream_context():
+    """stream= given while torch's current stream is another one: outputs and workspaces that
+    the binding allocates itself must belong to the stream the kernels run on.  While the side
+    stream works, the current stream allocates and overwrites buffers of the workspace's size;
+    if the workspace had been handed back to the current stream's pool, one of them would land
+    on it."""
+    print("case explicit_stream", flush=True)
+    B, H, S, D, causal = 2, 4, 1500, 128, True
+    x = wl.random_inputs(B, H, S, D, seed=47)
+    Q, K, V, dO = (to_dev(x[k]) for k in ("Q", "K", "V", "dO"))
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream()
+    results = []
+    for _ in range(5):
+        O, LSE = attn.attn_fwd(Q, K, V, x["scale"], causal, stream=st)
+        dQ, dK, dV = attn.attn_bwd(Q, K, V, O, dO, LSE, x["scale"], causal, stream=st)
+        # work of the current stream that would reuse a block freed to its pool
+        junk = [torch.full((attn.attn_bwd_workspace_bytes(B, H, S, D) // 4,), float("nan"),
+                           device="cuda") for _ in range(4)]
+        results.append((O, LSE, dQ, dK, dV))
+        del junk
+    st.synchronize()
+    torch.cuda.synchronize()
+    Oref, Lref = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], causal)
+    ref = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], causal)
+    for O, LSE, dQ, dK, dV in results:
+        check_bf16("O", to_f64(O), Oref)
+        check_lse(to_f64(LSE), Lref)
+        for nm, t, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), ref):
+            check_grad(nm, to_f64(t), r)
 
 
 def test_isolated_backward_from_oracle_O_and_LSE():
