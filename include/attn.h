@@ -212,6 +212,27 @@ int attn_bwd_rect(const void *Q, const void *K, const void *V, const void *O, co
                   const attn_rect_params_t *p, void *hip_stream);
 
 /*
+ * attn_bwd_rect for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * backward's scratch (two fp32 values per query row) lives in an array inside the library's
+ * device image, ATTN_NOALLOC_SCRATCH_BYTES long; each GPU the library runs on holds its own
+ * copy until the process ends.  Arguments, results (bit for bit those of attn_bwd_rect),
+ * validation and stream semantics are those of attn_bwd_rect without the workspace pair.
+ *   - Problems with more than ATTN_NOALLOC_SCRATCH_BYTES / 8 query rows (B*Hq*Sq) give
+ *     ATTN_ERR_WORKSPACE; nothing is launched.
+ *   - The call allocates and frees nothing.  The first call on a device asks the runtime for
+ *     the array's address on that device (make that call outside graph capture); failure to
+ *     obtain it gives ATTN_ERR_LAUNCH.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ *     (different streams, or threads) race on it and give wrong results.  Calls on one stream,
+ *     one after the other, are safe; nothing has to be cleared between them.
+ */
+#define ATTN_NOALLOC_SCRATCH_BYTES (8u << 20)
+int attn_bwd_rect_noalloc(const void *Q, const void *K, const void *V, const void *O,
+                          const void *dO, const float *LSE, void *dQ, void *dK, void *dV,
+                          const attn_rect_params_t *p, void *hip_stream);
+
+/*
  * IEEE fp16 variant of the rectangular entry points (the paper's kernels are written for
  * fp16/bf16 inputs): Q, K, V, O, dO, dQ, dK, dV hold fp16 instead of bf16; LSE, the
  * workspaces (same sizes, same *_workspace_bytes functions), parameters, errors and stream

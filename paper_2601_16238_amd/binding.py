@@ -25,7 +25,9 @@ EXPORTS = ("attn_params_contiguous", "attn_fwd", "attn_bwd_workspace_bytes", "at
            "attn_bwd_gqa_workspace_bytes", "attn_bwd_gqa", "attn_bwd_gqa_stages",
            "attn_rect_params_contiguous", "attn_fwd_rect_workspace_bytes", "attn_fwd_rect",
            "attn_bwd_rect_workspace_bytes", "attn_bwd_rect", "attn_fwd_rect_f16",
-           "attn_bwd_rect_f16", "attn_probe_mfma_bf16", "attn_status_string", "attn_version")
+           "attn_bwd_rect_f16", "attn_bwd_rect_noalloc", "attn_probe_mfma_bf16",
+           "attn_status_string", "attn_version")
+NOALLOC_SCRATCH_BYTES = 8 << 20
 STAGE_DELTA, STAGE_DKDV, STAGE_DQ = 1, 2, 4
 STAGE_ALL = 7
 
@@ -122,6 +124,8 @@ def lib():
         L.attn_fwd_rect_f16.restype = ctypes.c_int
         L.attn_bwd_rect_f16.argtypes = L.attn_bwd_rect.argtypes
         L.attn_bwd_rect_f16.restype = ctypes.c_int
+        L.attn_bwd_rect_noalloc.argtypes = [vp] * 9 + [rp, vp]
+        L.attn_bwd_rect_noalloc.restype = ctypes.c_int
         L.attn_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t,
                                            ctypes.POINTER(ctypes.c_double), vp]
         L.attn_probe_mfma_bf16.restype = ctypes.c_int
@@ -166,11 +170,23 @@ def make_params(B, H, S, D, scale, causal, strides=None):
     return p
 
 
+def _strides3(t):
+    """(stride_b, stride_h, stride_s) of a [B,H,S,D] tensor in elements.  The stride of an axis
+    of length 1 is never used to address anything and may hold any value (numpy and torch both
+    leave it arbitrary): it is replaced by the one a dense tensor would have, which always
+    passes the library's stride checks."""
+    B, H, S, D = t.shape
+    ss = t.stride(2) if S > 1 else D
+    sh = t.stride(1) if H > 1 else S * ss
+    sb = t.stride(0) if B > 1 else H * sh
+    return sb, sh, ss
+
+
 def _params_for(t, scale, causal):
     if t.dim() != 4 or t.stride(3) != 1:
         raise ValueError("expected a [B,H,S,D] tensor with a contiguous D axis")
     B, H, S, D = t.shape
-    return make_params(B, H, S, D, scale, causal, (t.stride(0), t.stride(1), t.stride(2)))
+    return make_params(B, H, S, D, scale, causal, _strides3(t))
 
 
 def _same_layout(ref, *ts):
@@ -324,7 +340,7 @@ def _gqa_params_for(q, k, scale, causal):
     B, Hq, S, D = q.shape
     if k.shape[0] != B or k.shape[2] != S or k.shape[3] != D:
         raise ValueError("K/V must be [B,Hkv,S,D] matching Q in B, S and D")
-    return make_gqa_params(B, Hq, k.shape[1], S, D, scale, causal, q.stride()[:3], k.stride()[:3])
+    return make_gqa_params(B, Hq, k.shape[1], S, D, scale, causal, _strides3(q), _strides3(k))
 
 
 def attn_fwd_gqa(Q, K, V, scale, causal, O=None, LSE=None, stream=None):
@@ -373,7 +389,7 @@ def _rect_params_for(q, k, scale, causal):
     if k.shape[0] != B or k.shape[3] != D:
         raise ValueError("K/V must be [B,Hkv,Sk,D] matching Q in B and D")
     return make_rect_params(B, Hq, k.shape[1], Sq, k.shape[2], D, scale, causal,
-                            q.stride()[:3], k.stride()[:3])
+                            _strides3(q), _strides3(k))
 
 
 def attn_fwd_rect_workspace_bytes(B, Hq, Hkv, Sq, Sk, D, causal=False):
@@ -408,3 +424,22 @@ def attn_bwd_rect(Q, K, V, O, dO, LSE, scale, causal, dQ=None, dK=None, dV=None,
     return _backward("attn_bwd_rect", entry, _rect_params_for(Q, K, scale, causal),
                      lib().attn_bwd_rect_workspace_bytes, Q, K, V, O, dO, LSE, dQ, dK, dV,
                      workspace, stream, _elem_types(torch))
+
+
+def attn_bwd_rect_noalloc(Q, K, V, O, dO, LSE, scale, causal, dQ, dK, dV, stream=None):
+    """attn_bwd_rect through the entry point that uses the library's static scratch: the
+    caller passes every output, nothing is allocated here or in the library."""
+    import torch
+    if Q.dtype != torch.bfloat16 or not Q.is_cuda:
+        raise ValueError("tensors must be bf16 on the GPU")
+    _same_layout(Q, O, dO, dQ)
+    _same_layout(K, V, dK, dV)
+    B, H, S, D = Q.shape
+    _check_lse(torch, LSE, (B, H, S))
+    p = _rect_params_for(Q, K, scale, causal)
+    rc = lib().attn_bwd_rect_noalloc(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(),
+                                     dO.data_ptr(), LSE.data_ptr(), dQ.data_ptr(), dK.data_ptr(),
+                                     dV.data_ptr(), ctypes.byref(p), _stream_ptr(torch, stream))
+    if rc != ATTN_OK:
+        raise AttnError(rc, "attn_bwd_rect_noalloc")
+    return dQ, dK, dV

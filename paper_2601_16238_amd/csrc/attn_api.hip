@@ -4,6 +4,7 @@
 
 #include <cmath>
 #include <limits>
+#include <mutex>
 
 namespace {
 
@@ -344,6 +345,56 @@ int attn_bwd_stages(const void *Q, const void *K, const void *V, const void *O, 
                                hip_stream, stages);
 }
 
+}  // extern "C"
+
+// Scratch of attn_bwd_rect_noalloc: the backward's row statistics, in an array that lives in
+// the library's device image instead of in memory the caller allocates.  Every GPU the library
+// runs on holds its own copy at its own address, so the address is looked up once per device
+// (with that device current) and kept; host code uses that pointer, never the array's name.
+static __device__ __align__(256) unsigned char scratch[ATTN_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];  // guarded by g_scratch_mutex; nullptr = not looked up yet
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device, or nullptr if the runtime refuses.
+void *scratch_of_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" {
+
+int attn_bwd_rect_noalloc(const void *Q, const void *K, const void *V, const void *O,
+                          const void *dO, const float *LSE, void *dQ, void *dK, void *dV,
+                          const attn_rect_params_t *p, void *hip_stream)
+{
+    // the same checks as attn_bwd_rect, before anything touches the device
+    if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_NULL;
+    const int rc = check_params(p);
+    if (rc != ATTN_OK) return rc;
+    const size_t need = attn_bwd_rect_workspace_bytes(p);
+    if (need == 0 || need > (size_t)ATTN_NOALLOC_SCRATCH_BYTES) return ATTN_ERR_WORKSPACE;
+    void *ws = scratch_of_current_device();
+    if (!ws) return ATTN_ERR_LAUNCH;
+    // Every value of the scratch that a kernel reads is written earlier in the same call (the
+    // dQ kernel stores the statistics of every query row, the dK/dV kernel reads only those),
+    // so nothing has to be cleared although the array keeps the last call's contents.
+    return bwd_impl<__bf16>(Q, K, V, O, dO, LSE, dQ, dK, dV, ws, ATTN_NOALLOC_SCRATCH_BYTES, p,
+                            hip_stream,
+                            ATTN_BWD_STAGE_DELTA | ATTN_BWD_STAGE_DKDV | ATTN_BWD_STAGE_DQ);
+}
+
 const char *attn_status_string(int status)
 {
     switch (status) {
@@ -359,6 +410,6 @@ const char *attn_status_string(int status)
     }
 }
 
-int attn_version(void) { return 1004; }
+int attn_version(void) { return 1005; }
 
 }  // extern "C"

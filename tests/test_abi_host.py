@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported_and_bound():
 
 
 def test_version_and_status_strings():
-    assert attn.attn_version() == 1004
+    assert attn.attn_version() == 1005
     seen = set()
     for code in range(0, -8, -1):
         s = attn.status_string(code)
