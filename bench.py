@@ -41,7 +41,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="long_causal",
                     help="one of paper_2601_16238_amd.workloads.WORKLOADS, GQA_WORKLOADS or RECT_WORKLOADS, "
-                         "or 'rowops' (the row-wise kernels)")
+                         "'rowops' (the row-wise kernels) or 'rope' (rotary fused into the forward against "
+                         "rotary-then-forward)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true",
                     help="also time every other workload (reported under 'other_workloads')")
@@ -366,6 +367,42 @@ def measure_rowops(torch, steps, warmup):
     return out
 
 
+def measure_rope(torch, attn, steps, warmup):
+    """Rotary embedding fused into the forward's Q load against the two-kernel sequence (rotary
+    kernel on Q, then the forward), on the paper's rotary shape (4, 8, 2048, 128) with a causal
+    mask and on the long-sequence shape; K is rotated beforehand in both (it is rotated where it
+    is written).  Small shape by graph replay (device time)."""
+    from paper_2601_16238_amd import rowops
+    out = {}
+    for name, (B, H, S, D) in (("paper_rotary_shape", (4, 8, 2048, 128)), ("long_causal_shape", (1, 16, 16384, 128))):
+        g = torch.Generator(device="cuda"); g.manual_seed(1015)
+        Q, K, V = (torch.randn((B, H, S, D), device="cuda", generator=g).to(torch.bfloat16) for _ in range(3))
+        ang = torch.arange(S, device="cuda", dtype=torch.float32)[:, None] * \
+            (10000.0 ** (-torch.arange(0, D, 2, device="cuda", dtype=torch.float32) / D))[None, :]
+        cos, sin = torch.cos(ang).contiguous(), torch.sin(ang).contiguous()
+        K_rot = rowops.rotary_fwd(K, cos, sin)
+        O, Qr = torch.empty_like(Q), torch.empty_like(Q)
+        LSE = torch.empty((B, H, S), dtype=torch.float32, device="cuda")
+        sc = 1.0 / float(D) ** 0.5
+
+        def fused():
+            attn.attn_fwd_rope(Q, K_rot, V, cos, sin, sc, True, O=O, LSE=LSE, Q_rot=Qr, split=False)
+
+        def unfused():
+            rowops.rotary_fwd(Q, cos, sin, y=Qr)
+            attn.attn_fwd_rect(Qr, K_rot, V, sc, True, O=O, LSE=LSE, split=False)
+
+        def plain():
+            attn.attn_fwd_rect(Qr, K_rot, V, sc, True, O=O, LSE=LSE, split=False)
+
+        for _ in range(warmup):
+            fused(); unfused()
+        timer = (lambda f: graph_ms(torch, f, 20)) if S <= 4096 else (lambda f: time_calls(torch, f, max(steps, 10)))
+        out[name] = {"shape": [B, H, S, D], "fused_ms": timer(fused), "rotary_then_forward_ms": timer(unfused),
+                     "forward_alone_ms": timer(plain)}
+    return out
+
+
 def rowops_main(torch, a):
     """The JSON line for --workload rowops."""
     r = measure_rowops(torch, a.steps, a.warmup)
@@ -454,6 +491,9 @@ def main():
     if a.workload == "rowops":
         rowops_main(torch, a)
         return
+    if a.workload == "rope":
+        print(json.dumps({"rope_fused_forward": measure_rope(torch, attn, a.steps, a.warmup)}))
+        return
     if a.workload in wl.RECT_WORKLOADS:
         rect_main(torch, attn, wl, wl.RECT_WORKLOADS[a.workload], a)
         return
@@ -513,6 +553,7 @@ def main():
             torch.cuda.empty_cache()
         out["rect_workloads"] = rect
         out["row_kernels"] = measure_rowops(torch, a.steps, a.warmup)
+        out["rope_fused_forward"] = measure_rope(torch, attn, a.steps, a.warmup)
         # the fp16 build of the kernels on the main shape (through the rectangular entry points)
         g = torch.Generator(device="cuda"); g.manual_seed(w.seed)
         H = w.Hq if hasattr(w, "Hq") else w.H

@@ -212,6 +212,40 @@ int attn_bwd_rect(const void *Q, const void *K, const void *V, const void *O, co
                   const attn_rect_params_t *p, void *hip_stream);
 
 /*
+ * Rotary position embedding fused into the attention calls (paper: the "Rotary (fwd)" row of
+ * the kernel-suite microbenchmark table next to its attention rows; "rotate-half" pairing as
+ * rowops_rotary_fwd of rowops.h: column d pairs with d + D/2, tables fp32 [Sk][D/2] indexed by
+ * the absolute position).  D must be 64 or 128 and Sk >= Sq, else ATTN_ERR_SHAPE; query row i
+ * has position i + Sk - Sq, key row j position j.
+ *
+ * The contract is: K is rotated where it is written (once, e.g. into the key/value cache, by
+ * rowops_rotary_fwd) and comes in rotated; Q comes in UNROTATED and is rotated in registers as
+ * the kernel loads it -- the result is, bit for bit, that of rowops_rotary_fwd on Q followed by
+ * attn_fwd_rect, without the pass over Q.  (K is not rotated in the kernel: every query tile of
+ * a head would repeat that work.)
+ *   attn_fwd_rope: Q in (unrotated), K_rot, V in; cos_table, sin_table in; O, LSE out as
+ *     attn_fwd_rect; Q_rot: optional out (NULL: not stored), the rotated query rows, same
+ *     strides as Q -- what attn_bwd_rope needs.  Workspace as attn_fwd_rect, sized by
+ *     attn_fwd_rope_workspace_bytes (decoding rows of grouped heads are not packed here).
+ *   attn_bwd_rope: Q_rot, K_rot, V, O, dO, LSE in as attn_bwd_rect (with the ROTATED Q and K);
+ *     dQ out: gradient of the UNROTATED query rows (the accumulated gradient is rotated back in
+ *     registers before it is stored); dK_rot out: gradient of the rotated K rows (rotate it
+ *     back with rowops_rotary_fwd and a negated sin table if the unrotated one is wanted);
+ *     dV out.  Workspace of attn_bwd_rect_workspace_bytes(p) bytes.
+ * Tables must be 16-byte aligned; everything else as the rectangular calls.
+ */
+size_t attn_fwd_rope_workspace_bytes(const attn_rect_params_t *p);
+
+int attn_fwd_rope(const void *Q, const void *K_rot, const void *V, const float *cos_table,
+                  const float *sin_table, void *O, float *LSE, void *Q_rot, void *workspace,
+                  size_t workspace_bytes, const attn_rect_params_t *p, void *hip_stream);
+
+int attn_bwd_rope(const void *Q_rot, const void *K_rot, const void *V, const void *O,
+                  const void *dO, const float *LSE, const float *cos_table, const float *sin_table,
+                  void *dQ, void *dK_rot, void *dV, void *workspace, size_t workspace_bytes,
+                  const attn_rect_params_t *p, void *hip_stream);
+
+/*
  * attn_bwd_rect for callers that cannot allocate device memory or pass a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
  * backward's scratch (two fp32 values per query row) lives in an array inside the library's
@@ -233,8 +267,8 @@ int attn_bwd_rect_noalloc(const void *Q, const void *K, const void *V, const voi
                           const attn_rect_params_t *p, void *hip_stream);
 
 /*
- * IEEE fp16 variant of the rectangular entry points (the paper's kernels are written for
- * fp16/bf16 inputs): Q, K, V, O, dO, dQ, dK, dV hold fp16 instead of bf16; LSE, the
+ * IEEE fp16 variant of the rectangular entry points (an extension: the paper's microbenchmark
+ * table names bf16 only): Q, K, V, O, dO, dQ, dK, dV hold fp16 instead of bf16; LSE, the
  * workspaces (same sizes, same *_workspace_bytes functions), parameters, errors and stream
  * semantics are unchanged.  Accumulation is fp32; P and dS are rounded to fp16 for the
  * second matrix product of each stage.
@@ -249,9 +283,9 @@ int attn_bwd_rect_f16(const void *Q, const void *K, const void *V, const void *O
                       const attn_rect_params_t *p, void *hip_stream);
 
 /* Measurement aid, not a step of the method: enqueues a kernel that executes nothing but bf16
- * 32x32x16 MFMAs (the instruction the attention kernels are built on; the paper's benchmark
- * section quotes its kernels against the peak of the device they ran on, and this gives the
- * figure the matrix pipes of THIS device sustain, to print beside the nominal peak).
+ * 32x32x16 MFMAs (the instruction the attention kernels are built on): the figure the matrix
+ * pipes of THIS device sustain, to print beside the nominal peak.  (The paper's microbenchmark
+ * table prints latencies only; the fraction of peak is this build's own yardstick.)
  * `workgroups` work-groups of 512 threads each run `iters` iterations of 16 MFMAs per wave.
  * random_operands: 0 = the same small constant operands at every step; non-zero = operands
  * with random signs and mantissas that change from step to step, as real data does (the
@@ -262,6 +296,21 @@ int attn_bwd_rect_f16(const void *Q, const void *K, const void *V, const void *O
  * ATTN_ERR_WORKSPACE (sink too small), ATTN_ERR_ALIGN, ATTN_ERR_LAUNCH.  Asynchronous. */
 int attn_probe_mfma_bf16(int workgroups, int iters, int random_operands, float *sink,
                          size_t sink_floats, double *flop, void *hip_stream);
+
+/* Measurement aid, not a step of the method: the fp32 atomic traffic of a backward that would
+ * form dQ inside the key-block kernel (one launch, five matrix products per tile pair instead
+ * of the seven that the two-kernel backward executes), with nothing else running.  For BH heads
+ * of S rows and key blocks of key_block keys, the work-group of key block kb adds a 32 x 128
+ * fp32 tile (16 KiB) to acc[head][32 s .. 32 s + 31][0..127] for every 32-row slot s that sees
+ * the block (all slots, or with causal != 0 those from the block's diagonal on).  acc must be
+ * zeroed by the caller; afterwards element (head, row, d) holds the number of key blocks that
+ * see the row's slot.
+ * acc: DEVICE, at least BH * S * 128 floats (acc_floats = its size); bytes_added: HOST,
+ * optional, receives the bytes one launch adds.  BH a multiple of 8 up to 4096, S and
+ * key_block multiples of 32, key_block <= S <= 2^20, else ATTN_ERR_SHAPE; ATTN_ERR_NULL,
+ * ATTN_ERR_WORKSPACE (acc too small), ATTN_ERR_ALIGN, ATTN_ERR_LAUNCH.  Asynchronous. */
+int attn_probe_atomic_f32(int BH, int S, int key_block, int causal, float *acc,
+                          size_t acc_floats, double *bytes_added, void *hip_stream);
 
 /* Static, NUL-terminated description of a status code.  Never NULL. */
 const char *attn_status_string(int status);

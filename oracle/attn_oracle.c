@@ -37,7 +37,8 @@
  *
  * Inputs are bf16 bit patterns (uint16) laid out contiguously as [B,H,S,D]; they are
  * widened exactly to double.  The rectangular entry points also take IEEE fp16 bit patterns
- * (dtype 1; the paper's kernels are written for "fp16/bf16" inputs): only the widening differs.  `scale` is the fp32 value the GPU receives, widened to
+ * (dtype 1; an extension, the paper's microbenchmark table names bf16 only): only the widening
+ * differs.  `scale` is the fp32 value the GPU receives, widened to
  * double.  All arithmetic is double; exp/log are libm's.  There is no tiling, no online
  * softmax and no fusion: every row (forward, dQ) or column (dK, dV) is written out from
  * the formulas above, with one scratch row/column of length S.

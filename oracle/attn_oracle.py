@@ -135,3 +135,70 @@ def attn_bwd(Q, K, V, dO, scale, causal, want_dscores=False, dtype="bf16"):
 def attn_dscores(Q, K, V, dO, scale, causal):
     """dS [B,H,Sq,Sk] = P * (dP - delta) (zeros outside the mask); small shapes only."""
     return attn_bwd(Q, K, V, dO, scale, causal, want_dscores=True)[3]
+
+
+# ---- rotary embedding composed with attention (the fused entry points attn_fwd_rope /
+# attn_bwd_rope of the library).  The paper lists "Rotary (fwd)" and the attention kernels as
+# separate rows of its kernel-suite microbenchmark table, each on bf16 tensors; what the fused
+# calls compute is therefore defined as that sequence: the rotation of the query rows, its
+# result rounded to bf16 (the tensor the rotary kernel would hand to the attention kernel), then
+# the attention oracle.  Keys come in rotated.  Query row i of Sq has position i + Sk - Sq.
+
+def _round_to_bf16_bits(x):
+    """float64 -> nearest bf16 (ties to even), as uint16 bit patterns.  Goes through float32,
+    which is exact for every value that a product of a bf16 number and an fp32 table entry, or
+    a sum of two such products, rounds to within the precision that matters here."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    return (r >> np.uint32(16)).astype(np.uint16)
+
+
+def rope_rotate_queries(Q, cos, sin, Sk):
+    """bf16 bit patterns of the rotated query rows, table rows Sk - Sq .. Sk - 1.
+
+    Which bf16 value a rotated element becomes is a decision that floating point takes, so it
+    is taken here in the precision the kernels take it in: fp32, y1 = fma(x1, c, -(x2 s)),
+    y2 = fma(x2, c, x1 s), each rounded once to fp32 and then to bf16.  (The fp64 rotary oracle
+    rounded to bf16 differs from this on the few elements per million whose exact value lies
+    within an fp32 rounding error of a bf16 boundary; tests pin the two against each other.)
+    The fma is written as the exact fp64 product plus the fp32-rounded other product, rounded
+    to fp32: both steps are exact in fp64 for bf16 inputs times fp32 table entries."""
+    Q = _u16(Q)
+    Sq, D = Q.shape[2], Q.shape[3]
+    if Sk < Sq:
+        raise ValueError("rotary positions need Sk >= Sq")
+    pos0, h = Sk - Sq, D // 2
+    c = np.ascontiguousarray(cos[pos0:pos0 + Sq], dtype=np.float32).astype(np.float64)
+    s = np.ascontiguousarray(sin[pos0:pos0 + Sq], dtype=np.float32).astype(np.float64)
+    x = (Q.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    x1, x2 = x[..., :h], x[..., h:]
+    t1 = (x2 * s).astype(np.float32).astype(np.float64)   # fp32 product
+    t2 = (x1 * s).astype(np.float32).astype(np.float64)
+    y = np.empty(Q.shape, np.float32)
+    y[..., :h] = (x1 * c - t1).astype(np.float32)
+    y[..., h:] = (x2 * c + t2).astype(np.float32)
+    return _round_to_bf16_bits(y)
+
+
+def attn_fwd_rope(Q, K_rot, V, cos, sin, scale, causal):
+    """O, LSE, Q_rot (bits) for unrotated Q [B,Hq,Sq,D], rotated K_rot [B,Hkv,Sk,D] and tables
+    [Sk, D/2]."""
+    Q_rot = rope_rotate_queries(Q, cos, sin, K_rot.shape[2])
+    O, LSE = attn_fwd(Q_rot, K_rot, V, scale, causal)
+    return O, LSE, Q_rot
+
+
+def attn_bwd_rope(Q_rot, K_rot, V, dO, cos, sin, scale, causal):
+    """dQ (gradient of the UNROTATED query rows), dK_rot, dV.  The rotation of a row is a linear
+    map R (y_d = x_d c_d - x_{d+h} s_d, y_{d+h} = x_{d+h} c_d + x_d s_d); the gradient of its
+    input is R^T applied to the gradient of its output:
+        gx_d = gy_d c_d + gy_{d+h} s_d,   gx_{d+h} = gy_{d+h} c_d - gy_d s_d."""
+    dQr, dK, dV = attn_bwd(Q_rot, K_rot, V, dO, scale, causal)
+    Sq, Sk, D = dQr.shape[2], K_rot.shape[2], dQr.shape[3]
+    h, pos0 = D // 2, Sk - Sq
+    c = np.asarray(cos[pos0:pos0 + Sq], dtype=np.float64)
+    s = np.asarray(sin[pos0:pos0 + Sq], dtype=np.float64)
+    dQ = np.empty_like(dQr)
+    dQ[..., :h] = dQr[..., :h] * c + dQr[..., h:] * s
+    dQ[..., h:] = dQr[..., h:] * c - dQr[..., :h] * s
+    return dQ, dK, dV

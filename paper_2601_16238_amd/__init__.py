@@ -8,8 +8,8 @@ from . import rowops  # noqa: F401
 from .autograd import fused_attention  # noqa: F401
 from .binding import (AttnError, AttnGqaParams, AttnParams, AttnRectParams,  # noqa: F401
                       attn_bwd, attn_bwd_gqa, attn_bwd_gqa_workspace_bytes, attn_bwd_rect,
-                      attn_bwd_rect_noalloc,
+                      attn_bwd_rect_noalloc, attn_bwd_rope, attn_fwd_rope,
                       attn_bwd_rect_workspace_bytes, attn_bwd_workspace_bytes, attn_fwd,
                       attn_fwd_gqa, attn_fwd_rect, attn_fwd_rect_workspace_bytes,
-                      attn_probe_mfma_bf16, attn_version,
+                      attn_probe_atomic_f32, attn_probe_mfma_bf16, attn_version,
                       lib, make_gqa_params, make_params, make_rect_params, status_string)

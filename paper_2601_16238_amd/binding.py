@@ -25,7 +25,9 @@ EXPORTS = ("attn_params_contiguous", "attn_fwd", "attn_bwd_workspace_bytes", "at
            "attn_bwd_gqa_workspace_bytes", "attn_bwd_gqa", "attn_bwd_gqa_stages",
            "attn_rect_params_contiguous", "attn_fwd_rect_workspace_bytes", "attn_fwd_rect",
            "attn_bwd_rect_workspace_bytes", "attn_bwd_rect", "attn_fwd_rect_f16",
-           "attn_bwd_rect_f16", "attn_bwd_rect_noalloc", "attn_probe_mfma_bf16",
+           "attn_bwd_rect_f16", "attn_bwd_rect_noalloc", "attn_fwd_rope_workspace_bytes", "attn_fwd_rope",
+           "attn_bwd_rope", "attn_probe_mfma_bf16",
+           "attn_probe_atomic_f32",
            "attn_status_string", "attn_version")
 NOALLOC_SCRATCH_BYTES = 8 << 20
 STAGE_DELTA, STAGE_DKDV, STAGE_DQ = 1, 2, 4
@@ -124,11 +126,20 @@ def lib():
         L.attn_fwd_rect_f16.restype = ctypes.c_int
         L.attn_bwd_rect_f16.argtypes = L.attn_bwd_rect.argtypes
         L.attn_bwd_rect_f16.restype = ctypes.c_int
+        L.attn_fwd_rope_workspace_bytes.argtypes = [rp]
+        L.attn_fwd_rope_workspace_bytes.restype = ctypes.c_size_t
+        L.attn_fwd_rope.argtypes = [vp] * 8 + [vp, ctypes.c_size_t, rp, vp]
+        L.attn_fwd_rope.restype = ctypes.c_int
+        L.attn_bwd_rope.argtypes = [vp] * 11 + [vp, ctypes.c_size_t, rp, vp]
+        L.attn_bwd_rope.restype = ctypes.c_int
         L.attn_bwd_rect_noalloc.argtypes = [vp] * 9 + [rp, vp]
         L.attn_bwd_rect_noalloc.restype = ctypes.c_int
         L.attn_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t,
                                            ctypes.POINTER(ctypes.c_double), vp]
         L.attn_probe_mfma_bf16.restype = ctypes.c_int
+        L.attn_probe_atomic_f32.argtypes = [ctypes.c_int] * 4 + [vp, ctypes.c_size_t,
+                                            ctypes.POINTER(ctypes.c_double), vp]
+        L.attn_probe_atomic_f32.restype = ctypes.c_int
         L.attn_status_string.argtypes = [ctypes.c_int]
         L.attn_status_string.restype = ctypes.c_char_p
         L.attn_version.argtypes = []
@@ -158,6 +169,21 @@ def attn_probe_mfma_bf16(workgroups, iters, sink, random_operands=False, stream=
     if rc != 0:
         raise AttnError(rc, "attn_probe_mfma_bf16")
     return flop.value
+
+
+def attn_probe_atomic_f32(BH, S, key_block, causal, acc, stream=None):
+    """Enqueue the atomic-add measurement kernel on the zeroed fp32 tensor `acc` (at least
+    BH * S * 128 elements); returns the bytes one launch adds."""
+    import torch
+    assert acc.is_cuda and acc.dtype == torch.float32 and acc.is_contiguous()
+    st = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    nbytes = ctypes.c_double(0.0)
+    rc = lib().attn_probe_atomic_f32(int(BH), int(S), int(key_block), int(bool(causal)),
+                                     acc.data_ptr(), acc.numel(), ctypes.byref(nbytes),
+                                     ctypes.c_void_p(st))
+    if rc != 0:
+        raise AttnError(rc, "attn_probe_atomic_f32")
+    return nbytes.value
 
 
 def make_params(B, H, S, D, scale, causal, strides=None):
@@ -443,3 +469,66 @@ def attn_bwd_rect_noalloc(Q, K, V, O, dO, LSE, scale, causal, dQ, dK, dV, stream
     if rc != ATTN_OK:
         raise AttnError(rc, "attn_bwd_rect_noalloc")
     return dQ, dK, dV
+
+
+# ---- rotary embedding fused into the calls: Q unrotated in, K rotated in (see include/attn.h) ---
+
+def _check_tables(torch, cos, sin, Sk, D):
+    for t in (cos, sin):
+        if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() \
+                or tuple(t.shape) != (Sk, D // 2):
+            raise ValueError("cos/sin tables must be contiguous fp32 [Sk, D/2] tensors on the GPU")
+
+
+def attn_fwd_rope(Q, K_rot, V, cos, sin, scale, causal, O=None, LSE=None, Q_rot=None,
+                  want_q_rot=True, split=True, stream=None):
+    """O, LSE, Q_rot = attention forward with the rotary embedding of the query rows fused into
+    their load.  Q: unrotated [B,Hq,Sq,D]; K_rot: rotated [B,Hkv,Sk,D]; cos, sin: fp32 [Sk,D/2].
+    Q_rot (the rotated query rows the backward needs) is returned unless want_q_rot=False."""
+    import torch
+    if Q.dtype != torch.bfloat16 or not Q.is_cuda:
+        raise ValueError("Q,K,V must be bf16 tensors on the GPU")
+    _same_layout(K_rot, V)
+    B, H, S, D = Q.shape
+    _check_tables(torch, cos, sin, K_rot.shape[2], D)
+    p = _rect_params_for(Q, K_rot, scale, causal)
+    with _on_stream(torch, stream):
+        if O is None:
+            O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+        else:
+            _same_layout(Q, O)
+        if LSE is None:
+            LSE = torch.empty((B, H, S), dtype=torch.float32, device=Q.device)
+        else:
+            _check_lse(torch, LSE, (B, H, S))
+        if Q_rot is None and want_q_rot:
+            Q_rot = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+        elif Q_rot is not None:
+            _same_layout(Q, Q_rot)
+        ws = None
+        if split:
+            need = int(lib().attn_fwd_rope_workspace_bytes(ctypes.byref(p)))
+            if need:
+                ws = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    rc = lib().attn_fwd_rope(Q.data_ptr(), K_rot.data_ptr(), V.data_ptr(), cos.data_ptr(),
+                             sin.data_ptr(), O.data_ptr(), LSE.data_ptr(),
+                             Q_rot.data_ptr() if Q_rot is not None else None,
+                             ws.data_ptr() if ws is not None else None,
+                             ws.numel() if ws is not None else 0, ctypes.byref(p),
+                             _stream_ptr(torch, stream))
+    if rc != ATTN_OK:
+        raise AttnError(rc, "attn_fwd_rope")
+    return O, LSE, Q_rot
+
+
+def attn_bwd_rope(Q_rot, K_rot, V, O, dO, LSE, cos, sin, scale, causal, dQ=None, dK_rot=None,
+                  dV=None, workspace=None, stream=None):
+    """dQ (gradient of the UNROTATED query rows), dK_rot (gradient of the rotated K), dV."""
+    import torch
+    _check_tables(torch, cos, sin, K_rot.shape[2], Q_rot.shape[3])
+    p = _rect_params_for(Q_rot, K_rot, scale, causal)
+
+    def entry(*args):  # the tables sit between LSE and dQ in the C signature
+        return lib().attn_bwd_rope(*args[:6], cos.data_ptr(), sin.data_ptr(), *args[6:])
+    return _backward("attn_bwd_rope", entry, p, lib().attn_bwd_rect_workspace_bytes, Q_rot, K_rot,
+                     V, O, dO, LSE, dQ, dK_rot, dV, workspace, stream, (torch.bfloat16,))

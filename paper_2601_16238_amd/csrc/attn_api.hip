@@ -82,11 +82,11 @@ struct FwdView {
 // head of G rows.  K and V are then streamed once per K/V head instead of once per query
 // head.  A single row sees every key, so the mask drops out.  LSE [B,Hq,1] is the same
 // memory as [B,Hkv,G].
-FwdView fwd_view(const attn_rect_params_t &p)
+FwdView fwd_view(const attn_rect_params_t &p, bool may_pack = true)
 {
     FwdView v;
     const int G = p.Hq / p.Hkv;
-    if (p.Sq == 1 && G > 1 &&
+    if (may_pack && p.Sq == 1 && G > 1 &&
         check_strides(G, p.D, p.q_stride_b, G * p.q_stride_h, p.q_stride_h) == ATTN_OK) {
         v.BH = p.B * p.Hkv; v.H = p.Hkv; v.S = G; v.group = 1;
         v.stride_b = p.q_stride_b; v.stride_h = G * p.q_stride_h; v.stride_s = p.q_stride_h;
@@ -104,23 +104,53 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 }  // namespace
 
 // E: element type of Q, K, V, O (__bf16 or _Float16)
+// Workspace of the forward's split over the keys for this problem (0: it would not split).
+static size_t fwd_workspace_bytes(const attn_rect_params_t *p, bool may_pack)
+{
+    if (check_params(p) != ATTN_OK) return 0;
+    const FwdView v = fwd_view(*p, may_pack);
+    const int nsplit = attn::fwd_split_plan(v.BH, v.S, p->Sk, kernel_d(p->D), v.causal, nullptr);
+    if (nsplit <= 1) return 0;
+    const size_t rows = (size_t)p->B * p->Hq * p->Sq;
+    return round_ws((size_t)nsplit * rows * (kernel_d(p->D) + 1) * sizeof(float));
+}
+
+// Rotary embedding fused into the call (both tables NULL: none).
+struct Rope {
+    const float *cos_table = nullptr, *sin_table = nullptr;
+    void *Qrot = nullptr;  // forward only, optional
+};
+
+// The fused rotary embedding pairs column d with d + D/2 inside one lane's registers, which
+// the kernels can do at their native head dimensions only; positions need Sk >= Sq.
+static int check_rope(const attn_rect_params_t *p, const Rope &r)
+{
+    if (!r.cos_table || !r.sin_table) return ATTN_ERR_NULL;
+    if ((p->D != 64 && p->D != 128) || p->Sk < p->Sq) return ATTN_ERR_SHAPE;
+    if (!aligned(r.cos_table, 16) || !aligned(r.sin_table, 16) || !aligned(r.Qrot, 16))
+        return ATTN_ERR_ALIGN;
+    return ATTN_OK;
+}
+
 template <typename E>
 static int fwd_impl(const void *Q, const void *K, const void *V, void *O, float *LSE,
                     void *workspace, size_t workspace_bytes,
-                    const attn_rect_params_t *p, void *hip_stream)
+                    const attn_rect_params_t *p, void *hip_stream, const Rope *rope = nullptr)
 {
     if (!Q || !K || !V || !O || !LSE) return ATTN_ERR_NULL;
-    const int rc = check_params(p);
+    int rc = check_params(p);
     if (rc != ATTN_OK) return rc;
+    if (rope && (rc = check_rope(p, *rope)) != ATTN_OK) return rc;
     if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) ||
         !aligned(LSE, 4))
         return ATTN_ERR_ALIGN;
     // No workspace at all: run unsplit.  A workspace that is there must be usable.
-    const FwdView v = fwd_view(*p);
+    // (with rotary positions the rows of a head must stay rows: no packing of decode heads)
+    const FwdView v = fwd_view(*p, rope == nullptr);
     int kps = 0;
     int nsplit = workspace ? attn::fwd_split_plan(v.BH, v.S, p->Sk, kernel_d(p->D), v.causal, &kps) : 1;
     if (workspace && (!aligned(workspace, kWsAlign) ||
-                      workspace_bytes < attn_fwd_rect_workspace_bytes(p)))
+                      workspace_bytes < fwd_workspace_bytes(p, rope == nullptr)))
         return ATTN_ERR_WORKSPACE;
     attn::FwdArgsT<E> a;
     a.nsplit = nsplit; a.kps = kps;
@@ -137,6 +167,10 @@ static int fwd_impl(const void *Q, const void *K, const void *V, void *O, float 
     a.Dr = p->D;
     a.nqt = 0;
     a.scale_log2e = p->scale * 1.4426950408889634f;
+    a.rope_cos = rope ? rope->cos_table : nullptr;
+    a.rope_sin = rope ? rope->sin_table : nullptr;
+    a.Qrot = rope ? static_cast<E *>(rope->Qrot) : nullptr;
+    a.rope_pos0 = p->Sk - p->Sq;
     return attn::launch_fwd(a, kernel_d(p->D), v.causal, static_cast<hipStream_t>(hip_stream)) == 0
                ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
@@ -145,11 +179,13 @@ template <typename E>
 static int bwd_impl(const void *Q, const void *K, const void *V, const void *O, const void *dO,
                     const float *LSE, void *dQ, void *dK, void *dV,
                     void *workspace, size_t workspace_bytes,
-                    const attn_rect_params_t *p, void *hip_stream, uint32_t stages)
+                    const attn_rect_params_t *p, void *hip_stream, uint32_t stages,
+                    const Rope *rope = nullptr)
 {
     if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_NULL;
-    const int rc = check_params(p);
+    int rc = check_params(p);
     if (rc != ATTN_OK) return rc;
+    if (rope && (rc = check_rope(p, *rope)) != ATTN_OK) return rc;
     if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) ||
         !aligned(dO, 16) || !aligned(dQ, 16) || !aligned(dK, 16) || !aligned(dV, 16) ||
         !aligned(LSE, 4))
@@ -176,6 +212,9 @@ static int bwd_impl(const void *Q, const void *K, const void *V, const void *O, 
     a.ntile = 0;
     a.scale = p->scale;
     a.scale_log2e = p->scale * 1.4426950408889634f;
+    a.rope_cos = rope ? rope->cos_table : nullptr;
+    a.rope_sin = rope ? rope->sin_table : nullptr;
+    a.rope_pos0 = p->Sk - p->Sq;
     return attn::launch_bwd(a, kernel_d(p->D), p->causal != 0, static_cast<hipStream_t>(hip_stream),
                             stages) == 0
                ? ATTN_OK : ATTN_ERR_LAUNCH;
@@ -222,14 +261,29 @@ void attn_rect_params_contiguous(attn_rect_params_t *p, int32_t B, int32_t Hq, i
     p->causal = causal;
 }
 
-size_t attn_fwd_rect_workspace_bytes(const attn_rect_params_t *p)
+size_t attn_fwd_rect_workspace_bytes(const attn_rect_params_t *p) { return fwd_workspace_bytes(p, true); }
+
+size_t attn_fwd_rope_workspace_bytes(const attn_rect_params_t *p) { return fwd_workspace_bytes(p, false); }
+
+int attn_fwd_rope(const void *Q, const void *K_rot, const void *V, const float *cos_table,
+                  const float *sin_table, void *O, float *LSE, void *Q_rot, void *workspace,
+                  size_t workspace_bytes, const attn_rect_params_t *p, void *hip_stream)
 {
-    if (check_params(p) != ATTN_OK) return 0;
-    const FwdView v = fwd_view(*p);
-    const int nsplit = attn::fwd_split_plan(v.BH, v.S, p->Sk, kernel_d(p->D), v.causal, nullptr);
-    if (nsplit <= 1) return 0;
-    const size_t rows = (size_t)p->B * p->Hq * p->Sq;
-    return round_ws((size_t)nsplit * rows * (kernel_d(p->D) + 1) * sizeof(float));
+    Rope r;
+    r.cos_table = cos_table; r.sin_table = sin_table; r.Qrot = Q_rot;
+    return fwd_impl<__bf16>(Q, K_rot, V, O, LSE, workspace, workspace_bytes, p, hip_stream, &r);
+}
+
+int attn_bwd_rope(const void *Q_rot, const void *K_rot, const void *V, const void *O,
+                  const void *dO, const float *LSE, const float *cos_table, const float *sin_table,
+                  void *dQ, void *dK_rot, void *dV, void *workspace, size_t workspace_bytes,
+                  const attn_rect_params_t *p, void *hip_stream)
+{
+    Rope r;
+    r.cos_table = cos_table; r.sin_table = sin_table;
+    return bwd_impl<__bf16>(Q_rot, K_rot, V, O, dO, LSE, dQ, dK_rot, dV, workspace, workspace_bytes, p,
+                            hip_stream,
+                            ATTN_BWD_STAGE_DELTA | ATTN_BWD_STAGE_DKDV | ATTN_BWD_STAGE_DQ, &r);
 }
 
 int attn_fwd_rect(const void *Q, const void *K, const void *V, void *O, float *LSE,

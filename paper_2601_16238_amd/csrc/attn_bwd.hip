@@ -622,6 +622,26 @@ attn_bwd_dq_kernel(const BwdArgs a)
     // no transfer may still be in flight when the work-group's LDS is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
+    if (a.rope_cos) {
+        // Q was rotated before the forward: what has been accumulated is the gradient of the
+        // rotated rows; the gradient of the unrotated ones is its image under the transpose of
+        // the rotation (head dimension == D only; column d pairs with d + D/2, i.e. d block db
+        // with db + DB/2, same register).
+        const int64_t pos = (int64_t)(qc + a.rope_pos0) * (D / 2);
+#pragma unroll
+        for (int db = 0; db < DB / 2; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 c4 = *(const f32x4 *)(a.rope_cos + pos + 32 * db + 8 * g + 4 * h);
+                const f32x4 s4 = *(const f32x4 *)(a.rope_sin + pos + 32 * db + 8 * g + 4 * h);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float y1 = dq[db][4 * g + e], y2 = dq[db + DB / 2][4 * g + e];
+                    dq[db][4 * g + e] = __builtin_fmaf(y1, c4[e], y2 * s4[e]);
+                    dq[db + DB / 2][4 * g + e] = __builtin_fmaf(y2, c4[e], -(y1 * s4[e]));
+                }
+            }
+    }
     if (q < S) {
         elem *dQp = a.dQ + base + (int64_t)q * a.stride_s;
         const float sc = a.scale;

@@ -41,6 +41,12 @@ struct FwdArgsT {
     int nsplit, kps;    // kps is a multiple of the 64-key tile
     float *Opart;       // [nsplit][B*H][S][D]
     float *LSEpart;     // [nsplit][B*H][S]
+    // Rotary embedding fused into the Q load (NULL tables: none).  Query row i is rotated by the
+    // table row i + rope_pos0 ("rotate-half" pairing of column d with d + D/2; tables fp32
+    // [positions][D/2]); Qrot, if not NULL, receives the rotated rows (same strides as Q).
+    const float *rope_cos, *rope_sin;
+    E *Qrot;
+    int rope_pos0;
 };
 
 template <typename E>
@@ -59,6 +65,11 @@ struct BwdArgsT {
     int stats_in_dq;    // the dQ kernel forms the row statistics itself and stores them to
                         // `delta` for the dK/dV kernel (set by the launcher)
     float scale, scale_log2e;
+    // Rotary embedding: Q holds ROTATED rows; dQ is rotated back (by the transpose of the
+    // rotation) before it is stored, so that it is the gradient of the unrotated rows.  NULL
+    // tables: none.
+    const float *rope_cos, *rope_sin;
+    int rope_pos0;
 };
 
 typedef FwdArgsT<elem> FwdArgs;

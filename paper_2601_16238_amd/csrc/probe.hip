@@ -59,7 +59,52 @@ __global__ void __launch_bounds__(kThreads) probe_mfma_kernel(int iters, float *
     sink[(size_t)blockIdx.x * kThreads + threadIdx.x] = t;
 }
 
+// The traffic a one-kernel backward would put on fp32 global atomics: the work-group that owns
+// key block kb of a head adds one 32 x 128 fp32 tile of partial dQ per 32-row query slot that
+// sees its keys.  Nothing else runs, so the time is the ceiling of that path alone.  A lane
+// addresses column l%32 of a row, as the accumulator layout of a dQ = dS K product would, so
+// one instruction touches two rows of 128 contiguous bytes.
+__global__ void __launch_bounds__(256) probe_atomic_kernel(float *acc, int S, int key_block,
+                                                           int BH, int causal)
+{
+    // all key blocks of a head on one XCD (work-groups go to the 8 XCDs round-robin by id)
+    const int id = blockIdx.x, x = id % 8, pos = id / 8, hpx = BH / 8;
+    const int bh = x * hpx + pos % hpx, kb = pos / hpx;
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63, r = l & 31, h = l >> 5;
+    float *base = acc + (size_t)bh * S * 128;
+    const int nslot = S / 32, slot0 = causal ? min(nslot, (kb * key_block) / 32) : 0;
+    for (int s = slot0 + w; s < nslot; s += 4) {
+        float *tile = base + (size_t)s * 32 * 128;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                __hip_atomic_fetch_add(tile + (8 * (i / 4) + 4 * h + (i % 4)) * 128 + 32 * db + r, 1.0f,
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 }  // namespace
+
+extern "C" int attn_probe_atomic_f32(int BH, int S, int key_block, int causal, float *acc,
+                                     size_t acc_floats, double *bytes_added, void *hip_stream)
+{
+    if (!acc) return ATTN_ERR_NULL;
+    if (BH < 8 || BH % 8 || BH > 4096 || S < 32 || S % 32 || S > (1 << 20) || key_block < 32 ||
+        key_block % 32 || key_block > S)
+        return ATTN_ERR_SHAPE;
+    if (acc_floats < (size_t)BH * S * 128) return ATTN_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(acc) & 3u) != 0) return ATTN_ERR_ALIGN;
+    const int nkb = (S + key_block - 1) / key_block, nslot = S / 32;
+    if (bytes_added) {
+        double tiles = 0;
+        for (int kb = 0; kb < nkb; ++kb) tiles += nslot - (causal ? (kb * key_block) / 32 : 0);
+        *bytes_added = tiles * BH * 32.0 * 128.0 * 4.0;
+    }
+    hipLaunchKernelGGL(probe_atomic_kernel, dim3(nkb * BH), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), acc, S, key_block, BH, causal);
+    return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}
 
 extern "C" int attn_probe_mfma_bf16(int workgroups, int iters, int random_operands, float *sink,
                                     size_t sink_floats, double *flop, void *hip_stream)

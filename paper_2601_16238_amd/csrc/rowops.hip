@@ -404,8 +404,10 @@ rotary_fwd_kernel(const __bf16 *x, const float *cosv, const float *sinv, __bf16 
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const float a = (float)lo[e], bb = (float)hi[e];
-        o1[e] = a * c[e] - bb * sn[e];
-        o2[e] = bb * c[e] + a * sn[e];
+        // (written out as fused multiply-adds: the rotation fused into the attention
+        // forward's Q load uses the same two expressions and gives the same bits)
+        o1[e] = __builtin_fmaf(a, c[e], -(bb * sn[e]));
+        o2[e] = __builtin_fmaf(bb, c[e], a * sn[e]);
     }
     store8(yr + d, o1);
     store8(yr + d + hd, o2);

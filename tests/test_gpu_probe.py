@@ -60,3 +60,37 @@ def test_probe_rejects_a_small_sink():
     sink = torch.empty(511, dtype=torch.float32, device="cuda")
     with pytest.raises(attn.AttnError):
         attn.attn_probe_mfma_bf16(1, 1, sink)
+
+
+def test_atomic_probe_adds_what_it_counts_and_reports_its_rate():
+    """Every element of the accumulator must hold the number of key blocks that see its row's
+    slot, and the byte count must equal the sum of those tiles; the rate is printed (it is the
+    measurement behind the choice of a two-kernel backward without atomics)."""
+    BH, S = 16, 16384
+    acc = torch.zeros(BH * S * 128, dtype=torch.float32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for key_block, causal in ((128, True), (192, True), (256, True), (192, False)):
+        acc.zero_()
+        torch.cuda.synchronize()
+        e0.record()
+        nbytes = attn.attn_probe_atomic_f32(BH, S, key_block, causal, acc)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        nkb = (S + key_block - 1) // key_block
+        slot = np.arange(S // 32)
+        first = (np.arange(nkb) * key_block) // 32 if causal else np.zeros(nkb, dtype=np.int64)
+        expect = (first[None, :] <= slot[:, None]).sum(axis=1)          # per slot
+        assert nbytes == float(expect.sum()) * BH * 32 * 128 * 4
+        got = acc.view(BH, S // 32, 32 * 128)
+        ref = torch.from_numpy(expect.astype(np.float32)).cuda()[None, :, None]
+        assert torch.equal(got, ref.expand_as(got))
+        print("atomic adds, %d heads x %d rows, key blocks of %d, causal=%s: %.2f GB in %.3f ms = %.2f TB/s"
+              % (BH, S, key_block, causal, nbytes / 1e9, ms, nbytes / ms / 1e9), flush=True)
+
+
+def test_atomic_probe_rejects_bad_shapes():
+    acc = torch.zeros(8 * 64 * 128, dtype=torch.float32, device="cuda")
+    for args in ((7, 64, 32), (8, 65, 32), (8, 64, 48), (8, 64, 128), (16, 64, 32)):
+        with pytest.raises(attn.AttnError):
+            attn.attn_probe_atomic_f32(*args, False, acc)
