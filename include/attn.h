@@ -82,8 +82,10 @@ int attn_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
              const attn_params_t *p, void *hip_stream);
 
 /*
- * Bytes of device workspace attn_bwd needs for this problem: two fp32 values per query row
- * ([B*H][2][S]: -rowsum(dO*O), and LSE rescaled to base 2), rounded up to 256 bytes.
+ * Bytes of device workspace attn_bwd asks for: two fp32 values per query row ([B*H][2][S]:
+ * -rowsum(dO*O), and LSE rescaled to base 2), rounded up to 256 bytes, plus -- for problems
+ * with so few query tiles that the dQ kernel is split over the keys, see
+ * attn_bwd_rect_workspace_bytes -- the fp32 partial results of that split.
  * Pure host function; returns 0 for an invalid problem.
  */
 size_t attn_bwd_workspace_bytes(const attn_params_t *p);
@@ -150,7 +152,7 @@ void attn_gqa_params_contiguous(attn_gqa_params_t *p, int32_t B, int32_t Hq, int
 int attn_fwd_gqa(const void *Q, const void *K, const void *V, void *O, float *LSE,
                  const attn_gqa_params_t *p, void *hip_stream);
 
-/* Two fp32 values per QUERY row ([B*Hq][2][S]), rounded up to 256 bytes; 0 if invalid. */
+/* As attn_bwd_rect_workspace_bytes with Sq == Sk == S; 0 if invalid. */
 size_t attn_bwd_gqa_workspace_bytes(const attn_gqa_params_t *p);
 
 int attn_bwd_gqa(const void *Q, const void *K, const void *V, const void *O, const void *dO,
@@ -183,8 +185,14 @@ int attn_bwd_gqa_stages(const void *Q, const void *K, const void *V, const void 
  * large, else ATTN_ERR_WORKSPACE; its contents are undefined on entry and exit.  The split
  * plan depends only on the shape, so results are deterministic.
  *
- * Backward: as attn_bwd_gqa, workspace of attn_bwd_rect_workspace_bytes(p) bytes (two fp32
- * per query row).  Keys that no row sees get zero gradients.
+ * Backward: as attn_bwd_gqa.  Keys that no row sees get zero gradients.  Workspace: the row
+ * statistics (two fp32 per query row, rounded up to 256 bytes) and, when B*Hq*ceil(Sq/256)
+ * work-groups of the dQ kernel would leave most of the chip idle (Sq >= 256, at least 1024
+ * keys), the fp32 partial dQ of a split of that kernel over the keys ([splits][B*Hq*Sq][64 or
+ * 128]); a third small kernel adds them.  attn_bwd_rect_workspace_bytes(p) is the sum.  A
+ * workspace that holds the statistics but not the partial results is accepted too: the dQ
+ * kernel then runs unsplit.  Either way the plan depends only on the shape and the workspace
+ * size, so results are deterministic.
  */
 typedef struct {
     int32_t B, Hq, Hkv, Sq, Sk, D;
@@ -250,8 +258,9 @@ int attn_bwd_rope(const void *Q_rot, const void *K_rot, const void *V, const voi
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
  * backward's scratch (two fp32 values per query row) lives in an array inside the library's
  * device image, ATTN_NOALLOC_SCRATCH_BYTES long; each GPU the library runs on holds its own
- * copy until the process ends.  Arguments, results (bit for bit those of attn_bwd_rect),
- * validation and stream semantics are those of attn_bwd_rect without the workspace pair.
+ * copy until the process ends.  Arguments, validation and stream semantics are those of
+ * attn_bwd_rect without the workspace pair; results are bit for bit those of attn_bwd_rect
+ * called with a workspace of ATTN_NOALLOC_SCRATCH_BYTES bytes.
  *   - Problems with more than ATTN_NOALLOC_SCRATCH_BYTES / 8 query rows (B*Hq*Sq) give
  *     ATTN_ERR_WORKSPACE; nothing is launched.
  *   - The call allocates and frees nothing.  The first call on a device asks the runtime for

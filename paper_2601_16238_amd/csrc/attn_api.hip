@@ -115,6 +115,12 @@ static size_t fwd_workspace_bytes(const attn_rect_params_t *p, bool may_pack)
     return round_ws((size_t)nsplit * rows * (kernel_d(p->D) + 1) * sizeof(float));
 }
 
+// The backward's row statistics: two fp32 values per query row.
+static size_t bwd_stats_bytes(const attn_rect_params_t *p)
+{
+    return round_ws(2 * (size_t)p->B * p->Hq * p->Sq * sizeof(float));
+}
+
 // Rotary embedding fused into the call (both tables NULL: none).
 struct Rope {
     const float *cos_table = nullptr, *sin_table = nullptr;
@@ -190,10 +196,16 @@ static int bwd_impl(const void *Q, const void *K, const void *V, const void *O, 
         !aligned(dO, 16) || !aligned(dQ, 16) || !aligned(dK, 16) || !aligned(dV, 16) ||
         !aligned(LSE, 4))
         return ATTN_ERR_ALIGN;
-    if (!workspace || !aligned(workspace, kWsAlign) ||
-        workspace_bytes < attn_bwd_rect_workspace_bytes(p))
+    // The row statistics always; the partial dQ of a key split only if they fit as well (a
+    // smaller workspace runs the dQ kernel unsplit).  No split with rotary tables: the merge
+    // does not rotate back.
+    const size_t stats_bytes = bwd_stats_bytes(p);
+    if (!workspace || !aligned(workspace, kWsAlign) || workspace_bytes < stats_bytes)
         return ATTN_ERR_WORKSPACE;
     if (stages == 0 || (stages & ~7u)) return ATTN_ERR_SHAPE;
+    int dq_kps = 0;
+    int dq_nsplit = attn::dq_split_plan(p->B * p->Hq, p->Sq, p->Sk, kernel_d(p->D), p->causal != 0, &dq_kps);
+    if (rope || workspace_bytes < attn_bwd_rect_workspace_bytes(p)) dq_nsplit = 1;
     attn::BwdArgsT<E> a;
     a.Q = static_cast<const E *>(Q);
     a.K = static_cast<const E *>(K);
@@ -202,6 +214,8 @@ static int bwd_impl(const void *Q, const void *K, const void *V, const void *O, 
     a.dO = static_cast<const E *>(dO);
     a.LSE = LSE;
     a.delta = static_cast<float *>(workspace);
+    a.dq_nsplit = dq_nsplit; a.dq_kps = dq_kps;
+    a.dQpart = reinterpret_cast<float *>(static_cast<char *>(workspace) + stats_bytes);
     a.dQ = static_cast<E *>(dQ);
     a.dK = static_cast<E *>(dK);
     a.dV = static_cast<E *>(dV);
@@ -320,7 +334,9 @@ size_t attn_bwd_rect_workspace_bytes(const attn_rect_params_t *p)
 {
     if (check_params(p) != ATTN_OK) return 0;
     const size_t rows = (size_t)p->B * p->Hq * p->Sq;
-    return round_ws(2 * rows * sizeof(float));
+    const int nsplit = attn::dq_split_plan(p->B * p->Hq, p->Sq, p->Sk, kernel_d(p->D), p->causal != 0, nullptr);
+    const size_t part = nsplit > 1 ? round_ws((size_t)nsplit * rows * kernel_d(p->D) * sizeof(float)) : 0;
+    return bwd_stats_bytes(p) + part;
 }
 
 size_t attn_bwd_gqa_workspace_bytes(const attn_gqa_params_t *p)
@@ -437,8 +453,8 @@ int attn_bwd_rect_noalloc(const void *Q, const void *K, const void *V, const voi
     if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV) return ATTN_ERR_NULL;
     const int rc = check_params(p);
     if (rc != ATTN_OK) return rc;
-    const size_t need = attn_bwd_rect_workspace_bytes(p);
-    if (need == 0 || need > (size_t)ATTN_NOALLOC_SCRATCH_BYTES) return ATTN_ERR_WORKSPACE;
+    const size_t need = bwd_stats_bytes(p);
+    if (need > (size_t)ATTN_NOALLOC_SCRATCH_BYTES) return ATTN_ERR_WORKSPACE;
     void *ws = scratch_of_current_device();
     if (!ws) return ATTN_ERR_LAUNCH;
     // Every value of the scratch that a kernel reads is written earlier in the same call (the

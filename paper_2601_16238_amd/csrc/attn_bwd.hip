@@ -404,7 +404,7 @@ struct DqCfg {
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 CU exceeded");
 };
 
-template <int D, int NW, bool CAUSAL>
+template <int D, int NW, bool CAUSAL, bool SPLIT>
 __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
 attn_bwd_dq_kernel(const BwdArgs a)
 {
@@ -426,11 +426,22 @@ attn_bwd_dq_kernel(const BwdArgs a)
     const int q0 = qt * C::kBlk + w * 32;
     const int q = q0 + r;
     const int qc = q < S ? q : S - 1;
-    const int Sk = a.Sk;      // key/value rows; S is the number of query rows
-    const int coff = Sk - S;  // causal: query row i sees keys 0 .. i + coff
+    // Keys seen by this work-group: all Sk of them, or one split's range (then K and V are
+    // simply re-based to the range and the causal offset moves with them; the row statistics
+    // belong to the whole row, so the partial dQ of the ranges just add up).
+    int Sk = a.Sk;      // key/value rows; S is the number of query rows
+    int coff = Sk - S;  // causal: query row i sees keys 0 .. i + coff
+    int64_t kv_first = 0;
+    if (SPLIT) {
+        const int k_begin = blockIdx.y * a.dq_kps;  // < Sk by the launcher's plan
+        kv_first = (int64_t)k_begin * a.kv_stride_s;
+        Sk = min(Sk - k_begin, a.dq_kps);
+        coff -= k_begin;
+    }
     const int q0e = q0 + coff;
     const int q_end = min(S, (qt + 1) * C::kBlk);
-    const int n_kt = ((CAUSAL ? q_end + coff : Sk) + C::kTile - 1) / C::kTile;
+    // (a split that lies wholly above the work-group's diagonal has no tile)
+    const int n_kt = max(0, (CAUSAL ? min(Sk, q_end + coff) : Sk) + C::kTile - 1) / C::kTile;
 
     // byte offset of 16-byte chunk `chunk` of row `row` within a tile tensor
     auto at = [](int row, int chunk) {
@@ -440,7 +451,8 @@ attn_bwd_dq_kernel(const BwdArgs a)
     // ---- streaming of tile kt into ring position pos; rows past S-1 read as zero
     const int Dr = a.Dr;  // columns Dr..D-1 read as zero (offset past the end of the resource)
     const uint32_t head_bytes = (uint32_t)(((int64_t)(Sk - 1) * a.kv_stride_s + Dr) * 2);
-    const desc_t Kd0 = make_desc(a.K + base_kv, head_bytes), Vd0 = make_desc(a.V + base_kv, head_bytes);
+    const desc_t Kd0 = make_desc(a.K + base_kv + kv_first, head_bytes),
+                 Vd0 = make_desc(a.V + base_kv + kv_first, head_bytes);
     const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2u;
     const uint32_t lds0 = lds_address(smem);
     // (the descriptors are passed by value: captured by reference through two levels of
@@ -461,7 +473,7 @@ attn_bwd_dq_kernel(const BwdArgs a)
                   voff, (kt * C::kTile + piece * PR) * row_bytes);
         }
     };
-    dma_tile(0, 0, Kd0, Vd0);
+    if (n_kt > 0) dma_tile(0, 0, Kd0, Vd0);
     if (n_kt > 1) dma_tile(1, 1, Kd0, Vd0);
 
     elem8 qf[KS], gf[KS];
@@ -485,7 +497,7 @@ attn_bwd_dq_kernel(const BwdArgs a)
         }
         ndelta = -xhalf_sum(acc);
         lse2 = a.LSE[(int64_t)bh * S + qc] * kLog2e;
-        if (q < S && h == 0) {
+        if (q < S && h == 0 && (!SPLIT || blockIdx.y == 0)) {
             a.delta[(int64_t)bh * 2 * S + q] = ndelta;
             a.delta[(int64_t)bh * 2 * S + S + q] = lse2;
         }
@@ -622,6 +634,22 @@ attn_bwd_dq_kernel(const BwdArgs a)
     // no transfer may still be in flight when the work-group's LDS is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
+    if (SPLIT) {
+        // unscaled fp32 partial of this key range (zeros if the range had no visible key)
+        if (q < S) {
+            float *dp = a.dQpart + (((int64_t)blockIdx.y * a.BH + bh) * S + q) * D;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    f32x4 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = dq[db][4 * g + e];
+                    *(f32x4 *)(dp + 32 * db + 8 * g + 4 * h) = v;
+                }
+        }
+        return;
+    }
     if (a.rope_cos) {
         // Q was rotated before the forward: what has been accumulated is the gradient of the
         // rotated rows; the gradient of the unrotated ones is its image under the transpose of
@@ -654,6 +682,29 @@ attn_bwd_dq_kernel(const BwdArgs a)
                         pack4(dq[db][4 * g] * sc, dq[db][4 * g + 1] * sc,
                               dq[db][4 * g + 2] * sc, dq[db][4 * g + 3] * sc);
     }
+}
+
+// Sum of the per-split partial dQ, times scale, rounded: one thread per (row, 4 consecutive d);
+// HBM-bound and small.
+template <int D>
+__global__ void __launch_bounds__(256) attn_bwd_dq_merge_kernel(const BwdArgs a)
+{
+    constexpr int TPR = D / 4;  // threads per row
+    const int64_t rows = (int64_t)a.BH * a.S;
+    const int64_t row = (int64_t)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
+    if (row >= rows) return;
+    const int d0 = (threadIdx.x % TPR) * 4;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int z = 0; z < a.dq_nsplit; ++z) {
+        const f32x4 v = *(const f32x4 *)(a.dQpart + ((int64_t)z * rows + row) * D + d0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] += v[e];
+    }
+    const int bh = (int)(row / a.S), q = (int)(row % a.S);
+    elem *dQp = a.dQ + (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h +
+                (int64_t)q * a.stride_s + d0;
+    const float sc = a.scale;
+    if (d0 < a.Dr) *(elem4 *)dQp = pack4(acc[0] * sc, acc[1] * sc, acc[2] * sc, acc[3] * sc);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -697,15 +748,33 @@ static int launch_dq(BwdArgs a, hipStream_t st)
 {
     using C = DqCfg<D, NW>;
     a.ntile = (a.S + C::kBlk - 1) / C::kBlk;
-    if (!allow_lds(attn_bwd_dq_kernel<D, NW, CAUSAL>, C::kLdsBytes)) return -1;
-    hipLaunchKernelGGL((attn_bwd_dq_kernel<D, NW, CAUSAL>), dim3(a.ntile * a.BH),
+    if (!allow_lds(attn_bwd_dq_kernel<D, NW, CAUSAL, false>, C::kLdsBytes)) return -1;
+    hipLaunchKernelGGL((attn_bwd_dq_kernel<D, NW, CAUSAL, false>), dim3(a.ntile * a.BH),
                        dim3(C::kThreads), C::kLdsBytes, st, a);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// Split over the keys: 256-row work-groups, one grid row per split, then the merge.
+template <int D, bool CAUSAL>
+static int launch_dq_split(BwdArgs a, hipStream_t st)
+{
+    using C = DqCfg<D, 8>;
+    a.ntile = (a.S + C::kBlk - 1) / C::kBlk;
+    if (!allow_lds(attn_bwd_dq_kernel<D, 8, CAUSAL, true>, C::kLdsBytes)) return -1;
+    hipLaunchKernelGGL((attn_bwd_dq_kernel<D, 8, CAUSAL, true>), dim3(a.ntile * a.BH, a.dq_nsplit),
+                       dim3(C::kThreads), C::kLdsBytes, st, a);
+    if (hipGetLastError() != hipSuccess) return -1;
+    const int64_t rows = (int64_t)a.BH * a.S;
+    constexpr int RPB = 256 / (D / 4);
+    hipLaunchKernelGGL((attn_bwd_dq_merge_kernel<D>), dim3((unsigned)((rows + RPB - 1) / RPB)),
+                       dim3(256), 0, st, a);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 template <int D, bool CAUSAL>
 static int launch_dq_for(const BwdArgs &a, hipStream_t st)
 {
+    if (a.dq_nsplit > 1) return launch_dq_split<D, CAUSAL>(a, st);
     const int blocks32 = (a.S + 31) / 32;
     // 256-row work-groups unless they would leave compute units (256) idle while 128-row
     // ones would not (few heads and rows against many keys, e.g. chunked prefill).  Under a
@@ -744,6 +813,30 @@ static int launch_bwd_d(BwdArgs a, bool causal, hipStream_t st, unsigned stages)
     if (stages & 2u) return causal ? launch_dkdv<D, true>(a, st) : launch_dkdv<D, false>(a, st);
     return 0;
 }
+
+// Split the dQ kernel over the keys when its 256-row work-groups would leave compute units
+// (256) idle: aim at one work-group per unit, every split at least eight 64-key tiles (the
+// merge reads and writes one fp32 partial per split and row).  Needs at least 256 query rows
+// per head (a 256-row work-group must have rows to work on) -- decoding shapes have one row per
+// head and many heads, and are not split.
+#ifndef ATTN_F16  // a function of the shape only: defined once, by the bf16 build
+int dq_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps)
+{
+    (void)D; (void)causal;
+    const int64_t wgs = (int64_t)BH * ((S + 255) / 256);
+    const int tiles = (Sk + 63) / 64;
+    int nsplit = 1;
+    if (S >= 256 && wgs < 256 && tiles >= 16) {
+        nsplit = (int)((256 + wgs - 1) / wgs);
+        if (nsplit > tiles / 8) nsplit = tiles / 8;
+        if (nsplit > 16) nsplit = 16;
+    }
+    const int tiles_per = (tiles + nsplit - 1) / nsplit;
+    nsplit = (tiles + tiles_per - 1) / tiles_per;  // no empty split
+    if (kps) *kps = tiles_per * 64;
+    return nsplit;
+}
+#endif
 
 int launch_bwd(const BwdArgs &a, int D, bool causal, hipStream_t st, unsigned stages)
 {

@@ -65,6 +65,12 @@ struct BwdArgsT {
     int stats_in_dq;    // the dQ kernel forms the row statistics itself and stores them to
                         // `delta` for the dK/dV kernel (set by the launcher)
     float scale, scale_log2e;
+    // dQ kernel split over the keys (few query tiles against many keys would leave most of the
+    // chip idle): split z (grid y) covers keys [z*dq_kps, (z+1)*dq_kps) and writes an unscaled
+    // fp32 partial dQ; attn_bwd_dq_merge_kernel adds the splits, scales and rounds.
+    // dq_nsplit == 1: dQ is written directly.
+    int dq_nsplit, dq_kps;   // dq_kps is a multiple of the 64-key tile
+    float *dQpart;           // [dq_nsplit][B*H][S][D]
     // Rotary embedding: Q holds ROTATED rows; dQ is rotated back (by the transpose of the
     // rotation) before it is stored, so that it is the gradient of the unrotated rows.  NULL
     // tables: none.
@@ -84,6 +90,9 @@ int launch_fwd(const FwdArgsT<_Float16> &a, int D, bool causal, hipStream_t st);
 int fwd_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps);
 // `stages`: bit 0 row statistics, bit 1 dK/dV, bit 2 dQ.  With bits 0 and 2 the dQ kernel
 // forms the statistics (and runs first); bit 0 without bit 2 runs the separate kernel.
+// Number of key splits the dQ kernel would use for this problem (1: none) and the keys per
+// split; a pure host function of the shape.
+int dq_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps);
 int launch_bwd(const BwdArgsT<__bf16> &a, int D, bool causal, hipStream_t st, unsigned stages);
 int launch_bwd(const BwdArgsT<_Float16> &a, int D, bool causal, hipStream_t st, unsigned stages);
 

@@ -177,3 +177,39 @@ def test_backward_with_192_key_work_groups(B, Hq, Hkv, Sq, Sk, D, causal):
     padded head dimensions, grouped heads and rectangular problems."""
     assert (B * Hkv) * ((Sk + 191) // 192) >= 512
     test_rect_parity(B, Hq, Hkv, Sq, Sk, D, causal)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D,causal", [
+    (1, 8, 2, 300, 2000, 128, True), (2, 4, 4, 512, 1100, 64, False), (1, 4, 4, 1030, 1030, 128, True),
+    (1, 2, 1, 257, 4100, 128, True), (1, 2, 2, 700, 3000, 64, True), (1, 32, 8, 512, 4096, 128, True)])
+def test_rect_backward_with_dq_split_over_the_keys(B, Hq, Hkv, Sq, Sk, D, causal):
+    """Few query tiles against many keys: the plan splits the dQ kernel over the keys (the
+    workspace then holds fp32 partial results next to the row statistics).  The merged dQ must
+    match the oracle, and the unsplit dQ (a workspace that only holds the statistics) to the
+    rounding of the output; dK and dV do not depend on the plan at all."""
+    print("case rect_dq_split", B, Hq, Hkv, Sq, Sk, D, causal, flush=True)
+    full = attn.attn_bwd_rect_workspace_bytes(B, Hq, Hkv, Sq, Sk, D)
+    stats = (8 * B * Hq * Sq + 255) // 256 * 256
+    assert full > stats, "plan does not split"
+    x = wl.random_rect_inputs(B, Hq, Hkv, Sq, Sk, D, seed=1400 + Sq + Sk)
+    ref = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], causal)
+    Q, K, V, dO = (to_dev(x[k]) for k in ("Q", "K", "V", "dO"))
+    O, LSE = attn.attn_fwd_rect(Q, K, V, x["scale"], causal)
+    ws = torch.full((full,), 0x7F, dtype=torch.uint8, device="cuda")   # poisoned: nothing may be relied on
+    dQ, dK, dV = attn.attn_bwd_rect(Q, K, V, O, dO, LSE, x["scale"], causal, workspace=ws)
+    dQ1, dK1, dV1 = attn.attn_bwd_rect(Q, K, V, O, dO, LSE, x["scale"], causal, workspace=ws[:stats])
+    torch.cuda.synchronize()
+    for name, g, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), ref):
+        check_grad(name, to_f64(g), r)
+    check_grad("unsplit dQ", to_f64(dQ1), ref[0])
+    assert torch.equal(dK.view(torch.int16), dK1.view(torch.int16))
+    assert torch.equal(dV.view(torch.int16), dV1.view(torch.int16))
+    # the two dQ differ only by the order of fp32 additions: rarely, and then by one bf16 step
+    # (or, where the terms cancel, by the fp32 rounding of the partial sums)
+    a, b = to_f64(dQ), to_f64(dQ1)
+    assert (a != b).mean() < 0.05
+    assert (np.abs(a - b) <= np.abs(b) * 2.0 ** -7 + 1e-4 * np.abs(b).max()).all()
+    # and a second call on the same workspace gives the same bits (nothing is accumulated)
+    dQ2, _, _ = attn.attn_bwd_rect(Q, K, V, O, dO, LSE, x["scale"], causal, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dQ.view(torch.int16), dQ2.view(torch.int16))

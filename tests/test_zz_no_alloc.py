@@ -1,6 +1,6 @@
 """The backward entry point that allocates nothing (static scratch inside the library) against
-attn_bwd_rect, which takes the same scratch as a workspace argument: same kernels, so the
-results must agree bit for bit -- on two calls in a row, the second on a smaller problem (the
+attn_bwd_rect, which takes the same scratch as a workspace argument (here of the same size):
+same kernels and the same plan, so the results must agree bit for bit -- on two calls in a row, the second on a smaller problem (the
 scratch keeps the first call's contents), and beyond the scratch's size the call must refuse."""
 import ctypes
 
@@ -18,7 +18,9 @@ def run_pair(B, Hq, Hkv, Sq, Sk, D, causal, seed):
     x = wl.random_rect_inputs(B, Hq, Hkv, Sq, Sk, D, seed=seed)
     Q, K, V, dO = (to_dev(x[k]) for k in ("Q", "K", "V", "dO"))
     O, LSE = attn.attn_fwd_rect(Q, K, V, x["scale"], causal)
-    ref = attn.attn_bwd_rect(Q, K, V, O, dO, LSE, x["scale"], causal)
+    # (a workspace of the static scratch's size: the same plan for the dQ kernel)
+    ws = torch.empty(binding.NOALLOC_SCRATCH_BYTES, dtype=torch.uint8, device="cuda")
+    ref = attn.attn_bwd_rect(Q, K, V, O, dO, LSE, x["scale"], causal, workspace=ws)
     got = tuple(torch.full_like(t, float("nan")) for t in ref)
     binding.attn_bwd_rect_noalloc(Q, K, V, O, dO, LSE, x["scale"], causal, *got)
     torch.cuda.synchronize()
@@ -48,4 +50,4 @@ def test_noalloc_backward_refuses_problems_beyond_its_scratch():
                                              ctypes.byref(p), None)
     assert rc == binding.ATTN_ERR_WORKSPACE, rc
     # one row fewer than the limit would be accepted by the size check (not launched here)
-    assert binding.attn_bwd_rect_workspace_bytes(B, H, H, rows // H, rows // H, D) <= binding.NOALLOC_SCRATCH_BYTES
+    assert 8 * B * H * (rows // H) <= binding.NOALLOC_SCRATCH_BYTES
