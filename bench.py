@@ -19,19 +19,35 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published)
 PEAK_HBM_GBS = 8000.0
 CALIB_COPY_BYTES = 256 * 1024 * 1024   # --calib-copy reads this many bytes and writes as many
-# HBM traffic per launch of the dominant kernel on the default workload, from the two
-# rocprofv3 --pmc passes summarised in profiles/ (None until measured for a workload).
+# HBM traffic per launch of the row-wise kernels, from the two rocprofv3 --pmc passes summarised in
+# profiles/rowops_hbm_traffic_pmc.txt: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (KiB); for the
+# backward: rows kernel + column kernel.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/long_causal_hbm_traffic_pmc.txt: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 (KiB)
-    ("long_causal", "attn_bwd_dkdv_kernel"): int((280343.5 * 2.0 + 131130.7) * 1024),
-    ("long_causal", "attn_fwd_kernel"): int((225755.4 * 2.0 + 66585.0) * 1024),
-    ("long_causal", "attn_bwd_dq_kernel"): int((316631.2 * 2.0 + 66901.3) * 1024),
-    # profiles/rowops_hbm_traffic_pmc.txt (for the backward: rows kernel + column kernel)
     ("rowops", "rmsnorm_fwd"): int((32927.1 * 2.0 + 65536.0) * 1024),
     ("rowops", "layernorm_fwd"): int((33062.6 * 2.0 + 65792.4) * 1024),
     ("rowops", "layernorm_bwd"): int(((65853.2 + 8210.1) * 2.0 + 81920.0 + 64.0) * 1024),
     ("rowops", "rotary_fwd"): int((8741.5 * 2.0 + 16384.0) * 1024),
 }
+
+
+def measured_traffic_bytes(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload` (read + written, scaled counter readings)
+    from the committed rocprofv3 summary of that workload, profiles/<workload>_kernel_trace_and_
+    hbm_traffic.txt; None if there is none.  The summaries are regenerated with the kernels, so
+    the figure cannot outlive the code it was measured on unnoticed."""
+    path = os.path.join(ROOT, "profiles", "%s_kernel_trace_and_hbm_traffic.txt" % workload)
+    try:
+        lines = open(path).read().splitlines()
+    except OSError:
+        return None
+    start = next((i for i, ln in enumerate(lines) if ln.startswith("HBM traffic counters")), None)
+    if start is None:
+        return None
+    for ln in lines[start:]:
+        f = ln.split()
+        if len(f) == 5 and f[0].startswith(kernel + "<"):
+            return int((float(f[3]) + float(f[4])) * 1024 * 1024)
+    return None
 
 
 def parse():
@@ -516,7 +532,7 @@ def main():
         "algorithmic_gbs": {"fwd": r["gbs_fwd"], "bwd": r["gbs_bwd"], "hbm_peak": PEAK_HBM_GBS},
         "roofline": {"kernel": dom, "bound": "mfma", "achieved": r["kernels"][dom]["achieved_tflops"],
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": r["kernels"][dom]["frac"],
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom))},
+                     "traffic": measured_traffic_bytes(w.name, dom)},
         "roofline_all": r["kernels"],
     }
     probe = measure_mfma_peak(torch, attn)

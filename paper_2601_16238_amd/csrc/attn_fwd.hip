@@ -114,36 +114,6 @@ attn_fwd_kernel(const FwdArgs a)
     for (int ks = 0; ks < KS; ++ks)
         qf[ks] = as_elem8(ld_row16(Qp + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
 
-    // Rotary embedding of the query rows, fused into their load (head dimension == D only):
-    // column d pairs with d + D/2, i.e. fragment ks with ks + KS/2, element by element, in this
-    // lane; fp32 arithmetic on the widened values, rounded once -- what a separate rotary pass
-    // would have written to memory as bf16.
-    if (a.rope_cos) {
-        const int64_t pos = (int64_t)(qc + a.rope_pos0) * (D / 2);
-        elem *qr = a.Qrot ? a.Qrot + base + (int64_t)qc * a.stride_s : nullptr;
-#pragma unroll
-        for (int ks = 0; ks < KS / 2; ++ks) {
-            const f32x4 c0 = *(const f32x4 *)(a.rope_cos + pos + 16 * ks + 8 * h);
-            const f32x4 c1 = *(const f32x4 *)(a.rope_cos + pos + 16 * ks + 8 * h + 4);
-            const f32x4 s0 = *(const f32x4 *)(a.rope_sin + pos + 16 * ks + 8 * h);
-            const f32x4 s1 = *(const f32x4 *)(a.rope_sin + pos + 16 * ks + 8 * h + 4);
-            float lo[8], hi[8];
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const float x1 = (float)qf[ks][t], x2 = (float)qf[ks + KS / 2][t];
-                const float cc = t < 4 ? c0[t & 3] : c1[t & 3], ss = t < 4 ? s0[t & 3] : s1[t & 3];
-                lo[t] = __builtin_fmaf(x1, cc, -(x2 * ss));
-                hi[t] = __builtin_fmaf(x2, cc, x1 * ss);
-            }
-            qf[ks] = pack8(lo[0], lo[1], lo[2], lo[3], lo[4], lo[5], lo[6], lo[7]);
-            qf[ks + KS / 2] = pack8(hi[0], hi[1], hi[2], hi[3], hi[4], hi[5], hi[6], hi[7]);
-            if (qr && q < S && (!SPLIT || blockIdx.y == 0)) {
-                *(elem8 *)(qr + 16 * ks + 8 * h) = qf[ks];
-                *(elem8 *)(qr + 16 * (ks + KS / 2) + 8 * h) = qf[ks + KS / 2];
-            }
-        }
-    }
-
     // Key tiles this work-group visits.
     const int q_end = min(S, (qt + 1) * C::kBR);
     const int k_end = CAUSAL ? min(Sk, q_end + coff) : Sk;  // <= 0: nothing visible (splits only)
@@ -376,8 +346,44 @@ attn_fwd_kernel(const FwdArgs a)
     dma_k(0, 0);
     dma_k(1, 1);
     load_v(0);
+    // Rotary embedding of the query rows, fused into their load (head dimension == D only):
+    // column d pairs with d + D/2, i.e. fragment ks with ks + KS/2, element by element, in this
+    // lane; fp32 arithmetic on the widened values, rounded once -- what a separate rotary pass
+    // would have written to memory as bf16.  The table rows are requested here, after the first
+    // K and V tiles, so that all of them are in flight together, and used further down.
+    f32x4 rc[KS][2], rs[KS][2];  // [ks][half of the 8 columns]; only ks < KS/2 is used
+    if (a.rope_cos) {
+        const int64_t pos = (int64_t)(qc + a.rope_pos0) * (D / 2);
+#pragma unroll
+        for (int ks = 0; ks < KS / 2; ++ks)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                rc[ks][j] = *(const f32x4 *)(a.rope_cos + pos + 16 * ks + 8 * h + 4 * j);
+                rs[ks][j] = *(const f32x4 *)(a.rope_sin + pos + 16 * ks + 8 * h + 4 * j);
+            }
+    }
     store_v(0);
     load_v(1);
+    if (a.rope_cos) {
+        elem *qr = a.Qrot ? a.Qrot + base + (int64_t)qc * a.stride_s : nullptr;
+#pragma unroll
+        for (int ks = 0; ks < KS / 2; ++ks) {
+            float lo[8], hi[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const float x1 = (float)qf[ks][t], x2 = (float)qf[ks + KS / 2][t];
+                const float cc = rc[ks][t >> 2][t & 3], ss = rs[ks][t >> 2][t & 3];
+                lo[t] = __builtin_fmaf(x1, cc, -(x2 * ss));
+                hi[t] = __builtin_fmaf(x2, cc, x1 * ss);
+            }
+            qf[ks] = pack8(lo[0], lo[1], lo[2], lo[3], lo[4], lo[5], lo[6], lo[7]);
+            qf[ks + KS / 2] = pack8(hi[0], hi[1], hi[2], hi[3], hi[4], hi[5], hi[6], hi[7]);
+            if (qr && q < S && (!SPLIT || blockIdx.y == 0)) {
+                *(elem8 *)(qr + 16 * ks + 8 * h) = qf[ks];
+                *(elem8 *)(qr + 16 * (ks + KS / 2) + 8 * h) = qf[ks + KS / 2];
+            }
+        }
+    }
     if constexpr (NW == 8) {
         // The main loop's first iteration multiplies an all-zero P by the second half of V
         // buffer 2, which nothing has written yet: give it finite contents.
