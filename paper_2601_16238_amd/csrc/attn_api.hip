@@ -27,7 +27,7 @@ int check_params(const attn_rect_params_t *p)
     if (!p) return ATTN_ERR_NULL;
     if (p->B < 1 || p->Hq < 1 || p->Hkv < 1 || p->Sq < 1 || p->Sk < 1) return ATTN_ERR_SHAPE;
     if (p->Hq % p->Hkv != 0) return ATTN_ERR_SHAPE;
-    if (p->D < 8 || p->D > 128 || p->D % 8 != 0) return ATTN_ERR_SHAPE;
+    if (p->D < 8 || p->D > 256 || p->D % 8 != 0) return ATTN_ERR_SHAPE;
     // the causal mask is aligned bottom-right: with fewer keys than rows some rows see none
     if (p->causal && p->Sk < p->Sq) return ATTN_ERR_SHAPE;
     // B*Hq*Sq and B*Hkv*Sk rows must be indexable with int32 (LSE / workspace offsets, grids).
@@ -64,9 +64,9 @@ attn_gqa_params_t as_gqa(const attn_params_t &p)
     return g;
 }
 
-// The kernels exist for D = 64 and D = 128; other head dimensions (multiples of 8) run in the
+// The kernels exist for D = 64, 128 and 256; other head dimensions (multiples of 8) run in the
 // next larger one with the missing columns read as zeros.
-int kernel_d(int D) { return D <= 64 ? 64 : 128; }
+int kernel_d(int D) { return D <= 64 ? 64 : D <= 128 ? 128 : 256; }
 
 size_t round_ws(size_t bytes) { return (bytes + kWsAlign - 1) / kWsAlign * kWsAlign; }
 
@@ -470,7 +470,7 @@ const char *attn_status_string(int status)
     switch (status) {
         case ATTN_OK: return "ok";
         case ATTN_ERR_NULL: return "a required pointer is NULL";
-        case ATTN_ERR_SHAPE: return "unsupported shape (B,H,S >= 1, D a multiple of 8 up to 128, Hkv divides Hq, B*H*S < 2^31, causal needs Sk >= Sq)";
+        case ATTN_ERR_SHAPE: return "unsupported shape (B,H,S >= 1, D a multiple of 8 up to 256, Hkv divides Hq, B*H*S < 2^31, causal needs Sk >= Sq)";
         case ATTN_ERR_STRIDE: return "bad stride (D contiguous, strides multiples of 8 elements, stride_s >= D)";
         case ATTN_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
         case ATTN_ERR_WORKSPACE: return "workspace missing, misaligned (256 B) or too small";

@@ -82,7 +82,8 @@ struct DkdvCfg {
     static constexpr int kThreads = kWaves * 64;
     static constexpr int kBlk = kPairs * 32;         // keys owned by the work-group
     static constexpr int kRows = 32;                 // query rows per slot
-    static constexpr int kAhead = 3;                 // slots requested ahead of the producer
+    // slots requested ahead of the producer (a slot of D = 256 is 32 KB: one fewer fits)
+    static constexpr int kAhead = D > 128 ? 2 : 3;
     static constexpr int kRing = kAhead + 2;
     static constexpr int kRowBytes = D * 2;
     static constexpr int kTensorBytes = kRows * kRowBytes;   // Q part of a slot; dO follows
@@ -101,7 +102,7 @@ struct DkdvCfg {
 };
 
 template <int D, int P, bool CAUSAL>
-__global__ void __launch_bounds__(P * 128) __attribute__((amdgpu_waves_per_eu(P / 2)))
+__global__ void __launch_bounds__(P * 128) __attribute__((amdgpu_waves_per_eu(P >= 4 ? P / 2 : 1)))
 attn_bwd_dkdv_kernel(const BwdArgs a)
 {
     using C = DkdvCfg<D, P>;
@@ -134,7 +135,7 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     // different 16-byte bank groups) and 4 consecutive rows differ in the upper two bits (the
     // 4 rows x 64 bytes of a transpose read spread over all banks)
     auto swz = [](int row) {
-        return CPR == 16 ? (((row & 3) << 2) | ((row >> 2) & 3))
+        return CPR >= 16 ? (((row & 3) << 2) | ((row >> 2) & 3))
                          : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
     };
 
@@ -387,7 +388,8 @@ template <int D, int NW>
 struct DqCfg {
     static constexpr int kThreads = NW * 64;
     static constexpr int kBlk = NW * 32;             // queries owned by the work-group
-    static constexpr int kTile = 64;                 // keys per tile
+    static constexpr int kTile = D > 128 ? 32 : 64;  // keys per tile (a ring of three must fit the LDS)
+    static constexpr int kSub = kTile / 32;          // 32-key sub-tiles per tile
     static constexpr int kRing = 3;
     static constexpr int kRowBytes = D * 2;
     static constexpr int kPieceRows = 1024 / kRowBytes;       // rows one 1 KB transfer fills
@@ -405,7 +407,7 @@ struct DqCfg {
 };
 
 template <int D, int NW, bool CAUSAL, bool SPLIT>
-__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2)))
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(D > 128 ? 1 : 2)))
 attn_bwd_dq_kernel(const BwdArgs a)
 {
     using C = DqCfg<D, NW>;
@@ -588,7 +590,7 @@ attn_bwd_dq_kernel(const BwdArgs a)
             }
         }
     };
-    // One tile of 64 keys at ring position `pos`.
+    // One tile at ring position `pos`.
     auto tile = [&](int kt, int pos, const char *Kt, int rowa, int tra0, int tra1, desc_t Kd,
                     desc_t Vd) __attribute__((always_inline)) {
         // tile kt must have landed; tile kt+1 (if any) may stay in flight
@@ -601,7 +603,7 @@ attn_bwd_dq_kernel(const BwdArgs a)
         const bool act0 = k0 < Sk && (!CAUSAL || k0 <= q0e + 31);
         const bool act1 = k0 + 32 < Sk && (!CAUSAL || k0 + 32 <= q0e + 31);
 #pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2) {
+        for (int kb2 = 0; kb2 < C::kSub; ++kb2) {
             if (!(kb2 ? act1 : act0)) continue;
             f32x16 s, dp;
             elem8 sb[2];
@@ -736,11 +738,16 @@ static int launch_dkdv_p(BwdArgs a, hipStream_t st)
 template <int D, bool CAUSAL>
 static int launch_dkdv(const BwdArgs &a, hipStream_t st)
 {
-    if constexpr (D == 128) {
-        const int64_t wgs6 = (int64_t)(a.BH / a.group) * ((a.Sk + 191) / 192);
-        if (wgs6 >= 512) return launch_dkdv_p<D, 6, CAUSAL>(a, st);
+    // D = 256: two pairs, one wave per SIMD (a consumer's two 32 x 256 accumulators alone are
+    // 256 registers), 64 keys per work-group
+    if constexpr (D > 128) return launch_dkdv_p<D, 2, CAUSAL>(a, st);
+    else {
+        if constexpr (D == 128) {
+            const int64_t wgs6 = (int64_t)(a.BH / a.group) * ((a.Sk + 191) / 192);
+            if (wgs6 >= 512) return launch_dkdv_p<D, 6, CAUSAL>(a, st);
+        }
+        return launch_dkdv_p<D, 4, CAUSAL>(a, st);
     }
-    return launch_dkdv_p<D, 4, CAUSAL>(a, st);
 }
 
 template <int D, int NW, bool CAUSAL>
@@ -774,6 +781,10 @@ static int launch_dq_split(BwdArgs a, hipStream_t st)
 template <int D, bool CAUSAL>
 static int launch_dq_for(const BwdArgs &a, hipStream_t st)
 {
+    // D = 256: always four waves, one per SIMD (Q and dO fragments plus the accumulator are
+    // 256 registers); never split
+    if constexpr (D > 128) return a.dq_nsplit > 1 ? -1 : launch_dq<D, 4, CAUSAL>(a, st);
+    else {
     if (a.dq_nsplit > 1) return launch_dq_split<D, CAUSAL>(a, st);
     const int blocks32 = (a.S + 31) / 32;
     // 256-row work-groups unless they would leave compute units (256) idle while 128-row
@@ -792,6 +803,7 @@ static int launch_dq_for(const BwdArgs &a, hipStream_t st)
     // one wave: only D = 64 (with D = 128 a lone wave would spill while it streams tiles)
     if constexpr (D < 128) return launch_dq<D, 1, CAUSAL>(a, st);
     return -1;
+    }
 }
 
 // Order of a full backward: dQ (which also forms the row statistics and stores them), then
@@ -822,7 +834,11 @@ static int launch_bwd_d(BwdArgs a, bool causal, hipStream_t st, unsigned stages)
 #ifndef ATTN_F16  // a function of the shape only: defined once, by the bf16 build
 int dq_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps)
 {
-    (void)D; (void)causal;
+    (void)causal;
+    if (D > 128) {  // the kernel for head dimensions above 128 is not split
+        if (kps) *kps = (Sk + 63) / 64 * 64;
+        return 1;
+    }
     const int64_t wgs = (int64_t)BH * ((S + 255) / 256);
     const int tiles = (Sk + 63) / 64;
     int nsplit = 1;
@@ -840,7 +856,8 @@ int dq_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps)
 
 int launch_bwd(const BwdArgs &a, int D, bool causal, hipStream_t st, unsigned stages)
 {
-    return D == 128 ? launch_bwd_d<128>(a, causal, st, stages)
+    return D == 256 ? launch_bwd_d<256>(a, causal, st, stages)
+         : D == 128 ? launch_bwd_d<128>(a, causal, st, stages)
                     : launch_bwd_d<64>(a, causal, st, stages);
 }
 

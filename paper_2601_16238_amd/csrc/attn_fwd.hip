@@ -704,6 +704,10 @@ static int launch_fwd_d(FwdArgs a, bool causal, hipStream_t st)
 #ifndef ATTN_F16  // a function of the shape only: defined once, by the bf16 build
 int fwd_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps)
 {
+    if (D > 128) {  // the kernel for head dimensions above 128 is not split
+        if (kps) *kps = (Sk + 63) / 64 * 64;
+        return 1;
+    }
     const int nw = fwd_waves_for(S, D, BH, causal);
     const int64_t wgs = (int64_t)BH * ((S + nw * 32 - 1) / (nw * 32));
     const int64_t target = 256;
@@ -723,6 +727,7 @@ int fwd_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps)
 
 int launch_fwd(const FwdArgs &a, int D, bool causal, hipStream_t st)
 {
+    if (D == 256) return launch_fwd_wide(a, causal, st);
     return D == 128 ? launch_fwd_d<128>(a, causal, st) : launch_fwd_d<64>(a, causal, st);
 }
 

@@ -31,7 +31,7 @@ struct FwdArgsT {
     int S, H, BH;
     int Sk;             // key/value rows
     int Dr;             // head dimension of the tensors (a multiple of 8); the kernels run at
-                        // D = 64 or 128 and treat columns Dr..D-1 as zeros
+                        // D = 64, 128 or 256 and treat columns Dr..D-1 as zeros
     int group;          // query heads per K/V head
     int nqt;            // query tiles per head (set by the launcher)
     float scale_log2e;  // scale * log2(e): the softmax runs on exp2
@@ -85,6 +85,9 @@ typedef BwdArgsT<elem> BwdArgs;
 // element type; each is defined by the build of the kernel sources for that type.
 int launch_fwd(const FwdArgsT<__bf16> &a, int D, bool causal, hipStream_t st);
 int launch_fwd(const FwdArgsT<_Float16> &a, int D, bool causal, hipStream_t st);
+// The forward for head dimensions 129..256 (called by launch_fwd with D == 256).
+int launch_fwd_wide(const FwdArgsT<__bf16> &a, bool causal, hipStream_t st);
+int launch_fwd_wide(const FwdArgsT<_Float16> &a, bool causal, hipStream_t st);
 // Number of key splits the forward would use for this problem (1: none), and the keys per
 // split; a pure host function of the shape.
 int fwd_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps);

@@ -144,7 +144,7 @@ def test_gqa_params_contiguous_and_workspace_size():
     (lambda p: setattr(p, "Hkv", 3), binding.ATTN_ERR_SHAPE),           # 3 does not divide 8
     (lambda p: setattr(p, "Hkv", 0), binding.ATTN_ERR_SHAPE),
     (lambda p: setattr(p, "Hkv", 16), binding.ATTN_ERR_SHAPE),          # more K/V than query heads
-    (lambda p: setattr(p, "D", 136), binding.ATTN_ERR_SHAPE),
+    (lambda p: setattr(p, "D", 264), binding.ATTN_ERR_SHAPE),           # above the widest kernel
     (lambda p: setattr(p, "kv_stride_s", 60), binding.ATTN_ERR_STRIDE),
     (lambda p: setattr(p, "kv_stride_h", 132), binding.ATTN_ERR_STRIDE),
     (lambda p: setattr(p, "q_stride_b", 4), binding.ATTN_ERR_STRIDE),
