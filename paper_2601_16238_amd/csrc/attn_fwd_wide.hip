@@ -36,13 +36,16 @@ struct WideCfg {
     static constexpr int kKHalfBytes = kKTileBytes / 2;     // 32 rows further
     static constexpr int kKStepBytes = 2 * kPR * 16;        // next contraction step
     static constexpr int kKDmaPerWave = kKPieces / kNW;
-    static constexpr int kLdV = kBC + 8;                    // V^T tile [d][key order], rows skewed
-    static constexpr int kVTileBytes = kD * kLdV * 2;
-    static constexpr int kVMicro = (kBC / 4) * (kD / 4);    // 4 keys x 4 d micro-tiles
-    static constexpr int kVPerThread = kVMicro / kThreads;
+    // V tile: the same transfers and chunk-major pieces, but pieces 128 bytes further apart
+    // than their size: the tile is only read with the LDS transpose read (the A operand of
+    // O^T += V^T P^T is V^T), whose 32 lanes per half wave fetch 4 rows x 64 bytes, i.e. 128
+    // contiguous bytes in each of two neighbouring pieces, which then fall into disjoint banks.
+    static constexpr int kVPieceBytes = 1024 + 128;
+    static constexpr int kVTileBytes = kKPieces * kVPieceBytes;
+    static constexpr int kVRows16 = (16 / kPR) * kVPieceBytes;   // 16 rows further
     static constexpr int kOffV = 2 * kKTileBytes;
     static constexpr int kLdsBytes = 2 * (kKTileBytes + kVTileBytes);
-    static_assert(kVMicro % kThreads == 0 && kKPieces % kNW == 0, "staging divides evenly");
+    static_assert(kKPieces % kNW == 0, "staging divides evenly");
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 CU exceeded");
 };
 
@@ -86,58 +89,30 @@ attn_fwd_wide_kernel(const FwdArgs a)
     // ---- staging.  Rows past Sk-1, tiles past the last one and columns Dr..D-1 lie outside
     // the head's buffer resource and read as zero.
     const uint32_t head_bytes = (uint32_t)(((int64_t)(Sk - 1) * a.kv_stride_s + Dr) * 2);
-    const rsrc_t Kr = make_rsrc(a.K + base_kv, head_bytes), Vr = make_rsrc(a.V + base_kv, head_bytes);
+    const desc_t Kd = make_desc(a.K + base_kv, head_bytes), Vd = make_desc(a.V + base_kv, head_bytes);
+    const uint32_t lds0 = lds_address(smem);
     const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2u;
     const uint32_t tile_bytes = C::kBC * row_bytes;
     // K: lane l of a transfer fetches chunk l / 2 of the piece's row l % 2
     const uint32_t k_voff = (l / PR) * 8 < Dr ? (l % PR) * row_bytes + ((l / PR) << 4) : head_bytes;
-    auto dma_k = [&](int kt, int buf) {
+    // (The transfers are issued from assembly, out of the compiler's sight: it would otherwise
+    // make the wave wait for all of them before its next transpose read of LDS.  stage() orders
+    // them against the reads.)
+    auto dma_k = [&](int kt, int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int n = 0; n < C::kKDmaPerWave; ++n) {
             const int ii = w + n * C::kNW;  // which piece of the tile: wave-uniform
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                Kr, (void __attribute__((address_space(3))) *)(smem + buf * C::kKTileBytes + ii * C::kKPieceBytes),
-                16, (int)k_voff, kt * tile_bytes + ii * PR * row_bytes, 0, 0);
+            dma16(Kd, lds0 + buf * C::kKTileBytes + ii * C::kKPieceBytes, k_voff,
+                  kt * tile_bytes + ii * PR * row_bytes);
         }
     };
-    // V: global -> registers -> transposed into LDS.  Micro-tile mt = 4 keys x 4 d; a wave
-    // covers 32 keys x 32 d as 8 key groups x 8 d groups.
-    auto v_coords = [&](int mt, int &key0, int &d0) {
-        const int blk = mt >> 6;
-        key0 = 32 * (blk & 1) + 4 * (mt & 7);
-        d0 = 32 * (blk >> 1) + 4 * ((mt >> 3) & 7);
-    };
-    u32x2 vreg[C::kVPerThread][4];
-    auto load_v = [&](int kt) {
+    // V goes the same way, row-major; it is transposed by the reads.
+    auto dma_v = [&](int kt, int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int n = 0; n < C::kVPerThread; ++n) {
-            int key0, d0;
-            v_coords(tid + n * C::kThreads, key0, d0);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                vreg[n][i] = buf_load8(Vr, d0 < Dr ? (key0 + i) * row_bytes + d0 * 2 : head_bytes,
-                                       kt * tile_bytes);
-        }
-    };
-    auto store_v = [&](int buf) {
-#pragma unroll
-        for (int n = 0; n < C::kVPerThread; ++n) {
-            int key0, d0;
-            v_coords(tid + n * C::kThreads, key0, d0);
-            // position of key0 (a multiple of 4) in the MFMA contraction order:
-            // key = 16 cc + 8 u + 4 hh + e  ->  16 cc + 8 hh + 4 u + e
-            const int kpos = (key0 & ~15) | ((key0 & 4) << 1) | ((key0 & 8) >> 1);
-            elem *dst = reinterpret_cast<elem *>(smem + C::kOffV + buf * C::kVTileBytes) + d0 * C::kLdV + kpos;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                // column d0 + j of the 4 x 4 micro-tile: keys key0 .. key0 + 3
-                const unsigned sel = (j & 1) ? 0x07060302u : 0x05040100u;
-                const int hw = j >> 1;
-                u32x2 col;
-                col.x = __builtin_amdgcn_perm(vreg[n][1][hw], vreg[n][0][hw], sel);
-                col.y = __builtin_amdgcn_perm(vreg[n][3][hw], vreg[n][2][hw], sel);
-                *(u32x2 *)(dst + j * C::kLdV) = col;
-            }
+        for (int n = 0; n < C::kKDmaPerWave; ++n) {
+            const int ii = w + n * C::kNW;
+            dma16(Vd, lds0 + C::kOffV + buf * C::kVTileBytes + ii * C::kVPieceBytes, k_voff,
+                  kt * tile_bytes + ii * PR * row_bytes);
         }
     };
 
@@ -152,7 +127,16 @@ attn_fwd_wide_kernel(const FwdArgs a)
     const float c = a.scale_log2e;
 
     const int k_lane = (r / PR) * C::kKPieceBytes + (h * PR + r % PR) * 16;
-    const int v_lane = C::kOffV + (r * C::kLdV + 8 * h) * 2;
+    // transpose reads of the V tile: the 16-lane group reads rows 4h + e (e = 0..3; +8 for the
+    // second read), 64 bytes of d block 0 of each row -- the keys of contraction half h in the
+    // order the accumulator of S^T holds them
+    auto v_at = [](int row, int chunk) {
+        return (row / PR) * C::kVPieceBytes + (chunk * PR + row % PR) * 16;
+    };
+    int v_lane[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+        v_lane[j] = C::kOffV + v_at(8 * j + 4 * h + ((l & 15) >> 2), 2 * ((l >> 4) & 1) + ((l >> 1) & 1)) + (l & 1) * 8;
 
     // S^T of sub-tile u of the tile in buffer buf
     auto scores = [&](int buf, int u, f32x16 &s) __attribute__((always_inline)) {
@@ -223,55 +207,105 @@ attn_fwd_wide_kernel(const FwdArgs a)
     };
     // O^T += V^T P^T for sub-tile u of the V tile in buffer buf
     auto pv = [&](int buf, int u, elem8 p0, elem8 p1) __attribute__((always_inline)) {
-        const char *Vt = smem + buf * C::kVTileBytes + 64 * u + v_lane;
+        const char *Vt = smem + buf * C::kVTileBytes + 2 * u * C::kVRows16;
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-            o[db] = mfma32(*(const elem8 *)(Vt + 32 * db * C::kLdV * 2), p0, o[db]);
-            o[db] = mfma32(*(const elem8 *)(Vt + 32 * db * C::kLdV * 2 + 32), p1, o[db]);
+            const char *Vd = Vt + db * 4 * PR * 16;  // d block db: four chunks further
+            const elem8 f0 = join8(lds_read_tr((const elem *)(Vd + v_lane[0])),
+                                    lds_read_tr((const elem *)(Vd + v_lane[1])));
+            const elem8 f1 = join8(lds_read_tr((const elem *)(Vd + C::kVRows16 + v_lane[0])),
+                                    lds_read_tr((const elem *)(Vd + C::kVRows16 + v_lane[1])));
+            o[db] = mfma32(f0, p0, o[db]);
+            o[db] = mfma32(f1, p1, o[db]);
         }
     };
-    // Start of iteration kt: V(kt) -> LDS (the buffer's previous tile, kt-2, was last read before
-    // the barrier of iteration kt-1); K(kt) has been on its way since iteration kt-1.  After the
-    // barrier the other buffers are free and take tile kt+1.
+    // Start of iteration kt: K(kt) and V(kt) have been on their way since iteration kt-1.  After
+    // the barrier the other buffers (tile kt-1, last read before the barrier) are free and take
+    // tile kt+1; its transfers are issued by the steps of the iteration (fetch_next), so that the
+    // waves do not all queue at the compute unit's vector-memory path at once while the matrix
+    // pipes idle.
     auto stage = [&](int kt) __attribute__((always_inline)) {
-        store_v(kt & 1);
+        (void)kt;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (kt + 1 < n_kt) {
-            dma_k(kt + 1, (kt & 1) ^ 1);
-            load_v(kt + 1);
+    };
+    // part 0: K(kt+1); part 1: V(kt+1)
+    auto fetch_next = [&](int kt, int part) __attribute__((always_inline)) {
+        if (kt + 1 >= n_kt) return;
+        if (part == 0) dma_k(kt + 1, (kt & 1) ^ 1);
+        if (part == 1) dma_v(kt + 1, (kt & 1) ^ 1);
+    };
+    auto commit = [&](elem8 p0, elem8 p1, float psum) __attribute__((always_inline)) {
+        lsum += psum;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            hsum = dot2_acc(p0[2 * i], p0[2 * i + 1], hsum);
+            hsum = dot2_acc(p1[2 * i], p1[2 * i + 1], hsum);
         }
     };
+    auto overflow = [&](float psum) { return __builtin_amdgcn_ballot_w64(psum > kWideOverflow) != 0; };
 
     if (n_kt > 0) {
         dma_k(0, 0);
-        load_v(0);
+        dma_v(0, 0);
     }
     // Tiles of which this wave sees some key come first; for the rest of the work-group's tiles
     // (under a causal mask, the waves with the earlier rows) it only takes part in the staging.
     // A second sub-tile that lies wholly above the wave's diagonal is computed with every score
     // masked: one code path, and it only happens on the diagonal tile.
     const int n_mine = CAUSAL ? __builtin_amdgcn_readfirstlane(min(n_kt, (q0e + 31) / C::kBC + 1)) : n_kt;
-    for (int kt = 0; kt < n_mine; ++kt) {
-        const int buf = kt & 1;
-        stage(kt);
-        f32x16 sA, sB;
-        elem8 pA0, pA1, pB0, pB1;
-        float sumA, sumB;
-        scores(buf, 0, sA);                         // A
-        mask(kt, 0, sA);
-        scores(buf, 1, sB);                         // B
-        probs(sA, pA0, pA1, sumA);
-        __builtin_amdgcn_sched_barrier(0);
-        settle(sA, pA0, pA1, sumA);
-        mask(kt, 1, sB);
-        pv(buf, 0, pA0, pA1);                       // C
-        probs(sB, pB0, pB1, sumB);
-        __builtin_amdgcn_sched_barrier(0);
-        settle(sB, pB0, pB1, sumB);
-        pv(buf, 1, pB0, pB1);                       // D
+    // The loop over the tiles is written twice.  The inner, fast form never touches the O^T
+    // accumulators with the vector ALU: when a sub-tile's probabilities show that the reference
+    // max must move, it leaves the loop before that sub-tile is added, and the slow form below
+    // finishes the tile (rescaling what has been accumulated) and hands back.  With the rescaling
+    // inside the one loop the register allocator moved all 128 accumulator registers between the
+    // two halves of the register file in every iteration.
+    int kt = 0;
+    while (kt < n_mine) {
+        int redo = -1;  // first sub-tile of tile kt that the slow form has to take over
+        for (; kt < n_mine; ++kt) {
+            const int buf = kt & 1;
+            stage(kt);
+            f32x16 sA, sB;
+            elem8 pA0, pA1, pB0, pB1;
+            float sumA, sumB;
+            scores(buf, 0, sA);                         // A
+            fetch_next(kt, 0);
+            mask(kt, 0, sA);
+            scores(buf, 1, sB);                         // B
+            fetch_next(kt, 1);
+            probs(sA, pA0, pA1, sumA);
+            __builtin_amdgcn_sched_barrier(0);
+            if (__builtin_expect(overflow(sumA), 0)) { redo = 0; break; }
+            commit(pA0, pA1, sumA);
+            mask(kt, 1, sB);
+            pv(buf, 0, pA0, pA1);                       // C
+            probs(sB, pB0, pB1, sumB);
+            __builtin_amdgcn_sched_barrier(0);
+            if (__builtin_expect(overflow(sumB), 0)) { redo = 1; break; }
+            commit(pB0, pB1, sumB);
+            pv(buf, 1, pB0, pB1);                       // D
+        }
+        if (redo >= 0) {
+            const int buf = kt & 1;
+            for (int u = redo; u < 2; ++u) {
+                f32x16 sx;
+                elem8 p0, p1;
+                float psum;
+                if (u == 0) scores(buf, 0, sx); else scores(buf, 1, sx);
+                mask(kt, u, sx);
+                probs(sx, p0, p1, psum);
+                settle(sx, p0, p1, psum);
+                if (u == 0) pv(buf, 0, p0, p1); else pv(buf, 1, p0, p1);
+            }
+            ++kt;
+        }
     }
-    for (int kt = n_mine; kt < n_kt; ++kt) stage(kt);
+    for (kt = n_mine; kt < n_kt; ++kt) {
+        stage(kt);
+        fetch_next(kt, 0);
+        fetch_next(kt, 1);
+    }
 
     // Epilogue: O = O_acc / l, LSE = ln2 * (m + log2 l).
     const float lt = xhalf_sum(lsum);

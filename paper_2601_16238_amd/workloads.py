@@ -32,6 +32,8 @@ WORKLOADS = {w.name: w for w in [
              "long-sequence causal, 1% of Q/K rows x8"),
     Workload("paper_table", 32, 10, 2048, 128, True, 1.0, 0.0, 1.0, 1006,
              "the microbenchmark table's own shape (context only)"),
+    Workload("headdim256", 4, 16, 4096, 256, True, 1.0, 0.0, 1.0, 1007,
+             "head dimension 256 (the kernels with one wave per SIMD), causal"),
 ]}
 
 
