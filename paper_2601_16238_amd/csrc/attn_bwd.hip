@@ -395,13 +395,23 @@ struct DqCfg {
     static constexpr int kPieceRows = 1024 / kRowBytes;       // rows one 1 KB transfer fills
     static constexpr int kPieceBytes = 1024 + kPieceRows * 16;
     static constexpr int kPieces = kTile / kPieceRows;        // per tensor
-    static constexpr int kTensorBytes = kPieces * kPieceBytes;   // K part of a tile; V follows
+    // D = 256 (two rows per piece): the uniform piece distance that spreads the row reads over
+    // the banks puts the four rows of a transpose read into overlapping banks.  Pieces are laid
+    // out in pairs instead: the second of a pair 1024 + 128 bytes after the first (the two pieces
+    // a transpose read touches then fall into different halves of the banks), pairs 2 * 1024 +
+    // 128 + 160 bytes apart (16 consecutive rows at a fixed chunk: 16 different 16-byte bank groups).
+    static constexpr int kPairBytes = 2 * 1024 + 128 + 160;
+    static constexpr int piece_base(int piece)
+    {
+        return D > 128 ? (piece >> 1) * kPairBytes + (piece & 1) * (1024 + 128) : piece * kPieceBytes;
+    }
+    static constexpr int kTensorBytes = piece_base(kPieces);     // K part of a tile; V follows
     static constexpr int kTileBytes = 2 * kTensorBytes;
     static constexpr int kLdsBytes = kRing * kTileBytes;
     static constexpr int kDmaPerTile = 2 * kPieces;           // wave-wide 1 KB transfers
     static constexpr int kDmaPerWave = (kDmaPerTile + NW - 1) / NW;
     static constexpr int kChunkStep = kPieceRows * 16;        // next 16-byte chunk of a row
-    static constexpr int kRows16 = (16 / kPieceRows) * kPieceBytes;  // 16 rows further
+    static constexpr int kRows16 = piece_base(16 / kPieceRows);      // 16 rows further
     static_assert(16 % kPieceRows == 0, "sub-tiles start at piece boundaries");
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 CU exceeded");
 };
@@ -447,7 +457,7 @@ attn_bwd_dq_kernel(const BwdArgs a)
 
     // byte offset of 16-byte chunk `chunk` of row `row` within a tile tensor
     auto at = [](int row, int chunk) {
-        return (row / PR) * C::kPieceBytes + (chunk * PR + row % PR) * 16;
+        return C::piece_base(row / PR) + (chunk * PR + row % PR) * 16;
     };
 
     // ---- streaming of tile kt into ring position pos; rows past S-1 read as zero
@@ -471,7 +481,7 @@ attn_bwd_dq_kernel(const BwdArgs a)
             const int i = (w + n * NW) % C::kDmaPerTile;
             const int tensor = i / C::kPieces, piece = i % C::kPieces;
             dma16(tensor ? Vd : Kd,
-                  lds0 + pos * C::kTileBytes + tensor * C::kTensorBytes + piece * C::kPieceBytes,
+                  lds0 + pos * C::kTileBytes + tensor * C::kTensorBytes + C::piece_base(piece),
                   voff, (kt * C::kTile + piece * PR) * row_bytes);
         }
     };
