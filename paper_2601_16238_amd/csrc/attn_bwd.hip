@@ -145,11 +145,13 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     // the end of the resource, so they read as zero like everything else outside it.
     const int Dr = a.Dr;
     const uint32_t head_bytes = (uint32_t)(((int64_t)(S - 1) * a.stride_s + Dr) * 2);
-    rsrc_t Qr, Gr, Wr;  // Q, dO and row statistics of the current query head
+    desc_t Qd, Gd;  // Q and dO of the current query head
+    rsrc_t Wr;      // its row statistics
+    const uint32_t lds0 = lds_address(smem);
     auto set_head = [&](int bh) {
         const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
-        Qr = make_rsrc(a.Q + base, head_bytes);
-        Gr = make_rsrc(a.dO + base, head_bytes);
+        Qd = make_desc(a.Q + base, head_bytes);
+        Gd = make_desc(a.dO + base, head_bytes);
         Wr = make_rsrc(a.delta + (int64_t)bh * 2 * S, (uint32_t)S * 8u);
     };
     const uint32_t row_bytes = (uint32_t)a.stride_s * 2u;
@@ -164,20 +166,31 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     }
     // stats: lanes 0-31 fetch lse2 (second half of the head's workspace), 32-63 delta
     const uint32_t stat_voff = (uint32_t)(h ? r : S + r) * 4u;
-    auto dma_slot = [&](int t, int rs) {
+    // The statistics first, then this wave's kDmaPerWave pieces of Q and dO.  The pieces are
+    // issued from assembly without a memory clobber: they fill a ring position that nobody reads
+    // before a later barrier, so the compiler may move this slot's LDS reads across them, which
+    // lets the producers issue them one by one between their MFMAs instead of in a burst in front
+    // (a burst makes the waves queue at the vector-memory path while the matrix pipe idles).  The
+    // waits and barriers that order them against the reads are volatile assembly too.
+    auto dma_stat = [&](int t, int rs) __attribute__((always_inline)) {
         if (w == C::kStatWave)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 Wr, (void __attribute__((address_space(3))) *)(smem + C::kOffStat + rs * C::kStatBytes),
                 4, (int)stat_voff, t * C::kRows * 4, 0, 0);
+    };
+    auto dma_piece = [&](int t, int rs, int n) __attribute__((always_inline)) {
+        const int tensor = n / (C::kDmaPerWave / 2);  // Q transfers first, then dO
+        const int grp = (pair + (n % (C::kDmaPerWave / 2)) * C::kPairs) % C::kDmaPerTensor;  // 1 KB piece
+        const uint32_t dst = lds0 + rs * C::kSlotBytes + tensor * C::kTensorBytes + grp * 1024;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     ::"s"(__builtin_amdgcn_readfirstlane(dst)), "v"(dma_voff[n]), "s"(tensor == 0 ? Qd : Gd),
+                     "s"(__builtin_amdgcn_readfirstlane((uint32_t)(t * C::kRows * row_bytes)))
+                     : "m0");
+    };
+    auto dma_slot = [&](int t, int rs) __attribute__((always_inline)) {
+        dma_stat(t, rs);
 #pragma unroll
-        for (int n = 0; n < C::kDmaPerWave; ++n) {
-            const int tensor = n / (C::kDmaPerWave / 2);  // Q transfers first, then dO
-            const int grp = (pair + (n % (C::kDmaPerWave / 2)) * C::kPairs) % C::kDmaPerTensor;  // 1 KB piece
-            char *dst = smem + rs * C::kSlotBytes + tensor * C::kTensorBytes + grp * 1024;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                tensor == 0 ? Qr : Gr, (void __attribute__((address_space(3))) *)dst, 16,
-                (int)dma_voff[n], (int)(t * C::kRows * row_bytes), 0, 0);
-        }
+        for (int n = 0; n < C::kDmaPerWave; ++n) dma_piece(t, rs, n);
     };
     // Before slot t is used: this wave's transfers of slot t must have landed (those of the
     // kAhead-1 newer slots may stay in flight) and everyone must be done with slot t-2.
@@ -217,8 +230,11 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
             slot_barrier();
             int rd = rs + C::kAhead;
             rd = rd >= C::kRing ? rd - C::kRing : rd;
-            dma_slot(t + C::kAhead, rd);
-            if (active(t)) {
+            dma_stat(t + C::kAhead, rd);
+            if (!active(t)) {
+#pragma unroll
+                for (int n = 0; n < C::kDmaPerWave; ++n) dma_piece(t + C::kAhead, rd, n);
+            } else {
                 const char *Qt = smem + rs * C::kSlotBytes;
                 const float *st = reinterpret_cast<const float *>(smem + C::kOffStat + rs * C::kStatBytes);
                 const int q_lo = t * C::kRows;
@@ -238,11 +254,17 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
                     s = mfma32(*(const elem8 *)(Qt + lane_off), kf[0], zero);
                     dp = mfma32(*(const elem8 *)(Qt + C::kTensorBytes + lane_off), vf[0], nd);
                 }
+                // the transfers of slot t + kAhead go between the MFMAs, evenly spread: piece j
+                // after contraction step (j + 1) * kEvery - 1
+                constexpr int kEvery = KS / C::kDmaPerWave;
+                static_assert(kEvery >= 1 && kEvery * C::kDmaPerWave == KS, "transfers spread evenly");
+                if (kEvery == 1) dma_piece(t + C::kAhead, rd, 0);
 #pragma unroll
                 for (int ks = 1; ks < KS; ++ks) {
                     const int off = lane_off ^ (ks * 32);
                     s = mfma32(*(const elem8 *)(Qt + off), kf[ks], s);
                     dp = mfma32(*(const elem8 *)(Qt + C::kTensorBytes + off), vf[ks], dp);
+                    if ((ks + 1) % kEvery == 0) dma_piece(t + C::kAhead, rd, (ks + 1) / kEvery - 1);
                 }
                 // the lane's key is fixed; P = exp2(c S - lse2) per row
 #pragma unroll

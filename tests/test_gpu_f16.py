@@ -17,6 +17,7 @@ CASES = [
     (1, 2, 2, 300, 300, 128, True), (1, 4, 1, 513, 513, 128, False), (1, 2, 2, 33, 64, 64, True),
     (2, 4, 2, 100, 356, 128, True), (2, 8, 2, 1, 300, 64, True), (1, 4, 4, 150, 77, 64, False),
     (1, 1, 1, 1, 1, 128, True), (1, 2, 2, 1024, 1024, 128, True),
+    (1, 2, 2, 300, 300, 256, True), (1, 4, 2, 130, 200, 192, False),   # the kernels for D > 128
 ]
 
 

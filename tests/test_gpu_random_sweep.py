@@ -16,12 +16,16 @@ from parity_util import bf16_round, check_lse, f16_round, to_dev, to_dev_f16, to
 pytestmark = pytest.mark.gpu
 
 
-def draw_cases(n, seed):
+DIMS = [8, 16, 32, 40, 64, 64, 96, 128, 128, 120]
+WIDE_DIMS = [136, 160, 192, 224, 256, 256]   # the kernels for head dimensions above 128
+
+
+def draw_cases(n, seed, dims=DIMS):
     rng = np.random.Generator(np.random.PCG64(seed))
     cases = []
     while len(cases) < n:
         Hkv = int(rng.integers(1, 4)); G = int(rng.choice([1, 1, 2, 4, 6]))
-        D = int(rng.choice([8, 16, 32, 40, 64, 64, 96, 128, 128, 120]))
+        D = int(rng.choice(dims))
         kind = rng.choice(["square", "decode", "chunk", "cross", "long_keys"])
         if kind == "square":
             Sq = Sk = int(rng.integers(1, 700))
@@ -47,8 +51,21 @@ CASES = draw_cases(int(os.environ.get("ATTN_SWEEP_CASES", "64")),
                    seed=int(os.environ.get("ATTN_SWEEP_SEED", "20260116")))
 
 
+WIDE_CASES = draw_cases(int(os.environ.get("ATTN_SWEEP_WIDE_CASES", "16")),
+                        seed=int(os.environ.get("ATTN_SWEEP_SEED", "20260116")) + 1, dims=WIDE_DIMS)
+
+
 @pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D,causal,split,f16,seed", CASES)
 def test_random_case(B, Hq, Hkv, Sq, Sk, D, causal, split, f16, seed):
+    run_case(B, Hq, Hkv, Sq, Sk, D, causal, split, f16, seed)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D,causal,split,f16,seed", WIDE_CASES)
+def test_random_case_wide_head_dimension(B, Hq, Hkv, Sq, Sk, D, causal, split, f16, seed):
+    run_case(B, Hq, Hkv, Sq, Sk, D, causal, split, f16, seed)
+
+
+def run_case(B, Hq, Hkv, Sq, Sk, D, causal, split, f16, seed):
     print("case sweep", B, Hq, Hkv, Sq, Sk, D, causal, split, f16, seed, flush=True)
     gen = wl.random_rect_inputs_f16 if f16 else wl.random_rect_inputs
     x = gen(B, Hq, Hkv, Sq, Sk, D, seed=seed)
