@@ -166,12 +166,10 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     }
     // stats: lanes 0-31 fetch lse2 (second half of the head's workspace), 32-63 delta
     const uint32_t stat_voff = (uint32_t)(h ? r : S + r) * 4u;
-    // The statistics first, then this wave's kDmaPerWave pieces of Q and dO.  The pieces are
-    // issued from assembly without a memory clobber: they fill a ring position that nobody reads
-    // before a later barrier, so the compiler may move this slot's LDS reads across them, which
-    // lets the producers issue them one by one between their MFMAs instead of in a burst in front
-    // (a burst makes the waves queue at the vector-memory path while the matrix pipe idles).  The
-    // waits and barriers that order them against the reads are volatile assembly too.
+    // The statistics first, then this wave's kDmaPerWave pieces of Q and dO.  The pieces fill a
+    // ring position that nobody reads before a later barrier, and the producers issue them one by
+    // one between their MFMAs instead of in a burst in front (D = 256, sixteen pieces per wave and
+    // slot: 1.46 -> 1.21 ms on B=4 H=16 S=4096; no difference with the four pieces of D = 128).
     auto dma_stat = [&](int t, int rs) __attribute__((always_inline)) {
         if (w == C::kStatWave)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
@@ -182,10 +180,7 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
         const int tensor = n / (C::kDmaPerWave / 2);  // Q transfers first, then dO
         const int grp = (pair + (n % (C::kDmaPerWave / 2)) * C::kPairs) % C::kDmaPerTensor;  // 1 KB piece
         const uint32_t dst = lds0 + rs * C::kSlotBytes + tensor * C::kTensorBytes + grp * 1024;
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                     ::"s"(__builtin_amdgcn_readfirstlane(dst)), "v"(dma_voff[n]), "s"(tensor == 0 ? Qd : Gd),
-                     "s"(__builtin_amdgcn_readfirstlane((uint32_t)(t * C::kRows * row_bytes)))
-                     : "m0");
+        dma16_between(tensor == 0 ? Qd : Gd, dst, dma_voff[n], (uint32_t)(t * C::kRows * row_bytes));
     };
     auto dma_slot = [&](int t, int rs) __attribute__((always_inline)) {
         dma_stat(t, rs);
@@ -444,6 +439,9 @@ attn_bwd_dq_kernel(const BwdArgs a)
 {
     using C = DqCfg<D, NW>;
     constexpr int KS = D / 16, DB = D / 32, PR = C::kPieceRows;
+    // D = 256: a wave's eight transfers per tile are issued between the MFMAs of the tile's first
+    // step instead of in a burst after the barrier
+    constexpr bool kBetween = D > 128 && KS % C::kDmaPerWave == 0;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     const int tid = threadIdx.x, l = tid & 63, r = l & 31, h = l >> 5;
@@ -495,17 +493,19 @@ attn_bwd_dq_kernel(const BwdArgs a)
     // piece's first row goes into the scalar offset (which takes part in the range check like
     // the per-lane one), so one per-lane offset serves every transfer.
     const uint32_t voff = (l / PR) * 8 < Dr ? (l % PR) * row_bytes + ((l / PR) << 4) : head_bytes;
+    auto dma_piece = [&](int kt, int pos, int n, desc_t Kd, desc_t Vd) __attribute__((always_inline)) {
+        // wave-uniform 1 KB piece; a wave with nothing left repeats an earlier piece so
+        // that every wave has the same number of transfers in flight
+        const int i = (w + n * NW) % C::kDmaPerTile;
+        const int tensor = i / C::kPieces, piece = i % C::kPieces;
+        const uint32_t dst = lds0 + pos * C::kTileBytes + tensor * C::kTensorBytes + C::piece_base(piece);
+        const uint32_t soff = (kt * C::kTile + piece * PR) * row_bytes;
+        if (kBetween) dma16_between(tensor ? Vd : Kd, dst, voff, soff);
+        else dma16(tensor ? Vd : Kd, dst, voff, soff);
+    };
     auto dma_tile = [&](int kt, int pos, desc_t Kd, desc_t Vd) __attribute__((always_inline)) {
 #pragma unroll
-        for (int n = 0; n < C::kDmaPerWave; ++n) {
-            // wave-uniform 1 KB piece; a wave with nothing left repeats an earlier piece so
-            // that every wave has the same number of transfers in flight
-            const int i = (w + n * NW) % C::kDmaPerTile;
-            const int tensor = i / C::kPieces, piece = i % C::kPieces;
-            dma16(tensor ? Vd : Kd,
-                  lds0 + pos * C::kTileBytes + tensor * C::kTensorBytes + C::piece_base(piece),
-                  voff, (kt * C::kTile + piece * PR) * row_bytes);
-        }
+        for (int n = 0; n < C::kDmaPerWave; ++n) dma_piece(kt, pos, n, Kd, Vd);
     };
     if (n_kt > 0) dma_tile(0, 0, Kd0, Vd0);
     if (n_kt > 1) dma_tile(1, 1, Kd0, Vd0);
@@ -585,6 +585,19 @@ attn_bwd_dq_kernel(const BwdArgs a)
         for (int ks = 1; ks < KS; ++ks)
             s = mfma32(*(const elem8 *)(Kt + kb2 * 2 * C::kRows16 + ks * 2 * C::kChunkStep + rowa), qf[ks], s);
     };
+    // the same with the transfers of tile kt_next (into ring position pos_next) between the MFMAs
+    auto step_s_fetch = [&](const char *Kt, int rowa, f32x16 &s, int kt_next, int pos_next, desc_t Kd,
+                            desc_t Vd) __attribute__((always_inline)) {
+        constexpr int kEvery = kBetween ? KS / C::kDmaPerWave : 1;
+        f32x16 zero;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            s = mfma32(*(const elem8 *)(Kt + ks * 2 * C::kChunkStep + rowa), qf[ks], ks ? s : zero);
+            if ((ks + 1) % kEvery == 0) dma_piece(kt_next, pos_next, (ks + 1) / kEvery - 1, Kd, Vd);
+        }
+    };
     auto step_dp = [&](const char *Kt, int rowa, int kb2, f32x16 &dp) __attribute__((always_inline)) {
         const char *Vt = Kt + C::kTensorBytes;
         dp = mfma32(*(const elem8 *)(Vt + kb2 * 2 * C::kRows16 + rowa), gf[0], nd);  // ends as dP - delta
@@ -628,18 +641,21 @@ attn_bwd_dq_kernel(const BwdArgs a)
         // tile kt must have landed; tile kt+1 (if any) may stay in flight
         if (kt + 1 < n_kt) wait_vm_and_barrier<C::kDmaPerWave>();
         else wait_vm_and_barrier<0>();
-        if (kt + 2 < n_kt) dma_tile(kt + 2, pos == 0 ? 2 : pos - 1, Kd, Vd);  // the tile freed by the barrier
+        const bool fetch = kt + 2 < n_kt;  // tile kt + 2 goes into the ring position freed by the barrier
+        if (fetch && !kBetween) dma_tile(kt + 2, pos == 0 ? 2 : pos - 1, Kd, Vd);
 
         const int k0 = kt * C::kTile;
         // wave-uniform: does this wave see any key of the first / second sub-tile
         const bool act0 = k0 < Sk && (!CAUSAL || k0 <= q0e + 31);
         const bool act1 = k0 + 32 < Sk && (!CAUSAL || k0 + 32 <= q0e + 31);
+        if (kBetween && fetch && !act0) dma_tile(kt + 2, pos == 0 ? 2 : pos - 1, Kd, Vd);
 #pragma unroll
         for (int kb2 = 0; kb2 < C::kSub; ++kb2) {
             if (!(kb2 ? act1 : act0)) continue;
             f32x16 s, dp;
             elem8 sb[2];
-            step_s(Kt, rowa, kb2, s);
+            if (kBetween && kb2 == 0 && fetch) step_s_fetch(Kt, rowa, s, kt + 2, pos == 0 ? 2 : pos - 1, Kd, Vd);
+            else step_s(Kt, rowa, kb2, s);
             step_dp(Kt, rowa, kb2, dp);
             step_p(k0 + kb2 * 32, s);
             step_ds(s, dp, sb);

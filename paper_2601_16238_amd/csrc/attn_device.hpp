@@ -155,6 +155,19 @@ __device__ __forceinline__ void dma16(desc_t desc, uint32_t lds_addr, uint32_t v
                  "s"(__builtin_amdgcn_readfirstlane(soff))
                  : "memory", "m0");
 }
+// The 16-byte transfer without the memory clobber, for a transfer into a buffer that no wave
+// reads before a later barrier: the compiler may then move the LDS reads of the current tile
+// across it, so it can be issued between the MFMAs of a step instead of in a burst in front of
+// them (a burst makes the waves of a compute unit queue at its vector-memory path while the
+// matrix pipes idle).  Volatile assembly keeps its order relative to the waits and barriers,
+// which are volatile too.
+__device__ __forceinline__ void dma16_between(desc_t desc, uint32_t lds_addr, uint32_t voff, uint32_t soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 ::"s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(desc),
+                 "s"(__builtin_amdgcn_readfirstlane(soff))
+                 : "m0");
+}
 // Same with 4 bytes per lane: lane i lands at lds_addr + 4 i.
 __device__ __forceinline__ void dma4(desc_t desc, uint32_t lds_addr, uint32_t voff, uint32_t soff)
 {

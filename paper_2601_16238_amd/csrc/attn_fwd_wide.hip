@@ -103,13 +103,7 @@ attn_fwd_wide_kernel(const FwdArgs a)
         const int ii = w + n * C::kNW;  // which piece of the tile: wave-uniform
         const uint32_t lds = tensor ? lds0 + C::kOffV + buf * C::kVTileBytes + ii * C::kVPieceBytes
                                     : lds0 + buf * C::kKTileBytes + ii * C::kKPieceBytes;
-        // no "memory" clobber: the transfer writes the buffer that nobody reads in this iteration,
-        // so the compiler may move LDS reads across it; the waits and barriers that order it
-        // against the next iteration's reads are volatile assembly too and keep their order
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                     ::"s"(__builtin_amdgcn_readfirstlane(lds)), "v"(k_voff), "s"(tensor ? Vd : Kd),
-                     "s"(__builtin_amdgcn_readfirstlane(kt * tile_bytes + ii * PR * row_bytes))
-                     : "m0");
+        dma16_between(tensor ? Vd : Kd, lds, k_voff, kt * tile_bytes + ii * PR * row_bytes);
     };
     auto dma_k = [&](int kt, int buf) __attribute__((always_inline)) {
 #pragma unroll
