@@ -44,7 +44,7 @@ extern "C" {
 typedef enum {
     ATTN_OK = 0,
     ATTN_ERR_NULL = -1,      /* a required pointer is NULL                                  */
-    ATTN_ERR_SHAPE = -2,     /* B,H,S < 1, D not a multiple of 8 in 8..128, Hkv not dividing Hq, or a size
+    ATTN_ERR_SHAPE = -2,     /* B,H,S < 1, D not a multiple of 8 in 8..256, Hkv not dividing Hq, or a size
                                 overflows int32                                             */
     ATTN_ERR_STRIDE = -3,    /* a stride is < its minimum, not a multiple of 8 elements, or
                                 (S + 512) * stride_s * 2 bytes does not fit in 32 bits        */
@@ -57,7 +57,7 @@ typedef enum {
 /* Problem description shared by forward and backward (host memory, read during the call). */
 typedef struct {
     int32_t B, H, S, D;   /* batch, heads, sequence length (S_q == S_k), head dim: a multiple of
-                             8, at most 128.  The kernels are built for 64 and 128; any other
+                             8, at most 256.  The kernels are built for 64, 128 and 256; any other
                              value runs in the next larger one, the missing columns read as zeros
                              (never loaded from or stored to memory)                          */
     int64_t stride_b;     /* element strides of all bf16 tensors; the D axis has stride 1     */
