@@ -627,6 +627,17 @@ __global__ void __launch_bounds__(256) attn_fwd_merge_kernel(const FwdArgs a)
     if (d0 == 0) a.LSE[row] = mx + logf(den);
 }
 
+template <int D>
+static int launch_fwd_merge(const FwdArgs &a, hipStream_t st)
+{
+    const int64_t rows = (int64_t)a.BH * a.S;
+    constexpr int TPR = D / 4;                       // threads per row
+    constexpr int RPB = 256 / (TPR > 256 ? 256 : TPR);
+    hipLaunchKernelGGL((attn_fwd_merge_kernel<D>), dim3((unsigned)((rows + RPB - 1) / RPB)),
+                       dim3(256), 0, st, a);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 template <int D, int NW, bool CAUSAL, bool SPLIT>
 static int launch_fwd_kernel(const FwdArgs &a, hipStream_t st)
 {
@@ -638,13 +649,7 @@ static int launch_fwd_kernel(const FwdArgs &a, hipStream_t st)
                        dim3(a.nqt * a.BH, SPLIT ? a.nsplit : 1), dim3(C::kThreads),
                        C::kLdsBytes, st, a);
     if (hipGetLastError() != hipSuccess) return -1;
-    if (SPLIT) {
-        const int64_t rows = (int64_t)a.BH * a.S;
-        constexpr int RPB = 256 / (D / 4);
-        hipLaunchKernelGGL((attn_fwd_merge_kernel<D>), dim3((unsigned)((rows + RPB - 1) / RPB)),
-                           dim3(256), 0, st, a);
-        if (hipGetLastError() != hipSuccess) return -1;
-    }
+    if (SPLIT) return launch_fwd_merge<D>(a, st);
     return 0;
 }
 
@@ -704,11 +709,8 @@ static int launch_fwd_d(FwdArgs a, bool causal, hipStream_t st)
 #ifndef ATTN_F16  // a function of the shape only: defined once, by the bf16 build
 int fwd_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps)
 {
-    if (D > 128) {  // the kernel for head dimensions above 128 is not split
-        if (kps) *kps = (Sk + 63) / 64 * 64;
-        return 1;
-    }
-    const int nw = fwd_waves_for(S, D, BH, causal);
+    // (head dimensions above 128: four waves, 128 rows per work-group)
+    const int nw = D > 128 ? 4 : fwd_waves_for(S, D, BH, causal);
     const int64_t wgs = (int64_t)BH * ((S + nw * 32 - 1) / (nw * 32));
     const int64_t target = 256;
     const int tiles = (Sk + 63) / 64;
@@ -718,6 +720,14 @@ int fwd_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps)
         if (nsplit > tiles / 4) nsplit = tiles / 4;
         if (nsplit > 128) nsplit = 128;
     }
+    // Decoding (at most 32 rows per head) runs in the streaming kernel, of which two work-groups
+    // fit a compute unit: aim at two per unit where that leaves every split 16 tiles or more
+    // (B=8 Hkv=8 Sk=8192: 8 splits, 55.0 -> 49.5 us; B=16 H=16 Sk=4096: 2 splits, 111 -> 103 us;
+    // with shorter ranges the prologues and the merge cost more than the second work-group gains).
+    if (S <= 32 && D <= 128 && wgs < 512) {
+        const int n2 = (int)((512 + wgs - 1) / wgs);
+        if (n2 <= 128 && tiles / n2 >= 16) nsplit = n2;
+    }
     const int tiles_per = (tiles + nsplit - 1) / nsplit;
     nsplit = (tiles + tiles_per - 1) / tiles_per;  // no empty split
     if (kps) *kps = tiles_per * 64;
@@ -725,9 +735,35 @@ int fwd_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps)
 }
 #endif
 
+// Which problems of D <= 128 go to the kernel that streams both tiles by direct transfers
+// (attn_fwd_wide.hip; 128-row work-groups, two K/V buffers) instead of the one above.  Measured,
+// forward only, graph replay, same box:
+//  - at most 32 query rows per head (decoding; one wave of four has rows, the problem is K/V
+//    streaming): B=8 Hq=32 Hkv=8 Sk=8192 62.8 -> 55.0 us (49.5 with the finer split below), B=16
+//    H=16 Sk=4096 129 -> 103, 8 rows on 512 keys at D = 64 12.1 -> 11.0;
+//  - D = 128 and at most 128 rows: S=96 causal 20.0 -> 13.7 us, 128 rows on 1024 keys 26.1 -> 25.4
+//    (the kernel above needs four waves at D = 128 whatever the length); not so at D = 64, where
+//    the short forms of the kernel above are faster (B=128 H=6 S=65: 10.8 against 12.7);
+//  - D = 64 under a causal mask on launches of fewer than four 256-row work-groups per compute
+//    unit: B=8 H=8 S=1024 27.6 -> 23.7 us, B=16 H=16 S=512 35.1 -> 28.3, B=2 H=8 S=4096 77.8 ->
+//    65.8 (large launches are 9 % slower this way, and so is everything else at D = 128 or
+//    without a mask, by 3-12 %).
+static bool prefer_streaming_forward(const FwdArgs &a, int D, bool causal)
+{
+    if (a.rope_cos) return false;  // the rotation of Q is fused into the kernel above only
+    if (a.S <= 32) return true;
+    if (D == 128) return a.S <= 128;
+    return causal && a.S >= 256 && (int64_t)a.BH * ((a.S + 255) / 256) < 1024;
+}
+
 int launch_fwd(const FwdArgs &a, int D, bool causal, hipStream_t st)
 {
-    if (D == 256) return launch_fwd_wide(a, causal, st);
+    if (D == 256 || prefer_streaming_forward(a, D, causal)) {
+        if (launch_fwd_wide(a, D, causal, st)) return -1;
+        if (a.nsplit <= 1) return 0;
+        return D == 256 ? launch_fwd_merge<256>(a, st)
+             : D == 128 ? launch_fwd_merge<128>(a, st) : launch_fwd_merge<64>(a, st);
+    }
     return D == 128 ? launch_fwd_d<128>(a, causal, st) : launch_fwd_d<64>(a, causal, st);
 }
 

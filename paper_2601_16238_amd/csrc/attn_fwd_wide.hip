@@ -1,17 +1,21 @@
-// Fused attention forward for head dimensions above 128 (up to 256) on gfx950: the same
-// computation and the same orientation of the score tiles as the kernel for D <= 128 (S^T =
-// K Q^T with one query per lane, O^T += V^T P^T, lazily moved reference max, two row sums), but
-// a different budget: the Q fragments (64 registers) and the 256 x 32 fp32 accumulator of O^T
-// (128 registers) leave room for one wave per SIMD only, and one K tile plus one V^T tile of 64
-// keys take 70 KB of LDS, so both are double-buffered, not triple-buffered.
+// Fused attention forward, the form in which BOTH the K and the V tile reach LDS by direct
+// global -> LDS transfers (V row-major, transposed by the LDS reads), four waves = 128 query rows
+// per work-group, K and V double-buffered.  The same computation and the same orientation of the
+// score tiles as the kernel in attn_fwd.hip (S^T = K Q^T with one query per lane, O^T += V^T P^T,
+// lazily moved reference max, two row sums).  It serves
+//  - head dimensions above 128 (D = 256): the Q fragments (64 registers) and the 256 x 32 fp32
+//    accumulator of O^T (128 registers) leave room for one wave per SIMD only, and one K tile plus
+//    one V tile of 64 keys take 70 KB of LDS;
+//  - D = 64 and 128 on problems with few query rows against many keys (decoding, short chunks),
+//    which only stream K and V: the transfers move a tile with a quarter of the vector-memory
+//    instructions of the register-staged V path and none of its transposing arithmetic.
 //
-// Work-group = 4 waves = 128 query rows of one head; one barrier per tile of 64 keys.  With a
-// single wave per SIMD the matrix pipe and the vector ALU can only overlap inside the wave, so a
-// tile is processed in four steps whose independent halves sit in one basic block each:
-//   A  S^T(0) = K Q^T                          (16 MFMAs)
+// One barrier per tile of 64 keys.  A tile is processed in four steps whose independent halves
+// sit in one basic block each, so that the matrix pipe and the vector ALU overlap inside a wave:
+//   A  S^T(0) = K Q^T                          (D/16 MFMAs)
 //   B  S^T(1) = K Q^T   with   P(0) = exp2(c S(0) - m)
 //   C  O^T += V^T P(0)^T   with   P(1) = exp2(c S(1) - m)
-//   D  O^T += V^T P(1)^T                       (16 MFMAs)
+//   D  O^T += V^T P(1)^T
 // Nothing is carried from one tile to the next except the accumulators, which is what lets
 // two K buffers do.
 #include "attn_device.hpp"
@@ -19,50 +23,54 @@
 
 namespace attn {
 
+template <int D>
 struct WideCfg {
-    static constexpr int kD = 256;
+    static constexpr int kD = D;
     static constexpr int kNW = 4;
     static constexpr int kThreads = kNW * 64;
     static constexpr int kBR = kNW * 32;
     static constexpr int kBC = 64;
-    // K tile: wave-wide transfers of 16 B per lane fill 1 KB pieces of two rows, chunk-major
-    // inside a piece (chunk c of row r at 16 * (2 c + r % 2)), pieces 32 bytes further apart
-    // than their size: the 16 rows a quarter wave reads at a fixed chunk fall into 16 different
-    // 16-byte bank groups.
-    static constexpr int kPR = 2;
+    // K tile: wave-wide transfers of 16 B per lane fill 1 KB pieces of kPR rows, chunk-major
+    // inside a piece (chunk c of row r at 16 * (kPR c + r % kPR)), pieces 16 kPR bytes further
+    // apart than their size: the 16 rows a quarter wave reads at a fixed chunk fall into 16
+    // different 16-byte bank groups.
+    static constexpr int kPR = 1024 / (D * 2);
     static constexpr int kKPieceBytes = 1024 + kPR * 16;
     static constexpr int kKPieces = kBC / kPR;
     static constexpr int kKTileBytes = kKPieces * kKPieceBytes;
     static constexpr int kKHalfBytes = kKTileBytes / 2;     // 32 rows further
     static constexpr int kKStepBytes = 2 * kPR * 16;        // next contraction step
     static constexpr int kKDmaPerWave = kKPieces / kNW;
-    // V tile: the same transfers and chunk-major pieces, but pieces 128 bytes further apart
-    // than their size: the tile is only read with the LDS transpose read (the A operand of
-    // O^T += V^T P^T is V^T), whose 32 lanes per half wave fetch 4 rows x 64 bytes, i.e. 128
-    // contiguous bytes in each of two neighbouring pieces, which then fall into disjoint banks.
-    static constexpr int kVPieceBytes = 1024 + 128;
+    // V tile: the same transfers and chunk-major pieces.  The tile is only read with the LDS
+    // transpose read (the A operand of O^T += V^T P^T is V^T), whose 32 lanes per half wave fetch
+    // 4 rows x 64 bytes.  With four or eight rows per piece those lie in one piece and the K
+    // tile's piece distance serves; with two rows per piece (D = 256) they are 128 contiguous
+    // bytes in each of two neighbouring pieces, which a distance of 1024 + 128 bytes puts into
+    // disjoint banks.
+    static constexpr int kVPieceBytes = D > 128 ? 1024 + 128 : kKPieceBytes;
     static constexpr int kVTileBytes = kKPieces * kVPieceBytes;
     static constexpr int kVRows16 = (16 / kPR) * kVPieceBytes;   // 16 rows further
     static constexpr int kOffV = 2 * kKTileBytes;
     static constexpr int kLdsBytes = 2 * (kKTileBytes + kVTileBytes);
-    static_assert(kKPieces % kNW == 0, "staging divides evenly");
+    static_assert(kKPieces % kNW == 0 && 2 * kKDmaPerWave == D / 16, "staging divides evenly");
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 CU exceeded");
 };
 
 constexpr float kWideOverflow = 1024.0f;   // a partial row sum above this moves the reference max
 constexpr float kWideMinusHuge = -1.0e30f;
 
-template <bool CAUSAL>
-__global__ void __launch_bounds__(WideCfg::kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+template <int D, bool CAUSAL, bool SPLIT>
+__global__ void __launch_bounds__(WideCfg<D>::kThreads)
+    __attribute__((amdgpu_waves_per_eu(D > 128 ? 1 : 2, D > 128 ? 1 : 2)))
 attn_fwd_wide_kernel(const FwdArgs a)
 {
-    using C = WideCfg;
-    constexpr int D = C::kD, KS = D / 16, DB = D / 32, PR = C::kPR;
+    using C = WideCfg<D>;
+    constexpr int KS = D / 16, DB = D / 32, PR = C::kPR;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int tid = threadIdx.x, l = tid & 63, r = l & 31, h = l >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int S = a.S, Dr = a.Dr, Sk = a.Sk, coff = a.Sk - a.S;
+    const int S = a.S, Dr = a.Dr;
 
     int bh, rank;
     xcd_tile_order<CAUSAL>(blockIdx.x, a.nqt, a.BH, bh, rank);
@@ -70,6 +78,18 @@ attn_fwd_wide_kernel(const FwdArgs a)
     const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
     const int64_t base_kv = (int64_t)(bh / a.H) * a.kv_stride_b +
                             (int64_t)((bh % a.H) / a.group) * a.kv_stride_h;
+
+    // Keys seen by this work-group: all Sk of them, or one split's range (then K and V are
+    // simply re-based to the range and the causal offset moves with them).  Query row i sees
+    // key j iff j <= i + coff.
+    int Sk = a.Sk, coff = a.Sk - S;
+    int64_t kv_first = 0;
+    if (SPLIT) {
+        const int k_begin = blockIdx.y * a.kps;  // < Sk by the launcher's plan
+        kv_first = (int64_t)k_begin * a.kv_stride_s;
+        Sk = min(Sk - k_begin, a.kps);
+        coff -= k_begin;
+    }
 
     const int q0 = qt * C::kBR + w * 32;
     const int q = q0 + r;
@@ -83,22 +103,23 @@ attn_fwd_wide_kernel(const FwdArgs a)
         qf[ks] = as_elem8(ld_row16(a.Q + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
 
     const int q_end = min(S, (qt + 1) * C::kBR);
-    const int k_end = CAUSAL ? min(Sk, q_end + coff) : Sk;
-    const int n_kt = (k_end + C::kBC - 1) / C::kBC;
+    const int k_end = CAUSAL ? min(Sk, q_end + coff) : Sk;  // <= 0: nothing visible (splits only)
+    const int n_kt = k_end > 0 ? (k_end + C::kBC - 1) / C::kBC : 0;
 
     // ---- staging.  Rows past Sk-1, tiles past the last one and columns Dr..D-1 lie outside
     // the head's buffer resource and read as zero.
     const uint32_t head_bytes = (uint32_t)(((int64_t)(Sk - 1) * a.kv_stride_s + Dr) * 2);
-    const desc_t Kd = make_desc(a.K + base_kv, head_bytes), Vd = make_desc(a.V + base_kv, head_bytes);
+    const desc_t Kd = make_desc(a.K + base_kv + kv_first, head_bytes),
+                 Vd = make_desc(a.V + base_kv + kv_first, head_bytes);
     const uint32_t lds0 = lds_address(smem);
     const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2u;
     const uint32_t tile_bytes = C::kBC * row_bytes;
-    // K: lane l of a transfer fetches chunk l / 2 of the piece's row l % 2
+    // lane l of a transfer fetches chunk l / kPR of the piece's row l % kPR
     const uint32_t k_voff = (l / PR) * 8 < Dr ? (l % PR) * row_bytes + ((l / PR) << 4) : head_bytes;
     // (The transfers are issued from assembly, out of the compiler's sight: it would otherwise
     // make the wave wait for all of them before its next transpose read of LDS.  stage() orders
     // them against the reads.)
-    // piece n (0..7) of this wave's share of tile kt; tensor 0: K, 1: V
+    // piece n of this wave's share of tile kt; tensor 0: K, 1: V
     auto dma_piece = [&](int tensor, int kt, int buf, int n) __attribute__((always_inline)) {
         const int ii = w + n * C::kNW;  // which piece of the tile: wave-uniform
         const uint32_t lds = tensor ? lds0 + C::kOffV + buf * C::kVTileBytes + ii * C::kVPieceBytes
@@ -265,7 +286,9 @@ attn_fwd_wide_kernel(const FwdArgs a)
     // (under a causal mask, the waves with the earlier rows) it only takes part in the staging.
     // A second sub-tile that lies wholly above the wave's diagonal is computed with every score
     // masked: one code path, and it only happens on the diagonal tile.
-    const int n_mine = CAUSAL ? __builtin_amdgcn_readfirstlane(min(n_kt, (q0e + 31) / C::kBC + 1)) : n_kt;
+    // A wave whose rows all lie past the end of the head computes nothing either.
+    const int n_seen = !CAUSAL ? n_kt : q0e + 31 < 0 ? 0 : min(n_kt, (q0e + 31) / C::kBC + 1);
+    const int n_mine = __builtin_amdgcn_readfirstlane(q0 < S ? n_seen : 0);
     // The loop over the tiles is written twice.  The inner, fast form never touches the O^T
     // accumulators with the vector ALU: when a sub-tile's probabilities show that the reference
     // max must move, it leaves the loop before that sub-tile is added, and the slow form below
@@ -318,9 +341,32 @@ attn_fwd_wide_kernel(const FwdArgs a)
         fetch_next(kt, 1);
     }
 
+    // no transfer may still be in flight when the work-group's LDS is released
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
     // Epilogue: O = O_acc / l, LSE = ln2 * (m + log2 l).
     const float lt = xhalf_sum(lsum);
     const float lr = xhalf_sum(hsum);
+    if (SPLIT) {
+        // normalised fp32 partial result of this key range; a row that saw no key of the
+        // range contributes O = 0 with LSE = -inf
+        const float inv = lr > 0.f ? 1.0f / lr : 0.f;
+        if (q < S) {
+            const int64_t row = ((int64_t)blockIdx.y * a.BH + bh) * S + q;
+            float *Op = a.Opart + row * D;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    f32x4 ov;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) ov[e] = o[db][4 * g + e] * inv;
+                    *(f32x4 *)(Op + 32 * db + 8 * g + 4 * h) = ov;
+                }
+            if (h == 0) a.LSEpart[row] = lt > 0.f ? (m + fast_log2(lt)) * kLn2 : -INFINITY;
+        }
+        return;
+    }
     const float inv = 1.0f / lr;
     if (q < S) {
         elem *Op = a.O + base + (int64_t)q * a.stride_s;
@@ -336,25 +382,35 @@ attn_fwd_wide_kernel(const FwdArgs a)
     }
 }
 
-template <bool CAUSAL>
+template <int D, bool CAUSAL, bool SPLIT>
 static int launch_wide(FwdArgs a, hipStream_t st)
 {
-    using C = WideCfg;
+    using C = WideCfg<D>;
     a.nqt = (a.S + C::kBR - 1) / C::kBR;
-    if (hipFuncSetAttribute((const void *)attn_fwd_wide_kernel<CAUSAL>,
+    if (hipFuncSetAttribute((const void *)attn_fwd_wide_kernel<D, CAUSAL, SPLIT>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes) != hipSuccess)
         return -1;
-    hipLaunchKernelGGL((attn_fwd_wide_kernel<CAUSAL>), dim3(a.nqt * a.BH), dim3(C::kThreads),
-                       C::kLdsBytes, st, a);
+    hipLaunchKernelGGL((attn_fwd_wide_kernel<D, CAUSAL, SPLIT>), dim3(a.nqt * a.BH, SPLIT ? a.nsplit : 1),
+                       dim3(C::kThreads), C::kLdsBytes, st, a);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-// Head dimensions 129..256 (D = 256 with the missing columns read as zeros); never split over
-// the keys, no fused rotary embedding.
-int launch_fwd_wide(const FwdArgs &a, bool causal, hipStream_t st)
+template <int D>
+static int launch_wide_d(const FwdArgs &a, bool causal, hipStream_t st)
 {
-    if (a.nsplit > 1 || a.rope_cos) return -1;
-    return causal ? launch_wide<true>(a, st) : launch_wide<false>(a, st);
+    if (a.nsplit > 1)
+        return causal ? launch_wide<D, true, true>(a, st) : launch_wide<D, false, true>(a, st);
+    return causal ? launch_wide<D, true, false>(a, st) : launch_wide<D, false, false>(a, st);
+}
+
+// The main kernel only: with a split over the keys the caller launches the merge of the partial
+// results afterwards.  No fused rotary embedding.
+int launch_fwd_wide(const FwdArgs &a, int D, bool causal, hipStream_t st)
+{
+    if (a.rope_cos) return -1;
+    return D == 256 ? launch_wide_d<256>(a, causal, st)
+         : D == 128 ? launch_wide_d<128>(a, causal, st)
+                    : launch_wide_d<64>(a, causal, st);
 }
 
 }  // namespace attn

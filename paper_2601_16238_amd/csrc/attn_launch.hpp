@@ -85,9 +85,10 @@ typedef BwdArgsT<elem> BwdArgs;
 // element type; each is defined by the build of the kernel sources for that type.
 int launch_fwd(const FwdArgsT<__bf16> &a, int D, bool causal, hipStream_t st);
 int launch_fwd(const FwdArgsT<_Float16> &a, int D, bool causal, hipStream_t st);
-// The forward for head dimensions 129..256 (called by launch_fwd with D == 256).
-int launch_fwd_wide(const FwdArgsT<__bf16> &a, bool causal, hipStream_t st);
-int launch_fwd_wide(const FwdArgsT<_Float16> &a, bool causal, hipStream_t st);
+// The forward that streams both K and V by direct transfers (attn_fwd_wide.hip; D = 64, 128 or
+// 256; called by launch_fwd, which also launches the merge of a split).
+int launch_fwd_wide(const FwdArgsT<__bf16> &a, int D, bool causal, hipStream_t st);
+int launch_fwd_wide(const FwdArgsT<_Float16> &a, int D, bool causal, hipStream_t st);
 // Number of key splits the forward would use for this problem (1: none), and the keys per
 // split; a pure host function of the shape.
 int fwd_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps);

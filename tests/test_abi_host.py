@@ -205,8 +205,11 @@ def test_rect_params_contiguous_and_workspace_sizes():
     assert attn.attn_fwd_rect_workspace_bytes(2, 8, 2, 1, 300, 64) == 0
     # ... otherwise (D+1) fp32 per split and query row; decoding 8 sequences of 32 heads
     # against 8192 keys: the 4 query heads of a group are packed into one head of 4 rows (64
-    # work-groups), which splits 4 ways: one work-group per compute unit
-    assert attn.attn_fwd_rect_workspace_bytes(8, 32, 8, 1, 8192, 128) == 4 * 256 * 129 * 4
+    # work-groups), which splits 8 ways: two work-groups per compute unit, 16 tiles each
+    assert attn.attn_fwd_rect_workspace_bytes(8, 32, 8, 1, 8192, 128) == 8 * 256 * 129 * 4
+    # a sixteenth of the keys: 2 ways with one work-group per compute unit would leave 4 tiles per
+    # split, which is the floor (no finer split for a second work-group per unit)
+    assert attn.attn_fwd_rect_workspace_bytes(8, 32, 8, 1, 512, 128) == 2 * 256 * 129 * 4
     assert attn.attn_fwd_rect_workspace_bytes(1, 6, 4, 1, 8192, 64) == 0      # invalid heads
 
 
