@@ -49,17 +49,16 @@ struct FwdCfg {
     static constexpr int kKHalf = kKTile / 2;                  // 32 rows further
     static constexpr int kKStep = 2 * kKRowsPerDma * 16 / 2;   // next contraction step, in elements
     static constexpr int kKDmaPerWave = (kKDmas + NW - 1) / NW;
-    static constexpr int kLdV = kBC + 8;            // V^T tile [d][key order], rows skewed
-    static constexpr int kVTile = D * kLdV;
-    static constexpr int kVMicro = (kBC / 4) * (D / 4);   // 4 keys x 4 d micro-tiles of a V tile
-    static constexpr int kVPerThread = (kVMicro + kThreads - 1) / kThreads;
-    // V^T tiles: two, or three for the eight-wave kernel, whose main loop multiplies P of a
+    // V tile: the same transfers and layout as the K tile (row-major rows in chunk-major pieces);
+    // it is transposed by the reads (LDS transpose read), whose 64 lanes fetch 4 rows x 4 chunks
+    // x 2 halves = 512 contiguous bytes of a piece.
+    static constexpr int kVTile = kKTile;                                  // in elements
+    static constexpr int kVRows16 = (16 / kKRowsPerDma) * kKPieceBytes;   // 16 rows further, in bytes
+    // V tiles: two, or three for the eight-wave kernel, whose main loop multiplies P of a
     // sub-tile by V one sub-tile later and therefore still reads tile kt-1 while tile kt+1 is
-    // being stored
+    // arriving
     static constexpr int kVBufs = NW == 8 ? 3 : 2;
     static constexpr int kLdsBytes = (3 * kKTile + kVBufs * kVTile) * 2;
-    // register loads of V that a thread issues per tile (after the K transfers of that tile)
-    static constexpr int kVLoads = 4 * kVPerThread;
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 CU exceeded");
 };
 
@@ -120,84 +119,38 @@ attn_fwd_kernel(const FwdArgs a)
     const int n_kt = k_end > 0 ? (k_end + C::kBC - 1) / C::kBC : 0;
     const int q0e = q0 + coff;  // the wave's first row in key coordinates
 
-    // ---- staging: global -> registers -> LDS.  Rows past S-1 and tiles past the last one
+    // ---- staging: global -> LDS.  Rows past S-1 and tiles past the last one
     // lie outside the head's buffer resource and read as zero (masked to probability 0).
     // Columns Dr..D-1 (head dimensions below the kernel's D) are fetched at an offset past the
     // end of the resource, so they read as zero like everything else outside it.
     const uint32_t head_bytes = (uint32_t)(((int64_t)(Sk - 1) * a.kv_stride_s + Dr) * 2);
-    const rsrc_t Kr = make_rsrc(Kp, head_bytes), Vr = make_rsrc(Vp, head_bytes);
+    const desc_t Kd = make_desc(Kp, head_bytes), Vd = make_desc(Vp, head_bytes);
+    const uint32_t lds0 = lds_address(smem);
     const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2u;
     const uint32_t tile_bytes = C::kBC * row_bytes;
-    // K goes global -> LDS directly (no registers): one wave-wide load of 16 B per lane fills
-    // 1 KB of LDS in lane order; lane l fetches the chunk that belongs at its position of the
+    // K and V go global -> LDS directly (no registers): one wave-wide transfer of 16 B per lane
+    // fills 1 KB of LDS in lane order; lane l fetches the chunk that belongs at its position of the
     // piece, chunk l / rows of row l % rows.  The piece's first row goes into the scalar
-    // offset (which takes part in the range check like the per-lane one).
+    // offset (which takes part in the range check like the per-lane one).  The transfers are
+    // issued from assembly, out of the compiler's sight (it would otherwise make the wave wait for
+    // all of them before its next transpose read of LDS); tile_barrier() orders them against the
+    // reads.  They fill buffers that nobody reads before the next barrier.
     constexpr int PR = C::kKRowsPerDma;
-    u32x2 vreg[C::kVPerThread][4];
     const uint32_t k_voff = (l / PR) * 8 < Dr ? (l % PR) * row_bytes + ((l / PR) << 4) : head_bytes;
-    auto dma_k = [&](int kt, int buf) {
+    auto dma_tile = [&](desc_t desc, uint32_t lds_tile, int kt) __attribute__((always_inline)) {
 #pragma unroll
         for (int n = 0; n < C::kKDmaPerWave; ++n) {
-            // which 1 KB piece of the tile: wave-uniform, and said so, because it goes into the
-            // transfer's scalar offset and LDS base
+            // which 1 KB piece of the tile: wave-uniform
             const int ii = __builtin_amdgcn_readfirstlane(w) + n * NW;
             if (C::kKDmas % NW == 0 || ii < C::kKDmas)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                    Kr, (void __attribute__((address_space(3))) *)(Ks + buf * C::kKTile + ii * (C::kKPieceBytes / 2)),
-                    16, (int)k_voff, kt * tile_bytes + ii * PR * row_bytes, 0, 0);
+                dma16_between(desc, lds_tile + ii * C::kKPieceBytes, k_voff, kt * tile_bytes + ii * PR * row_bytes);
         }
     };
-    // V micro-tile mt: a wave covers 32 keys x 32 d as 8 key groups x 8 d groups.
-    auto v_coords = [&](int mt, int &key0, int &d0) {
-        const int blk = mt >> 6;
-        key0 = 32 * (blk & 1) + 4 * (mt & 7);
-        d0 = 32 * (blk >> 1) + 4 * ((mt >> 3) & 7);
+    auto dma_k = [&](int kt, int buf) __attribute__((always_inline)) {
+        dma_tile(Kd, lds0 + buf * (C::kKTile * 2), kt);
     };
-    auto load_v = [&](int kt) {
-#pragma unroll
-        for (int n = 0; n < C::kVPerThread; ++n) {
-            const int mt = tid + n * C::kThreads;
-            if (C::kVMicro % C::kThreads == 0 || mt < C::kVMicro) {
-                int key0, d0;
-                v_coords(mt, key0, d0);
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    vreg[n][i] = buf_load8(Vr, d0 < Dr ? (key0 + i) * row_bytes + d0 * 2 : head_bytes,
-                                           kt * tile_bytes);
-            }
-        }
-    };
-    // byte address within V buffer 0 of this thread's micro-tile(s): one opaque register each,
-    // so that the buffer and the column are immediate offsets of the LDS writes
-    int vst_lane[C::kVPerThread];
-#pragma unroll
-    for (int n = 0; n < C::kVPerThread; ++n) {
-        int key0, d0;
-        v_coords(tid + n * C::kThreads, key0, d0);
-        // position of key0 (a multiple of 4) in the MFMA contraction order:
-        // key = 16cc + 8u + 4hh + e  ->  16cc + 8hh + 4u + e
-        const int kpos = (key0 & ~15) | ((key0 & 4) << 1) | ((key0 & 8) >> 1);
-        vst_lane[n] = (3 * C::kKTile + d0 * C::kLdV + kpos) * 2;
-        asm volatile("" : "+v"(vst_lane[n]));
-    }
-    auto store_v = [&](int buf) {
-#pragma unroll
-        for (int n = 0; n < C::kVPerThread; ++n) {
-            const int mt = tid + n * C::kThreads;
-            if (C::kVMicro % C::kThreads == 0 || mt < C::kVMicro) {
-                elem *dst = reinterpret_cast<elem *>(smem + buf * (C::kVTile * 2) + vst_lane[n]);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    // column d0+j of the 4x4 micro-tile: keys key0..key0+3
-                    const unsigned sel = (j & 1) ? 0x07060302u : 0x05040100u;
-                    const int hw = j >> 1;  // which dword of the 8-byte row piece
-                    u32x2 col;
-                    col.x = __builtin_amdgcn_perm(vreg[n][1][hw], vreg[n][0][hw], sel);
-                    col.y = __builtin_amdgcn_perm(vreg[n][3][hw], vreg[n][2][hw], sel);
-                    *(u32x2 *)(dst + j * C::kLdV) = col;
-                }
-            }
-        }
+    auto dma_v = [&](int kt, int buf) __attribute__((always_inline)) {
+        dma_tile(Vd, lds0 + (3 * C::kKTile + buf * C::kVTile) * 2, kt);
     };
 
     float m = kMinusHuge;  // reference max of c*s (log2 units), identical in lanes l and l^32
@@ -221,9 +174,15 @@ attn_fwd_kernel(const FwdArgs a)
     // offset of the LDS instruction instead of into further address registers.  (The V region
     // starts beyond what an immediate reaches from zero, so its registers include its base.)
     int k_lane = ((r / PR) * (C::kKPieceBytes / 2) + (h * PR + r % PR) * 8) * 2;
-    int v_lane = (3 * C::kKTile + r * C::kLdV + 8 * h) * 2;
-    asm volatile("" : "+v"(k_lane), "+v"(v_lane));
-    const elem *const L0 = reinterpret_cast<const elem *>(smem);  // V fragment reads: tile offsets from here
+    // transpose reads of a V tile: the 16-lane group reads rows 4h + e (e = 0..3; +8 for the
+    // second read), 64 bytes of d block 0 of each row -- the keys of contraction half h in the
+    // order the accumulator of S^T holds them
+    auto v_at = [](int row, int chunk) {
+        return (row / PR) * C::kKPieceBytes + (chunk * PR + row % PR) * 16;
+    };
+    int v_lane0 = 3 * C::kKTile * 2 + v_at(4 * h + ((l & 15) >> 2), 2 * ((l >> 4) & 1) + ((l >> 1) & 1)) + (l & 1) * 8;
+    int v_lane1 = 3 * C::kKTile * 2 + v_at(8 + 4 * h + ((l & 15) >> 2), 2 * ((l >> 4) & 1) + ((l >> 1) & 1)) + (l & 1) * 8;
+    asm volatile("" : "+v"(k_lane), "+v"(v_lane0), "+v"(v_lane1));
     auto ld_k = [&](const elem *Kt, int kq, elem8 (&f)[4]) {
 #pragma unroll
         for (int t = 0; t < 4; ++t)
@@ -233,12 +192,15 @@ attn_fwd_kernel(const FwdArgs a)
 #pragma unroll
         for (int t = 0; t < 4; ++t) t0 = mfma32(f[t], qf[4 * kq + t], t0);
     };
-    // V^T fragment: lane (d = 32*db + l%32, half h) holds the 8 keys of contraction step cc
-    // that its half owns, contiguous in the staged order.
-    auto ld_v = [&](const elem *Vt, int cc, elem8 (&f)[4]) {  // Vt: tile and sub-tile, from L0
+    // V^T fragment: lane (d = 32*db + l%32, half h) gets the 8 keys of contraction step cc
+    // that its half owns, from two transpose reads.  Vt: byte offset of tile and sub-tile
+    // within the V region.
+    auto ld_v = [&](int Vt, int cc, elem8 (&f)[4]) {
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
-            f[db] = *(const elem8 *)((const char *)(Vt + 32 * db * C::kLdV + 16 * cc) + v_lane);
+        for (int db = 0; db < DB; ++db) {
+            const char *p = smem + Vt + cc * C::kVRows16 + db * 4 * PR * 16;  // d block db: four chunks further
+            f[db] = join8(lds_read_tr((const elem *)(p + v_lane0)), lds_read_tr((const elem *)(p + v_lane1)));
+        }
     };
     // Row sums of the ROUNDED probabilities (one packed dot product with a vector of ones per
     // element pair; this lane's half of the keys, both halves are added at the end like the
@@ -299,7 +261,7 @@ attn_fwd_kernel(const FwdArgs a)
     auto subtile = [&](int kt, int u, int kbuf_next, int kbuf_fill, int vb, int vb_fill, bool masked,
                        f32x16 &cur, f32x16 &nxt) __attribute__((always_inline)) {
         const elem *Kn = Ks + kbuf_next * C::kKTile + u * C::kKHalf;  // rows of sub-tile g+2
-        const elem *Vt = L0 + vb * C::kVTile + 32 * u;
+        const int Vt = vb * (C::kVTile * 2) + 2 * u * C::kVRows16;
         // ---- K0
         ld_v(Vt, 0, f2);
         if (NKQ == 1) ld_v(Vt, 1, f3);
@@ -328,15 +290,14 @@ attn_fwd_kernel(const FwdArgs a)
         // what has been accumulated, and redo this sub-tile's probabilities.
         if (__builtin_expect(__builtin_amdgcn_ballot_w64(psum > kOverflow) != 0, 0)) move_reference(cur, p0, p1, psum);
         ATTN_FENCE();
-        // ---- V0 (first sub-tile: V(kt+1), fetched an iteration ago, is transposed into LDS)
+        // ---- V0 (first sub-tile: V(kt+1) -> the buffer freed at the last barrier)
         ld_k(Kn, 0, f0);
         mm_v(f2, p0);
-        if (u == 0) store_v(vb_fill);
+        if (u == 0) dma_v(kt + 1, vb_fill);
         ATTN_FENCE();
-        // ---- V1 (first sub-tile: start fetching V(kt+2))
+        // ---- V1
         if (NKQ > 1) ld_k(Kn, 1, f1);
         mm_v(f3, p1);
-        if (u == 0) load_v(kt + 2);
         lsum += psum;
         ATTN_FENCE();
     };
@@ -345,7 +306,7 @@ attn_fwd_kernel(const FwdArgs a)
     // the K fragments of the second sub-tile on their way.
     dma_k(0, 0);
     dma_k(1, 1);
-    load_v(0);
+    dma_v(0, 0);
     // Rotary embedding of the query rows, fused into their load (head dimension == D only):
     // column d pairs with d + D/2, i.e. fragment ks with ks + KS/2, element by element, in this
     // lane; fp32 arithmetic on the widened values, rounded once -- what a separate rotary pass
@@ -362,8 +323,6 @@ attn_fwd_kernel(const FwdArgs a)
                 rs[ks][j] = *(const f32x4 *)(a.rope_sin + pos + 16 * ks + 8 * h + 4 * j);
             }
     }
-    store_v(0);
-    load_v(1);
     if (a.rope_cos) {
         elem *qr = a.Qrot ? a.Qrot + base + (int64_t)qc * a.stride_s : nullptr;
 #pragma unroll
@@ -391,6 +350,7 @@ attn_fwd_kernel(const FwdArgs a)
         for (int i = tid; i < C::kVTile / 8; i += C::kThreads)
             *(u32x4 *)(Vs + 2 * C::kVTile + 8 * i) = z;
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // K(0), K(1), V(0) have landed
     __syncthreads();
     f32x16 sa, sb;
     {
@@ -420,7 +380,7 @@ attn_fwd_kernel(const FwdArgs a)
     auto subtile_main = [&](int kt, int u, int kbuf_next, int kbuf_fill, int vprev, int vb_fill,
                             f32x16 &cur, f32x16 &nxt) __attribute__((always_inline)) {
         const elem *Kn = Ks + kbuf_next * C::kKTile + u * C::kKHalf;  // rows of sub-tile g+2
-        const elem *Vt = L0 + vprev * C::kVTile + 32 * (1 - u);     // rows of sub-tile g-1
+        const int Vt = vprev * (C::kVTile * 2) + 2 * (1 - u) * C::kVRows16;  // rows of sub-tile g-1
         // The softmax arithmetic of g is spread evenly over the four MFMA steps (four scores
         // each), so that every step has about three quarters as many vector-ALU cycles as
         // matrix-pipe cycles.
@@ -463,14 +423,13 @@ attn_fwd_kernel(const FwdArgs a)
         ld_k(Kn, 0, f0);
         mm_o(f2, pp0);
         exp4(8);
-        if (u == 0) store_v(vb_fill);
+        if (u == 0) dma_v(kt + 1, vb_fill);
         ATTN_FENCE();
         // ---- V1
         if (NKQ > 1) ld_k(Kn, 1, f1);
         mm_o(f3, pp1);
         exp4(12);
         elem8 p1 = pack8(e[8], e[9], e[10], e[11], e[12], e[13], e[14], e[15]);
-        if (u == 0) load_v(kt + 2);
         ATTN_FENCE();
         // rare: some probability of g outgrew 2^10 (always so for a wave's first sub-tile);
         // what has been accumulated (up to g-1) is rescaled, P(g) redone
@@ -479,13 +438,10 @@ attn_fwd_kernel(const FwdArgs a)
         pp0 = p0;
         pp1 = p1;
     };
-    // The K transfers of a tile are issued before the V register loads of the same tile, so
-    // "at most kVLoads vector-memory operations outstanding" means that this wave's piece of
-    // K(kt+2) has landed in LDS; only then may the other waves be let past the barrier to
-    // read it.  (When some threads have no V micro-tile the count is not uniform: wait for all.)
+    // Every transfer this wave issued during the tile (its pieces of K(kt+2) and V(kt+1)) must
+    // have landed before the other waves are let past the barrier to read them.
     auto tile_barrier = [&]() {
-        if (C::kVMicro % C::kThreads == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::kVLoads) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     };
 
@@ -517,7 +473,7 @@ attn_fwd_kernel(const FwdArgs a)
         }
         if (n_main > 0) {
             // the last sub-tile's P V is still owed: second half of V(n_main - 1), buffer 2
-            const elem *Vt = L0 + 2 * C::kVTile + 32;
+            const int Vt = 2 * (C::kVTile * 2) + 2 * C::kVRows16;
             ld_v(Vt, 0, f2);
             ld_v(Vt, 1, f3);
             mm_v(f2, pp0);
@@ -535,8 +491,7 @@ attn_fwd_kernel(const FwdArgs a)
             subtile(kt, 0, kb1, kb2, vb, vb1, (kb + 32 > Sk) || (CAUSAL && kb + 31 > q0e), sa, sb);
         } else {
             dma_k(kt + 2, kb2);
-            store_v(vb1);
-            load_v(kt + 2);
+            dma_v(kt + 1, vb1);
         }
         if (!CAUSAL || kb + 32 <= q0e + 31)
             subtile(kt, 1, kb1, kb2, vb, vb1, (kb + 64 > Sk) || (CAUSAL && kb + 63 > q0e), sb, sa);
