@@ -690,30 +690,25 @@ int fwd_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps)
 }
 #endif
 
-// Which problems of D <= 128 go to the kernel that streams both tiles by direct transfers
-// (attn_fwd_wide.hip; 128-row work-groups, two K/V buffers) instead of the one above.  Measured,
+// Which problems of D <= 128 go to the kernel of attn_fwd_wide.hip (128-row work-groups, two K/V
+// buffers, two work-groups per compute unit at D = 128) instead of the one above.  Measured,
 // forward only, graph replay, same box:
 //  - at most 32 query rows per head (decoding; one wave of four has rows, the problem is K/V
-//    streaming): B=8 Hq=32 Hkv=8 Sk=8192 62.8 -> 55.0 us (49.5 with the finer split below), B=16
-//    H=16 Sk=4096 129 -> 103, 8 rows on 512 keys at D = 64 12.1 -> 11.0;
-//  - D = 128 and at most 128 rows: S=96 causal 20.0 -> 13.7 us, 128 rows on 1024 keys 26.1 -> 25.4
-//    (the kernel above needs four waves at D = 128 whatever the length); not so at D = 64, where
-//    the short forms of the kernel above are faster (B=128 H=6 S=65: 10.8 against 12.7);
-//  - D = 64 under a causal mask on launches of fewer than four 256-row work-groups per compute
-//    unit: B=8 H=8 S=1024 27.6 -> 23.7 us, B=16 H=16 S=512 35.1 -> 28.3, B=2 H=8 S=4096 77.8 ->
-//    65.8 (large launches are 9 % slower this way, and so is everything else at D = 128 or
-//    without a mask, by 3-12 %).
-static bool prefer_streaming_forward(const FwdArgs &a, int D, bool causal)
+//    streaming): B=8 Hq=32 Hkv=8 Sk=8192 66.7 -> 49.7 us, B=16 H=16 Sk=4096 143 -> 103;
+//  - D = 128 and at most 128 rows: S=96 causal 18.8 -> 14.3 us (the kernel above needs four waves
+//    at D = 128 whatever the length); 128 rows on 1024 keys the same either way.
+// Everything else is faster above: mid-size causal D = 64 launches by 3-5 % (B=8 H=8 S=1024 22.5
+// against 23.6 us), large launches by 7-12 %.
+static bool prefer_streaming_forward(const FwdArgs &a, int D)
 {
     if (a.rope_cos) return false;  // the rotation of Q is fused into the kernel above only
     if (a.S <= 32) return true;
-    if (D == 128) return a.S <= 128;
-    return causal && a.S >= 256 && (int64_t)a.BH * ((a.S + 255) / 256) < 1024;
+    return D == 128 && a.S <= 128;
 }
 
 int launch_fwd(const FwdArgs &a, int D, bool causal, hipStream_t st)
 {
-    if (D == 256 || prefer_streaming_forward(a, D, causal)) {
+    if (D == 256 || prefer_streaming_forward(a, D)) {
         if (launch_fwd_wide(a, D, causal, st)) return -1;
         if (a.nsplit <= 1) return 0;
         return D == 256 ? launch_fwd_merge<256>(a, st)
