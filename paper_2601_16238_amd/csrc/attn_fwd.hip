@@ -13,9 +13,11 @@
 //   - elem(P^T) is already in the B-operand layout of the second MFMA,
 //     O^T = V^T P^T (d x queries), once the contraction index is enumerated in the order
 //     the accumulator holds it (key = 8*(t/4) + 4*(l/32) + t%4 within 16 keys).
-// V is transposed once per work-group while it is staged into LDS (4x4 register
-// transposes), in exactly that key order, so both MFMA operands that come from LDS are
-// plain 16-byte reads (the LDS transpose read runs at about a third of that rate).
+// K and V tiles reach LDS by direct global -> LDS transfers, both row-major.  The K operand is a
+// plain 16-byte read; V^T is produced by the reads themselves (two LDS transpose reads per
+// fragment, which deliver the keys in exactly that order).  Staging V through registers with a
+// 4x4 register transpose, so that its operand is a plain read as well, costs more vector
+// instructions than the slower transpose reads do (measured in the kernel: 3-5 % slower).
 //
 // Software pipeline (per wave): the MFMAs of S^T(j+1) are issued in the same block as the
 // softmax arithmetic of tile j, so the matrix pipe and the vector ALU overlap inside one
@@ -76,7 +78,7 @@ attn_fwd_kernel(const FwdArgs a)
     constexpr int DB = D / 32;  // 32-row blocks of O^T
     extern __shared__ __attribute__((aligned(16))) char smem[];
     elem *Ks = reinterpret_cast<elem *>(smem);  // [3][64][D] swizzled
-    elem *Vs = Ks + 3 * C::kKTile;              // [kVBufs][D][kLdV]
+    elem *Vs = Ks + 3 * C::kKTile;              // [kVBufs] tiles in the K tile's layout
 
     const int tid = threadIdx.x, l = tid & 63, r = l & 31, h = l >> 5;
     const int w = tid >> 6;
@@ -619,9 +621,10 @@ static int launch_fwd_nw(const FwdArgs &a, bool causal, hipStream_t st)
 }
 
 // Waves per work-group: 8 (256 query rows) unless the sequence is too short to fill them.
-// With D = 128 at least 4: fewer waves could not hold their share of a V tile in registers
-// while staging it (waves whose rows lie past the end compute and store nothing useful, but
-// still take part in the staging).
+// With D = 128 at least 4 (waves whose rows lie past the end compute and store nothing useful,
+// but still take part in the staging): the one- and two-wave forms are only built for D = 64,
+// and short problems at D = 128 go to the kernel of attn_fwd_wide.hip unless the rotary
+// embedding is fused into the call.
 static int fwd_waves_for(int S, int D, int BH, bool causal)
 {
     const int blocks32 = (S + 31) / 32;
