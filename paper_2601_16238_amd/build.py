@@ -12,6 +12,8 @@ LIB = os.path.join(HERE, "libmi355attn.so")
 SOURCES = [("attn_api.hip", [], "attn_api.o"),
            ("attn_fwd.hip", [], "attn_fwd.o"), ("attn_bwd.hip", [], "attn_bwd.o"),
            ("attn_fwd_wide.hip", [], "attn_fwd_wide.o"),
+           ("attn_bwd_small.hip", [], "attn_bwd_small.o"),
+           ("attn_bwd_small.hip", ["-DATTN_F16"], "attn_bwd_small_f16.o"),
            ("attn_fwd_wide.hip", ["-DATTN_F16"], "attn_fwd_wide_f16.o"),
            ("attn_fwd.hip", ["-DATTN_F16"], "attn_fwd_f16.o"),
            ("attn_bwd.hip", ["-DATTN_F16"], "attn_bwd_f16.o"),

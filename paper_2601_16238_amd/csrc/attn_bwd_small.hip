@@ -1,0 +1,300 @@
+// Fused attention backward for short sequences on gfx950: when a head's query rows and keys
+// both fit 128, ONE work-group per head computes dQ, dK and dV in one launch.  The two-kernel
+// backward of attn_bwd.hip spends most of its time on such shapes in two launches and in
+// reading the head's tensors twice; here Q, K, V and dO are brought into LDS once (direct
+// global -> LDS transfers), and nothing is exchanged between work-groups.
+//
+// Wave w (of up to four) owns query block w (32 rows) and key block w (32 keys):
+//   as the owner of query block i (the dQ kernel's orientation, one query per lane):
+//     for every key block j:  S^T = K_j Q_i^T,  dP^T = V_j dO_i^T - delta,  P, dS,
+//                             dQ_i^T += K_j^T dS^T
+//   as the owner of key block j (the dK/dV kernel's orientation, one key per lane):
+//     for every query block i:  S = Q_i K_j^T,  dP = dO_i V_j^T - delta,  P, dS,
+//                               dV_j^T += dO_i^T P,  dK_j^T += Q_i^T dS
+// P and dS stay in registers in both parts (their accumulator layout is the B-operand layout of
+// the GEMM that consumes them).  The row statistics (delta, LSE in log2 units) are formed by the
+// owners of the query blocks and shared through LDS; that is the only barrier after the tiles
+// have landed.  Multi-head attention only (one query head per K/V head), no fused rotary
+// embedding; everything else takes the two-kernel path.
+#include "attn_device.hpp"
+#include "attn_launch.hpp"
+
+namespace attn {
+
+template <int D>
+struct SmallCfg {
+    static constexpr int kMaxRows = 128;                       // query rows and keys per head
+    static constexpr int kWaves = 4;
+    static constexpr int kThreads = kWaves * 64;
+    static constexpr int kRowBytes = D * 2;
+    static constexpr int kCPR = D / 8;                         // 16-byte chunks per row
+    static constexpr int kPieceRows = 1024 / kRowBytes;        // rows one 1 KB transfer fills
+    // LDS: lse2[128], -delta[128], then Q, dO, K, V, each padded to whole 32-row blocks of the
+    // longer of the two lengths (sized at launch: three work-groups of the 65-row shape fit a
+    // compute unit that way).  Rows are stored unpadded with the 16-byte chunk index XOR-swizzled
+    // by the row, as in the slots of the dK/dV kernel: conflict free for row reads and for
+    // transpose reads.
+    static constexpr int kStatBytes = 2 * kMaxRows * 4;
+    static constexpr int lds_bytes(int rows_pad) { return kStatBytes + 4 * rows_pad * kRowBytes; }
+    static_assert(lds_bytes(kMaxRows) <= 160 * 1024, "LDS budget of a gfx950 CU exceeded");
+};
+
+template <int D, bool CAUSAL>
+// (D = 64: at most 168 registers, so that three work-groups share a compute unit)
+__global__ void __launch_bounds__(SmallCfg<D>::kThreads) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 1)))
+attn_bwd_small_kernel(const BwdArgs a)
+{
+    using C = SmallCfg<D>;
+    constexpr int KS = D / 16, DB = D / 32, PR = C::kPieceRows, CPR = C::kCPR, RB = C::kRowBytes;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int tid = threadIdx.x, l = tid & 63, r = l & 31, h = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int S = a.S, Sk = a.Sk, Dr = a.Dr;
+    const int coff = Sk - S;  // causal: query row i sees keys 0 .. i + coff
+    const int bh = blockIdx.x;
+    const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
+    const int64_t base_kv = (int64_t)(bh / a.H) * a.kv_stride_b + (int64_t)(bh % a.H) * a.kv_stride_h;
+    const int nqb = (S + 31) / 32, nkb = (Sk + 31) / 32;  // query / key blocks of the head
+    const int tensor_bytes = 32 * max(nqb, nkb) * RB;
+    const int offQ = C::kStatBytes, offG = offQ + tensor_bytes, offK = offG + tensor_bytes, offV = offK + tensor_bytes;
+    // chunk position swizzle: rows 0..15 get 16 distinct values (row reads of 16 lanes hit 16
+    // different 16-byte bank groups) and 4 consecutive rows differ in the upper two bits (the
+    // 4 rows x 64 bytes of a transpose read spread over all banks)
+    auto swz = [](int row) {
+        return CPR >= 16 ? (((row & 3) << 2) | ((row >> 2) & 3))
+                         : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+    };
+
+    // ---- the four tensors -> LDS.  Rows past the end and columns Dr..D-1 lie outside the
+    // buffer resources and read as zero.
+    const uint32_t q_bytes = (uint32_t)(((int64_t)(S - 1) * a.stride_s + Dr) * 2);
+    const uint32_t k_bytes = (uint32_t)(((int64_t)(Sk - 1) * a.kv_stride_s + Dr) * 2);
+    const desc_t Qd = make_desc(a.Q + base, q_bytes), Gd = make_desc(a.dO + base, q_bytes);
+    const desc_t Kd = make_desc(a.K + base_kv, k_bytes), Vd = make_desc(a.V + base_kv, k_bytes);
+    const uint32_t lds0 = lds_address(smem);
+    const uint32_t q_row = (uint32_t)a.stride_s * 2u, k_row = (uint32_t)a.kv_stride_s * 2u;
+    // a transfer fills 1 KB = PR rows in lane order: lane l lands in row l / CPR of the piece, at
+    // chunk position l % CPR, and fetches the chunk that the swizzle puts there
+    auto voff = [&](int piece, uint32_t row_bytes, uint32_t end) {
+        const int row = piece * PR + l / CPR;
+        const int chunk = (l % CPR) ^ swz(row);
+        return chunk * 8 < Dr ? (uint32_t)(l / CPR) * row_bytes + ((uint32_t)chunk << 4) : end;
+    };
+    const int q_pieces = nqb * (32 / PR), k_pieces = nkb * (32 / PR);
+    for (int i = w; i < q_pieces; i += C::kWaves) {
+        const uint32_t vo = voff(i, q_row, q_bytes);
+        dma16(Qd, lds0 + offQ + i * 1024, vo, i * PR * q_row);
+        dma16(Gd, lds0 + offG + i * 1024, vo, i * PR * q_row);
+    }
+    for (int i = w; i < k_pieces; i += C::kWaves) {
+        const uint32_t vo = voff(i, k_row, k_bytes);
+        dma16(Kd, lds0 + offK + i * 1024, vo, i * PR * k_row);
+        dma16(Vd, lds0 + offV + i * 1024, vo, i * PR * k_row);
+    }
+
+    // ---- this wave's query block: Q and dO fragments (B operands: lane holds row q, columns
+    // 16 ks + 8 h .. +7) and the row statistics, as in the dQ kernel
+    const int q = 32 * w + r, qc = q < S ? q : S - 1;
+    elem8 qf[KS], gf[KS];
+    float lse2 = 0.f, ndelta = 0.f;
+    if (w < nqb) {
+        float acc = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            qf[ks] = as_elem8(ld_row16(a.Q + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
+            gf[ks] = as_elem8(ld_row16(a.dO + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
+            const elem8 of = as_elem8(ld_row16(a.O + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
+#pragma unroll
+            for (int t = 0; t < 8; ++t) acc += (float)of[t] * (float)gf[ks][t];
+        }
+        ndelta = -xhalf_sum(acc);
+        lse2 = a.LSE[(int64_t)bh * S + qc] * kLog2e;
+        if (h == 0) {
+            float *st = reinterpret_cast<float *>(smem);
+            st[q] = lse2;
+            st[C::kMaxRows + q] = ndelta;
+            if (q < S) {  // the workspace receives them as it does from the two-kernel backward
+                a.delta[(int64_t)bh * 2 * S + q] = ndelta;
+                a.delta[(int64_t)bh * 2 * S + S + q] = lse2;
+            }
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    const float c = a.scale_log2e;
+    // per-lane LDS offsets within a 32-row block: row fragment = chunk 2 ks + h of row r (the
+    // step enters by XOR: ^ (ks * 32)); transpose reads = rows 4h + e (+8), 64 bytes of d block 0
+    // of each row (d block db flips bits 6.. of the swizzled offset)
+    const int row_lane = r * RB + ((h ^ swz(r)) << 4);
+    int tr_lane[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int row = 8 * j + 4 * h + ((l & 15) >> 2);
+        const int chunk = 2 * ((l >> 4) & 1) + ((l >> 1) & 1);
+        tr_lane[j] = row * RB + ((chunk ^ swz(row)) << 4) + (l & 1) * 8;
+    }
+    // A operand = rows [32 blk, 32 blk + 32) of a tensor, contraction step ks
+    auto row_frag = [&](int tensor_off, int blk, int ks) {
+        return *(const elem8 *)(smem + tensor_off + blk * 32 * RB + (row_lane ^ (ks * 32)));
+    };
+    // A operand = the transpose of 16 rows (16-row step cc of block blk), d block db
+    auto tr_frag = [&](int tensor_off, int blk, int cc, int db) {
+        const char *p = smem + tensor_off + (blk * 2 + cc) * 16 * RB;
+        return join8(lds_read_tr((const elem *)(p + (tr_lane[0] ^ (db << 6)))),
+                     lds_read_tr((const elem *)(p + (tr_lane[1] ^ (db << 6)))));
+    };
+
+    // ---- part 1: dQ of query block w
+    if (w < nqb) {
+        f32x16 nd, dq[DB];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) nd[i] = ndelta;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dq[db][i] = 0.f;
+        const int q0e = 32 * w + coff;  // the wave's first row in key coordinates
+        for (int j = 0; j < nkb; ++j) {
+            const int k_lo = 32 * j;
+            if (CAUSAL && k_lo > q0e + 31) break;  // wholly above the diagonal
+            f32x16 s, dp = nd;  // register i <-> key k_lo + 8*(i/4) + 4h + i%4 (this lane's query is fixed)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                s = mfma32(row_frag(offK, j, ks), qf[ks], s);
+                dp = mfma32(row_frag(offV, j, ks), gf[ks], dp);  // ends as dP - delta
+            }
+            const int lim = (CAUSAL ? min(qc + coff, Sk - 1) : Sk - 1) - k_lo - 4 * h;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float p = fast_exp2(__builtin_fmaf(s[i], c, -lse2));
+                dp[i] *= (8 * (i / 4) + (i % 4) > lim) ? 0.f : p;  // dS = P o (dP - delta)
+            }
+            const elem8 sb[2] = {pack8(dp[0], dp[1], dp[2], dp[3], dp[4], dp[5], dp[6], dp[7]),
+                                 pack8(dp[8], dp[9], dp[10], dp[11], dp[12], dp[13], dp[14], dp[15])};
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+                for (int db = 0; db < DB; ++db) dq[db] = mfma32(tr_frag(offK, j, cc, db), sb[cc], dq[db]);
+        }
+        if (q < S) {
+            elem *dQp = a.dQ + base + (int64_t)q * a.stride_s;
+            const float sc = a.scale;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    if (32 * db + 8 * g + 4 * h < Dr)
+                        *(elem4 *)(dQp + 32 * db + 8 * g + 4 * h) =
+                            pack4(dq[db][4 * g] * sc, dq[db][4 * g + 1] * sc,
+                                  dq[db][4 * g + 2] * sc, dq[db][4 * g + 3] * sc);
+        }
+    }
+
+    // ---- part 2: dK and dV of key block w
+    if (w < nkb) {
+        const int key = 32 * w + r, keyc = key < Sk ? key : Sk - 1;
+        elem8 kf[KS], vf[KS];  // B operands: lane holds row `key`, columns 16 ks + 8 h .. +7
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int o = keyc * RB + (((2 * ks + h) ^ swz(keyc)) << 4);
+            kf[ks] = *(const elem8 *)(smem + offK + o);
+            vf[ks] = *(const elem8 *)(smem + offV + o);
+        }
+        f32x16 dk[DB], dv[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dk[db][i] = dv[db][i] = 0.f;
+        const float *st = reinterpret_cast<const float *>(smem);
+        // first query block with a row that sees a key of this block (row >= key - coff)
+        const int i0 = CAUSAL ? max(0, 32 * w - coff) / 32 : 0;
+        for (int i = i0; i < nqb; ++i) {
+            const int q_lo = 32 * i;
+            // register t <-> query row q_lo + 8*(t/4) + 4h + t%4 (this lane's key is fixed); the
+            // dP accumulator starts from -delta of its row
+            f32x16 s, dp;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 d4 = *(const f32x4 *)(st + C::kMaxRows + q_lo + 8 * g + 4 * h);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { dp[4 * g + e] = d4[e]; s[4 * g + e] = 0.f; }
+            }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                s = mfma32(row_frag(offQ, i, ks), kf[ks], s);
+                dp = mfma32(row_frag(offG, i, ks), vf[ks], dp);
+            }
+            // visible row offsets: >= key - coff - q_lo (causal) and <= S - 1 - q_lo; keys past
+            // the end see nothing
+            const int lo = (CAUSAL ? key - coff - q_lo : -64) - 4 * h;
+            const int hi = (key < Sk ? S - 1 - q_lo : -64) - 4 * h;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 l4 = *(const f32x4 *)(st + q_lo + 8 * g + 4 * h);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int ro = 8 * g + e;
+                    const float p = fast_exp2(__builtin_fmaf(s[4 * g + e], c, -l4[e]));
+                    s[4 * g + e] = (ro < lo || ro > hi) ? 0.f : p;
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 16; ++t) dp[t] *= s[t];  // dS = P o (dP - delta)
+            const elem8 pb[2] = {pack8(s[0], s[1], s[2], s[3], s[4], s[5], s[6], s[7]),
+                                 pack8(s[8], s[9], s[10], s[11], s[12], s[13], s[14], s[15])};
+            const elem8 sb[2] = {pack8(dp[0], dp[1], dp[2], dp[3], dp[4], dp[5], dp[6], dp[7]),
+                                 pack8(dp[8], dp[9], dp[10], dp[11], dp[12], dp[13], dp[14], dp[15])};
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    dv[db] = mfma32(tr_frag(offG, i, cc, db), pb[cc], dv[db]);
+                    dk[db] = mfma32(tr_frag(offQ, i, cc, db), sb[cc], dk[db]);
+                }
+        }
+        if (key < Sk) {
+            elem *dKp = a.dK + base_kv + (int64_t)key * a.kv_stride_s;
+            elem *dVp = a.dV + base_kv + (int64_t)key * a.kv_stride_s;
+            const float sc = a.scale;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    if (32 * db + 8 * g + 4 * h < Dr) {
+                        *(elem4 *)(dKp + 32 * db + 8 * g + 4 * h) =
+                            pack4(dk[db][4 * g] * sc, dk[db][4 * g + 1] * sc,
+                                  dk[db][4 * g + 2] * sc, dk[db][4 * g + 3] * sc);
+                        *(elem4 *)(dVp + 32 * db + 8 * g + 4 * h) =
+                            pack4(dv[db][4 * g], dv[db][4 * g + 1], dv[db][4 * g + 2], dv[db][4 * g + 3]);
+                    }
+        }
+    }
+}
+
+template <int D, bool CAUSAL>
+static int launch_small(const BwdArgs &a, hipStream_t st)
+{
+    using C = SmallCfg<D>;
+    const int rows_pad = ((a.S > a.Sk ? a.S : a.Sk) + 31) / 32 * 32;
+    if (hipFuncSetAttribute((const void *)attn_bwd_small_kernel<D, CAUSAL>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, C::lds_bytes(C::kMaxRows)) != hipSuccess)
+        return -1;
+    hipLaunchKernelGGL((attn_bwd_small_kernel<D, CAUSAL>), dim3(a.BH), dim3(C::kThreads),
+                       C::lds_bytes(rows_pad), st, a);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// Whole backward of a problem with at most 128 query rows and 128 keys per head, one query head
+// per K/V head, D = 64 or 128, no fused rotary embedding (the caller checks).
+int launch_bwd_small(const BwdArgs &a, int D, bool causal, hipStream_t st)
+{
+    if (a.S > 128 || a.Sk > 128 || a.group != 1 || a.rope_cos || D > 128) return -1;
+    if (D == 128) return causal ? launch_small<128, true>(a, st) : launch_small<128, false>(a, st);
+    return causal ? launch_small<64, true>(a, st) : launch_small<64, false>(a, st);
+}
+
+}  // namespace attn
