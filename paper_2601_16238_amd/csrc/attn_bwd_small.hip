@@ -21,15 +21,15 @@
 
 namespace attn {
 
-template <int D>
+template <int D, int NW>
 struct SmallCfg {
-    static constexpr int kMaxRows = 128;                       // query rows and keys per head
-    static constexpr int kWaves = 4;
+    static constexpr int kWaves = NW;                          // 4, or 8 (D = 64 only)
+    static constexpr int kMaxRows = 32 * NW;                   // query rows and keys per head
     static constexpr int kThreads = kWaves * 64;
     static constexpr int kRowBytes = D * 2;
     static constexpr int kCPR = D / 8;                         // 16-byte chunks per row
     static constexpr int kPieceRows = 1024 / kRowBytes;        // rows one 1 KB transfer fills
-    // LDS: lse2[128], -delta[128], then Q, dO, K, V, each padded to whole 32-row blocks of the
+    // LDS: lse2[kMaxRows], -delta[kMaxRows], then Q, dO, K, V, each padded to whole 32-row blocks of the
     // longer of the two lengths (sized at launch: three work-groups of the 65-row shape fit a
     // compute unit that way).  Rows are stored unpadded with the 16-byte chunk index XOR-swizzled
     // by the row, as in the slots of the dK/dV kernel: conflict free for row reads and for
@@ -39,12 +39,13 @@ struct SmallCfg {
     static_assert(lds_bytes(kMaxRows) <= 160 * 1024, "LDS budget of a gfx950 CU exceeded");
 };
 
-template <int D, bool CAUSAL>
-// (D = 64: at most 168 registers, so that three work-groups share a compute unit)
-__global__ void __launch_bounds__(SmallCfg<D>::kThreads) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 1)))
+template <int D, int NW, bool CAUSAL>
+// (D = 64, four waves: at most 168 registers, so that three work-groups share a compute unit)
+__global__ void __launch_bounds__(NW * 64)
+    __attribute__((amdgpu_waves_per_eu(D == 64 ? (NW == 4 ? 3 : 2) : 1)))
 attn_bwd_small_kernel(const BwdArgs a)
 {
-    using C = SmallCfg<D>;
+    using C = SmallCfg<D, NW>;
     constexpr int KS = D / 16, DB = D / 32, PR = C::kPieceRows, CPR = C::kCPR, RB = C::kRowBytes;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
@@ -275,26 +276,33 @@ attn_bwd_small_kernel(const BwdArgs a)
     }
 }
 
-template <int D, bool CAUSAL>
+template <int D, int NW, bool CAUSAL>
 static int launch_small(const BwdArgs &a, hipStream_t st)
 {
-    using C = SmallCfg<D>;
+    using C = SmallCfg<D, NW>;
     const int rows_pad = ((a.S > a.Sk ? a.S : a.Sk) + 31) / 32 * 32;
-    if (hipFuncSetAttribute((const void *)attn_bwd_small_kernel<D, CAUSAL>,
+    if (hipFuncSetAttribute((const void *)attn_bwd_small_kernel<D, NW, CAUSAL>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, C::lds_bytes(C::kMaxRows)) != hipSuccess)
         return -1;
-    hipLaunchKernelGGL((attn_bwd_small_kernel<D, CAUSAL>), dim3(a.BH), dim3(C::kThreads),
+    hipLaunchKernelGGL((attn_bwd_small_kernel<D, NW, CAUSAL>), dim3(a.BH), dim3(C::kThreads),
                        C::lds_bytes(rows_pad), st, a);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-// Whole backward of a problem with at most 128 query rows and 128 keys per head, one query head
-// per K/V head, D = 64 or 128, no fused rotary embedding (the caller checks).
+// Longest head (query rows and keys) the fused form takes at kernel head dimension D.
+#ifndef ATTN_F16  // a function of the head dimension only: defined once, by the bf16 build
+int bwd_small_max_rows(int D) { return D == 64 ? 256 : D == 128 ? 128 : 0; }
+#endif
+
+// Whole backward of a problem whose heads have at most bwd_small_max_rows(D) query rows and keys,
+// one query head per K/V head, no fused rotary embedding (the caller checks).
 int launch_bwd_small(const BwdArgs &a, int D, bool causal, hipStream_t st)
 {
-    if (a.S > 128 || a.Sk > 128 || a.group != 1 || a.rope_cos || D > 128) return -1;
-    if (D == 128) return causal ? launch_small<128, true>(a, st) : launch_small<128, false>(a, st);
-    return causal ? launch_small<64, true>(a, st) : launch_small<64, false>(a, st);
+    const int rows = a.S > a.Sk ? a.S : a.Sk;
+    if (rows > bwd_small_max_rows(D) || a.group != 1 || a.rope_cos) return -1;
+    if (D == 128) return causal ? launch_small<128, 4, true>(a, st) : launch_small<128, 4, false>(a, st);
+    if (rows <= 128) return causal ? launch_small<64, 4, true>(a, st) : launch_small<64, 4, false>(a, st);
+    return causal ? launch_small<64, 8, true>(a, st) : launch_small<64, 8, false>(a, st);
 }
 
 }  // namespace attn

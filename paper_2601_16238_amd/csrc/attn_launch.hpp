@@ -97,8 +97,9 @@ int fwd_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps);
 // Number of key splits the dQ kernel would use for this problem (1: none) and the keys per
 // split; a pure host function of the shape.
 int dq_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps);
-// The whole backward in one launch for heads of at most 128 query rows and 128 keys
+// The whole backward in one launch for heads of at most bwd_small_max_rows(D) query rows and keys
 // (attn_bwd_small.hip; called by launch_bwd when all three stages are asked for).
+int bwd_small_max_rows(int D);
 int launch_bwd_small(const BwdArgsT<__bf16> &a, int D, bool causal, hipStream_t st);
 int launch_bwd_small(const BwdArgsT<_Float16> &a, int D, bool causal, hipStream_t st);
 int launch_bwd(const BwdArgsT<__bf16> &a, int D, bool causal, hipStream_t st, unsigned stages);
