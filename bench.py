@@ -420,6 +420,33 @@ def measure_rope(torch, attn, steps, warmup):
         timer = (lambda f: graph_ms(torch, f, 20)) if S <= 4096 else (lambda f: time_calls(torch, f, max(steps, 10)))
         out[name] = {"shape": [B, H, S, D], "fused_ms": timer(fused), "rotary_then_forward_ms": timer(unfused),
                      "forward_alone_ms": timer(plain)}
+    # decoding: one new row per sequence against a rotated cache (the decode_cmp shape); the
+    # forward splits the keys, so both forms get the workspace
+    B, Hq, Hkv, Sk, D = 8, 32, 8, 8192, 128
+    g = torch.Generator(device="cuda"); g.manual_seed(1016)
+    Q = torch.randn((B, Hq, 1, D), device="cuda", generator=g).to(torch.bfloat16)
+    K, V = (torch.randn((B, Hkv, Sk, D), device="cuda", generator=g).to(torch.bfloat16) for _ in range(2))
+    ang = torch.arange(Sk, device="cuda", dtype=torch.float32)[:, None] * \
+        (10000.0 ** (-torch.arange(0, D, 2, device="cuda", dtype=torch.float32) / D))[None, :]
+    cos, sin = torch.cos(ang).contiguous(), torch.sin(ang).contiguous()
+    last_c, last_s = cos[Sk - 1:].contiguous(), sin[Sk - 1:].contiguous()
+    O, Qr = torch.empty_like(Q), torch.empty_like(Q)
+    LSE = torch.empty((B, Hq, 1), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(256, attn.attn_fwd_rect_workspace_bytes(B, Hq, Hkv, 1, Sk, D, True)),
+                     dtype=torch.uint8, device="cuda")
+    sc = 1.0 / float(D) ** 0.5
+
+    def fused_d():
+        attn.attn_fwd_rope(Q, K, V, cos, sin, sc, True, O=O, LSE=LSE, Q_rot=Qr)   # allocates its workspace
+
+    def unfused_d():
+        rowops.rotary_fwd(Q, last_c, last_s, y=Qr)
+        attn.attn_fwd_rect(Qr, K, V, sc, True, O=O, LSE=LSE, workspace=ws)
+
+    for _ in range(warmup):
+        fused_d(); unfused_d()
+    out["decode_shape"] = {"shape": [B, Hq, Hkv, 1, Sk, D], "fused_ms": graph_ms(torch, fused_d, 20),
+                           "rotary_then_forward_ms": graph_ms(torch, unfused_d, 20)}
     return out
 
 

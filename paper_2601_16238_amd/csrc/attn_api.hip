@@ -73,6 +73,7 @@ size_t round_ws(size_t bytes) { return (bytes + kWsAlign - 1) / kWsAlign * kWsAl
 // The forward's view of a problem: (B*H) independent heads of S query rows each.
 struct FwdView {
     int BH, H, S, group;
+    bool packed;  // decoding: the rows of a head are the query heads of one K/V head
     int64_t stride_b, stride_h, stride_s;
     bool causal;
 };
@@ -90,11 +91,11 @@ FwdView fwd_view(const attn_rect_params_t &p, bool may_pack = true)
         check_strides(G, p.D, p.q_stride_b, G * p.q_stride_h, p.q_stride_h) == ATTN_OK) {
         v.BH = p.B * p.Hkv; v.H = p.Hkv; v.S = G; v.group = 1;
         v.stride_b = p.q_stride_b; v.stride_h = G * p.q_stride_h; v.stride_s = p.q_stride_h;
-        v.causal = false;
+        v.causal = false; v.packed = true;
     } else {
         v.BH = p.B * p.Hq; v.H = p.Hq; v.S = p.Sq; v.group = G;
         v.stride_b = p.q_stride_b; v.stride_h = p.q_stride_h; v.stride_s = p.q_stride_s;
-        v.causal = p.causal != 0;
+        v.causal = p.causal != 0; v.packed = false;
     }
     return v;
 }
@@ -151,12 +152,11 @@ static int fwd_impl(const void *Q, const void *K, const void *V, void *O, float 
         !aligned(LSE, 4))
         return ATTN_ERR_ALIGN;
     // No workspace at all: run unsplit.  A workspace that is there must be usable.
-    // (with rotary positions the rows of a head must stay rows: no packing of decode heads)
-    const FwdView v = fwd_view(*p, rope == nullptr);
+    const FwdView v = fwd_view(*p);
     int kps = 0;
     int nsplit = workspace ? attn::fwd_split_plan(v.BH, v.S, p->Sk, kernel_d(p->D), v.causal, &kps) : 1;
     if (workspace && (!aligned(workspace, kWsAlign) ||
-                      workspace_bytes < fwd_workspace_bytes(p, rope == nullptr)))
+                      workspace_bytes < fwd_workspace_bytes(p, true)))
         return ATTN_ERR_WORKSPACE;
     attn::FwdArgsT<E> a;
     a.nsplit = nsplit; a.kps = kps;
@@ -177,6 +177,7 @@ static int fwd_impl(const void *Q, const void *K, const void *V, void *O, float 
     a.rope_sin = rope ? rope->sin_table : nullptr;
     a.Qrot = rope ? static_cast<E *>(rope->Qrot) : nullptr;
     a.rope_pos0 = p->Sk - p->Sq;
+    a.rope_row_step = v.packed ? 0 : 1;  // packed decoding heads all sit at the last position
     return attn::launch_fwd(a, kernel_d(p->D), v.causal, static_cast<hipStream_t>(hip_stream)) == 0
                ? ATTN_OK : ATTN_ERR_LAUNCH;
 }
@@ -277,7 +278,7 @@ void attn_rect_params_contiguous(attn_rect_params_t *p, int32_t B, int32_t Hq, i
 
 size_t attn_fwd_rect_workspace_bytes(const attn_rect_params_t *p) { return fwd_workspace_bytes(p, true); }
 
-size_t attn_fwd_rope_workspace_bytes(const attn_rect_params_t *p) { return fwd_workspace_bytes(p, false); }
+size_t attn_fwd_rope_workspace_bytes(const attn_rect_params_t *p) { return fwd_workspace_bytes(p, true); }
 
 int attn_fwd_rope(const void *Q, const void *K_rot, const void *V, const float *cos_table,
                   const float *sin_table, void *O, float *LSE, void *Q_rot, void *workspace,

@@ -316,7 +316,7 @@ attn_fwd_kernel(const FwdArgs a)
     // K and V tiles, so that all of them are in flight together, and used further down.
     f32x4 rc[KS][2], rs[KS][2];  // [ks][half of the 8 columns]; only ks < KS/2 is used
     if (a.rope_cos) {
-        const int64_t pos = (int64_t)(qc + a.rope_pos0) * (D / 2);
+        const int64_t pos = (int64_t)(qc * a.rope_row_step + a.rope_pos0) * (D / 2);
 #pragma unroll
         for (int ks = 0; ks < KS / 2; ++ks)
 #pragma unroll
@@ -704,7 +704,6 @@ int fwd_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps)
 // against 23.6 us), large launches by 7-12 %.
 static bool prefer_streaming_forward(const FwdArgs &a, int D)
 {
-    if (a.rope_cos) return false;  // the rotation of Q is fused into the kernel above only
     if (a.S <= 32) return true;
     return D == 128 && a.S <= 128;
 }

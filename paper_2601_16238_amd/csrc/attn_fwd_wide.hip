@@ -102,6 +102,39 @@ attn_fwd_wide_kernel(const FwdArgs a)
     for (int ks = 0; ks < KS; ++ks)
         qf[ks] = as_elem8(ld_row16(a.Q + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
 
+    // Rotary embedding of the query rows, fused into their load (D <= 128, head dimension == D):
+    // column d pairs with d + D/2, i.e. fragment ks with ks + KS/2, element by element, in this
+    // lane; the same two fused multiply-adds per pair as the rotary kernel and the forward of
+    // attn_fwd.hip, so that all three give the same bits.
+    if constexpr (D <= 128) {
+        if (a.rope_cos) {
+            const int64_t pos = (int64_t)(qc * a.rope_row_step + a.rope_pos0) * (D / 2);
+            elem *qr = a.Qrot ? a.Qrot + base + (int64_t)qc * a.stride_s : nullptr;
+#pragma unroll
+            for (int ks = 0; ks < KS / 2; ++ks) {
+                float lo[8], hi[8];
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const f32x4 c4 = *(const f32x4 *)(a.rope_cos + pos + 16 * ks + 8 * h + 4 * j);
+                    const f32x4 s4 = *(const f32x4 *)(a.rope_sin + pos + 16 * ks + 8 * h + 4 * j);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int t = 4 * j + e;
+                        const float x1 = (float)qf[ks][t], x2 = (float)qf[ks + KS / 2][t];
+                        lo[t] = __builtin_fmaf(x1, c4[e], -(x2 * s4[e]));
+                        hi[t] = __builtin_fmaf(x2, c4[e], x1 * s4[e]);
+                    }
+                }
+                qf[ks] = pack8(lo[0], lo[1], lo[2], lo[3], lo[4], lo[5], lo[6], lo[7]);
+                qf[ks + KS / 2] = pack8(hi[0], hi[1], hi[2], hi[3], hi[4], hi[5], hi[6], hi[7]);
+                if (qr && q < S && (!SPLIT || blockIdx.y == 0)) {
+                    *(elem8 *)(qr + 16 * ks + 8 * h) = qf[ks];
+                    *(elem8 *)(qr + 16 * (ks + KS / 2) + 8 * h) = qf[ks + KS / 2];
+                }
+            }
+        }
+    }
+
     const int q_end = min(S, (qt + 1) * C::kBR);
     const int k_end = CAUSAL ? min(Sk, q_end + coff) : Sk;  // <= 0: nothing visible (splits only)
     const int n_kt = k_end > 0 ? (k_end + C::kBC - 1) / C::kBC : 0;
@@ -404,10 +437,10 @@ static int launch_wide_d(const FwdArgs &a, bool causal, hipStream_t st)
 }
 
 // The main kernel only: with a split over the keys the caller launches the merge of the partial
-// results afterwards.  No fused rotary embedding.
+// results afterwards.  The rotary embedding can be fused at D = 64 and 128.
 int launch_fwd_wide(const FwdArgs &a, int D, bool causal, hipStream_t st)
 {
-    if (a.rope_cos) return -1;
+    if (a.rope_cos && D > 128) return -1;
     return D == 256 ? launch_wide_d<256>(a, causal, st)
          : D == 128 ? launch_wide_d<128>(a, causal, st)
                     : launch_wide_d<64>(a, causal, st);

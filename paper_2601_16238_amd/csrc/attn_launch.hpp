@@ -42,11 +42,12 @@ struct FwdArgsT {
     float *Opart;       // [nsplit][B*H][S][D]
     float *LSEpart;     // [nsplit][B*H][S]
     // Rotary embedding fused into the Q load (NULL tables: none).  Query row i is rotated by the
-    // table row i + rope_pos0 ("rotate-half" pairing of column d with d + D/2; tables fp32
+    // table row i * rope_row_step + rope_pos0 (step 1; step 0 when the rows of a head are the query
+    // heads of one decoding position, which all sit at position rope_pos0) ("rotate-half" pairing of column d with d + D/2; tables fp32
     // [positions][D/2]); Qrot, if not NULL, receives the rotated rows (same strides as Q).
     const float *rope_cos, *rope_sin;
     E *Qrot;
-    int rope_pos0;
+    int rope_pos0, rope_row_step;
 };
 
 template <typename E>

@@ -28,6 +28,8 @@ CASES = [  # B, Hq, Hkv, Sq, Sk, D, causal
     (2, 8, 8, 513, 513, 64, True),
     (1, 8, 2, 3, 4096, 128, True),       # few rows against a long cache: forward split over the keys
     (1, 2, 1, 641, 641, 128, False),
+    (2, 8, 2, 1, 3000, 128, True),       # decoding: the query heads of a K/V head share the last position
+    (1, 8, 8, 1, 513, 64, True), (1, 4, 2, 20, 700, 64, True),
 ]
 
 
