@@ -906,7 +906,7 @@ int dq_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps)
 int launch_bwd(const BwdArgs &a, int D, bool causal, hipStream_t st, unsigned stages)
 {
     // short heads, the full backward: one fused launch
-    if (stages == 7u && (a.S > a.Sk ? a.S : a.Sk) <= bwd_small_max_rows(D) && a.group == 1 && !a.rope_cos)
+    if (stages == 7u && (a.S > a.Sk ? a.S : a.Sk) <= bwd_small_max_rows(D) && a.group == 1)
         return launch_bwd_small(a, D, causal, st);
     return D == 256 ? launch_bwd_d<256>(a, causal, st, stages)
          : D == 128 ? launch_bwd_d<128>(a, causal, st, stages)

@@ -14,8 +14,8 @@
 // P and dS stay in registers in both parts (their accumulator layout is the B-operand layout of
 // the GEMM that consumes them).  The row statistics (delta, LSE in log2 units) are formed by the
 // owners of the query blocks and shared through LDS; that is the only barrier after the tiles
-// have landed.  Multi-head attention only (one query head per K/V head), no fused rotary
-// embedding; everything else takes the two-kernel path.
+// have landed.  Multi-head attention only (one query head per K/V head); everything else takes
+// the two-kernel path.
 #include "attn_device.hpp"
 #include "attn_launch.hpp"
 
@@ -181,6 +181,26 @@ attn_bwd_small_kernel(const BwdArgs a)
 #pragma unroll
                 for (int db = 0; db < DB; ++db) dq[db] = mfma32(tr_frag(offK, j, cc, db), sb[cc], dq[db]);
         }
+        if (a.rope_cos) {
+            // Q was rotated before the forward: what has been accumulated is the gradient of the
+            // rotated rows; the gradient of the unrotated ones is its image under the transpose of
+            // the rotation (head dimension == D; column d pairs with d + D/2, i.e. d block db with
+            // db + DB/2, same register) -- as in the dQ kernel's epilogue
+            const int64_t pos = (int64_t)(qc + a.rope_pos0) * (D / 2);
+#pragma unroll
+            for (int db = 0; db < DB / 2; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 c4 = *(const f32x4 *)(a.rope_cos + pos + 32 * db + 8 * g + 4 * h);
+                    const f32x4 s4 = *(const f32x4 *)(a.rope_sin + pos + 32 * db + 8 * g + 4 * h);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float y1 = dq[db][4 * g + e], y2 = dq[db + DB / 2][4 * g + e];
+                        dq[db][4 * g + e] = __builtin_fmaf(y1, c4[e], y2 * s4[e]);
+                        dq[db + DB / 2][4 * g + e] = __builtin_fmaf(y2, c4[e], -(y1 * s4[e]));
+                    }
+                }
+        }
         if (q < S) {
             elem *dQp = a.dQ + base + (int64_t)q * a.stride_s;
             const float sc = a.scale;
@@ -295,11 +315,11 @@ int bwd_small_max_rows(int D) { return D == 64 ? 256 : D == 128 ? 128 : 0; }
 #endif
 
 // Whole backward of a problem whose heads have at most bwd_small_max_rows(D) query rows and keys,
-// one query head per K/V head, no fused rotary embedding (the caller checks).
+// one query head per K/V head (the caller checks).
 int launch_bwd_small(const BwdArgs &a, int D, bool causal, hipStream_t st)
 {
     const int rows = a.S > a.Sk ? a.S : a.Sk;
-    if (rows > bwd_small_max_rows(D) || a.group != 1 || a.rope_cos) return -1;
+    if (rows > bwd_small_max_rows(D) || a.group != 1) return -1;
     if (D == 128) return causal ? launch_small<128, 4, true>(a, st) : launch_small<128, 4, false>(a, st);
     if (rows <= 128) return causal ? launch_small<64, 4, true>(a, st) : launch_small<64, 4, false>(a, st);
     return causal ? launch_small<64, 8, true>(a, st) : launch_small<64, 8, false>(a, st);
