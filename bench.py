@@ -171,7 +171,7 @@ def measure(torch, attn, wl, w, steps, warmup):
     gemm = f_fwd / 2.0
     kern = {"attn_fwd_kernel": (2 * gemm, ms["fwd"]), "attn_bwd_dkdv_kernel": (4 * gemm, ms["bwd_dkdv"]),
             "attn_bwd_dq_kernel": (1 * gemm, ms["bwd_dq"])}
-    if not gqa and w.S <= (256 if w.D <= 64 else 128 if w.D <= 128 else 0):
+    if (not gqa or w.B * Hkv >= 256) and w.S <= (256 if w.D <= 64 else 128 if w.D <= 128 else 0):
         # short heads: the full backward call is ONE fused kernel (5 algorithmic GEMMs); the
         # stage-wise timings above still show the two-kernel path that it replaces
         kern["attn_bwd_small_kernel"] = (5 * gemm, ms.get("bwd_graph_replay", ms["bwd"]))

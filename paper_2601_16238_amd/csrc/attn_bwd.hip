@@ -905,8 +905,12 @@ int dq_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps)
 
 int launch_bwd(const BwdArgs &a, int D, bool causal, hipStream_t st, unsigned stages)
 {
-    // short heads, the full backward: one fused launch
-    if (stages == 7u && (a.S > a.Sk ? a.S : a.Sk) <= bwd_small_max_rows(D) && a.group == 1)
+    // short heads, the full backward: one fused launch.  With grouped-query heads its work-group
+    // walks the query heads of a K/V head one after the other, which pays once there is a K/V
+    // head for every compute unit (measured: 10-26 % faster from 256 K/V heads on, slower below,
+    // where the two-kernel form spreads the query heads over the chip)
+    if (stages == 7u && (a.S > a.Sk ? a.S : a.Sk) <= bwd_small_max_rows(D) &&
+        (a.group == 1 || a.BH / a.group >= 256))
         return launch_bwd_small(a, D, causal, st);
     return D == 256 ? launch_bwd_d<256>(a, causal, st, stages)
          : D == 128 ? launch_bwd_d<128>(a, causal, st, stages)

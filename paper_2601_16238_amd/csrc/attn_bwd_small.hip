@@ -14,8 +14,9 @@
 // P and dS stay in registers in both parts (their accumulator layout is the B-operand layout of
 // the GEMM that consumes them).  The row statistics (delta, LSE in log2 units) are formed by the
 // owners of the query blocks and shared through LDS; that is the only barrier after the tiles
-// have landed.  Multi-head attention only (one query head per K/V head); everything else takes
-// the two-kernel path.
+// have landed.  With grouped-query heads the work-group owns a K/V head and walks the query heads
+// that read it one after the other (their Q and dO tiles replace each other in LDS; dK and dV
+// accumulate across them).
 #include "attn_device.hpp"
 #include "attn_launch.hpp"
 
@@ -39,10 +40,12 @@ struct SmallCfg {
     static_assert(lds_bytes(kMaxRows) <= 160 * 1024, "LDS budget of a gfx950 CU exceeded");
 };
 
-template <int D, int NW, bool CAUSAL>
-// (D = 64, four waves: at most 168 registers, so that three work-groups share a compute unit)
+template <int D, int NW, bool CAUSAL, bool GQA>
+// (D = 64, four waves, one query head per K/V head: at most 168 registers, so that three
+// work-groups share a compute unit; with grouped heads the dK/dV accumulators stay live while dQ
+// of the next query head is formed, which takes more)
 __global__ void __launch_bounds__(NW * 64)
-    __attribute__((amdgpu_waves_per_eu(D == 64 ? (NW == 4 ? 3 : 2) : 1)))
+    __attribute__((amdgpu_waves_per_eu(D == 64 ? (NW == 4 && !GQA ? 3 : 2) : 1)))
 attn_bwd_small_kernel(const BwdArgs a)
 {
     using C = SmallCfg<D, NW>;
@@ -53,9 +56,10 @@ attn_bwd_small_kernel(const BwdArgs a)
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int S = a.S, Sk = a.Sk, Dr = a.Dr;
     const int coff = Sk - S;  // causal: query row i sees keys 0 .. i + coff
-    const int bh = blockIdx.x;
-    const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
-    const int64_t base_kv = (int64_t)(bh / a.H) * a.kv_stride_b + (int64_t)(bh % a.H) * a.kv_stride_h;
+    // the work-group owns one K/V head and sums dK, dV over the `group` query heads that read it
+    const int Hkv = a.H / a.group, bkv = blockIdx.x;
+    const int64_t base_kv = (int64_t)(bkv / Hkv) * a.kv_stride_b + (int64_t)(bkv % Hkv) * a.kv_stride_h;
+    const int bh0 = (bkv / Hkv) * a.H + (bkv % Hkv) * a.group;  // first query head of the group
     const int nqb = (S + 31) / 32, nkb = (Sk + 31) / 32;  // query / key blocks of the head
     const int tensor_bytes = 32 * max(nqb, nkb) * RB;
     const int offQ = C::kStatBytes, offG = offQ + tensor_bytes, offK = offG + tensor_bytes, offV = offK + tensor_bytes;
@@ -71,7 +75,6 @@ attn_bwd_small_kernel(const BwdArgs a)
     // buffer resources and read as zero.
     const uint32_t q_bytes = (uint32_t)(((int64_t)(S - 1) * a.stride_s + Dr) * 2);
     const uint32_t k_bytes = (uint32_t)(((int64_t)(Sk - 1) * a.kv_stride_s + Dr) * 2);
-    const desc_t Qd = make_desc(a.Q + base, q_bytes), Gd = make_desc(a.dO + base, q_bytes);
     const desc_t Kd = make_desc(a.K + base_kv, k_bytes), Vd = make_desc(a.V + base_kv, k_bytes);
     const uint32_t lds0 = lds_address(smem);
     const uint32_t q_row = (uint32_t)a.stride_s * 2u, k_row = (uint32_t)a.kv_stride_s * 2u;
@@ -83,20 +86,36 @@ attn_bwd_small_kernel(const BwdArgs a)
         return chunk * 8 < Dr ? (uint32_t)(l / CPR) * row_bytes + ((uint32_t)chunk << 4) : end;
     };
     const int q_pieces = nqb * (32 / PR), k_pieces = nkb * (32 / PR);
-    for (int i = w; i < q_pieces; i += C::kWaves) {
-        const uint32_t vo = voff(i, q_row, q_bytes);
-        dma16(Qd, lds0 + offQ + i * 1024, vo, i * PR * q_row);
-        dma16(Gd, lds0 + offG + i * 1024, vo, i * PR * q_row);
-    }
     for (int i = w; i < k_pieces; i += C::kWaves) {
         const uint32_t vo = voff(i, k_row, k_bytes);
         dma16(Kd, lds0 + offK + i * 1024, vo, i * PR * k_row);
         dma16(Vd, lds0 + offV + i * 1024, vo, i * PR * k_row);
     }
 
+    const int q = 32 * w + r, qc = q < S ? q : S - 1;
+    const int key = 32 * w + r, keyc = key < Sk ? key : Sk - 1;
+    f32x16 dk[DB], dv[DB];  // part 2's accumulators, summed over the query heads of the group
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dk[db][i] = dv[db][i] = 0.f;
+
+    const int n_heads = GQA ? a.group : 1;
+    for (int gq = 0; gq < n_heads; ++gq) {
+    const int bh = bh0 + gq;
+    const int64_t base = (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h;
+    // every wave is done with the previous query head's tiles and statistics
+    if (GQA && gq > 0) __syncthreads();
+    {
+        const desc_t Qd = make_desc(a.Q + base, q_bytes), Gd = make_desc(a.dO + base, q_bytes);
+        for (int i = w; i < q_pieces; i += C::kWaves) {
+            const uint32_t vo = voff(i, q_row, q_bytes);
+            dma16(Qd, lds0 + offQ + i * 1024, vo, i * PR * q_row);
+            dma16(Gd, lds0 + offG + i * 1024, vo, i * PR * q_row);
+        }
+    }
     // ---- this wave's query block: Q and dO fragments (B operands: lane holds row q, columns
     // 16 ks + 8 h .. +7) and the row statistics, as in the dQ kernel
-    const int q = 32 * w + r, qc = q < S ? q : S - 1;
     elem8 qf[KS], gf[KS];
     float lse2 = 0.f, ndelta = 0.f;
     if (w < nqb) {
@@ -217,7 +236,6 @@ attn_bwd_small_kernel(const BwdArgs a)
 
     // ---- part 2: dK and dV of key block w
     if (w < nkb) {
-        const int key = 32 * w + r, keyc = key < Sk ? key : Sk - 1;
         elem8 kf[KS], vf[KS];  // B operands: lane holds row `key`, columns 16 ks + 8 h .. +7
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -225,11 +243,6 @@ attn_bwd_small_kernel(const BwdArgs a)
             kf[ks] = *(const elem8 *)(smem + offK + o);
             vf[ks] = *(const elem8 *)(smem + offV + o);
         }
-        f32x16 dk[DB], dv[DB];
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) dk[db][i] = dv[db][i] = 0.f;
         const float *st = reinterpret_cast<const float *>(smem);
         // first query block with a row that sees a key of this block (row >= key - coff)
         const int i0 = CAUSAL ? max(0, 32 * w - coff) / 32 : 0;
@@ -277,6 +290,10 @@ attn_bwd_small_kernel(const BwdArgs a)
                     dk[db] = mfma32(tr_frag(offQ, i, cc, db), sb[cc], dk[db]);
                 }
         }
+    }
+    }  // query heads of the group
+
+    if (w < nkb) {
         if (key < Sk) {
             elem *dKp = a.dK + base_kv + (int64_t)key * a.kv_stride_s;
             elem *dVp = a.dV + base_kv + (int64_t)key * a.kv_stride_s;
@@ -296,30 +313,36 @@ attn_bwd_small_kernel(const BwdArgs a)
     }
 }
 
-template <int D, int NW, bool CAUSAL>
-static int launch_small(const BwdArgs &a, hipStream_t st)
+template <int D, int NW, bool CAUSAL, bool GQA>
+static int launch_small_g(const BwdArgs &a, hipStream_t st)
 {
     using C = SmallCfg<D, NW>;
     const int rows_pad = ((a.S > a.Sk ? a.S : a.Sk) + 31) / 32 * 32;
-    if (hipFuncSetAttribute((const void *)attn_bwd_small_kernel<D, NW, CAUSAL>,
+    if (hipFuncSetAttribute((const void *)attn_bwd_small_kernel<D, NW, CAUSAL, GQA>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, C::lds_bytes(C::kMaxRows)) != hipSuccess)
         return -1;
-    hipLaunchKernelGGL((attn_bwd_small_kernel<D, NW, CAUSAL>), dim3(a.BH), dim3(C::kThreads),
+    hipLaunchKernelGGL((attn_bwd_small_kernel<D, NW, CAUSAL, GQA>), dim3(a.BH / a.group), dim3(C::kThreads),
                        C::lds_bytes(rows_pad), st, a);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-// Longest head (query rows and keys) the fused form takes at kernel head dimension D.
+template <int D, int NW, bool CAUSAL>
+static int launch_small(const BwdArgs &a, hipStream_t st)
+{
+    return a.group > 1 ? launch_small_g<D, NW, CAUSAL, true>(a, st) : launch_small_g<D, NW, CAUSAL, false>(a, st);
+}
+
 #ifndef ATTN_F16  // a function of the head dimension only: defined once, by the bf16 build
+// Longest head (query rows and keys) the fused form takes at kernel head dimension D.
 int bwd_small_max_rows(int D) { return D == 64 ? 256 : D == 128 ? 128 : 0; }
 #endif
 
-// Whole backward of a problem whose heads have at most bwd_small_max_rows(D) query rows and keys,
-// one query head per K/V head (the caller checks).
+// Whole backward of a problem whose heads have at most bwd_small_max_rows(D) query rows and keys
+// (the caller checks).
 int launch_bwd_small(const BwdArgs &a, int D, bool causal, hipStream_t st)
 {
     const int rows = a.S > a.Sk ? a.S : a.Sk;
-    if (rows > bwd_small_max_rows(D) || a.group != 1) return -1;
+    if (rows > bwd_small_max_rows(D)) return -1;
     if (D == 128) return causal ? launch_small<128, 4, true>(a, st) : launch_small<128, 4, false>(a, st);
     if (rows <= 128) return causal ? launch_small<64, 4, true>(a, st) : launch_small<64, 4, false>(a, st);
     return causal ? launch_small<64, 8, true>(a, st) : launch_small<64, 8, false>(a, st);

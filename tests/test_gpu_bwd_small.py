@@ -1,6 +1,6 @@
 """GPU parity for the fused backward of short heads (one work-group per head computes dQ, dK
-and dV in one launch): at most 128 query rows and keys at D = 128, at most 256 at D = 64, one
-query head per K/V head.  Shapes sit on both sides of every boundary of that form (block counts,
+and dV in one launch): at most 128 query rows and keys at D = 128, at most 256 at D = 64, with
+one or several query heads per K/V head.  Shapes sit on both sides of every boundary of that form (block counts,
 the four- and the eight-wave kernel, lengths that differ, padded head dimensions); each is
 compared with the fp64 oracle and, where the lengths are equal, with the two-kernel backward called stage by
 stage."""
@@ -58,6 +58,34 @@ def test_fused_small_backward(B, H, Sq, Sk, D, causal):
     ref = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], causal)
     for nm, g, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), ref):
         if min(Sq, Sk) < 32 or D < 32:
+            check_bf16(nm, to_f64(g), r, floor_gate=False)
+        else:
+            check_grad(nm, to_f64(g), r)
+
+
+# (B,Hq,Hkv,Sq,Sk,D,causal): several query heads read one K/V head; the work-group of that K/V
+# head walks them and sums their dK and dV.  The fused form takes grouped heads from 256 K/V
+# heads (B * Hkv) on; the last two cases sit just below and take the two-kernel path.
+GQA_CASES = [
+    (128, 4, 2, 64, 64, 64, True), (256, 8, 1, 100, 100, 64, False), (128, 6, 2, 33, 97, 64, True),
+    (64, 8, 4, 256, 256, 64, True), (86, 6, 3, 200, 130, 48, False), (256, 4, 1, 128, 128, 128, True),
+    (128, 8, 2, 77, 128, 128, False), (128, 4, 2, 1, 50, 128, True), (86, 6, 3, 129, 255, 64, True),
+    (85, 6, 3, 64, 64, 64, True), (255, 2, 1, 96, 96, 128, False),
+]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D,causal", GQA_CASES)
+def test_fused_small_backward_grouped_heads(B, Hq, Hkv, Sq, Sk, D, causal):
+    print("case bwd_small gqa", B, Hq, Hkv, Sq, Sk, D, causal, flush=True)
+    x = wl.random_rect_inputs(B, Hq, Hkv, Sq, Sk, D, seed=3300 + 7 * Sq + Sk + D + Hq)
+    Q, K, V, dO = (to_dev(x[k]) for k in ("Q", "K", "V", "dO"))
+    O, LSE = attn.attn_fwd_rect(Q, K, V, x["scale"], causal)
+    nan = lambda t: torch.full_like(t, float("nan"))
+    dQ, dK, dV = attn.attn_bwd_rect(Q, K, V, O, dO, LSE, x["scale"], causal, dQ=nan(Q), dK=nan(K), dV=nan(V))
+    torch.cuda.synchronize()
+    ref = oracle.attn_bwd(x["Q"], x["K"], x["V"], x["dO"], x["scale"], causal)
+    for nm, g, r in zip(("dQ", "dK", "dV"), (dQ, dK, dV), ref):
+        if min(Sq, Sk) < 32:
             check_bf16(nm, to_f64(g), r, floor_gate=False)
         else:
             check_grad(nm, to_f64(g), r)
