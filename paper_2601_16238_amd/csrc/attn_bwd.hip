@@ -130,6 +130,7 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     const int n_slot = (S + C::kRows - 1) / C::kRows;
     // first slot with a row that sees a key of this block (row >= key - coff)
     const int t0 = CAUSAL ? max(0, kt * C::kBlk - coff) / C::kRows : 0;
+    const int n_seq = n_slot > t0 ? a.group * (n_slot - t0) : 0;  // slots of all heads of the group
 
     // chunk position swizzle: rows 0..15 get 16 distinct values (row reads of 16 lanes hit 16
     // different 16-byte bank groups) and 4 consecutive rows differ in the upper two bits (the
@@ -214,21 +215,33 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
         const float c = a.scale_log2e;
         const int lane_off = r * RB + ((h ^ swz(r)) << 4);  // chunk 2ks+h of row r: ^ (ks*32)
 
-        for (int gq = 0; gq < a.group; ++gq) {
-        // every wave is done with the previous query head's ring and exchange buffers
-        if (gq > 0) wait_vm_and_barrier<0>();
-        set_head(bh0 + gq);
+        // The slots of the group's query heads form ONE sequence (head after head, slots t0 ..
+        // n_slot-1 of each), so that the ring stays full across the change of head: the
+        // transfers run kAhead slots in front and switch to the next head's rows on their own.
+        int tf = t0, gqf = 0;  // slot and head of the next transfer
+        set_head(bh0);
+        auto advance_fetch = [&]() __attribute__((always_inline)) {
+            ++tf;  // past the last head: rows beyond S, which read as zero
+            if (tf == n_slot && gqf + 1 < a.group) {
+                tf = t0;
+                set_head(bh0 + ++gqf);
+            }
+        };
 #pragma unroll
-        for (int i = 0; i < C::kAhead; ++i) dma_slot(t0 + i, i);
-        int rs = 0;  // ring position of slot t
-        for (int t = t0; t < n_slot; ++t) {
+        for (int i = 0; i < C::kAhead; ++i) {
+            dma_slot(tf, i);
+            advance_fetch();
+        }
+        int rs = 0;  // ring position of the current slot
+        int t = t0;  // its rows: slot t of the current head
+        for (int g = 0; g < n_seq; ++g) {
             slot_barrier();
             int rd = rs + C::kAhead;
             rd = rd >= C::kRing ? rd - C::kRing : rd;
-            dma_stat(t + C::kAhead, rd);
+            dma_stat(tf, rd);
             if (!active(t)) {
 #pragma unroll
-                for (int n = 0; n < C::kDmaPerWave; ++n) dma_piece(t + C::kAhead, rd, n);
+                for (int n = 0; n < C::kDmaPerWave; ++n) dma_piece(tf, rd, n);
             } else {
                 const char *Qt = smem + rs * C::kSlotBytes;
                 const float *st = reinterpret_cast<const float *>(smem + C::kOffStat + rs * C::kStatBytes);
@@ -253,13 +266,13 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
                 // after contraction step (j + 1) * kEvery - 1
                 constexpr int kEvery = KS / C::kDmaPerWave;
                 static_assert(kEvery >= 1 && kEvery * C::kDmaPerWave == KS, "transfers spread evenly");
-                if (kEvery == 1) dma_piece(t + C::kAhead, rd, 0);
+                if (kEvery == 1) dma_piece(tf, rd, 0);
 #pragma unroll
                 for (int ks = 1; ks < KS; ++ks) {
                     const int off = lane_off ^ (ks * 32);
                     s = mfma32(*(const elem8 *)(Qt + off), kf[ks], s);
                     dp = mfma32(*(const elem8 *)(Qt + C::kTensorBytes + off), vf[ks], dp);
-                    if ((ks + 1) % kEvery == 0) dma_piece(t + C::kAhead, rd, (ks + 1) / kEvery - 1);
+                    if ((ks + 1) % kEvery == 0) dma_piece(tf, rd, (ks + 1) / kEvery - 1);
                 }
                 // the lane's key is fixed; P = exp2(c S - lse2) per row
 #pragma unroll
@@ -281,16 +294,17 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
                 }
 #pragma unroll
                 for (int i = 0; i < 16; ++i) dp[i] *= s[i];  // dS = P o (dP - delta)
-                elem8 *x = Xs + (t & 1) * (C::kPairs * 256);
+                elem8 *x = Xs + (g & 1) * (C::kPairs * 256);
                 x[0] = pack8(s[0], s[1], s[2], s[3], s[4], s[5], s[6], s[7]);
                 x[64] = pack8(s[8], s[9], s[10], s[11], s[12], s[13], s[14], s[15]);
                 x[128] = pack8(dp[0], dp[1], dp[2], dp[3], dp[4], dp[5], dp[6], dp[7]);
                 x[192] = pack8(dp[8], dp[9], dp[10], dp[11], dp[12], dp[13], dp[14], dp[15]);
             }
+            advance_fetch();
             rs = ring_next(rs);
+            if (++t == n_slot) t = t0;
         }
         wait_vm_and_barrier<0>();  // the consumers' last slot
-        }
     } else {
         // Consumers.  Wave 4+cw accumulates ONE output for the 64 keys of two producers
         // (2*(cw>>1) and the next): dV^T += dO^T P for even cw, dK^T += Q^T dS for odd cw.
@@ -322,11 +336,11 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
         };
         const elem8 *const Xc = reinterpret_cast<const elem8 *>(smem + C::kOffXchg) +
                                  (2 * half) * 256 + kind * 128 + l;
-        auto consume = [&](int t, int rs) {
+        auto consume = [&](int t, int g, int rs) {
             const bool actA = block_active(t, kA), actB = block_active(t, kB);
             if (!actA) return;  // kA < kB: then the second block is not active either
             const char *Tt = smem + rs * C::kSlotBytes + (kind ? 0 : C::kTensorBytes);
-            const elem8 *x = Xc + (t & 1) * (C::kPairs * 256);
+            const elem8 *x = Xc + (g & 1) * (C::kPairs * 256);
             const elem8 opA[2] = {x[0], x[64]};
             // Slots above the diagonal of the second key block: its producer wrote nothing,
             // so the block gets zero operands (a second code path without its MFMAs makes
@@ -350,17 +364,17 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
             }
         };
 
-        for (int gq = 0; gq < a.group; ++gq) {
-        if (gq > 0) wait_vm_and_barrier<0>();
-        int rs = 0;  // ring position of the producers' slot t; the consumers' is one behind
-        for (int t = t0; t < n_slot; ++t) {
+        int rs = 0;  // ring position of the producers' slot; the consumers' is one behind
+        int t = t0, tp = t0;  // rows of the producers' slot and of the one before it
+        for (int g = 0; g < n_seq; ++g) {
             wait_vm_and_barrier<0>();
-            if (t > t0) consume(t - 1, rs == 0 ? C::kRing - 1 : rs - 1);
+            if (g > 0) consume(tp, g - 1, rs == 0 ? C::kRing - 1 : rs - 1);
             rs = ring_next(rs);
+            tp = t;
+            if (++t == n_slot) t = t0;
         }
         wait_vm_and_barrier<0>();
-        if (n_slot > t0) consume(n_slot - 1, rs == 0 ? C::kRing - 1 : rs - 1);
-        }
+        if (n_seq > 0) consume(tp, n_seq - 1, rs == 0 ? C::kRing - 1 : rs - 1);
 
         elem *const out = kind ? a.dK : a.dV;
         const float sc = kind ? a.scale : 1.f;
