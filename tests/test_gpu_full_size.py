@@ -96,6 +96,21 @@ def test_paper_table_sampled_heads():
             check_bf16(nm, head(out[nm], w, bh), r[0, 0])
 
 
+def test_headdim256_sampled_heads():
+    """Head dimension 256 at the size bench.py times (one wave per SIMD in all three kernels,
+    32-key tiles): a sample of its 64 heads, every element."""
+    w, x, out = full_run("headdim256")
+    for bh in (0, 29, 63):
+        print("case full_size headdim256 head", bh, flush=True)
+        sub = heads_of(x, w, bh, bh + 1)
+        Oref, Lref = oracle.attn_fwd(sub["Q"], sub["K"], sub["V"], x["scale"], w.causal)
+        gref = oracle.attn_bwd(sub["Q"], sub["K"], sub["V"], sub["dO"], x["scale"], w.causal)
+        check_bf16_auto("O", head(out["O"], w, bh), Oref[0, 0])
+        check_lse(head(out["LSE"], w, bh), Lref[0, 0])
+        for nm, r in zip(("dQ", "dK", "dV"), gref):
+            check_grad(nm, head(out[nm], w, bh), r[0, 0])
+
+
 @pytest.mark.parametrize("lo,hi", [(lo, lo + 2) for lo in range(0, 16, 2)])
 def test_long_causal_every_head(lo, hi):
     """All sixteen heads of the long-sequence causal workload with outlier rows.
