@@ -55,6 +55,34 @@ WIDE_CASES = draw_cases(int(os.environ.get("ATTN_SWEEP_WIDE_CASES", "16")),
                         seed=int(os.environ.get("ATTN_SWEEP_SEED", "20260116")) + 1, dims=WIDE_DIMS)
 
 
+def draw_short_cases(n, seed):
+    """Many short heads: at least 256 K/V heads of at most 256 rows and keys, the shapes for which
+    the backward is one fused launch also with grouped-query heads."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    cases = []
+    while len(cases) < n:
+        Hkv = int(rng.integers(1, 5)); G = int(rng.choice([1, 2, 2, 4, 6]))
+        D = int(rng.choice(DIMS))
+        top = 128 if D > 64 else 256
+        Sq, Sk = int(rng.integers(1, top + 1)), int(rng.integers(1, top + 1))
+        causal = bool(rng.integers(0, 2)) and Sk >= Sq
+        B = -(-256 // Hkv) + int(rng.integers(0, 24))
+        if B * Hkv * G * Sq * Sk * D > 1.5e9:
+            continue
+        cases.append((B, Hkv * G, Hkv, Sq, Sk, D, causal, False,
+                      bool(rng.integers(0, 4) == 0), int(rng.integers(1 << 30))))
+    return cases
+
+
+SHORT_CASES = draw_short_cases(int(os.environ.get("ATTN_SWEEP_SHORT_CASES", "12")),
+                               seed=int(os.environ.get("ATTN_SWEEP_SEED", "20260116")) + 2)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D,causal,split,f16,seed", SHORT_CASES)
+def test_random_case_many_short_heads(B, Hq, Hkv, Sq, Sk, D, causal, split, f16, seed):
+    run_case(B, Hq, Hkv, Sq, Sk, D, causal, split, f16, seed)
+
+
 @pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D,causal,split,f16,seed", CASES)
 def test_random_case(B, Hq, Hkv, Sq, Sk, D, causal, split, f16, seed):
     run_case(B, Hq, Hkv, Sq, Sk, D, causal, split, f16, seed)
