@@ -60,7 +60,11 @@ struct FwdCfg {
     // sub-tile by V one sub-tile later and therefore still reads tile kt-1 while tile kt+1 is
     // arriving
     static constexpr int kVBufs = NW == 8 ? 3 : 2;
-    static constexpr int kLdsBytes = (3 * kKTile + kVBufs * kVTile) * 2;
+    // Eight waves: the query rows reach the registers through LDS (see the kernel's prologue):
+    // the 64 rows of a pair of waves are staged like a K tile, pair 0 in K buffer 2, pair 1 in
+    // V buffer 1 (both free until the first tile barrier), pairs 2 and 3 behind the V buffers.
+    static constexpr int kQStage = NW == 8 ? 2 * kKTile : 0;
+    static constexpr int kLdsBytes = (3 * kKTile + kVBufs * kVTile + kQStage) * 2;
     static_assert(kLdsBytes <= 160 * 1024, "LDS budget of a gfx950 CU exceeded");
 };
 
@@ -109,11 +113,17 @@ attn_fwd_kernel(const FwdArgs a)
     const int q = q0 + r;                 // this lane's query row
     const int qc = q < S ? q : S - 1;     // clamped for loads; rows >= S are never stored
 
-    // Q fragments, B operand of K Q^T: lane holds Q[q][16*ks + 8h .. +7].
+    // Q fragments, B operand of K Q^T: lane holds Q[q][16*ks + 8h .. +7].  Fewer than eight
+    // waves load them straight from memory.  Eight waves take them through LDS (below): a load
+    // in which every lane fetches 16 bytes of its own row touches 32 rows per instruction, and
+    // the 64 such instructions of a work-group took its last wave 5000-7000 cycles to get issued
+    // (measured) -- time in which the compute unit, which holds one such work-group, does nothing.
     elem8 qf[KS];
+    if constexpr (NW != 8) {
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-        qf[ks] = as_elem8(ld_row16(Qp + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
+        for (int ks = 0; ks < KS; ++ks)
+            qf[ks] = as_elem8(ld_row16(Qp + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
+    }
 
     // Key tiles this work-group visits.
     const int q_end = min(S, (qt + 1) * C::kBR);
@@ -306,6 +316,26 @@ attn_fwd_kernel(const FwdArgs a)
 
     // ---- prologue: K(0), K(1), V(0) resident; V(1) in flight; first S^T block computed and
     // the K fragments of the second sub-tile on their way.
+    // Eight waves: the wave's 32 query rows as half of a K-layout tile, by the same direct
+    // transfers (whole rows of four per instruction), issued before those of K and V.  Rows past
+    // S-1 and columns Dr..D-1 read as zero.
+    uint32_t q_stage = 0;
+    if constexpr (NW == 8) {
+        const int pair = __builtin_amdgcn_readfirstlane(w) >> 1, half = __builtin_amdgcn_readfirstlane(w) & 1;
+        q_stage = (pair == 0 ? 2 * C::kKTile : pair == 1 ? 3 * C::kKTile + C::kVTile
+                                                          : 3 * C::kKTile + 3 * C::kVTile + (pair - 2) * C::kKTile) * 2 +
+                  half * (C::kKHalf * 2);
+        const int row0 = qt * C::kBR + pair * 64;
+        const int rows = min(64, S - row0);
+        const uint32_t q_bytes = rows > 0 ? (uint32_t)(((int64_t)(rows - 1) * a.stride_s + Dr) * 2) : 0u;
+        const desc_t Qd = make_desc(Qp + (int64_t)(rows > 0 ? row0 : 0) * a.stride_s, q_bytes);
+        const uint32_t q_row_bytes = (uint32_t)a.stride_s * 2u;
+        const uint32_t q_voff = (l / PR) * 8 < Dr ? (l % PR) * q_row_bytes + ((l / PR) << 4) : q_bytes;
+#pragma unroll
+        for (int n = 0; n < C::kKDmas / 2; ++n)
+            dma16_between(Qd, lds0 + q_stage + n * C::kKPieceBytes, q_voff,
+                          (half * (C::kKDmas / 2) + n) * PR * q_row_bytes);
+    }
     dma_k(0, 0);
     dma_k(1, 1);
     dma_v(0, 0);
@@ -324,6 +354,18 @@ attn_fwd_kernel(const FwdArgs a)
                 rc[ks][j] = *(const f32x4 *)(a.rope_cos + pos + 16 * ks + 8 * h + 4 * j);
                 rs[ks][j] = *(const f32x4 *)(a.rope_sin + pos + 16 * ks + 8 * h + 4 * j);
             }
+    }
+    if constexpr (NW == 8) {
+        // the wave's own query rows have landed once at most the later transfers (K(0), K(1),
+        // V(0)) are outstanding; with the rotary table rows in flight as well, whose place in the
+        // order of issue is the compiler's choice, everything is awaited
+        if (a.rope_cos) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * C::kKDmaPerWave) : "memory");
+        const char *Qs = smem + q_stage + ((r / PR) * C::kKPieceBytes + (h * PR + r % PR) * 16);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const elem8 *)(Qs + ks * (C::kKStep * 2));
+        // ... and are in registers before anybody may overwrite the staging space
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     }
     if (a.rope_cos) {
         elem *qr = a.Qrot ? a.Qrot + base + (int64_t)qc * a.stride_s : nullptr;
