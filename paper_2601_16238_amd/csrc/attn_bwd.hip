@@ -438,7 +438,13 @@ struct DqCfg {
     }
     static constexpr int kTensorBytes = piece_base(kPieces);     // K part of a tile; V follows
     static constexpr int kTileBytes = 2 * kTensorBytes;
-    static constexpr int kLdsBytes = kRing * kTileBytes;
+    // D <= 128: the rows of Q, dO and O reach the fragment registers through a per-wave staging
+    // area of 32 rows in the tile tensors' layout (see the kernel's prologue).  The areas start
+    // at ring position 2, which is free until the first barrier of the key loop.
+    static constexpr bool kStageRows = D <= 128;
+    static constexpr int kStageBytes = kStageRows ? piece_base(32 / kPieceRows) : 0;
+    static constexpr int kLdsBytes = kRing * kTileBytes > 2 * kTileBytes + NW * kStageBytes
+                                         ? kRing * kTileBytes : 2 * kTileBytes + NW * kStageBytes;
     static constexpr int kDmaPerTile = 2 * kPieces;           // wave-wide 1 KB transfers
     static constexpr int kDmaPerWave = (kDmaPerTile + NW - 1) / NW;
     static constexpr int kChunkStep = kPieceRows * 16;        // next 16-byte chunk of a row
@@ -525,11 +531,49 @@ attn_bwd_dq_kernel(const BwdArgs a)
     if (n_kt > 0) dma_tile(0, 0, Kd0, Vd0);
     if (n_kt > 1) dma_tile(1, 1, Kd0, Vd0);
 
-    elem8 qf[KS], gf[KS];
+    // Q and dO fragments (B operands: lane holds row q, columns 16 ks + 8 h .. +7) and, in a full
+    // backward, the O rows for the row statistics.  A load in which every lane fetches 16 bytes
+    // of its own row touches 32 rows per instruction, and a work-group issues 192 of them here:
+    // measured in the forward, 64 such loads alone took the last wave 5000-7000 cycles to get
+    // issued, with the compute unit idle.  At D <= 128 the rows are therefore fetched whole (an
+    // instruction covers 64 / (D/8) consecutive rows), all in flight together, and sorted into
+    // the fragment layout through the wave's staging area in LDS, one tensor after the other.
+    elem8 qf[KS], gf[KS], of[KS];
+    if constexpr (C::kStageRows) {
+        constexpr int CPR = D / 8, RPI = 64 / CPR;  // chunks per row; rows per load instruction
+        const int lr = l / CPR, lc = l % CPR;
+        u32x4 tq[KS], tg[KS], to[KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        qf[ks] = as_elem8(ld_row16(a.Q + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
-        gf[ks] = as_elem8(ld_row16(a.dO + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
+        for (int j = 0; j < KS; ++j) {
+            const int64_t off = base + (int64_t)min(q0 + RPI * j + lr, S - 1) * a.stride_s;
+            tq[j] = ld_row16(a.Q + off, lc * 8, Dr);
+            tg[j] = ld_row16(a.dO + off, lc * 8, Dr);
+            if (a.stats_in_dq) to[j] = ld_row16(a.O + off, lc * 8, Dr);
+        }
+        char *stage = smem + 2 * C::kTileBytes + w * C::kStageBytes;
+        const int rd = at(r, h);  // chunk h of row r; contraction step ks: 2 ks chunks further
+        auto sort_rows = [&](const u32x4 (&t)[KS], elem8 (&f)[KS]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int j = 0; j < KS; ++j) *(u32x4 *)(stage + at(RPI * j + lr, lc)) = t[j];
+            asm volatile("" ::: "memory");  // a wave's LDS accesses execute in order
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) f[ks] = *(const elem8 *)(stage + rd + ks * 2 * C::kChunkStep);
+            asm volatile("" ::: "memory");
+        };
+        sort_rows(tq, qf);
+        sort_rows(tg, gf);
+        if (a.stats_in_dq) sort_rows(to, of);
+    } else {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            qf[ks] = as_elem8(ld_row16(a.Q + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
+            gf[ks] = as_elem8(ld_row16(a.dO + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
+        }
+        if (a.stats_in_dq) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                of[ks] = as_elem8(ld_row16(a.O + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
+        }
     }
     // Row statistics of this lane's query: lse2 = LSE * log2(e) and -delta = -rowsum(dO * O).
     // In a full backward this kernel runs first and forms them itself (the dO row is in
@@ -540,9 +584,8 @@ attn_bwd_dq_kernel(const BwdArgs a)
         float acc = 0.f;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const elem8 of = as_elem8(ld_row16(a.O + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
 #pragma unroll
-            for (int t = 0; t < 8; ++t) acc += (float)of[t] * (float)gf[ks][t];
+            for (int t = 0; t < 8; ++t) acc += (float)of[ks][t] * (float)gf[ks][t];
         }
         ndelta = -xhalf_sum(acc);
         lse2 = a.LSE[(int64_t)bh * S + qc] * kLog2e;
