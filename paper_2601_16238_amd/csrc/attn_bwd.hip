@@ -204,11 +204,41 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
 
     if (producer) {
         // K and V fragments (B operands): lane holds K[key][16ks + 8h .. +7].
+        // At D <= 128 the 32 rows are fetched whole (an instruction covers 64 / (D/8) consecutive
+        // rows instead of 16 bytes of each of 32) and sorted into the fragment layout through LDS:
+        // the producer's own two slices of the exchange buffer (2 x 4 KB, nobody else touches
+        // them) take rows 0-15 and 16-31, chunks XOR-swizzled by the row like the slots.
         elem8 kf[KS], vf[KS];
+        if constexpr (D <= 128) {
+            constexpr int RPI = 64 / CPR;  // rows per load instruction
+            const int lr = l / CPR, lc = l % CPR;
+            u32x4 tk[KS], tv[KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            kf[ks] = as_elem8(ld_row16(a.K + base_kv + (int64_t)keyc * a.kv_stride_s, ks * 16 + 8 * h, Dr));
-            vf[ks] = as_elem8(ld_row16(a.V + base_kv + (int64_t)keyc * a.kv_stride_s, ks * 16 + 8 * h, Dr));
+            for (int j = 0; j < KS; ++j) {
+                const int64_t off = base_kv + (int64_t)min(k0 + RPI * j + lr, Sk - 1) * a.kv_stride_s;
+                tk[j] = ld_row16(a.K + off, lc * 8, Dr);
+                tv[j] = ld_row16(a.V + off, lc * 8, Dr);
+            }
+            char *const mine = smem + C::kOffXchg + pair * 4096;
+            auto slot_of = [&](int row, int chunk) {  // byte offset of a chunk of a staged row
+                return (row >> 4) * (C::kPairs * 4096) + (row & 15) * RB + ((chunk ^ swz(row & 15)) << 4);
+            };
+            auto sort_rows = [&](const u32x4 (&t)[KS], elem8 (&f)[KS]) __attribute__((always_inline)) {
+#pragma unroll
+                for (int j = 0; j < KS; ++j) *(u32x4 *)(mine + slot_of(RPI * j + lr, lc)) = t[j];
+                asm volatile("" ::: "memory");  // a wave's LDS accesses execute in order
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) f[ks] = *(const elem8 *)(mine + slot_of(r, 2 * ks + h));
+                asm volatile("" ::: "memory");
+            };
+            sort_rows(tk, kf);
+            sort_rows(tv, vf);
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                kf[ks] = as_elem8(ld_row16(a.K + base_kv + (int64_t)keyc * a.kv_stride_s, ks * 16 + 8 * h, Dr));
+                vf[ks] = as_elem8(ld_row16(a.V + base_kv + (int64_t)keyc * a.kv_stride_s, ks * 16 + 8 * h, Dr));
+            }
         }
         // make sure no register load is counted among the streamed transfers any more
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
