@@ -204,12 +204,14 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
 
     if (producer) {
         // K and V fragments (B operands): lane holds K[key][16ks + 8h .. +7].
-        // At D <= 128 the 32 rows are fetched whole (an instruction covers 64 / (D/8) consecutive
-        // rows instead of 16 bytes of each of 32) and sorted into the fragment layout through LDS:
-        // the producer's own two slices of the exchange buffer (2 x 4 KB, nobody else touches
-        // them) take rows 0-15 and 16-31, chunks XOR-swizzled by the row like the slots.
+        // The 32 rows are fetched whole (an instruction covers 64 / (D/8) consecutive rows instead
+        // of 16 bytes of each of 32) and sorted into the fragment layout through LDS that nobody
+        // else touches before the first barrier of the slot loop: at D <= 128 the producer's own
+        // two slices of the exchange buffer (2 x 4 KB: rows 0-15 and 16-31), at D = 256 (two
+        // producers, 16 KB each) the two tensors of the first ring slot that no transfer has been
+        // issued for; chunks XOR-swizzled by the row like the slots.
         elem8 kf[KS], vf[KS];
-        if constexpr (D <= 128) {
+        {
             constexpr int RPI = 64 / CPR;  // rows per load instruction
             const int lr = l / CPR, lc = l % CPR;
             u32x4 tk[KS], tv[KS];
@@ -219,9 +221,12 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
                 tk[j] = ld_row16(a.K + off, lc * 8, Dr);
                 tv[j] = ld_row16(a.V + off, lc * 8, Dr);
             }
-            char *const mine = smem + C::kOffXchg + pair * 4096;
+            static_assert(D <= 128 || C::kPairs <= 2, "staging space of the producers");
+            char *const mine = D <= 128 ? smem + C::kOffXchg + pair * 4096
+                                        : smem + C::kAhead * C::kSlotBytes + pair * C::kTensorBytes;
             auto slot_of = [&](int row, int chunk) {  // byte offset of a chunk of a staged row
-                return (row >> 4) * (C::kPairs * 4096) + (row & 15) * RB + ((chunk ^ swz(row & 15)) << 4);
+                return D <= 128 ? (row >> 4) * (C::kPairs * 4096) + (row & 15) * RB + ((chunk ^ swz(row & 15)) << 4)
+                                : row * RB + ((chunk ^ swz(row)) << 4);
             };
             auto sort_rows = [&](const u32x4 (&t)[KS], elem8 (&f)[KS]) __attribute__((always_inline)) {
 #pragma unroll
@@ -233,12 +238,6 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
             };
             sort_rows(tk, kf);
             sort_rows(tv, vf);
-        } else {
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                kf[ks] = as_elem8(ld_row16(a.K + base_kv + (int64_t)keyc * a.kv_stride_s, ks * 16 + 8 * h, Dr));
-                vf[ks] = as_elem8(ld_row16(a.V + base_kv + (int64_t)keyc * a.kv_stride_s, ks * 16 + 8 * h, Dr));
-            }
         }
         // make sure no register load is counted among the streamed transfers any more
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -471,7 +470,7 @@ struct DqCfg {
     // D <= 128: the rows of Q, dO and O reach the fragment registers through a per-wave staging
     // area of 32 rows in the tile tensors' layout (see the kernel's prologue).  The areas start
     // at ring position 2, which is free until the first barrier of the key loop.
-    static constexpr bool kStageRows = D <= 128;
+    static constexpr bool kStageRows = true;
     static constexpr int kStageBytes = kStageRows ? piece_base(32 / kPieceRows) : 0;
     static constexpr int kLdsBytes = kRing * kTileBytes > 2 * kTileBytes + NW * kStageBytes
                                          ? kRing * kTileBytes : 2 * kTileBytes + NW * kStageBytes;

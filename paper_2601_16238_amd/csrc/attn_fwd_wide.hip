@@ -96,11 +96,17 @@ attn_fwd_wide_kernel(const FwdArgs a)
     const int qc = q < S ? q : S - 1;  // clamped for loads; rows >= S are never stored
     const int q0e = q0 + coff;         // the wave's first row in key coordinates
 
-    // Q fragments, B operand of K Q^T: lane holds Q[q][16 ks + 8 h .. +7]
+    // Q fragments, B operand of K Q^T: lane holds Q[q][16 ks + 8 h .. +7].  At D = 256 they come
+    // through LDS (further down, where the transfers are set up): sixteen loads per wave in
+    // which every lane fetches 16 bytes of its own row touch 32 rows per instruction and keep
+    // the work-group's last wave from even issuing its K and V transfers for thousands of cycles.
+    constexpr bool kStageQ = D > 128;
     elem8 qf[KS];
+    if constexpr (!kStageQ) {
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-        qf[ks] = as_elem8(ld_row16(a.Q + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
+        for (int ks = 0; ks < KS; ++ks)
+            qf[ks] = as_elem8(ld_row16(a.Q + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
+    }
 
     // Rotary embedding of the query rows, fused into their load (D <= 128, head dimension == D):
     // column d pairs with d + D/2, i.e. fragment ks with ks + KS/2, element by element, in this
@@ -311,9 +317,38 @@ attn_fwd_wide_kernel(const FwdArgs a)
     };
     auto overflow = [&](float psum) { return __builtin_amdgcn_ballot_w64(psum > kWideOverflow) != 0; };
 
+    // D = 256: the wave's 32 query rows as half of a K-layout tile, by the same direct transfers
+    // (whole rows, two per instruction), into the second buffer pair, which takes tile 1 only
+    // after the first barrier: waves 0 and 1 into the K buffer, 2 and 3 into the V buffer.  Rows
+    // past S-1 and columns Dr..D-1 read as zero.
+    uint32_t q_stage = 0;
+    if constexpr (kStageQ) {
+        const int pair = w >> 1, half = w & 1;
+        q_stage = (pair == 0 ? C::kKTileBytes : C::kOffV + C::kVTileBytes) + half * C::kKHalfBytes;
+        const int row0 = qt * C::kBR + pair * 64;
+        const int rows = min(64, S - row0);
+        const uint32_t q_bytes = rows > 0 ? (uint32_t)(((int64_t)(rows - 1) * a.stride_s + Dr) * 2) : 0u;
+        const desc_t Qd = make_desc(a.Q + base + (int64_t)(rows > 0 ? row0 : 0) * a.stride_s, q_bytes);
+        const uint32_t q_row_bytes = (uint32_t)a.stride_s * 2u;
+        const uint32_t q_voff = (l / PR) * 8 < Dr ? (l % PR) * q_row_bytes + ((l / PR) << 4) : q_bytes;
+#pragma unroll
+        for (int n = 0; n < C::kKPieces / 2; ++n)
+            dma16_between(Qd, lds0 + q_stage + n * C::kKPieceBytes, q_voff,
+                          (half * (C::kKPieces / 2) + n) * PR * q_row_bytes);
+    }
     if (n_kt > 0) {
         dma_k(0, 0);
         dma_v(0, 0);
+    }
+    if constexpr (kStageQ) {
+        // the query rows have landed once at most the transfers of K(0) and V(0) are outstanding
+        if (n_kt > 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * C::kKDmaPerWave) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const char *Qs = smem + q_stage + ((r / PR) * C::kKPieceBytes + (h * PR + r % PR) * 16);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = *(const elem8 *)(Qs + ks * C::kKStepBytes);
+        // ... and are in registers before anybody may overwrite the staging space
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     }
     // Tiles of which this wave sees some key come first; for the rest of the work-group's tiles
     // (under a causal mask, the waves with the earlier rows) it only takes part in the staging.
