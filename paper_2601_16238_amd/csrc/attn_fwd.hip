@@ -583,7 +583,36 @@ attn_fwd_kernel(const FwdArgs a)
         return;
     }
     const float inv = 1.0f / lr;
-    if (q < S) {
+    if constexpr (NW == 8) {
+        // The accumulator holds 4 consecutive columns of one row per register group, so a direct
+        // store writes 16 bytes to each of 32 rows per instruction, sixteen times per wave.  The
+        // rows go through LDS instead and leave whole, 16 bytes per lane and four (D = 128) or
+        // eight rows per instruction: half as many stores, each over contiguous memory.  The
+        // wave's staging space (32 rows in the K tile's layout) lies in the K buffers and the
+        // query staging space, which nobody reads after the last tile barrier.
+        constexpr int CPR = D / 8, RPI = 64 / CPR;  // chunks per row; rows per store instruction
+        constexpr int kWaveBytes = C::kKHalf * 2;
+        char *stg = smem + (w < 6 ? w * kWaveBytes
+                                  : (3 * C::kKTile + 3 * C::kVTile) * 2 + (w - 6) * kWaveBytes);
+        auto at = [](int row, int chunk) {
+            return (row / PR) * C::kKPieceBytes + (chunk * PR + row % PR) * 16;
+        };
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                *(elem4 *)(stg + at(r, 4 * db + g) + 8 * h) =
+                    pack4(o[db][4 * g] * inv, o[db][4 * g + 1] * inv, o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
+        asm volatile("" ::: "memory");  // a wave's LDS accesses execute in order
+        const int lr = l / CPR, lc = l % CPR;
+#pragma unroll
+        for (int j = 0; j < 32 / RPI; ++j) {
+            const u32x4 v = *(const u32x4 *)(stg + at(RPI * j + lr, lc));
+            const int row = q0 + RPI * j + lr;
+            if (row < S && lc * 8 < Dr) *(u32x4 *)(a.O + base + (int64_t)row * a.stride_s + lc * 8) = v;
+        }
+        if (q < S && h == 0) a.LSE[(int64_t)bh * S + q] = (m + fast_log2(lt)) * kLn2;
+    } else if (q < S) {
         elem *Op = a.O + base + (int64_t)q * a.stride_s;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
