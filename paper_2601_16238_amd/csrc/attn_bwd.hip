@@ -405,21 +405,40 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
         wait_vm_and_barrier<0>();
         if (n_seq > 0) consume(tp, n_seq - 1, rs == 0 ? C::kRing - 1 : rs - 1);
 
+        // The accumulators hold 4 consecutive columns of one key per register group: stored
+        // directly, every instruction writes 8-byte pieces of 32 rows (32 such stores per wave).
+        // The rows of a key block go through LDS instead and leave whole, 16 bytes per lane: each
+        // consumer takes one tensor's worth of a ring slot other than the last one, which other
+        // consumers may still be reading (the producers have issued their last transfer and all
+        // of them have landed), in the slots' swizzled row layout.
         elem *const out = kind ? a.dK : a.dV;
         const float sc = kind ? a.scale : 1.f;
+        {
+            constexpr int RPI = 64 / CPR;  // rows per store instruction
+            const int last = rs == 0 ? C::kRing - 1 : rs - 1;  // ring position of the last slot
+            int slot = cw >> 1;
+            slot += slot >= last ? 1 : 0;
+            char *stg = smem + slot * C::kSlotBytes + (cw & 1) * C::kTensorBytes;
+            const int lr = l / CPR, lc = l % CPR;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            const int okey = kA + 32 * kb + r;
-            if (okey < Sk) {
-                elem *op = out + base_kv + (int64_t)okey * a.kv_stride_s;
+            for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
                     for (int g = 0; g < 4; ++g)
-                        if (32 * db + 8 * g + 4 * h < Dr)
-                            *(elem4 *)(op + 32 * db + 8 * g + 4 * h) =
-                                pack4(acc[kb][db][4 * g] * sc, acc[kb][db][4 * g + 1] * sc,
-                                      acc[kb][db][4 * g + 2] * sc, acc[kb][db][4 * g + 3] * sc);
+                        *(elem4 *)(stg + r * RB + (((4 * db + g) ^ swz(r)) << 4) + 8 * h) =
+                            pack4(acc[kb][db][4 * g] * sc, acc[kb][db][4 * g + 1] * sc,
+                                  acc[kb][db][4 * g + 2] * sc, acc[kb][db][4 * g + 3] * sc);
+                asm volatile("" ::: "memory");  // a wave's LDS accesses execute in order
+#pragma unroll
+                for (int j = 0; j < 32 / RPI; ++j) {
+                    const int row = RPI * j + lr;
+                    const u32x4 v = *(const u32x4 *)(stg + row * RB + ((lc ^ swz(row)) << 4));
+                    const int okey = kA + 32 * kb + row;
+                    if (okey < Sk && lc * 8 < Dr)
+                        *(u32x4 *)(out + base_kv + (int64_t)okey * a.kv_stride_s + lc * 8) = v;
+                }
+                asm volatile("" ::: "memory");
             }
         }
     }
@@ -807,17 +826,31 @@ attn_bwd_dq_kernel(const BwdArgs a)
                 }
             }
     }
-    if (q < S) {
-        elem *dQp = a.dQ + base + (int64_t)q * a.stride_s;
+    {
+        // The accumulator holds 4 consecutive columns of one row per register group: stored
+        // directly, every instruction writes 8-byte pieces of 32 rows.  The rows go through the
+        // wave's staging area in LDS instead and leave whole, 16 bytes per lane.  The areas that
+        // lie in ring position 2 move to the position that the last two tiles did not use (other
+        // waves may still be reading those).
+        constexpr int CPR = D / 8, RPI = 64 / CPR;  // chunks per row; rows per store instruction
+        char *stg = smem + ((w + 1) * C::kStageBytes <= C::kTileBytes
+                                ? (n_kt % 3) * C::kTileBytes + w * C::kStageBytes
+                                : 2 * C::kTileBytes + w * C::kStageBytes);
         const float sc = a.scale;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int g = 0; g < 4; ++g)
-                if (32 * db + 8 * g + 4 * h < Dr)
-                    *(elem4 *)(dQp + 32 * db + 8 * g + 4 * h) =
-                        pack4(dq[db][4 * g] * sc, dq[db][4 * g + 1] * sc,
-                              dq[db][4 * g + 2] * sc, dq[db][4 * g + 3] * sc);
+                *(elem4 *)(stg + at(r, 4 * db + g) + 8 * h) =
+                    pack4(dq[db][4 * g] * sc, dq[db][4 * g + 1] * sc, dq[db][4 * g + 2] * sc, dq[db][4 * g + 3] * sc);
+        asm volatile("" ::: "memory");  // a wave's LDS accesses execute in order
+        const int lr = l / CPR, lc = l % CPR;
+#pragma unroll
+        for (int j = 0; j < 32 / RPI; ++j) {
+            const u32x4 v = *(const u32x4 *)(stg + at(RPI * j + lr, lc));
+            const int row = q0 + RPI * j + lr;
+            if (row < S && lc * 8 < Dr) *(u32x4 *)(a.dQ + base + (int64_t)row * a.stride_s + lc * 8) = v;
+        }
     }
 }
 
