@@ -790,19 +790,37 @@ attn_bwd_dq_kernel(const BwdArgs a)
     // no transfer may still be in flight when the work-group's LDS is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
+    // Output rows leave through the wave's staging area in LDS (see the end of the kernel).  The
+    // areas that lie in ring position 2 move to the position that the last two tiles did not use
+    // (other waves may still be reading those).
+    constexpr int CPR = D / 8, RPI = 64 / CPR;  // chunks per bf16 row; rows per store instruction
+    char *const stg = smem + ((w + 1) * C::kStageBytes <= C::kTileBytes
+                                  ? (n_kt % 3) * C::kTileBytes + w * C::kStageBytes
+                                  : 2 * C::kTileBytes + w * C::kStageBytes);
+    const int lr = l / CPR, lc = l % CPR;
     if (SPLIT) {
-        // unscaled fp32 partial of this key range (zeros if the range had no visible key)
-        if (q < S) {
-            float *dp = a.dQpart + (((int64_t)blockIdx.y * a.BH + bh) * S + q) * D;
+        // unscaled fp32 partial of this key range (zeros if the range had no visible key); an
+        // fp32 row is twice as long as the staging area's, so it goes in two halves
+        const int64_t row0 = ((int64_t)blockIdx.y * a.BH + bh) * S;
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+        for (int hp = 0; hp < 2; ++hp) {
+#pragma unroll
+            for (int db = hp * (DB / 2); db < (hp + 1) * (DB / 2); ++db)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     f32x4 v;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = dq[db][4 * g + e];
-                    *(f32x4 *)(dp + 32 * db + 8 * g + 4 * h) = v;
+                    *(f32x4 *)(stg + at(r, (db % (DB / 2)) * 8 + 2 * g + h)) = v;
                 }
+            asm volatile("" ::: "memory");  // a wave's LDS accesses execute in order
+#pragma unroll
+            for (int j = 0; j < 32 / RPI; ++j) {
+                const f32x4 v = *(const f32x4 *)(stg + at(RPI * j + lr, lc));
+                const int row = q0 + RPI * j + lr;
+                if (row < S) *(f32x4 *)(a.dQpart + (row0 + row) * D + hp * (D / 2) + lc * 4) = v;
+            }
+            asm volatile("" ::: "memory");
         }
         return;
     }
@@ -832,10 +850,6 @@ attn_bwd_dq_kernel(const BwdArgs a)
         // wave's staging area in LDS instead and leave whole, 16 bytes per lane.  The areas that
         // lie in ring position 2 move to the position that the last two tiles did not use (other
         // waves may still be reading those).
-        constexpr int CPR = D / 8, RPI = 64 / CPR;  // chunks per row; rows per store instruction
-        char *stg = smem + ((w + 1) * C::kStageBytes <= C::kTileBytes
-                                ? (n_kt % 3) * C::kTileBytes + w * C::kStageBytes
-                                : 2 * C::kTileBytes + w * C::kStageBytes);
         const float sc = a.scale;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
@@ -844,7 +858,6 @@ attn_bwd_dq_kernel(const BwdArgs a)
                 *(elem4 *)(stg + at(r, 4 * db + g) + 8 * h) =
                     pack4(dq[db][4 * g] * sc, dq[db][4 * g + 1] * sc, dq[db][4 * g + 2] * sc, dq[db][4 * g + 3] * sc);
         asm volatile("" ::: "memory");  // a wave's LDS accesses execute in order
-        const int lr = l / CPR, lc = l % CPR;
 #pragma unroll
         for (int j = 0; j < 32 / RPI; ++j) {
             const u32x4 v = *(const u32x4 *)(stg + at(RPI * j + lr, lc));

@@ -562,13 +562,50 @@ attn_fwd_kernel(const FwdArgs a)
     // Epilogue: O = O_acc / l, LSE = ln2 * (m + log2 l).
     const float lt = xhalf_sum(lsum);
     const float lr = xhalf_sum(hsum);  // sum of the rounded probabilities
+    // Eight waves.  The accumulator holds 4 consecutive columns of one row per register group, so
+    // a direct store writes 16 bytes to each of 32 rows per instruction, sixteen times per wave.
+    // The rows go through LDS instead and leave whole, 16 bytes per lane and four (D = 128) or
+    // eight rows per instruction: half as many stores, each over contiguous memory.  The wave's
+    // staging space (32 rows in the K tile's layout) lies in the K buffers and the query staging
+    // space, which nobody reads after the last tile barrier.
+    constexpr int kWaveBytes = C::kKHalf * 2;
+    char *const stg = smem + (NW != 8 ? 0 : w < 6 ? w * kWaveBytes
+                                                  : (3 * C::kKTile + 3 * C::kVTile) * 2 + (w - 6) * kWaveBytes);
+    auto at = [](int row, int chunk) {
+        return (row / PR) * C::kKPieceBytes + (chunk * PR + row % PR) * 16;
+    };
     if (SPLIT) {
         // normalised fp32 partial result of this key range; a row that saw no key of the
         // range contributes O = 0 with LSE = -inf
         const float inv = lr > 0.f ? 1.0f / lr : 0.f;
-        if (q < S) {
-            const int64_t row = ((int64_t)blockIdx.y * a.BH + bh) * S + q;
-            float *Op = a.Opart + row * D;
+        const int64_t row0 = ((int64_t)blockIdx.y * a.BH + bh) * S;
+        if constexpr (NW == 8) {
+            // through LDS like O below; an fp32 row is twice as long, so it goes in two halves
+            constexpr int CPR = D / 8, RPI = 64 / CPR;
+            const int lr_ = l / CPR, lc = l % CPR;
+#pragma unroll
+            for (int hp = 0; hp < 2; ++hp) {
+#pragma unroll
+                for (int db = hp * (DB / 2); db < (hp + 1) * (DB / 2); ++db)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        f32x4 ov;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) ov[e] = o[db][4 * g + e] * inv;
+                        *(f32x4 *)(stg + at(r, (db % (DB / 2)) * 8 + 2 * g + h)) = ov;
+                    }
+                asm volatile("" ::: "memory");  // a wave's LDS accesses execute in order
+#pragma unroll
+                for (int j = 0; j < 32 / RPI; ++j) {
+                    const f32x4 v = *(const f32x4 *)(stg + at(RPI * j + lr_, lc));
+                    const int row = q0 + RPI * j + lr_;
+                    if (row < S) *(f32x4 *)(a.Opart + (row0 + row) * D + hp * (D / 2) + lc * 4) = v;
+                }
+                asm volatile("" ::: "memory");
+            }
+            if (q < S && h == 0) a.LSEpart[row0 + q] = lt > 0.f ? (m + fast_log2(lt)) * kLn2 : -INFINITY;
+        } else if (q < S) {
+            float *Op = a.Opart + (row0 + q) * D;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -578,25 +615,13 @@ attn_fwd_kernel(const FwdArgs a)
                     for (int e = 0; e < 4; ++e) ov[e] = o[db][4 * g + e] * inv;
                     *(f32x4 *)(Op + 32 * db + 8 * g + 4 * h) = ov;
                 }
-            if (h == 0) a.LSEpart[row] = lt > 0.f ? (m + fast_log2(lt)) * kLn2 : -INFINITY;
+            if (h == 0) a.LSEpart[row0 + q] = lt > 0.f ? (m + fast_log2(lt)) * kLn2 : -INFINITY;
         }
         return;
     }
     const float inv = 1.0f / lr;
     if constexpr (NW == 8) {
-        // The accumulator holds 4 consecutive columns of one row per register group, so a direct
-        // store writes 16 bytes to each of 32 rows per instruction, sixteen times per wave.  The
-        // rows go through LDS instead and leave whole, 16 bytes per lane and four (D = 128) or
-        // eight rows per instruction: half as many stores, each over contiguous memory.  The
-        // wave's staging space (32 rows in the K tile's layout) lies in the K buffers and the
-        // query staging space, which nobody reads after the last tile barrier.
         constexpr int CPR = D / 8, RPI = 64 / CPR;  // chunks per row; rows per store instruction
-        constexpr int kWaveBytes = C::kKHalf * 2;
-        char *stg = smem + (w < 6 ? w * kWaveBytes
-                                  : (3 * C::kKTile + 3 * C::kVTile) * 2 + (w - 6) * kWaveBytes);
-        auto at = [](int row, int chunk) {
-            return (row / PR) * C::kKPieceBytes + (chunk * PR + row % PR) * 16;
-        };
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
