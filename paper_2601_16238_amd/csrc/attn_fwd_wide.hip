@@ -436,17 +436,34 @@ attn_fwd_wide_kernel(const FwdArgs a)
         return;
     }
     const float inv = 1.0f / lr;
-    if (q < S) {
-        elem *Op = a.O + base + (int64_t)q * a.stride_s;
+    {
+        // The accumulator holds 4 consecutive columns of one row per register group: stored
+        // directly, every instruction writes 8-byte pieces of 32 rows.  The rows go through LDS
+        // instead and leave whole, 16 bytes per lane: the wave's 32 rows as half of a K-layout
+        // tile in the buffer pair that the last tile did not use (other waves may still be
+        // reading that one), waves 0 and 1 in its K buffer, 2 and 3 in its V buffer.
+        constexpr int CPR = D / 8, RPI = 64 / CPR;  // chunks per row; rows per store instruction
+        const int b = n_kt & 1;
+        char *stg = smem + ((w >> 1) == 0 ? b * C::kKTileBytes : C::kOffV + b * C::kVTileBytes) +
+                    (w & 1) * C::kKHalfBytes;
+        auto at = [](int row, int chunk) {
+            return (row / PR) * C::kKPieceBytes + (chunk * PR + row % PR) * 16;
+        };
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const elem4 ov = pack4(o[db][4 * g] * inv, o[db][4 * g + 1] * inv,
-                                        o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
-                if (32 * db + 8 * g + 4 * h < Dr) *(elem4 *)(Op + 32 * db + 8 * g + 4 * h) = ov;
-            }
-        if (h == 0) a.LSE[(int64_t)bh * S + q] = (m + fast_log2(lt)) * kLn2;
+            for (int g = 0; g < 4; ++g)
+                *(elem4 *)(stg + at(r, 4 * db + g) + 8 * h) =
+                    pack4(o[db][4 * g] * inv, o[db][4 * g + 1] * inv, o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
+        asm volatile("" ::: "memory");  // a wave's LDS accesses execute in order
+        const int lr_ = l / CPR, lc = l % CPR;
+#pragma unroll
+        for (int j = 0; j < 32 / RPI; ++j) {
+            const u32x4 v = *(const u32x4 *)(stg + at(RPI * j + lr_, lc));
+            const int row = q0 + RPI * j + lr_;
+            if (row < S && lc * 8 < Dr) *(u32x4 *)(a.O + base + (int64_t)row * a.stride_s + lc * 8) = v;
+        }
+        if (q < S && h == 0) a.LSE[(int64_t)bh * S + q] = (m + fast_log2(lt)) * kLn2;
     }
 }
 
