@@ -203,6 +203,25 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     elem8 *const Xs = reinterpret_cast<elem8 *>(smem + C::kOffXchg) + pair * 256 + l;
 
     if (producer) {
+        // The slots of the group's query heads form ONE sequence (head after head, slots t0 ..
+        // n_slot-1 of each), so that the ring stays full across the change of head: the
+        // transfers run kAhead slots in front and switch to the next head's rows on their own.
+        // The first kAhead slots are requested before anything else, so that their way from memory
+        // overlaps the fetch of the K and V rows below.
+        int tf = t0, gqf = 0;  // slot and head of the next transfer
+        set_head(bh0);
+        auto advance_fetch = [&]() __attribute__((always_inline)) {
+            ++tf;  // past the last head: rows beyond S, which read as zero
+            if (tf == n_slot && gqf + 1 < a.group) {
+                tf = t0;
+                set_head(bh0 + ++gqf);
+            }
+        };
+#pragma unroll
+        for (int i = 0; i < C::kAhead; ++i) {
+            dma_slot(tf, i);
+            advance_fetch();
+        }
         // K and V fragments (B operands): lane holds K[key][16ks + 8h .. +7].
         // The 32 rows are fetched whole (an instruction covers 64 / (D/8) consecutive rows instead
         // of 16 bytes of each of 32) and sorted into the fragment layout through LDS that nobody
@@ -244,23 +263,6 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
         const float c = a.scale_log2e;
         const int lane_off = r * RB + ((h ^ swz(r)) << 4);  // chunk 2ks+h of row r: ^ (ks*32)
 
-        // The slots of the group's query heads form ONE sequence (head after head, slots t0 ..
-        // n_slot-1 of each), so that the ring stays full across the change of head: the
-        // transfers run kAhead slots in front and switch to the next head's rows on their own.
-        int tf = t0, gqf = 0;  // slot and head of the next transfer
-        set_head(bh0);
-        auto advance_fetch = [&]() __attribute__((always_inline)) {
-            ++tf;  // past the last head: rows beyond S, which read as zero
-            if (tf == n_slot && gqf + 1 < a.group) {
-                tf = t0;
-                set_head(bh0 + ++gqf);
-            }
-        };
-#pragma unroll
-        for (int i = 0; i < C::kAhead; ++i) {
-            dma_slot(tf, i);
-            advance_fetch();
-        }
         int rs = 0;  // ring position of the current slot
         int t = t0;  // its rows: slot t of the current head
         for (int g = 0; g < n_seq; ++g) {

@@ -233,21 +233,25 @@ __device__ __forceinline__ int xcd_contiguous_order(int id, int total)
 // (B=8 H=8 S=1024 backward, two rounds: 66 us against 74 us with groups of four).
 // Falls back to the contiguous order when the heads do not divide evenly over the XCDs.
 template <bool CAUSAL>
-__device__ __forceinline__ void xcd_tile_order(int id, int ntile, int BH, int &bh, int &rank)
+__device__ __forceinline__ void xcd_tile_order(int id_, int ntile_, int BH_, int &bh, int &rank)
 {
-    constexpr int kXcd = 8, kCuPerXcd = 32;
+    // (unsigned throughout: nothing here is negative, and an unsigned division by a run-time
+    // value is a third shorter than a signed one)
+    constexpr unsigned kXcd = 8, kCuPerXcd = 32;
+    const unsigned id = id_, ntile = ntile_, BH = BH_;
     if (BH % kXcd == 0) {
-        const int hpx = BH / kXcd, x = id % kXcd, pos = id / kXcd;
-        int G = 1;  // heads per group
-        if (CAUSAL) G = hpx * ntile >= 4 * kCuPerXcd ? max(4, (kCuPerXcd + ntile - 1) / ntile) : hpx;
-        const int group = pos / (G * ntile), within = pos - group * (G * ntile);
-        const int heads = min(G, hpx - group * G);  // the last group may be smaller
-        rank = within / heads;
-        bh = x * hpx + group * G + within % heads;
+        const unsigned hpx = BH / kXcd, x = id % kXcd, pos = id / kXcd;
+        unsigned G = 1;  // heads per group
+        if (CAUSAL) G = hpx * ntile >= 4 * kCuPerXcd ? max(4u, (kCuPerXcd + ntile - 1) / ntile) : hpx;
+        const unsigned group = pos / (G * ntile), within = pos - group * (G * ntile);
+        const unsigned heads = min(G, hpx - group * G);  // the last group may be smaller
+        const unsigned rk = within / heads;
+        rank = (int)rk;
+        bh = (int)(x * hpx + group * G + (within - rk * heads));
     } else {
-        const int v = xcd_contiguous_order(id, ntile * BH);
-        bh = v / ntile;
-        rank = v % ntile;
+        const unsigned v = (unsigned)xcd_contiguous_order(id_, ntile_ * BH_);
+        bh = (int)(v / ntile);
+        rank = (int)(v - (v / ntile) * ntile);
     }
 }
 
