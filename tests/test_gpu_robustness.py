@@ -52,11 +52,12 @@ def test_poisoned_outputs_and_workspace_repeat_bit_identical(B, H, S, D, causal)
         check_bf16(nm, to_f64(t), r)
 
 
-def test_bshd_strides_and_side_stream():
+@pytest.mark.parametrize("B,H,S,D,causal", [(2, 3, 200, 64, True), (1, 3, 333, 128, True), (1, 2, 300, 256, False)])
+def test_bshd_strides_and_side_stream(B, H, S, D, causal):
     """[B,S,H,D] storage viewed as [B,H,S,D] (stride_h = D, stride_s = H*D), launched on a
-    non-default stream."""
-    print("case bshd_strides", flush=True)
-    B, H, S, D, causal = 2, 3, 200, 64, True
+    non-default stream.  (The second shape runs the eight-wave kernels, the third the D = 256
+    ones: their rows enter and leave through LDS in whole-row transfers, strided here.)"""
+    print("case bshd_strides", B, H, S, D, causal, flush=True)
     x = wl.random_inputs(B, H, S, D, seed=41)
 
     def bshd(bits):
