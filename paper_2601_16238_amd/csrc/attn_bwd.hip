@@ -159,7 +159,7 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     uint32_t dma_voff[C::kDmaPerWave];
 #pragma unroll
     for (int n = 0; n < C::kDmaPerWave; ++n) {
-        // (with a pair count that does not divide the pieces some are fetched twice)
+        // (with a pair count that does not divide the pieces the last index wraps; dma_piece skips it)
         const int grp = (pair + (n % (C::kDmaPerWave / 2)) * C::kPairs) % C::kDmaPerTensor;
         const int row = grp * (64 / CPR) + l / CPR;
         const int chunk = (l % CPR) ^ swz(row);
@@ -177,8 +177,12 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
                 Wr, (void __attribute__((address_space(3))) *)(smem + C::kOffStat + rs * C::kStatBytes),
                 4, (int)stat_voff, t * C::kRows * 4, 0, 0);
     };
+    // (With a pair count that does not divide the pieces of a tensor -- six pairs, eight pieces --
+    // the first producers take two pieces of each tensor and the others one: `extra`.)
+    const bool extra = pair + (C::kDmaPerWave / 2 - 1) * C::kPairs < C::kDmaPerTensor;
     auto dma_piece = [&](int t, int rs, int n) __attribute__((always_inline)) {
         const int tensor = n / (C::kDmaPerWave / 2);  // Q transfers first, then dO
+        if (C::kDmaPerTensor % C::kPairs != 0 && n % (C::kDmaPerWave / 2) == C::kDmaPerWave / 2 - 1 && !extra) return;
         const int grp = (pair + (n % (C::kDmaPerWave / 2)) * C::kPairs) % C::kDmaPerTensor;  // 1 KB piece
         const uint32_t dst = lds0 + rs * C::kSlotBytes + tensor * C::kTensorBytes + grp * 1024;
         dma16_between(tensor == 0 ? Qd : Gd, dst, dma_voff[n], (uint32_t)(t * C::kRows * row_bytes));
@@ -191,8 +195,15 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     // Before slot t is used: this wave's transfers of slot t must have landed (those of the
     // kAhead-1 newer slots may stay in flight) and everyone must be done with slot t-2.
     auto slot_barrier = [&]() {
-        if (w == C::kStatWave) wait_vm_and_barrier<(C::kAhead - 1) * (C::kDmaPerWave + 1)>();
-        else wait_vm_and_barrier<(C::kAhead - 1) * C::kDmaPerWave>();
+        if constexpr (C::kDmaPerTensor % C::kPairs != 0) {
+            // (the statistics wave is the last producer: never one with the extra pieces)
+            if (w == C::kStatWave) wait_vm_and_barrier<(C::kAhead - 1) * (C::kDmaPerWave - 2 + 1)>();
+            else if (extra) wait_vm_and_barrier<(C::kAhead - 1) * C::kDmaPerWave>();
+            else wait_vm_and_barrier<(C::kAhead - 1) * (C::kDmaPerWave - 2)>();
+        } else {
+            if (w == C::kStatWave) wait_vm_and_barrier<(C::kAhead - 1) * (C::kDmaPerWave + 1)>();
+            else wait_vm_and_barrier<(C::kAhead - 1) * C::kDmaPerWave>();
+        }
     };
     // wave-uniform: does slot t hold a real row that sees some key of the pair
     auto active = [&](int t) {
