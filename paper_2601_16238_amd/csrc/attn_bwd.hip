@@ -167,10 +167,12 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     }
     // stats: lanes 0-31 fetch lse2 (second half of the head's workspace), 32-63 delta
     const uint32_t stat_voff = (uint32_t)(h ? r : S + r) * 4u;
-    // The statistics first, then this wave's kDmaPerWave pieces of Q and dO.  The pieces fill a
-    // ring position that nobody reads before a later barrier, and the producers issue them one by
-    // one between their MFMAs instead of in a burst in front (D = 256, sixteen pieces per wave and
-    // slot: 1.46 -> 1.21 ms on B=4 H=16 S=4096; no difference with the four pieces of D = 128).
+    // The statistics of a slot are requested by one producer, its Q and dO pieces by the
+    // CONSUMERS, consumer c taking the pieces that pair c is assigned (they have no other vector
+    // memory traffic and are the shorter chain of a slot; with the producers issuing them between
+    // their MFMAs the kernel was 2-5 % slower), right after the slot barrier, into a ring position
+    // that nobody reads before a later barrier.  (Spread between the consumers' MFMAs instead they
+    // measured the same or up to 2.5 % slower.)
     auto dma_stat = [&](int t, int rs) __attribute__((always_inline)) {
         if (w == C::kStatWave)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
@@ -187,22 +189,32 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
         const uint32_t dst = lds0 + rs * C::kSlotBytes + tensor * C::kTensorBytes + grp * 1024;
         dma16_between(tensor == 0 ? Qd : Gd, dst, dma_voff[n], (uint32_t)(t * C::kRows * row_bytes));
     };
-    auto dma_slot = [&](int t, int rs) __attribute__((always_inline)) {
-        dma_stat(t, rs);
+    auto dma_pieces = [&](int t, int rs) __attribute__((always_inline)) {
 #pragma unroll
         for (int n = 0; n < C::kDmaPerWave; ++n) dma_piece(t, rs, n);
     };
     // Before slot t is used: this wave's transfers of slot t must have landed (those of the
     // kAhead-1 newer slots may stay in flight) and everyone must be done with slot t-2.
     auto slot_barrier = [&]() {
-        if constexpr (C::kDmaPerTensor % C::kPairs != 0) {
-            // (the statistics wave is the last producer: never one with the extra pieces)
-            if (w == C::kStatWave) wait_vm_and_barrier<(C::kAhead - 1) * (C::kDmaPerWave - 2 + 1)>();
-            else if (extra) wait_vm_and_barrier<(C::kAhead - 1) * C::kDmaPerWave>();
-            else wait_vm_and_barrier<(C::kAhead - 1) * (C::kDmaPerWave - 2)>();
+        if (producer) {
+            if (w == C::kStatWave) wait_vm_and_barrier<C::kAhead - 1>();
+            else wait_vm_and_barrier<0>();
+        } else if (C::kDmaPerTensor % C::kPairs != 0 && !extra) {
+            wait_vm_and_barrier<(C::kAhead - 1) * (C::kDmaPerWave - 2)>();
         } else {
-            if (w == C::kStatWave) wait_vm_and_barrier<(C::kAhead - 1) * (C::kDmaPerWave + 1)>();
-            else wait_vm_and_barrier<(C::kAhead - 1) * C::kDmaPerWave>();
+            wait_vm_and_barrier<(C::kAhead - 1) * C::kDmaPerWave>();
+        }
+    };
+    // slot and head of the next transfer (both roles keep count: the producers for the statistics,
+    // the consumers for the rows): the slots of the group's query heads form ONE sequence (head
+    // after head, slots t0 .. n_slot-1 of each), so that the ring stays full across the change of
+    // head; past the last head the rows lie beyond S and read as zero
+    int tf = t0, gqf = 0;
+    auto advance_fetch = [&]() __attribute__((always_inline)) {
+        ++tf;
+        if (tf == n_slot && gqf + 1 < a.group) {
+            tf = t0;
+            set_head(bh0 + ++gqf);
         }
     };
     // wave-uniform: does slot t hold a real row that sees some key of the pair
@@ -214,23 +226,12 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     elem8 *const Xs = reinterpret_cast<elem8 *>(smem + C::kOffXchg) + pair * 256 + l;
 
     if (producer) {
-        // The slots of the group's query heads form ONE sequence (head after head, slots t0 ..
-        // n_slot-1 of each), so that the ring stays full across the change of head: the
-        // transfers run kAhead slots in front and switch to the next head's rows on their own.
-        // The first kAhead slots are requested before anything else, so that their way from memory
-        // overlaps the fetch of the K and V rows below.
-        int tf = t0, gqf = 0;  // slot and head of the next transfer
+        // The statistics of the first kAhead slots are requested before anything else (the
+        // consumers request the rows meanwhile).
         set_head(bh0);
-        auto advance_fetch = [&]() __attribute__((always_inline)) {
-            ++tf;  // past the last head: rows beyond S, which read as zero
-            if (tf == n_slot && gqf + 1 < a.group) {
-                tf = t0;
-                set_head(bh0 + ++gqf);
-            }
-        };
 #pragma unroll
         for (int i = 0; i < C::kAhead; ++i) {
-            dma_slot(tf, i);
+            dma_stat(tf, i);
             advance_fetch();
         }
         // K and V fragments (B operands): lane holds K[key][16ks + 8h .. +7].
@@ -281,10 +282,7 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
             int rd = rs + C::kAhead;
             rd = rd >= C::kRing ? rd - C::kRing : rd;
             dma_stat(tf, rd);
-            if (!active(t)) {
-#pragma unroll
-                for (int n = 0; n < C::kDmaPerWave; ++n) dma_piece(tf, rd, n);
-            } else {
+            if (active(t)) {
                 const char *Qt = smem + rs * C::kSlotBytes;
                 const float *st = reinterpret_cast<const float *>(smem + C::kOffStat + rs * C::kStatBytes);
                 const int q_lo = t * C::kRows;
@@ -304,17 +302,11 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
                     s = mfma32(*(const elem8 *)(Qt + lane_off), kf[0], zero);
                     dp = mfma32(*(const elem8 *)(Qt + C::kTensorBytes + lane_off), vf[0], nd);
                 }
-                // the transfers of slot t + kAhead go between the MFMAs, evenly spread: piece j
-                // after contraction step (j + 1) * kEvery - 1
-                constexpr int kEvery = KS / C::kDmaPerWave;
-                static_assert(kEvery >= 1 && kEvery * C::kDmaPerWave == KS, "transfers spread evenly");
-                if (kEvery == 1) dma_piece(tf, rd, 0);
 #pragma unroll
                 for (int ks = 1; ks < KS; ++ks) {
                     const int off = lane_off ^ (ks * 32);
                     s = mfma32(*(const elem8 *)(Qt + off), kf[ks], s);
                     dp = mfma32(*(const elem8 *)(Qt + C::kTensorBytes + off), vf[ks], dp);
-                    if ((ks + 1) % kEvery == 0) dma_piece(tf, rd, (ks + 1) / kEvery - 1);
                 }
                 // the lane's key is fixed; P = exp2(c S - lse2) per row
 #pragma unroll
@@ -406,10 +398,22 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
             }
         };
 
+        // the rows of the first kAhead slots
+        set_head(bh0);
+#pragma unroll
+        for (int i = 0; i < C::kAhead; ++i) {
+            dma_pieces(tf, i);
+            advance_fetch();
+        }
         int rs = 0;  // ring position of the producers' slot; the consumers' is one behind
         int t = t0, tp = t0;  // rows of the producers' slot and of the one before it
         for (int g = 0; g < n_seq; ++g) {
-            wait_vm_and_barrier<0>();
+            slot_barrier();
+            // slot g + kAhead goes into the ring position that slot g - 2 has left
+            int rd = rs + C::kAhead;
+            rd = rd >= C::kRing ? rd - C::kRing : rd;
+            dma_pieces(tf, rd);
+            advance_fetch();
             if (g > 0) consume(tp, g - 1, rs == 0 ? C::kRing - 1 : rs - 1);
             rs = ring_next(rs);
             tp = t;
