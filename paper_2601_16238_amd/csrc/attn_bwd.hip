@@ -126,7 +126,6 @@ attn_bwd_dkdv_kernel(const BwdArgs a)
     const int coff = Sk - S;      // causal: query row i sees keys 0 .. i + coff
     const int k0 = kt * C::kBlk + pair * 32;  // first key of this pair
     const int key = k0 + r;
-    const int keyc = key < Sk ? key : Sk - 1;
     const int n_slot = (S + C::kRows - 1) / C::kRows;
     // first slot with a row that sees a key of this block (row >= key - coff)
     const int t0 = CAUSAL ? max(0, kt * C::kBlk - coff) / C::kRows : 0;
