@@ -447,7 +447,12 @@ attn_fwd_kernel(const FwdArgs a)
         // ---- K0
         ld_v(Vt, 0, f2);
         if (NKQ == 1) ld_v(Vt, 1, f3);
-        if (u == 0) dma_k(kt + 2, kbuf_fill);
+        // (both tiles' transfers right after the barrier: the V buffer being filled was last read
+        // before the previous barrier; measured the same or up to 1 % faster than V two steps later)
+        if (u == 0) {
+            dma_k(kt + 2, kbuf_fill);
+            dma_v(kt + 1, vb_fill);
+        }
 #pragma unroll
         for (int i = 0; i < 16; ++i) nxt[i] = 0.f;
         exp4(0);
@@ -467,7 +472,6 @@ attn_fwd_kernel(const FwdArgs a)
         ld_k(Kn, 0, f0);
         mm_o(f2, pp0);
         exp4(8);
-        if (u == 0) dma_v(kt + 1, vb_fill);
         ATTN_FENCE();
         // ---- V1
         if (NKQ > 1) ld_k(Kn, 1, f1);
