@@ -57,23 +57,24 @@ __global__ void __launch_bounds__(256) attn_bwd_delta_kernel(const BwdArgs a)
 }
 
 // ---------------------------------------------------------------------------------------
-// 2. dK, dV.  Work-group = 8 waves = 4 producers + 4 consumers (wave w and w+4 share a SIMD);
-// it owns 128 keys and streams the head's Q and dO rows through LDS in slots of 32 rows.
-// The K/V fragments plus two 32 x D fp32 accumulators do not fit one wave's 256 registers,
-// and a wave alternating between the exp-heavy and the accumulate-heavy half cannot overlap
-// them, so the halves go to different waves:
-//   producer p (waves 0-3), slot t: 32 keys; S = Q K^T, dP = dO V^T, P = exp2(c S - lse2),
-//                                   dS = P o (dP - delta); elem P and dS -> LDS exchange
-//   consumer (waves 4-7), slot t-1: 64 keys (two producers) and ONE output: even consumers
-//                                   dV^T += dO^T P, odd ones dK^T += Q^T dS; every transposed
-//                                   LDS fragment feeds two MFMAs (one per 32-key block)
-// Both issue 16 MFMAs per slot (D = 128); the producer's VALU work overlaps the consumer's
+// 2. dK, dV.  Work-group = 2P waves = P producers (waves 0 .. P-1) + P consumers (P = 4: two
+// waves per SIMD; P = 6 at D = 128: three); it owns 32 P keys and streams the head's Q and dO
+// rows through LDS in slots of 32 rows.
+// The K/V fragments plus two 32 x D fp32 accumulators do not fit one wave's registers, and a
+// wave alternating between the exp-heavy and the accumulate-heavy half cannot overlap them, so
+// the halves go to different waves:
+//   producer p, slot t:   32 keys; S = Q K^T, dP = dO V^T, P = exp2(c S - lse2),
+//                         dS = P o (dP - delta); elem P and dS -> LDS exchange
+//   consumer, slot t-1:   64 keys (two producers) and ONE output: even consumers
+//                         dV^T += dO^T P, odd ones dK^T += Q^T dS; every transposed
+//                         LDS fragment feeds two MFMAs (one per 32-key block)
+// Both issue 16 MFMAs per slot (D = 128); the producers' VALU work overlaps the consumers'
 // MFMAs on the shared SIMD.  One barrier per slot.
 //
 // Q/dO slots go global -> LDS directly, kAhead slots ahead, into a ring of kAhead + 2 slots
-// (the producer's, the consumer's, and those in flight); rows are stored unpadded with the
-// 16-byte chunk index XOR-swizzled by the row so that both the producer's row reads and the
-// consumer's transpose reads are bank-conflict free.
+// (the producer's, the consumer's, and those in flight), requested by the consumers; rows are
+// stored unpadded with the 16-byte chunk index XOR-swizzled by the row so that both the
+// producer's row reads and the consumer's transpose reads are bank-conflict free.
 // ---------------------------------------------------------------------------------------
 template <int D, int P>
 struct DkdvCfg {
@@ -94,8 +95,7 @@ struct DkdvCfg {
     static constexpr int kOffXchg = kOffStat + kRing * kStatBytes;
     static constexpr int kLdsBytes = kOffXchg + kXchgBytes;
     static constexpr int kDmaPerTensor = kTensorBytes / 1024; // wave-wide 1 KB transfers
-    // Only the producers stream: the compiler makes every wave wait for all of its own
-    // outstanding transfers before a transpose read, which would stall the consumers.
+    // transfers of a slot that one consumer requests: its share of the Q pieces, then of the dO pieces
     static constexpr int kDmaPerWave = 2 * ((kDmaPerTensor + kPairs - 1) / kPairs);
     static constexpr int kStatWave = kPairs - 1;     // the producer that also fetches the stats
     static_assert(kOffXchg % 16 == 0 && kLdsBytes <= 160 * 1024, "LDS layout");
