@@ -656,43 +656,104 @@ attn_fwd_kernel(const FwdArgs a)
 }
 
 // Combine the per-split partial results: LSE = log sum_z exp(LSE_z), O = sum_z exp(LSE_z - LSE) O_z.
-// One thread per (row, 4 consecutive d); HBM-bound and small.
-template <int D>
+// A thread owns 4 consecutive d of one row and every ZG-th split, four splits per step with their
+// loads issued together (a thread that walks all splits one load after the other spends a memory
+// latency per split: 21 us for 32 splits of 32 rows), as a running (max, sum, weighted O) triple;
+// the ZG triples of a row are then combined through LDS.  The order of the sums is a function of
+// the shape only.  HBM-bound and small.
+template <int D, int ZG>
 __global__ void __launch_bounds__(256) attn_fwd_merge_kernel(const FwdArgs a)
 {
-    constexpr int TPR = D / 4;  // threads per row
+    constexpr int TPR = D / 4;               // threads per row and split group
+    constexpr int RPB = 256 / (TPR * ZG);    // rows per work-group
+    static_assert(RPB >= 1, "a row's threads fit the work-group");
     const int64_t rows = (int64_t)a.BH * a.S;
-    const int64_t row = (int64_t)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
-    if (row >= rows) return;
-    const int d0 = (threadIdx.x % TPR) * 4;
-    float mx = -INFINITY;
-    for (int z = 0; z < a.nsplit; ++z) mx = fmaxf(mx, a.LSEpart[(int64_t)z * rows + row]);
-    float den = 0.f;
+    const int t = threadIdx.x;
+    const int d0 = (t % TPR) * 4, zg = (t / TPR) % ZG;
+    const int64_t row_raw = (int64_t)blockIdx.x * RPB + t / (TPR * ZG);
+    const bool live = row_raw < rows;
+    const int64_t row = live ? row_raw : rows - 1;  // clamped: every thread reaches the barrier
+    const int nsplit = a.nsplit;
+    float m = -INFINITY, den = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int z = 0; z < a.nsplit; ++z) {
-        const float wz = expf(a.LSEpart[(int64_t)z * rows + row] - mx);  // 0 for an empty split
-        const f32x4 oz = *(const f32x4 *)(a.Opart + ((int64_t)z * rows + row) * D + d0);
-        den += wz;
+    for (int z0 = zg; z0 < nsplit; z0 += 4 * ZG) {
+        float lz[4];
+        f32x4 oz[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[e] += wz * oz[e];
+        for (int k = 0; k < 4; ++k) {
+            const int z = z0 + k * ZG;
+            const int64_t at = (int64_t)(z < nsplit ? z : z0) * rows + row;
+            lz[k] = a.LSEpart[at];
+            oz[k] = *(const f32x4 *)(a.Opart + at * D + d0);
+            if (z >= nsplit) lz[k] = -INFINITY;
+        }
+        const float mk = fmaxf(fmaxf(m, fmaxf(lz[0], lz[1])), fmaxf(lz[2], lz[3]));
+        if (mk > -INFINITY) {  // (an empty split has LSE = -inf and weight 0)
+            const float sc = expf(m - mk);
+            den *= sc;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] *= sc;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float wz = expf(lz[k] - mk);
+                den += wz;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] += wz * oz[k][e];
+            }
+            m = mk;
+        }
     }
+    if constexpr (ZG > 1) {
+        __shared__ float red[256 * 6];
+        red[t] = m;
+        red[256 + t] = den;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) red[(2 + e) * 256 + t] = acc[e];
+        __syncthreads();
+        if (zg != 0) return;
+        float mm = m;
+#pragma unroll
+        for (int g = 1; g < ZG; ++g) mm = fmaxf(mm, red[t + g * TPR]);
+        const float s0 = mm > -INFINITY ? expf(m - mm) : 0.f;
+        den *= s0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] *= s0;
+#pragma unroll
+        for (int g = 1; g < ZG; ++g) {
+            const int u = t + g * TPR;
+            const float sg = mm > -INFINITY ? expf(red[u] - mm) : 0.f;
+            den += sg * red[256 + u];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] += sg * red[(2 + e) * 256 + u];
+        }
+        m = mm;
+    }
+    if (!live) return;
     const float inv = 1.0f / den;
     const int bh = (int)(row / a.S), q = (int)(row % a.S);
     elem *Op = a.O + (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h +
                (int64_t)q * a.stride_s + d0;
     if (d0 < a.Dr) *(elem4 *)Op = pack4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
-    if (d0 == 0) a.LSE[row] = mx + logf(den);
+    if (d0 == 0) a.LSE[row] = m + logf(den);
 }
 
+template <int D, int ZG>
+static int launch_fwd_merge_zg(const FwdArgs &a, hipStream_t st)
+{
+    const int64_t rows = (int64_t)a.BH * a.S;
+    constexpr int RPB = 256 / ((D / 4) * ZG);
+    hipLaunchKernelGGL((attn_fwd_merge_kernel<D, ZG>), dim3((unsigned)((rows + RPB - 1) / RPB)),
+                       dim3(256), 0, st, a);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+// Up to four splits: one thread per (row, 4 d) takes them all in one step.  More: a row's splits
+// are spread over as many thread groups as fit the work-group with it.
 template <int D>
 static int launch_fwd_merge(const FwdArgs &a, hipStream_t st)
 {
-    const int64_t rows = (int64_t)a.BH * a.S;
-    constexpr int TPR = D / 4;                       // threads per row
-    constexpr int RPB = 256 / (TPR > 256 ? 256 : TPR);
-    hipLaunchKernelGGL((attn_fwd_merge_kernel<D>), dim3((unsigned)((rows + RPB - 1) / RPB)),
-                       dim3(256), 0, st, a);
-    return hipGetLastError() == hipSuccess ? 0 : -1;
+    if (a.nsplit <= 4) return launch_fwd_merge_zg<D, 1>(a, st);
+    return launch_fwd_merge_zg<D, (D > 128 ? 4 : 8)>(a, st);
 }
 
 template <int D, int NW, bool CAUSAL, bool SPLIT>
