@@ -840,12 +840,15 @@ int fwd_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps)
         if (nsplit > 128) nsplit = 128;
     }
     // Decoding (at most 32 rows per head) runs in the streaming kernel, of which two work-groups
-    // fit a compute unit: aim at two per unit where that leaves every split 16 tiles or more
+    // fit a compute unit: aim at two per unit as far as that leaves every split 8 tiles or more
     // (B=8 Hkv=8 Sk=8192: 8 splits, 55.0 -> 49.5 us; B=16 H=16 Sk=4096: 2 splits, 111 -> 103 us;
-    // with shorter ranges the prologues and the merge cost more than the second work-group gains).
+    // B=1 Hkv=8 Sk=32768: 64 splits of 8 tiles 28.2 us against 30.0 with 32 of 16; four work-groups
+    // per unit are 4-5 % slower again).
     if (S <= 32 && D <= 128 && wgs < 512) {
-        const int n2 = (int)((512 + wgs - 1) / wgs);
-        if (n2 <= 128 && tiles / n2 >= 16) nsplit = n2;
+        int n2 = (int)((512 + wgs - 1) / wgs);
+        if (n2 > tiles / 8) n2 = tiles / 8;
+        if (n2 > 128) n2 = 128;
+        if (n2 > nsplit) nsplit = n2;
     }
     const int tiles_per = (tiles + nsplit - 1) / nsplit;
     nsplit = (tiles + tiles_per - 1) / tiles_per;  // no empty split
