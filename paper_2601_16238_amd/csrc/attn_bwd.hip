@@ -97,8 +97,8 @@ struct DkdvCfg {
     static constexpr int kDmaPerTensor = kTensorBytes / 1024; // wave-wide 1 KB transfers
     // transfers of a slot that one consumer requests: its share of the Q pieces, then of the dO pieces
     static constexpr int kDmaPerWave = 2 * ((kDmaPerTensor + kPairs - 1) / kPairs);
-    // the producer that also fetches the stats (six pairs: one of the two that share their SIMD with
-    // one other producer instead of two; -0.3..0.6 %)
+    // the producer that also fetches the stats (six pairs: waves 2 and 3 are the only producers on
+    // their SIMDs, waves 0/4 and 1/5 share one; -0.3..0.6 %)
     static constexpr int kStatWave = kPairs == 6 ? 3 : kPairs - 1;
     static_assert(kOffXchg % 16 == 0 && kLdsBytes <= 160 * 1024, "LDS layout");
 };
