@@ -54,7 +54,10 @@ def test_rect_parity(B, Hq, Hkv, Sq, Sk, D, causal):
     (1, 4, 2, 1, 4096, 128, True), (2, 2, 2, 16, 2100, 64, True), (1, 2, 1, 200, 3000, 128, True),
     (1, 8, 8, 1, 1024, 64, False), (1, 2, 2, 300, 1500, 128, False),
     # many splits (the merge walks a row's splits in several steps): 125, 63, and 32 at D = 256
-    (1, 8, 2, 1, 40000, 128, True), (1, 4, 4, 1, 20000, 64, False), (1, 2, 2, 64, 8192, 256, False)])
+    (1, 8, 2, 1, 40000, 128, True), (1, 4, 4, 1, 20000, 64, False), (1, 2, 2, 64, 8192, 256, False),
+    # a single row (the merge's work-group holds two rows at D = 64: one of them is past the end),
+    # and four splits at D = 256
+    (1, 1, 1, 1, 3000, 64, False), (1, 2, 2, 64, 1024, 256, True)])
 def test_rect_forward_split_matches_unsplit_and_oracle(B, Hq, Hkv, Sq, Sk, D, causal):
     """Shapes for which the library's plan splits the keys: the merged result must match the
     oracle, and the one-kernel result (no workspace) as well."""
