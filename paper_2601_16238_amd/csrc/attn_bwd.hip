@@ -896,10 +896,20 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_merge_kernel(const BwdArgs a)
     if (row >= rows) return;
     const int d0 = (threadIdx.x % TPR) * 4;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int z = 0; z < a.dq_nsplit; ++z) {
-        const f32x4 v = *(const f32x4 *)(a.dQpart + ((int64_t)z * rows + row) * D + d0);
+    // four splits per step, their loads issued together (one dependent load per split costs a
+    // memory latency each); added in the order of the splits
+    const int n = a.dq_nsplit;
+    for (int z0 = 0; z0 < n; z0 += 4) {
+        f32x4 v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[e] += v[e];
+        for (int k = 0; k < 4; ++k)
+            v[k] = *(const f32x4 *)(a.dQpart + ((int64_t)(z0 + k < n ? z0 + k : z0) * rows + row) * D + d0);
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (z0 + k < n) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] += v[k][e];
+            }
     }
     const int bh = (int)(row / a.S), q = (int)(row % a.S);
     elem *dQp = a.dQ + (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h +
