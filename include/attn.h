@@ -322,6 +322,25 @@ int attn_probe_mfma_bf16(int workgroups, int iters, int random_operands, float *
 int attn_probe_atomic_f32(int BH, int S, int key_block, int causal, float *acc,
                           size_t acc_floats, double *bytes_added, void *hip_stream);
 
+/* Measurement aid, not a step of the method: what work-groups that only read can stream from
+ * device memory -- the ceiling for decoding, whose forward reads K and V once and does little
+ * else (the paper reports its kernel's weak spot on small-batch prefill and decode shapes
+ * without a bandwidth figure; this is the build's own yardstick for them).
+ * `workgroups` work-groups of 256 threads read `bytes` bytes from src, each a contiguous share,
+ * and write the XOR of all 32-bit words they read to checksum[work-group].
+ * direct bit 0 clear: plain 16-byte loads, eight in flight per lane, work-group g reads
+ *   [g * bytes/workgroups, (g+1) * bytes/workgroups).
+ * direct bit 1: the loads or transfers carry the non-temporal hint.
+ * direct bit 0 set: direct global -> LDS transfers in the shape of the decoding forward: src is taken
+ *   as two tensors (its halves); work-group g reads its contiguous share of each, in tiles of
+ *   16 KB per tensor, two tile buffers, one tile in flight, one barrier per tile, 1 KB per
+ *   transfer with neighbouring lanes on neighbouring 256-byte rows.
+ * src: DEVICE, 16-byte aligned, bytes a multiple of workgroups * 32768 and at most 2 GiB per
+ * work-group; checksum: DEVICE, workgroups uint32, fully overwritten.
+ * Errors: ATTN_ERR_NULL, ATTN_ERR_SHAPE, ATTN_ERR_ALIGN, ATTN_ERR_LAUNCH.  Asynchronous. */
+int attn_probe_stream(const void *src, size_t bytes, int workgroups, int direct,
+                      uint32_t *checksum, void *hip_stream);
+
 /* Static, NUL-terminated description of a status code.  Never NULL. */
 const char *attn_status_string(int status);
 

@@ -11,5 +11,5 @@ from .binding import (AttnError, AttnGqaParams, AttnParams, AttnRectParams,  # n
                       attn_bwd_rect_noalloc, attn_bwd_rope, attn_fwd_rope,
                       attn_bwd_rect_workspace_bytes, attn_bwd_workspace_bytes, attn_fwd,
                       attn_fwd_gqa, attn_fwd_rect, attn_fwd_rect_workspace_bytes,
-                      attn_probe_atomic_f32, attn_probe_mfma_bf16, attn_version,
+                      attn_probe_atomic_f32, attn_probe_mfma_bf16, attn_probe_stream, attn_version,
                       lib, make_gqa_params, make_params, make_rect_params, status_string)

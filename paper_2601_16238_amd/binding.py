@@ -27,7 +27,7 @@ EXPORTS = ("attn_params_contiguous", "attn_fwd", "attn_bwd_workspace_bytes", "at
            "attn_bwd_rect_workspace_bytes", "attn_bwd_rect", "attn_fwd_rect_f16",
            "attn_bwd_rect_f16", "attn_bwd_rect_noalloc", "attn_fwd_rope_workspace_bytes", "attn_fwd_rope",
            "attn_bwd_rope", "attn_probe_mfma_bf16",
-           "attn_probe_atomic_f32",
+           "attn_probe_atomic_f32", "attn_probe_stream",
            "attn_status_string", "attn_version")
 NOALLOC_SCRATCH_BYTES = 8 << 20
 STAGE_DELTA, STAGE_DKDV, STAGE_DQ = 1, 2, 4
@@ -140,6 +140,8 @@ def lib():
         L.attn_probe_atomic_f32.argtypes = [ctypes.c_int] * 4 + [vp, ctypes.c_size_t,
                                             ctypes.POINTER(ctypes.c_double), vp]
         L.attn_probe_atomic_f32.restype = ctypes.c_int
+        L.attn_probe_stream.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, vp, vp]
+        L.attn_probe_stream.restype = ctypes.c_int
         L.attn_status_string.argtypes = [ctypes.c_int]
         L.attn_status_string.restype = ctypes.c_char_p
         L.attn_version.argtypes = []
@@ -184,6 +186,23 @@ def attn_probe_atomic_f32(BH, S, key_block, causal, acc, stream=None):
     if rc != 0:
         raise AttnError(rc, "attn_probe_atomic_f32")
     return nbytes.value
+
+
+def attn_probe_stream(src, workgroups, checksum, direct=False, nontemporal=False, stream=None):
+    """Enqueue the read-streaming measurement kernel over the CUDA tensor `src` (all of its
+    bytes); `checksum`: int32 CUDA tensor of `workgroups` elements, receives the XOR of the
+    32-bit words each work-group read.  Returns the bytes one launch reads."""
+    import torch
+    assert src.is_cuda and src.is_contiguous() and checksum.is_cuda and checksum.is_contiguous()
+    assert checksum.dtype == torch.int32 and checksum.numel() >= workgroups
+    st = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    nbytes = src.numel() * src.element_size()
+    rc = lib().attn_probe_stream(src.data_ptr(), nbytes, int(workgroups),
+                                 int(bool(direct)) | (int(bool(nontemporal)) << 1),
+                                 checksum.data_ptr(), ctypes.c_void_p(st))
+    if rc != 0:
+        raise AttnError(rc, "attn_probe_stream")
+    return nbytes
 
 
 def make_params(B, H, S, D, scale, causal, strides=None):

@@ -168,6 +168,16 @@ __device__ __forceinline__ void dma16_between(desc_t desc, uint32_t lds_addr, ui
                  "s"(__builtin_amdgcn_readfirstlane(soff))
                  : "m0");
 }
+// The same with the non-temporal hint, for data that is read once: a stream larger than the
+// last-level cache then moves 12-14 % faster (stand-alone loops over 512 MiB: 5.98 -> 6.71 TB/s),
+// one that fits it and is read again by the next launch 2-3 % slower.
+__device__ __forceinline__ void dma16_between_nt(desc_t desc, uint32_t lds_addr, uint32_t voff, uint32_t soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen nt lds"
+                 ::"s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(voff), "s"(desc),
+                 "s"(__builtin_amdgcn_readfirstlane(soff))
+                 : "m0");
+}
 // Same with 4 bytes per lane: lane i lands at lds_addr + 4 i.
 __device__ __forceinline__ void dma4(desc_t desc, uint32_t lds_addr, uint32_t voff, uint32_t soff)
 {

@@ -277,6 +277,18 @@ def test_f16_entry_points_validate_like_the_bf16_ones():
         binding.ATTN_ERR_SHAPE
 
 
+def test_stream_probe_validates_its_arguments():
+    L = attn.lib()
+    MB = 1 << 20
+    assert L.attn_probe_stream(None, 8 * MB, 64, 0, FAKE, None) == binding.ATTN_ERR_NULL
+    assert L.attn_probe_stream(FAKE, 8 * MB, 64, 0, None, None) == binding.ATTN_ERR_NULL
+    assert L.attn_probe_stream(FAKE, 8 * MB, 0, 0, FAKE, None) == binding.ATTN_ERR_SHAPE
+    assert L.attn_probe_stream(FAKE, 8 * MB + 4096, 64, 1, FAKE, None) == binding.ATTN_ERR_SHAPE   # not whole 32 KB steps
+    assert L.attn_probe_stream(FAKE, 0, 64, 1, FAKE, None) == binding.ATTN_ERR_SHAPE
+    assert L.attn_probe_stream(FAKE + 8, 8 * MB, 64, 0, FAKE, None) == binding.ATTN_ERR_ALIGN
+    assert L.attn_probe_stream(FAKE, 8 * MB, 64, 1, FAKE + 2, None) == binding.ATTN_ERR_ALIGN
+
+
 def test_mfma_probe_validates_its_arguments():
     L = attn.lib()
     assert L.attn_probe_mfma_bf16(4, 10, 0, None, 4 * 512, None, None) == binding.ATTN_ERR_NULL

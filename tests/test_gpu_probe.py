@@ -94,3 +94,47 @@ def test_atomic_probe_rejects_bad_shapes():
     for args in ((7, 64, 32), (8, 65, 32), (8, 64, 48), (8, 64, 128), (16, 64, 32)):
         with pytest.raises(attn.AttnError):
             attn.attn_probe_atomic_f32(*args, False, acc)
+
+
+def test_stream_probe_reads_every_byte_and_reports_its_rate():
+    """The per-work-group XOR of both forms must equal the XOR of the words of the work-group's
+    share (so every byte was read, none twice); the rates over 256 MiB and 512 MiB are printed
+    (they are the ceiling the decoding forward is compared with)."""
+    print("case stream_probe checksum", flush=True)
+    words = torch.randint(-2**31, 2**31 - 1, (8 << 18,), dtype=torch.int32, device="cuda")   # 8 MiB
+    host = words.cpu().numpy().view(np.uint32)
+    for wgs in (64, 256):
+        per = host.size // wgs
+        out = torch.empty(wgs, dtype=torch.int32, device="cuda")
+        for nt in (False, True):
+            out.fill_(0)
+            attn.attn_probe_stream(words, wgs, out, direct=False, nontemporal=nt)
+            torch.cuda.synchronize()
+            expect = np.bitwise_xor.reduce(host.reshape(wgs, per), axis=1)
+            assert np.array_equal(out.cpu().numpy().view(np.uint32), expect)
+            out.fill_(0)
+            attn.attn_probe_stream(words, wgs, out, direct=True, nontemporal=nt)
+            torch.cuda.synchronize()
+            halves = host.reshape(2, wgs, per // 2)
+            expect = np.bitwise_xor.reduce(halves[0], axis=1) ^ np.bitwise_xor.reduce(halves[1], axis=1)
+            assert np.array_equal(out.cpu().numpy().view(np.uint32), expect)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for mib in (256, 512):
+        print("case stream_probe rate", mib, flush=True)
+        buf = torch.ones(mib << 18, dtype=torch.int32, device="cuda")
+        out = torch.empty(512, dtype=torch.int32, device="cuda")
+        for direct, nt in ((False, False), (False, True), (True, False), (True, True)):
+            for _ in range(3):
+                attn.attn_probe_stream(buf, 512, out, direct=direct, nontemporal=nt)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(10):
+                nbytes = attn.attn_probe_stream(buf, 512, out, direct=direct, nontemporal=nt)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 10
+            assert nbytes == mib << 20 and nbytes / ms / 1e9 > 1.0       # TB/s; a sanity floor only
+            print("read-only streaming, %d MiB, 512 work-groups, %s%s: %.1f us = %.2f TB/s"
+                  % (mib, "direct transfers to LDS" if direct else "plain loads",
+                     ", non-temporal" if nt else "", ms * 1e3, nbytes / ms / 1e9), flush=True)
+        del buf

@@ -9,7 +9,7 @@ import torch
 import oracle
 import paper_2601_16238_amd as attn
 from paper_2601_16238_amd import workloads as wl
-from parity_util import check_bf16, check_grad, check_lse, to_dev, to_f64
+from parity_util import bf16_round, check_bf16, check_grad, check_lse, f16_round, to_dev, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -168,6 +168,39 @@ def test_rect_full_size_sampled_heads():
                 check_bf16("dQ", to_f64(dQ[b, qs]), ref[0][0], floor_gate=False)
                 check_bf16("dK", to_f64(dK[b, hk]), ref[1][0, 0], floor_gate=False)
                 check_bf16("dV", to_f64(dV[b, hk]), ref[2][0, 0], floor_gate=False)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Sk,D,f16", [
+    (16, 16, 16, 4099, 128, False),    # every head its own K/V: the masked kernel
+    (8, 32, 8, 16389, 128, False),     # grouped heads packed into one head of 4 rows: no mask
+    (32, 16, 16, 4200, 64, True),      # D = 64, fp16
+])
+def test_decode_with_more_keys_and_values_than_the_last_level_cache(B, Hq, Hkv, Sk, D, f16):
+    """Decoding against more K and V than the last-level cache holds (every byte then really comes
+    from HBM, through the decoding launches' non-temporal transfers): sampled heads against the
+    oracle, with the planned split and in one kernel."""
+    print("case decode_large", B, Hq, Hkv, Sk, D, f16, flush=True)
+    assert B * Hkv * Sk * D * 4 > 256 << 20
+    dt = torch.float16 if f16 else torch.bfloat16
+    g = torch.Generator(device="cuda"); g.manual_seed(1500 + Sk)
+    Q = torch.randn((B, Hq, 1, D), device="cuda", generator=g).to(dt)
+    K = torch.randn((B, Hkv, Sk, D), device="cuda", generator=g).to(dt)
+    V = torch.randn((B, Hkv, Sk, D), device="cuda", generator=g).to(dt)
+    scale = wl.default_scale(D)
+    # (the first two shapes split their keys, the third has a work-group per head and does not)
+    assert (attn.attn_fwd_rect_workspace_bytes(B, Hq, Hkv, 1, Sk, D) > 0) == (B * Hkv < 512)
+    O, LSE = attn.attn_fwd_rect(Q, K, V, scale, True)
+    O1, LSE1 = attn.attn_fwd_rect(Q, K, V, scale, True, split=False)
+    torch.cuda.synchronize()
+    G = Hq // Hkv
+    bits = (lambda t: t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16))
+    for b, hk in ((0, 0), (B // 2, Hkv - 1), (B - 1, Hkv // 2)):
+        qs = slice(hk * G, hk * G + G)
+        q, k, v = bits(Q[b:b + 1, qs]), bits(K[b:b + 1, hk:hk + 1]), bits(V[b:b + 1, hk:hk + 1])
+        Oref, Lref = oracle.attn_fwd(q, k, v, scale, True, dtype="f16" if f16 else "bf16")
+        for name, o, l in (("split", O, LSE), ("one kernel", O1, LSE1)):
+            check_bf16("O " + name, to_f64(o[b:b + 1, qs]), Oref, rnd=f16_round if f16 else bf16_round)
+            check_lse(to_f64(l[b:b + 1, qs]), Lref)
 
 
 @pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D,causal", [
