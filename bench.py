@@ -319,6 +319,20 @@ def rect_main(torch, attn, wl, w, a):
             {"kernel": "attn_fwd_kernel (+ merge)", "bound": "mfma", "achieved": r["tflops_fwd"],
              "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": r["tflops_fwd"] / PEAK_BF16_TFLOPS,
              "traffic": None})
+    if hbm_bound:
+        # what work-groups that only read stream from HBM on this machine (512 MiB, more than the
+        # last-level cache holds; plain loads with the non-temporal hint, and the direct transfers
+        # in the decoding kernel's shape), beside the nominal peak the fraction is quoted against
+        buf = torch.ones(512 << 18, dtype=torch.int32, device="cuda")
+        chk = torch.empty(512, dtype=torch.int32, device="cuda")
+        probe = {}
+        for key, direct in (("loads", False), ("direct_transfers", True)):
+            fn = lambda: attn.attn_probe_stream(buf, 512, chk, direct=direct, nontemporal=True)
+            fn()
+            probe[key + "_gbs"] = buf.numel() * 4 / (time_calls(torch, fn, 10) * 1e-3) / 1e9
+        del buf
+        roof["measured_stream_gbs"] = probe
+        roof["frac_of_measured_stream"] = gbs / max(probe.values())
     out = {
         "metric": "attention fwd+bwd TFLOP/s (FLOPs = 4*D fwd + 10*D bwd per visible query-key pair)",
         "value": r["tflops_fwdbwd"], "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps,
