@@ -219,7 +219,7 @@ attn_fwd_wide_kernel(const FwdArgs a)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             s = mfma32(*(const elem8 *)(Kt + ks * C::kKStepBytes), qf[ks], s);
-            if (fetch >= 0 && (ks & 1) && kt + 1 < n_kt) dma_piece(fetch, kt + 1, (kt & 1) ^ 1, ks >> 1);
+            if (!NT && fetch >= 0 && (ks & 1) && kt + 1 < n_kt) dma_piece(fetch, kt + 1, (kt & 1) ^ 1, ks >> 1);
         }
     };
     // ragged tail and causal mask of sub-tile (kt, u); wave-uniform test whether any is needed
@@ -307,8 +307,24 @@ attn_fwd_wide_kernel(const FwdArgs a)
     // (waves that only take part in the staging: part 0 K(kt+1), part 1 V(kt+1))
     auto fetch_next = [&](int kt, int part) __attribute__((always_inline)) {
         if (kt + 1 >= n_kt) return;
-        if (part == 0) dma_k(kt + 1, (kt & 1) ^ 1);
-        if (part == 1) dma_v(kt + 1, (kt & 1) ^ 1);
+        if constexpr (NT) {
+            // decoding: the wave with the query rows (wave 0) requests nothing in the loop; the
+            // 2 kKPieces pieces of a tile are dealt to the three waves that only stage
+            if (part != 0 || w == 0) return;
+            constexpr int kN = (2 * C::kKPieces + 2) / 3;
+#pragma unroll
+            for (int n = 0; n < kN; ++n) {
+                const int pc = (w - 1) + 3 * n;  // wave-uniform
+                if (pc >= 2 * C::kKPieces) continue;
+                const int tensor = pc / C::kKPieces, ii = pc % C::kKPieces, buf = (kt & 1) ^ 1;
+                const uint32_t lds = tensor ? lds0 + C::kOffV + buf * C::kVTileBytes + ii * C::kVPieceBytes
+                                            : lds0 + buf * C::kKTileBytes + ii * C::kKPieceBytes;
+                dma16_between_nt(tensor ? Vd : Kd, lds, k_voff, (kt + 1) * tile_bytes + ii * PR * row_bytes);
+            }
+        } else {
+            if (part == 0) dma_k(kt + 1, (kt & 1) ^ 1);
+            if (part == 1) dma_v(kt + 1, (kt & 1) ^ 1);
+        }
     };
     auto commit = [&](elem8 p0, elem8 p1, float psum) __attribute__((always_inline)) {
         lsum += psum;
