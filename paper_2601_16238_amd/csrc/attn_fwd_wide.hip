@@ -508,7 +508,7 @@ static int launch_wide_d(const FwdArgs &a, bool causal, hipStream_t st)
     // layers do: 6-10 % faster at every size (B=8 Hkv=8 Sk=8192: 55 -> 50 us); with every byte from
     // HBM in one call (B=16 H=16 Sk=4096, 512 MiB) 98.6 -> 86.5 us.  A loop that re-reads ONE set
     // that fits the cache is 2-3 % slower for it.
-    if constexpr (D <= 128) {
+    {
         // (not for an unsplit launch of few work-groups, i.e. a caller without a workspace: B=8
         // Hkv=8 Sk=8192 in 64 work-groups 156 -> 180 us with the hint)
         if (a.S <= 32 && a.group == 1 && (a.nsplit > 1 || a.BH >= 256)) {
