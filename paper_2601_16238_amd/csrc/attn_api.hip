@@ -74,6 +74,7 @@ size_t round_ws(size_t bytes) { return (bytes + kWsAlign - 1) / kWsAlign * kWsAl
 struct FwdView {
     int BH, H, S, group;
     bool packed;  // decoding: the rows of a head are the query heads of one K/V head
+    int pack_sq;  // ... times this many new positions each (0: not packed, or one position)
     int64_t stride_b, stride_h, stride_s;
     bool causal;
 };
@@ -83,15 +84,26 @@ struct FwdView {
 // head of G rows.  K and V are then streamed once per K/V head instead of once per query
 // head.  A single row sees every key, so the mask drops out.  LSE [B,Hq,1] is the same
 // memory as [B,Hkv,G].
-FwdView fwd_view(const attn_rect_params_t &p, bool may_pack = true)
+// A few new positions per sequence (Sq = 2 .. 32 / G, e.g. speculative decoding): with the rows of
+// a query head contiguous to the next head's (q_stride_h == Sq * q_stride_s) the G x Sq rows of
+// a K/V head are again rows at one uniform distance and are packed the same way; row r is
+// position r % Sq, which only the causal mask needs to know.  Not with the rotary embedding
+// fused (the table row of a packed row would depend on r % Sq as well).
+FwdView fwd_view(const attn_rect_params_t &p, bool rope)
 {
     FwdView v;
+    v.pack_sq = 0;
     const int G = p.Hq / p.Hkv;
-    if (may_pack && p.Sq == 1 && G > 1 &&
+    if (p.Sq == 1 && G > 1 &&
         check_strides(G, p.D, p.q_stride_b, G * p.q_stride_h, p.q_stride_h) == ATTN_OK) {
         v.BH = p.B * p.Hkv; v.H = p.Hkv; v.S = G; v.group = 1;
         v.stride_b = p.q_stride_b; v.stride_h = G * p.q_stride_h; v.stride_s = p.q_stride_h;
         v.causal = false; v.packed = true;
+    } else if (!rope && p.Sq > 1 && G > 1 && G * p.Sq <= 32 && p.q_stride_h == (int64_t)p.Sq * p.q_stride_s &&
+               check_strides(G * p.Sq, p.D, p.q_stride_b, G * p.q_stride_h, p.q_stride_s) == ATTN_OK) {
+        v.BH = p.B * p.Hkv; v.H = p.Hkv; v.S = G * p.Sq; v.group = 1;
+        v.stride_b = p.q_stride_b; v.stride_h = G * p.q_stride_h; v.stride_s = p.q_stride_s;
+        v.causal = p.causal != 0; v.packed = true; v.pack_sq = p.Sq;
     } else {
         v.BH = p.B * p.Hq; v.H = p.Hq; v.S = p.Sq; v.group = G;
         v.stride_b = p.q_stride_b; v.stride_h = p.q_stride_h; v.stride_s = p.q_stride_s;
@@ -106,10 +118,10 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 
 // E: element type of Q, K, V, O (__bf16 or _Float16)
 // Workspace of the forward's split over the keys for this problem (0: it would not split).
-static size_t fwd_workspace_bytes(const attn_rect_params_t *p, bool may_pack)
+static size_t fwd_workspace_bytes(const attn_rect_params_t *p, bool rope)
 {
     if (check_params(p) != ATTN_OK) return 0;
-    const FwdView v = fwd_view(*p, may_pack);
+    const FwdView v = fwd_view(*p, rope);
     const int nsplit = attn::fwd_split_plan(v.BH, v.S, p->Sk, kernel_d(p->D), v.causal, nullptr);
     if (nsplit <= 1) return 0;
     const size_t rows = (size_t)p->B * p->Hq * p->Sq;
@@ -152,11 +164,11 @@ static int fwd_impl(const void *Q, const void *K, const void *V, void *O, float 
         !aligned(LSE, 4))
         return ATTN_ERR_ALIGN;
     // No workspace at all: run unsplit.  A workspace that is there must be usable.
-    const FwdView v = fwd_view(*p);
+    const FwdView v = fwd_view(*p, rope != nullptr);
     int kps = 0;
     int nsplit = workspace ? attn::fwd_split_plan(v.BH, v.S, p->Sk, kernel_d(p->D), v.causal, &kps) : 1;
     if (workspace && (!aligned(workspace, kWsAlign) ||
-                      workspace_bytes < fwd_workspace_bytes(p, true)))
+                      workspace_bytes < fwd_workspace_bytes(p, rope != nullptr)))
         return ATTN_ERR_WORKSPACE;
     attn::FwdArgsT<E> a;
     a.nsplit = nsplit; a.kps = kps;
@@ -169,7 +181,7 @@ static int fwd_impl(const void *Q, const void *K, const void *V, void *O, float 
     a.LSE = LSE;
     a.stride_b = v.stride_b; a.stride_h = v.stride_h; a.stride_s = v.stride_s;
     a.kv_stride_b = p->kv_stride_b; a.kv_stride_h = p->kv_stride_h; a.kv_stride_s = p->kv_stride_s;
-    a.S = v.S; a.Sk = p->Sk; a.H = v.H; a.BH = v.BH; a.group = v.group;
+    a.S = v.S; a.Sk = p->Sk; a.H = v.H; a.BH = v.BH; a.group = v.group; a.pack_sq = v.pack_sq;
     a.Dr = p->D;
     a.nqt = 0;
     a.scale_log2e = p->scale * 1.4426950408889634f;
@@ -276,7 +288,7 @@ void attn_rect_params_contiguous(attn_rect_params_t *p, int32_t B, int32_t Hq, i
     p->causal = causal;
 }
 
-size_t attn_fwd_rect_workspace_bytes(const attn_rect_params_t *p) { return fwd_workspace_bytes(p, true); }
+size_t attn_fwd_rect_workspace_bytes(const attn_rect_params_t *p) { return fwd_workspace_bytes(p, false); }
 
 size_t attn_fwd_rope_workspace_bytes(const attn_rect_params_t *p) { return fwd_workspace_bytes(p, true); }
 

@@ -84,7 +84,7 @@ attn_fwd_wide_kernel(const FwdArgs a)
     // Keys seen by this work-group: all Sk of them, or one split's range (then K and V are
     // simply re-based to the range and the causal offset moves with them).  Query row i sees
     // key j iff j <= i + coff.
-    int Sk = a.Sk, coff = a.Sk - S;
+    int Sk = a.Sk, coff = a.Sk - (a.pack_sq ? a.pack_sq : S);  // (packed rows: Sq positions per head)
     int64_t kv_first = 0;
     if (SPLIT) {
         const int k_begin = blockIdx.y * a.kps;  // < Sk by the launcher's plan
@@ -97,6 +97,9 @@ attn_fwd_wide_kernel(const FwdArgs a)
     const int q = q0 + r;
     const int qc = q < S ? q : S - 1;  // clamped for loads; rows >= S are never stored
     const int q0e = q0 + coff;         // the wave's first row in key coordinates
+    // position of the lane's row among the new rows of its sequence (packed heads: row r is
+    // position r % Sq, so the wave's rows see at least the keys that q0e says and at most 31 more)
+    const int qpos = a.pack_sq ? qc % a.pack_sq : qc;
 
     // Q fragments, B operand of K Q^T: lane holds Q[q][16 ks + 8 h .. +7].  At D = 256 they come
     // through LDS (further down, where the transfers are set up): sixteen loads per wave in
@@ -226,7 +229,7 @@ attn_fwd_wide_kernel(const FwdArgs a)
     auto mask = [&](int kt, int u, f32x16 &s) __attribute__((always_inline)) {
         const int kb = kt * C::kBC + 32 * u;
         if ((kb + 32 > Sk) || (CAUSAL && kb + 31 > q0e)) {
-            const int lim = (CAUSAL ? min(qc + coff, Sk - 1) : Sk - 1) - kb - 4 * h;
+            const int lim = (CAUSAL ? min(qpos + coff, Sk - 1) : Sk - 1) - kb - 4 * h;
 #pragma unroll
             for (int i = 0; i < 16; ++i)
                 if (8 * (i / 4) + (i % 4) > lim) s[i] = -INFINITY;

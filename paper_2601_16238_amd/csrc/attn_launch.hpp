@@ -33,6 +33,9 @@ struct FwdArgsT {
     int Dr;             // head dimension of the tensors (a multiple of 8); the kernels run at
                         // D = 64, 128 or 256 and treat columns Dr..D-1 as zeros
     int group;          // query heads per K/V head
+    int pack_sq;        // 0, or: the S rows of a head are G query heads x pack_sq positions of one
+                        // K/V head (row r is position r % pack_sq of S_q = pack_sq new rows); only
+                        // the mask needs to know
     int nqt;            // query tiles per head (set by the launcher)
     float scale_log2e;  // scale * log2(e): the softmax runs on exp2
     // Split over the keys (small problems that would leave most of the chip idle): split z

@@ -20,6 +20,10 @@ CASES = [
     (2, 4, 2, 100, 356, 128, True), (1, 2, 2, 33, 64, 64, True), (1, 2, 1, 257, 300, 64, True),
     (1, 4, 4, 150, 77, 64, False), (1, 2, 2, 64, 1000, 128, False), (1, 3, 3, 300, 513, 128, True),
     (1, 2, 2, 7, 2049, 64, True), (1, 1, 1, 129, 129, 128, True),
+    # a few new rows per sequence with grouped heads: the G x Sq rows of a K/V head run as one
+    # packed head (mask by position r % Sq); 16, 30 and 32 rows; ragged last key tile
+    (2, 8, 2, 4, 3000, 128, True), (1, 12, 2, 5, 1025, 64, True), (1, 16, 2, 4, 777, 128, False),
+    (1, 8, 4, 3, 5, 128, True), (2, 4, 2, 16, 4100, 128, True),
 ]
 
 
@@ -57,7 +61,10 @@ def test_rect_parity(B, Hq, Hkv, Sq, Sk, D, causal):
     (1, 8, 2, 1, 40000, 128, True), (1, 4, 4, 1, 20000, 64, False), (1, 2, 2, 64, 8192, 256, False),
     # a single row (the merge's work-group holds two rows at D = 64: one of them is past the end),
     # and four splits at D = 256
-    (1, 1, 1, 1, 3000, 64, False), (1, 2, 2, 64, 1024, 256, True)])
+    (1, 1, 1, 1, 3000, 64, False), (1, 2, 2, 64, 1024, 256, True),
+    # packed grouped heads with several new rows: the last split starts inside the last Sq keys
+    # (rows that see none of its keys), many splits, D = 256
+    (1, 8, 2, 4, 8193, 128, True), (1, 4, 1, 8, 40000, 128, True), (1, 8, 2, 3, 5000, 256, True)])
 def test_rect_forward_split_matches_unsplit_and_oracle(B, Hq, Hkv, Sq, Sk, D, causal):
     """Shapes for which the library's plan splits the keys: the merged result must match the
     oracle, and the one-kernel result (no workspace) as well."""
