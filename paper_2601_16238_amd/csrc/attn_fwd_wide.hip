@@ -96,7 +96,8 @@ attn_fwd_wide_kernel(const FwdArgs a)
     const int q0 = qt * C::kBR + w * 32;
     const int q = q0 + r;
     const int qc = q < S ? q : S - 1;  // clamped for loads; rows >= S are never stored
-    const int q0e = q0 + coff;         // the wave's first row in key coordinates
+    // the wave's first row in key coordinates (packed rows: every wave holds a row at position 0)
+    const int q0e = (a.pack_sq ? 0 : q0) + coff;
     // position of the lane's row among the new rows of its sequence (packed heads: row r is
     // position r % Sq, so the wave's rows see at least the keys that q0e says and at most 31 more)
     const int qpos = a.pack_sq ? qc % a.pack_sq : qc;
