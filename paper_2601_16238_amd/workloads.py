@@ -187,6 +187,8 @@ RECT_WORKLOADS = {w.name: w for w in [
                  "one new token per sequence against an 8K cache, grouped-query heads"),
     RectWorkload("prefill_chunk", 1, 32, 8, 512, 4096, 128, True, 1.0, 1010,
                  "small-batch chunked prefill: 512 new rows after 3584 cached ones"),
+    RectWorkload("spec_decode", 8, 32, 8, 4, 8192, 128, True, 1.0, 1013,
+                 "four new tokens per sequence (speculative decoding) against an 8K cache, grouped-query heads"),
     RectWorkload("decode_small", 2, 8, 2, 1, 300, 64, True, 1.0, 1011, "parity-size decode"),
     RectWorkload("cross_small", 1, 4, 4, 150, 77, 64, False, 1.0, 1012,
                  "more rows than keys, no mask"),

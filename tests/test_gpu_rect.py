@@ -153,7 +153,7 @@ def test_rect_strided_cache_and_poisoned_outputs():
 def test_rect_full_size_sampled_heads():
     """The bench shapes at full size, in the launch configuration bench.py times: sampled K/V
     heads (with their query groups) against the oracle."""
-    for name, heads in (("decode_cmp", [0, 37, 63]), ("prefill_chunk", [5])):
+    for name, heads in (("decode_cmp", [0, 37, 63]), ("spec_decode", [1, 62]), ("prefill_chunk", [5])):
         w = wl.RECT_WORKLOADS[name]
         print("case rect_full", name, flush=True)
         full = wl.make_rect_inputs(w)
