@@ -75,6 +75,7 @@ struct FwdView {
     int BH, H, S, group;
     bool packed;  // decoding: the rows of a head are the query heads of one K/V head
     int pack_sq;  // ... times this many new positions each (0: not packed, or one position)
+    int64_t pack_stride_g;  // distance between the packed query heads when their rows are not at one distance
     int64_t stride_b, stride_h, stride_s;
     bool causal;
 };
@@ -92,7 +93,7 @@ struct FwdView {
 FwdView fwd_view(const attn_rect_params_t &p, bool rope)
 {
     FwdView v;
-    v.pack_sq = 0;
+    v.pack_sq = 0; v.pack_stride_g = 0;
     const int G = p.Hq / p.Hkv;
     if (p.Sq == 1 && G > 1 &&
         check_strides(G, p.D, p.q_stride_b, G * p.q_stride_h, p.q_stride_h) == ATTN_OK) {
@@ -101,11 +102,16 @@ FwdView fwd_view(const attn_rect_params_t &p, bool rope)
         v.causal = false; v.packed = true;
     } else if (!rope && p.Sq > 1 && p.Sq <= 32 && G > 1 &&
                // (one query tile of the streaming kernel: up to 32 rows at D <= 64, 128 above)
-               G * p.Sq <= (kernel_d(p.D) >= 128 ? 128 : 32) && p.q_stride_h == (int64_t)p.Sq * p.q_stride_s &&
+               G * p.Sq <= (kernel_d(p.D) >= 128 ? 128 : 32) &&
+               // rows of a head contiguous to the next head's: one distance; otherwise (e.g. [B,S,H,D]
+               // tensors) the kernels address a packed row by (head, position); not at D = 256, whose
+               // query rows arrive by direct transfers of whole tiles
+               (p.q_stride_h == (int64_t)p.Sq * p.q_stride_s || kernel_d(p.D) <= 128) &&
                check_strides(G * p.Sq, p.D, p.q_stride_b, G * p.q_stride_h, p.q_stride_s) == ATTN_OK) {
         v.BH = p.B * p.Hkv; v.H = p.Hkv; v.S = G * p.Sq; v.group = 1;
         v.stride_b = p.q_stride_b; v.stride_h = G * p.q_stride_h; v.stride_s = p.q_stride_s;
         v.causal = p.causal != 0; v.packed = true; v.pack_sq = p.Sq;
+        if (p.q_stride_h != (int64_t)p.Sq * p.q_stride_s) v.pack_stride_g = p.q_stride_h;
     } else {
         v.BH = p.B * p.Hq; v.H = p.Hq; v.S = p.Sq; v.group = G;
         v.stride_b = p.q_stride_b; v.stride_h = p.q_stride_h; v.stride_s = p.q_stride_s;
@@ -183,7 +189,7 @@ static int fwd_impl(const void *Q, const void *K, const void *V, void *O, float 
     a.LSE = LSE;
     a.stride_b = v.stride_b; a.stride_h = v.stride_h; a.stride_s = v.stride_s;
     a.kv_stride_b = p->kv_stride_b; a.kv_stride_h = p->kv_stride_h; a.kv_stride_s = p->kv_stride_s;
-    a.S = v.S; a.Sk = p->Sk; a.H = v.H; a.BH = v.BH; a.group = v.group; a.pack_sq = v.pack_sq;
+    a.S = v.S; a.Sk = p->Sk; a.H = v.H; a.BH = v.BH; a.group = v.group; a.pack_sq = v.pack_sq; a.pack_stride_g = v.pack_stride_g;
     a.Dr = p->D;
     a.nqt = 0;
     a.scale_log2e = p->scale * 1.4426950408889634f;

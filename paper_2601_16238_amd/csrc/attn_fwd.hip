@@ -732,7 +732,7 @@ __global__ void __launch_bounds__(256) attn_fwd_merge_kernel(const FwdArgs a)
     const float inv = 1.0f / den;
     const int bh = (int)(row / a.S), q = (int)(row % a.S);
     elem *Op = a.O + (int64_t)(bh / a.H) * a.stride_b + (int64_t)(bh % a.H) * a.stride_h +
-               (int64_t)q * a.stride_s + d0;
+               a.row_offset(q) + d0;
     if (d0 < a.Dr) *(elem4 *)Op = pack4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
     if (d0 == 0) a.LSE[row] = m + logf(den);
 }

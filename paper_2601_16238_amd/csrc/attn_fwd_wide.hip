@@ -111,7 +111,7 @@ attn_fwd_wide_kernel(const FwdArgs a)
     if constexpr (!kStageQ) {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-            qf[ks] = as_elem8(ld_row16(a.Q + base + (int64_t)qc * a.stride_s, ks * 16 + 8 * h, Dr));
+            qf[ks] = as_elem8(ld_row16(a.Q + base + a.row_offset(qc), ks * 16 + 8 * h, Dr));
     }
 
     // Rotary embedding of the query rows, fused into their load (D <= 128, head dimension == D):
@@ -484,7 +484,7 @@ attn_fwd_wide_kernel(const FwdArgs a)
         for (int j = 0; j < 32 / RPI; ++j) {
             const u32x4 v = *(const u32x4 *)(stg + at(RPI * j + lr_, lc));
             const int row = q0 + RPI * j + lr_;
-            if (row < S && lc * 8 < Dr) *(u32x4 *)(a.O + base + (int64_t)row * a.stride_s + lc * 8) = v;
+            if (row < S && lc * 8 < Dr) *(u32x4 *)(a.O + base + a.row_offset(row) + lc * 8) = v;
         }
         if (q < S && h == 0) a.LSE[(int64_t)bh * S + q] = (m + fast_log2(lt)) * kLn2;
     }

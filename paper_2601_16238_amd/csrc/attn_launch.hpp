@@ -36,6 +36,8 @@ struct FwdArgsT {
     int pack_sq;        // 0, or: the S rows of a head are G query heads x pack_sq positions of one
                         // K/V head (row r is position r % pack_sq of S_q = pack_sq new rows); only
                         // the mask needs to know
+    int64_t pack_stride_g;  // packed rows that are NOT at one distance (e.g. [B,S,H,D] tensors): row r lies
+                        // (r / pack_sq) * pack_stride_g + (r % pack_sq) * stride_s past the head; 0: r * stride_s
     int nqt;            // query tiles per head (set by the launcher)
     float scale_log2e;  // scale * log2(e): the softmax runs on exp2
     // Split over the keys (small problems that would leave most of the chip idle): split z
@@ -51,6 +53,12 @@ struct FwdArgsT {
     const float *rope_cos, *rope_sin;
     E *Qrot;
     int rope_pos0, rope_row_step;
+    // element offset of query row r from its head's first row (Q, O, Qrot share the strides)
+    __host__ __device__ int64_t row_offset(int r) const
+    {
+        return pack_stride_g ? (int64_t)(r / pack_sq) * pack_stride_g + (int64_t)(r % pack_sq) * stride_s
+                             : (int64_t)r * stride_s;
+    }
 };
 
 template <typename E>

@@ -262,3 +262,25 @@ def test_rect_backward_with_dq_split_over_the_keys(B, Hq, Hkv, Sq, Sk, D, causal
     dQ2, _, _ = attn.attn_bwd_rect(Q, K, V, O, dO, LSE, x["scale"], causal, workspace=ws)
     torch.cuda.synchronize()
     assert torch.equal(dQ.view(torch.int16), dQ2.view(torch.int16))
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Sq,Sk,D,causal", [
+    (2, 8, 2, 4, 3000, 128, True), (1, 12, 2, 5, 1025, 64, True), (1, 16, 2, 8, 2000, 128, True),
+    (1, 8, 2, 4, 700, 256, True)])
+def test_packed_rows_of_grouped_heads_in_bshd_tensors(B, Hq, Hkv, Sq, Sk, D, causal):
+    """A few new rows per sequence with Q and O stored [B,S,H,D]: the rows of a query head are
+    not contiguous to the next head's, so a packed row is addressed by (head, position) (at
+    D = 256 the problem runs unpacked).  Forward with the planned split and in one kernel."""
+    print("case packed_bshd", B, Hq, Hkv, Sq, Sk, D, causal, flush=True)
+    x = wl.random_rect_inputs(B, Hq, Hkv, Sq, Sk, D, seed=1600 + Sq + Sk)
+    Oref, Lref = oracle.attn_fwd(x["Q"], x["K"], x["V"], x["scale"], causal)
+    Q = to_dev(x["Q"]).permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)   # BSHD memory
+    assert Q.stride() == (Sq * Hq * D, D, Hq * D, 1)
+    K, V = to_dev(x["K"]), to_dev(x["V"])
+    for split in (True, False):
+        O = torch.full((B, Sq, Hq, D), float("nan"), dtype=torch.bfloat16, device="cuda").permute(0, 2, 1, 3)
+        LSE = torch.full((B, Hq, Sq), float("nan"), dtype=torch.float32, device="cuda")
+        attn.attn_fwd_rect(Q, K, V, x["scale"], causal, O=O, LSE=LSE, split=split)
+        torch.cuda.synchronize()
+        check_bf16("O split=%s" % split, to_f64(O), Oref)
+        check_lse(to_f64(LSE), Lref)
