@@ -183,7 +183,7 @@ int attn_bwd_gqa_stages(const void *Q, const void *K, const void *V, const void 
  * problem, 0 when it would not split.  workspace == NULL (with any size) is allowed and
  * means: do not split.  A non-NULL workspace must be 256-byte aligned and at least that
  * large, else ATTN_ERR_WORKSPACE; its contents are undefined on entry and exit.  The split
- * plan depends only on the shape, so results are deterministic.
+ * plan depends only on the shape and the strides, so results are deterministic.
  *
  * Backward: as attn_bwd_gqa.  Keys that no row sees get zero gradients.  Workspace: the row
  * statistics (two fp32 per query row, rounded up to 256 bytes) and, when B*Hq*ceil(Sq/256)
@@ -234,8 +234,11 @@ int attn_bwd_rect(const void *Q, const void *K, const void *V, const void *O, co
  *   attn_fwd_rope: Q in (unrotated), K_rot, V in; cos_table, sin_table in; O, LSE out as
  *     attn_fwd_rect; Q_rot: optional out (NULL: not stored), the rotated query rows, same
  *     strides as Q -- what attn_bwd_rope needs.  Workspace as attn_fwd_rect, sized by
- *     attn_fwd_rope_workspace_bytes (the same plan as attn_fwd_rect: when decoding, Sq == 1, the
- *     query heads of a K/V head are handled as rows of one head, all at the last position).
+ *     attn_fwd_rope_workspace_bytes (when decoding, Sq == 1, the query heads of a K/V head are
+ *     handled as rows of one head, all at the last position, as in attn_fwd_rect; with a few new
+ *     rows per sequence, 1 < Sq <= 32, attn_fwd_rect packs them as well and this call does not,
+ *     so the two plans, and workspace sizes, can differ: size each call's workspace with its own
+ *     function).
  *   attn_bwd_rope: Q_rot, K_rot, V, O, dO, LSE in as attn_bwd_rect (with the ROTATED Q and K);
  *     dQ out: gradient of the UNROTATED query rows (the accumulated gradient is rotated back in
  *     registers before it is stored); dK_rot out: gradient of the rotated K rows (rotate it
