@@ -234,11 +234,8 @@ int attn_bwd_rect(const void *Q, const void *K, const void *V, const void *O, co
  *   attn_fwd_rope: Q in (unrotated), K_rot, V in; cos_table, sin_table in; O, LSE out as
  *     attn_fwd_rect; Q_rot: optional out (NULL: not stored), the rotated query rows, same
  *     strides as Q -- what attn_bwd_rope needs.  Workspace as attn_fwd_rect, sized by
- *     attn_fwd_rope_workspace_bytes (when decoding, Sq == 1, the query heads of a K/V head are
- *     handled as rows of one head, all at the last position, as in attn_fwd_rect; with a few new
- *     rows per sequence, 1 < Sq <= 32, attn_fwd_rect packs them as well and this call does not,
- *     so the two plans, and workspace sizes, can differ: size each call's workspace with its own
- *     function).
+ *     attn_fwd_rope_workspace_bytes (the same plan as attn_fwd_rect: when decoding, Sq == 1, the
+ *     query heads of a K/V head are handled as rows of one head, all at the last position).
  *   attn_bwd_rope: Q_rot, K_rot, V, O, dO, LSE in as attn_bwd_rect (with the ROTATED Q and K);
  *     dQ out: gradient of the UNROTATED query rows (the accumulated gradient is rotated back in
  *     registers before it is stored); dK_rot out: gradient of the rotated K rows (rotate it

@@ -88,10 +88,10 @@ struct FwdView {
 // A few new positions per sequence (Sq = 2 .. 32, G x Sq rows in one query tile, e.g. speculative decoding): with the rows of
 // a query head contiguous to the next head's (q_stride_h == Sq * q_stride_s) the G x Sq rows of
 // a K/V head are again rows at one uniform distance and are packed the same way; row r is
-// position r % Sq, which only the causal mask needs to know.  Not with the rotary embedding
-// fused (the table row of a packed row would depend on r % Sq as well).
+// position r % Sq, which the causal mask and the fused rotary embedding need to know.
 FwdView fwd_view(const attn_rect_params_t &p, bool rope)
 {
+    (void)rope;  // the plan is the same with and without the fused rotary embedding
     FwdView v;
     v.pack_sq = 0; v.pack_stride_g = 0;
     const int G = p.Hq / p.Hkv;
@@ -100,7 +100,7 @@ FwdView fwd_view(const attn_rect_params_t &p, bool rope)
         v.BH = p.B * p.Hkv; v.H = p.Hkv; v.S = G; v.group = 1;
         v.stride_b = p.q_stride_b; v.stride_h = G * p.q_stride_h; v.stride_s = p.q_stride_h;
         v.causal = false; v.packed = true;
-    } else if (!rope && p.Sq > 1 && p.Sq <= 32 && G > 1 &&
+    } else if (p.Sq > 1 && p.Sq <= 32 && G > 1 &&
                // (one query tile of the streaming kernel: up to 32 rows at D <= 64, 128 above)
                G * p.Sq <= (kernel_d(p.D) >= 128 ? 128 : 32) &&
                // rows of a head contiguous to the next head's: one distance; otherwise (e.g. [B,S,H,D]

@@ -120,8 +120,10 @@ attn_fwd_wide_kernel(const FwdArgs a)
     // attn_fwd.hip, so that all three give the same bits.
     if constexpr (D <= 128) {
         if (a.rope_cos) {
-            const int64_t pos = (int64_t)(qc * a.rope_row_step + a.rope_pos0) * (D / 2);
-            elem *qr = a.Qrot ? a.Qrot + base + (int64_t)qc * a.stride_s : nullptr;
+            // (packed rows: row r sits at position r % Sq of the new rows)
+            const int rpos = a.pack_sq ? qc % a.pack_sq : qc * a.rope_row_step;
+            const int64_t pos = (int64_t)(rpos + a.rope_pos0) * (D / 2);
+            elem *qr = a.Qrot ? a.Qrot + base + a.row_offset(qc) : nullptr;
 #pragma unroll
             for (int ks = 0; ks < KS / 2; ++ks) {
                 float lo[8], hi[8];

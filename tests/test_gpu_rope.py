@@ -32,6 +32,7 @@ CASES = [  # B, Hq, Hkv, Sq, Sk, D, causal
     (1, 8, 8, 1, 513, 64, True), (1, 4, 2, 20, 700, 64, True),
     (2, 3, 3, 100, 100, 128, True), (1, 4, 4, 200, 256, 64, True),   # short heads: the fused one-launch backward
     (64, 8, 4, 60, 90, 64, True),         # ... and its grouped-head form (256 K/V heads)
+    (2, 16, 2, 8, 2500, 128, True), (1, 12, 2, 5, 1100, 64, True),   # a few new rows, grouped heads: packed rows, each at its position
 ]
 
 
