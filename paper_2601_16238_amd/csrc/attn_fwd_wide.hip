@@ -9,6 +9,11 @@
 //  - D = 64 and 128 on problems with few query rows against many keys (decoding, short chunks),
 //    which only stream K and V: the transfers move a tile with a quarter of the vector-memory
 //    instructions of the register-staged V path and none of its transposing arithmetic.
+//    Decoding proper (at most 32 rows per head, so that only the first wave holds rows; the rows
+//    may be the query heads of one K/V head, times a few new positions each, packed into one head
+//    by the caller of the launcher) runs in the NT form of the kernel: K and V, which the launch
+//    reads exactly once, come by non-temporal transfers, and those are requested by the three waves
+//    without rows, so that the computing wave never delays a tile.
 //
 // One barrier per tile of 64 keys.  A tile is processed in four steps whose independent halves
 // sit in one basic block each, so that the matrix pipe and the vector ALU overlap inside a wave:
