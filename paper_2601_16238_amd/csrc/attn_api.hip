@@ -85,7 +85,7 @@ struct FwdView {
 // head of G rows.  K and V are then streamed once per K/V head instead of once per query
 // head.  A single row sees every key, so the mask drops out.  LSE [B,Hq,1] is the same
 // memory as [B,Hkv,G].
-// A few new positions per sequence (Sq = 2 .. 32, G x Sq rows in one query tile, e.g. speculative decoding): with the rows of
+// A few new positions per sequence (Sq = 2 .. 32, G x Sq <= 128 rows: one query tile, e.g. speculative decoding): with the rows of
 // a query head contiguous to the next head's (q_stride_h == Sq * q_stride_s) the G x Sq rows of
 // a K/V head are again rows at one uniform distance and are packed the same way; row r is
 // position r % Sq, which the causal mask and the fused rotary embedding need to know.
@@ -101,8 +101,7 @@ FwdView fwd_view(const attn_rect_params_t &p, bool rope)
         v.stride_b = p.q_stride_b; v.stride_h = G * p.q_stride_h; v.stride_s = p.q_stride_h;
         v.causal = false; v.packed = true;
     } else if (p.Sq > 1 && p.Sq <= 32 && G > 1 &&
-               // (one query tile of the streaming kernel: up to 32 rows at D <= 64, 128 above)
-               G * p.Sq <= (kernel_d(p.D) >= 128 ? 128 : 32) &&
+               G * p.Sq <= 128 &&  // one query tile of the streaming kernel
                // rows of a head contiguous to the next head's: one distance; otherwise (e.g. [B,S,H,D]
                // tensors) the kernels address a packed row by (head, position); not at D = 256, whose
                // query rows arrive by direct transfers of whole tiles

@@ -868,7 +868,7 @@ int fwd_split_plan(int BH, int S, int Sk, int D, bool causal, int *kps)
 // against 23.6 us), large launches by 7-12 %.
 static bool prefer_streaming_forward(const FwdArgs &a, int D)
 {
-    if (a.S <= 32) return true;
+    if (a.S <= 32 || a.pack_sq) return true;  // (packed rows: only that kernel knows their positions)
     return D == 128 && a.S <= 128;
 }
 

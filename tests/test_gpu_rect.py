@@ -24,8 +24,8 @@ CASES = [
     # packed head (mask by position r % Sq); 16, 30 and 32 rows; ragged last key tile
     (2, 8, 2, 4, 3000, 128, True), (1, 12, 2, 5, 1025, 64, True), (1, 16, 2, 4, 777, 128, False),
     (1, 8, 4, 3, 5, 128, True), (2, 4, 2, 16, 4100, 128, True),
-    # ... up to one query tile of 128 packed rows at D >= 128 (64, 128 and 108 rows: the last wave
-    # partly filled; D = 256), and 48 rows at D = 64, which stay unpacked
+    # ... up to one query tile of 128 packed rows (64, 128 and 108 rows: the last wave partly
+    # filled; D = 256; 48 rows at D = 64 and 64 rows at D = 96)
     (1, 16, 2, 8, 3000, 128, True), (2, 8, 1, 16, 2100, 128, True), (1, 24, 2, 9, 1000, 128, True),
     (1, 32, 4, 6, 1500, 256, True), (1, 12, 2, 8, 700, 64, True), (1, 16, 2, 8, 900, 96, False),
 ]
